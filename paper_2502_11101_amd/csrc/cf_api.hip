@@ -1,0 +1,199 @@
+// C-ABI entry points of libcachefocus: host-side validation and launch planning.
+// Every argument that lives on the host is checked here, before any HIP call, so the error
+// paths can be exercised without a GPU.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "cf_common.h"
+
+namespace cf {
+
+namespace {
+thread_local char g_err[512] = "";
+}
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+size_t elem_size(int32_t dtype) { return dtype == CF_F32 ? 4 : 2; }
+
+cf_status check_desc(const cf_layer_desc* d) {
+    CF_REQUIRE(d != nullptr, CF_ERR_INVALID_ARG, "desc is NULL");
+    CF_REQUIRE(d->n_q_heads > 0 && d->n_kv_heads > 0, CF_ERR_INVALID_ARG, "head counts must be positive");
+    CF_REQUIRE(d->n_q_heads % d->n_kv_heads == 0, CF_ERR_INVALID_ARG,
+               "n_q_heads (%d) is not a multiple of n_kv_heads (%d)", d->n_q_heads, d->n_kv_heads);
+    CF_REQUIRE(d->dtype == CF_F32 || d->dtype == CF_BF16 || d->dtype == CF_F16, CF_ERR_INVALID_ARG,
+               "unknown dtype %d", d->dtype);
+    CF_REQUIRE(d->rope_pairing == CF_ROPE_HALF || d->rope_pairing == CF_ROPE_INTERLEAVED, CF_ERR_INVALID_ARG,
+               "unknown rope_pairing %d", d->rope_pairing);
+    CF_REQUIRE(d->head_dim > 0, CF_ERR_INVALID_ARG, "head_dim must be positive");
+    CF_REQUIRE(d->head_dim % 16 == 0 && d->head_dim <= kMaxHeadDim, CF_ERR_UNSUPPORTED,
+               "head_dim %d unsupported (multiple of 16, at most %d)", d->head_dim, kMaxHeadDim);
+    CF_REQUIRE(std::isfinite(d->rope_base) && d->rope_base > 1.0, CF_ERR_INVALID_ARG, "rope_base must be > 1");
+    CF_REQUIRE(d->max_positions > 0, CF_ERR_INVALID_ARG, "max_positions must be positive");
+    CF_REQUIRE(std::isfinite(d->softmax_scale) && d->softmax_scale >= 0.f, CF_ERR_INVALID_ARG,
+               "softmax_scale must be >= 0");
+    CF_REQUIRE(d->reserved == 0, CF_ERR_INVALID_ARG, "desc.reserved must be 0");
+    return CF_OK;
+}
+
+void fill_rope_freq(const cf_layer_desc* d, RopeFreq* f) {
+    const int half = d->head_dim / 2;
+    const double two_pi = 6.283185307179586476925286766559;
+    for (int m = 0; m < kMaxHalf; ++m)
+        f->rev[m] = m < half ? std::pow(d->rope_base, -2.0 * m / d->head_dim) / two_pi : 0.0;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace cf
+
+using namespace cf;
+
+extern "C" {
+
+const char* cf_last_error(void) { return g_err; }
+
+int32_t cf_version(void) { return 100; }
+
+cf_status cf_reposition_keys(const cf_layer_desc* desc, const void* k_in, void* k_out, const cf_segment* segs,
+                             int32_t n_seg, int64_t n_store_tokens, int32_t max_seg_len, int32_t* dev_flag,
+                             void* stream) {
+    cf_status st = check_desc(desc);
+    if (st != CF_OK) return st;
+    CF_REQUIRE(n_seg >= 0, CF_ERR_INVALID_ARG, "n_seg is negative");
+    CF_REQUIRE(n_store_tokens >= 0, CF_ERR_INVALID_ARG, "n_store_tokens is negative");
+    CF_REQUIRE(max_seg_len >= 1, CF_ERR_INVALID_ARG, "max_seg_len must be >= 1");
+    if (n_seg == 0) return CF_OK;
+    CF_REQUIRE(k_in && k_out && segs, CF_ERR_INVALID_ARG, "k_in, k_out and segs must not be NULL");
+    CF_REQUIRE(aligned16(k_in) && aligned16(k_out), CF_ERR_INVALID_ARG, "k_in/k_out must be 16-byte aligned");
+    RopeFreq f;
+    fill_rope_freq(desc, &f);
+    return launch_reposition(desc, f, k_in, k_out, segs, n_seg, n_store_tokens, max_seg_len, dev_flag,
+                             static_cast<hipStream_t>(stream));
+}
+
+size_t cf_prefill_workspace_bytes(const cf_layer_desc* desc, int32_t batch, int32_t max_tq, int32_t seg_stride,
+                                  int64_t max_kv_tokens) {
+    if (check_desc(desc) != CF_OK) return 0;
+    if (batch <= 0 || max_tq <= 0 || seg_stride <= 0 || max_kv_tokens < 0) return 0;
+    size_t n = mfma_path_supported(desc) ? mfma_workspace_bytes(desc, batch, max_tq, seg_stride, max_kv_tokens)
+                                         : generic_workspace_bytes(desc, batch, max_tq, seg_stride);
+    return (n + 255) & ~(size_t)255;
+}
+
+cf_status cf_prefill_attention(const cf_layer_desc* desc, const void* q, const int32_t* q_off,
+                               int32_t q_stored_start, const int32_t* q_new_start, const void* k_store,
+                               const void* v_store, int64_t n_store_tokens, const void* k_self,
+                               const void* v_self, const cf_segment* segs, const int32_t* n_seg,
+                               int32_t seg_stride, int32_t batch, int32_t max_tq, int64_t max_kv_tokens,
+                               void* out, float* mass, float* score_accum, int32_t score_stride,
+                               void* workspace, size_t workspace_bytes, int32_t* dev_flag, void* stream) {
+    cf_status st = check_desc(desc);
+    if (st != CF_OK) return st;
+    CF_REQUIRE(batch >= 0, CF_ERR_INVALID_ARG, "batch is negative");
+    CF_REQUIRE(max_tq >= 1, CF_ERR_INVALID_ARG, "max_tq must be >= 1");
+    CF_REQUIRE(seg_stride >= 1, CF_ERR_INVALID_ARG, "seg_stride must be >= 1");
+    CF_REQUIRE(n_store_tokens >= 0 && max_kv_tokens >= 0, CF_ERR_INVALID_ARG, "negative token count");
+    CF_REQUIRE(score_accum == nullptr || score_stride >= 1, CF_ERR_INVALID_ARG,
+               "score_stride must be >= 1 when score_accum is given");
+    if (batch == 0) return CF_OK;
+    CF_REQUIRE(q && q_off && q_new_start && segs && n_seg && out && mass, CF_ERR_INVALID_ARG,
+               "q, q_off, q_new_start, segs, n_seg, out and mass must not be NULL");
+    CF_REQUIRE((k_self == nullptr) == (v_self == nullptr), CF_ERR_INVALID_ARG,
+               "k_self and v_self must be given together");
+    CF_REQUIRE(n_store_tokens == 0 || (k_store && v_store), CF_ERR_INVALID_ARG,
+               "k_store/v_store are NULL but n_store_tokens > 0");
+    CF_REQUIRE(aligned16(q) && aligned16(k_store) && aligned16(v_store) && aligned16(k_self) &&
+                   aligned16(v_self) && aligned16(out),
+               CF_ERR_INVALID_ARG, "tensor base pointers must be 16-byte aligned");
+    CF_REQUIRE(q_stored_start >= 0 && q_stored_start < desc->max_positions, CF_ERR_RANGE,
+               "q_stored_start outside [0, max_positions)");
+    const size_t need = cf_prefill_workspace_bytes(desc, batch, max_tq, seg_stride, max_kv_tokens);
+    CF_REQUIRE(workspace != nullptr && workspace_bytes >= need, CF_ERR_WORKSPACE,
+               "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+    CF_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, CF_ERR_WORKSPACE,
+               "workspace must be 256-byte aligned");
+
+    AttnArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.q = q; a.q_off = q_off; a.q_stored_start = q_stored_start; a.q_new_start = q_new_start;
+    a.k_store = k_store; a.v_store = v_store; a.n_store_tokens = n_store_tokens;
+    a.k_self = k_self; a.v_self = v_self; a.segs = segs; a.n_seg = n_seg; a.seg_stride = seg_stride;
+    a.batch = batch; a.max_tq = max_tq; a.max_kv_tokens = max_kv_tokens; a.out = out; a.mass = mass;
+    a.score_accum = score_accum; a.score_stride = score_stride; a.workspace = workspace;
+    a.workspace_bytes = workspace_bytes; a.dev_flag = dev_flag;
+    a.n_q_heads = desc->n_q_heads; a.n_kv_heads = desc->n_kv_heads; a.head_dim = desc->head_dim;
+    a.dtype = desc->dtype; a.pairing = desc->rope_pairing;
+    const double scale = desc->softmax_scale > 0.f ? (double)desc->softmax_scale : 1.0 / std::sqrt((double)desc->head_dim);
+    a.scale_log2e = (float)(scale * 1.4426950408889634073599246810019);
+    RopeFreq f;
+    fill_rope_freq(desc, &f);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (mfma_path_supported(desc)) return launch_attention_mfma(a, f, s);
+    return launch_attention_generic(a, f, s);
+}
+
+cf_status cf_prune_topk(const float* score, const int32_t* len, const int32_t* cand, const int32_t* n_cand,
+                        int32_t keep, int32_t batch, int32_t stride, int32_t* keep_idx, int32_t* n_keep,
+                        int32_t* dev_flag, void* stream) {
+    CF_REQUIRE(batch >= 0, CF_ERR_INVALID_ARG, "batch is negative");
+    CF_REQUIRE(stride >= 1 && stride <= kMaxSelectStride, CF_ERR_INVALID_ARG, "stride must be in [1, %d]",
+               kMaxSelectStride);
+    CF_REQUIRE(keep >= 0 && keep <= stride, CF_ERR_INVALID_ARG, "keep (%d) must be in [0, stride = %d]", keep,
+               stride);
+    if (batch == 0) return CF_OK;
+    CF_REQUIRE(score && cand && n_cand && keep_idx && n_keep, CF_ERR_INVALID_ARG,
+               "score, cand, n_cand, keep_idx and n_keep must not be NULL");
+    CF_REQUIRE(keep_idx != cand, CF_ERR_INVALID_ARG, "keep_idx must not alias cand");
+    return launch_prune(score, len, cand, n_cand, keep, batch, stride, keep_idx, n_keep, dev_flag,
+                        static_cast<hipStream_t>(stream));
+}
+
+cf_status cf_assign_positions(const int32_t* len, const int32_t* ranked, const int32_t* n_ranked, int32_t batch,
+                              int32_t stride, int32_t pos_begin, int32_t pos_end, int32_t strategy,
+                              int32_t force_n_reuse, int32_t* new_start, int32_t* q_start, int32_t* n_reuse,
+                              int32_t* order, int32_t* dev_flag, void* stream) {
+    CF_REQUIRE(batch >= 0, CF_ERR_INVALID_ARG, "batch is negative");
+    CF_REQUIRE(stride >= 1 && stride <= kMaxSelectStride, CF_ERR_INVALID_ARG, "stride must be in [1, %d]",
+               kMaxSelectStride);
+    CF_REQUIRE(strategy == CF_ALLOC_KEEP || strategy == CF_ALLOC_ALIGN || strategy == CF_ALLOC_SORT,
+               CF_ERR_INVALID_ARG, "unknown strategy %d", strategy);
+    CF_REQUIRE(force_n_reuse >= 0, CF_ERR_INVALID_ARG, "force_n_reuse is negative");
+    CF_REQUIRE(pos_begin >= 0 && pos_end > pos_begin, CF_ERR_RANGE, "need 0 <= pos_begin < pos_end (got %d, %d)",
+               pos_begin, pos_end);
+    if (batch == 0) return CF_OK;
+    CF_REQUIRE(len && ranked && n_ranked && order, CF_ERR_INVALID_ARG,
+               "len, ranked, n_ranked and order must not be NULL");
+    CF_REQUIRE(order != ranked, CF_ERR_INVALID_ARG, "order must not alias ranked");
+    CF_REQUIRE(strategy == CF_ALLOC_KEEP || (new_start && q_start && n_reuse), CF_ERR_INVALID_ARG,
+               "new_start, q_start and n_reuse must not be NULL");
+    return launch_assign(len, ranked, n_ranked, batch, stride, pos_begin, pos_end, strategy, force_n_reuse,
+                         new_start, q_start, n_reuse, order, dev_flag, static_cast<hipStream_t>(stream));
+}
+
+cf_status cf_gather_segments(const int64_t* doc_tok_offset, const int32_t* len, const int32_t* order,
+                             const int32_t* n_order, const int32_t* new_start, const int32_t* q_start,
+                             const int32_t* q_off, int32_t batch, int32_t stride, int32_t prefix_len,
+                             int32_t doc_stored_start, int32_t q_stored_start, cf_segment* segs, int32_t* n_seg,
+                             int32_t seg_stride, int32_t* dev_flag, void* stream) {
+    CF_REQUIRE(batch >= 0, CF_ERR_INVALID_ARG, "batch is negative");
+    CF_REQUIRE(stride >= 1, CF_ERR_INVALID_ARG, "stride must be >= 1");
+    CF_REQUIRE(prefix_len >= 0, CF_ERR_INVALID_ARG, "prefix_len is negative");
+    CF_REQUIRE(doc_stored_start >= 0 && q_stored_start >= 0, CF_ERR_RANGE, "stored positions are negative");
+    CF_REQUIRE(seg_stride >= 2, CF_ERR_INVALID_ARG, "seg_stride must be >= 2");
+    if (batch == 0) return CF_OK;
+    CF_REQUIRE(doc_tok_offset && len && order && n_order && new_start && q_start && q_off && segs && n_seg,
+               CF_ERR_INVALID_ARG, "NULL table pointer");
+    return launch_gather(doc_tok_offset, len, order, n_order, new_start, q_start, q_off, batch, stride,
+                         prefix_len, doc_stored_start, q_stored_start, segs, n_seg, seg_stride, dev_flag,
+                         static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

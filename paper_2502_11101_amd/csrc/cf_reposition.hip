@@ -1,0 +1,159 @@
+// Cache Re-Positioning, materialised (Sec. 2.3, Eq. 5): every key of every listed segment is
+// rotated from the position it was cached at to its new position.  Pure streaming kernel:
+// 16-byte loads and stores, one read and one write of K, bound by HBM bandwidth.
+#include "cf_common.h"
+
+namespace cf {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kTokPerBlock = 16;   // tokens one block handles per sweep of the segment
+
+// Eight consecutive elements held as floats.
+template <int DT> struct Vec8;
+template <> struct Vec8<CF_F32> {
+    static __device__ __forceinline__ void load(const void* base, int64_t idx, float (&v)[8]) {
+        const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(base) + idx);
+        float4 a = p[0], b = p[1];
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+    static __device__ __forceinline__ void store(void* base, int64_t idx, const float (&v)[8]) {
+        float4* p = reinterpret_cast<float4*>(static_cast<float*>(base) + idx);
+        p[0] = make_float4(v[0], v[1], v[2], v[3]);
+        p[1] = make_float4(v[4], v[5], v[6], v[7]);
+    }
+};
+template <int DT> struct Vec8Half {
+    static __device__ __forceinline__ void load(const void* base, int64_t idx, float (&v)[8]) {
+        uint4 r = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(base) + idx);
+        uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (DT == CF_BF16) {
+                v[2 * i] = bf16_bits_to_float(w[i] & 0xffffu);
+                v[2 * i + 1] = bf16_bits_to_float(w[i] >> 16);
+            } else {
+                v[2 * i] = f16_bits_to_float(w[i] & 0xffffu);
+                v[2 * i + 1] = f16_bits_to_float(w[i] >> 16);
+            }
+        }
+    }
+    static __device__ __forceinline__ void store(void* base, int64_t idx, const float (&v)[8]) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (DT == CF_BF16)
+                w[i] = float_to_bf16_bits(v[2 * i]) | (float_to_bf16_bits(v[2 * i + 1]) << 16);
+            else
+                w[i] = float_to_f16_bits(v[2 * i]) | (float_to_f16_bits(v[2 * i + 1]) << 16);
+        }
+        *reinterpret_cast<uint4*>(static_cast<uint16_t*>(base) + idx) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+template <> struct Vec8<CF_BF16> : Vec8Half<CF_BF16> {};
+template <> struct Vec8<CF_F16> : Vec8Half<CF_F16> {};
+
+// grid = (n_seg, sweeps); block = 256 threads.  A work item is 8 pairs of one (token, kv head):
+// under half-split pairing the 8 first elements [8j, 8j+8) and their partners [d/2+8j, ...);
+// under interleaved pairing 16 consecutive elements.  Consecutive threads take consecutive
+// items, so each load instruction covers contiguous 128-byte (or longer) runs of a token row.
+template <int DT, int PAIRING>
+__global__ __launch_bounds__(kThreads) void reposition_kernel(
+    const void* k_in, void* k_out, const cf_segment* __restrict__ segs,
+    int64_t n_store_tokens, int n_kv_heads, int head_dim, RopeFreq freq, int32_t* dev_flag) {
+    __shared__ float2 cs[kMaxHalf];
+    const cf_segment seg = segs[blockIdx.x];
+    const int half = head_dim >> 1;
+    if (seg.len < 0 || seg.tok_offset < 0 || seg.tok_offset + seg.len > n_store_tokens) {
+        if (threadIdx.x == 0 && blockIdx.y == 0) raise_flag(dev_flag, CF_FLAG_BAD_SEGMENT);
+        return;
+    }
+    const int delta = seg.new_start - seg.stored_start;
+    for (int m = threadIdx.x; m < half; m += kThreads) cs[m] = rope_cos_sin(delta, freq.rev[m]);
+    __syncthreads();
+
+    const int items_per_head = half / 8;                 // head_dim % 16 == 0 checked on the host
+    const int items_per_tok = n_kv_heads * items_per_head;
+    const int64_t row_elems = (int64_t)n_kv_heads * head_dim;
+    for (int tok0 = blockIdx.y * kTokPerBlock; tok0 < seg.len; tok0 += gridDim.y * kTokPerBlock) {
+        const int ntok = min(kTokPerBlock, seg.len - tok0);
+        const int n_items = ntok * items_per_tok;
+        for (int it = threadIdx.x; it < n_items; it += kThreads) {
+            const int tok = it / items_per_tok;
+            const int r = it - tok * items_per_tok;
+            const int head = r / items_per_head;
+            const int j = r - head * items_per_head;
+            const int64_t base = (seg.tok_offset + tok0 + tok) * row_elems + (int64_t)head * head_dim;
+            float a[8], b[8];
+            if (PAIRING == CF_ROPE_HALF) {
+                Vec8<DT>::load(k_in, base + 8 * j, a);
+                Vec8<DT>::load(k_in, base + half + 8 * j, b);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float2 w = cs[8 * j + e];
+                    const float na = a[e] * w.x - b[e] * w.y;
+                    const float nb = a[e] * w.y + b[e] * w.x;
+                    a[e] = na;
+                    b[e] = nb;
+                }
+                Vec8<DT>::store(k_out, base + 8 * j, a);
+                Vec8<DT>::store(k_out, base + half + 8 * j, b);
+            } else {
+                Vec8<DT>::load(k_in, base + 16 * j, a);
+                Vec8<DT>::load(k_in, base + 16 * j + 8, b);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float2 w0 = cs[8 * j + e];
+                    const float x0 = a[2 * e] * w0.x - a[2 * e + 1] * w0.y;
+                    const float y0 = a[2 * e] * w0.y + a[2 * e + 1] * w0.x;
+                    a[2 * e] = x0;
+                    a[2 * e + 1] = y0;
+                    const float2 w1 = cs[8 * j + 4 + e];
+                    const float x1 = b[2 * e] * w1.x - b[2 * e + 1] * w1.y;
+                    const float y1 = b[2 * e] * w1.y + b[2 * e + 1] * w1.x;
+                    b[2 * e] = x1;
+                    b[2 * e + 1] = y1;
+                }
+                Vec8<DT>::store(k_out, base + 16 * j, a);
+                Vec8<DT>::store(k_out, base + 16 * j + 8, b);
+            }
+        }
+    }
+}
+
+template <int DT>
+cf_status launch_dt(const cf_layer_desc* d, const RopeFreq& f, const void* k_in, void* k_out,
+                    const cf_segment* segs, int32_t n_seg, int64_t n_store_tokens, int32_t max_seg_len,
+                    int32_t* dev_flag, hipStream_t s) {
+    int sweeps = (max_seg_len + kTokPerBlock - 1) / kTokPerBlock;
+    // enough blocks to cover the chip a few times over, no more
+    const int64_t want = 256 * 8;
+    int64_t cap = (want + n_seg - 1) / n_seg;
+    if (cap < 1) cap = 1;
+    if (sweeps > cap) sweeps = (int)cap;
+    if (sweeps < 1) sweeps = 1;
+    if (sweeps > 65535) sweeps = 65535;
+    dim3 grid(n_seg, sweeps);
+    if (d->rope_pairing == CF_ROPE_HALF)
+        hipLaunchKernelGGL((reposition_kernel<DT, CF_ROPE_HALF>), grid, dim3(kThreads), 0, s, k_in, k_out,
+                           segs, n_store_tokens, d->n_kv_heads, d->head_dim, f, dev_flag);
+    else
+        hipLaunchKernelGGL((reposition_kernel<DT, CF_ROPE_INTERLEAVED>), grid, dim3(kThreads), 0, s, k_in,
+                           k_out, segs, n_store_tokens, d->n_kv_heads, d->head_dim, f, dev_flag);
+    CF_HIP(hipGetLastError());
+    return CF_OK;
+}
+
+}  // namespace
+
+cf_status launch_reposition(const cf_layer_desc* d, const RopeFreq& f, const void* k_in, void* k_out,
+                            const cf_segment* segs, int32_t n_seg, int64_t n_store_tokens,
+                            int32_t max_seg_len, int32_t* dev_flag, hipStream_t s) {
+    switch (d->dtype) {
+        case CF_F32: return launch_dt<CF_F32>(d, f, k_in, k_out, segs, n_seg, n_store_tokens, max_seg_len, dev_flag, s);
+        case CF_BF16: return launch_dt<CF_BF16>(d, f, k_in, k_out, segs, n_seg, n_store_tokens, max_seg_len, dev_flag, s);
+        default: return launch_dt<CF_F16>(d, f, k_in, k_out, segs, n_seg, n_store_tokens, max_seg_len, dev_flag, s);
+    }
+}
+
+}  // namespace cf

@@ -1,0 +1,106 @@
+"""Sequencing of the cf_* calls for Alg. 2, Phase 1 (per-layer prefill with pruning).
+
+Nothing is computed here: this module owns the device-resident tables of a batch of
+queries (candidate lists, accumulated scores S, positions, segment tables, workspace) and
+issues the library calls in the order of Alg. 2.  All state lives in torch CUDA tensors;
+nothing returns to the host between layers.
+"""
+
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as cf
+
+TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+
+
+def to_device(x: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
+    """Upload values that are already exactly representable in ``dtype``."""
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    return t.to(device=device, dtype=TORCH_DTYPE[dtype])
+
+
+class PrefillBatch:
+    """Device tables of ``batch`` queries, each with up to ``stride`` candidate documents.
+
+    doc_tok_offset / doc_len: [batch, stride] host arrays (slot order = retriever rank).
+    All queries have ``tq`` rows.  Positions for documents are [prefix_len, max_positions - tq).
+    """
+
+    def __init__(self, desc: cf.cf_layer_desc, doc_tok_offset: np.ndarray, doc_len: np.ndarray, tq: int,
+                 prefix_len: int, doc_stored_start: int, n_store_tokens: int, q_stored_start: int = 0,
+                 device="cuda"):
+        self.desc = desc
+        self.device = device
+        self.batch, self.stride = doc_len.shape
+        self.tq = tq
+        self.prefix_len = prefix_len
+        self.doc_stored_start = doc_stored_start
+        self.q_stored_start = q_stored_start
+        self.n_store_tokens = n_store_tokens
+        self.seg_stride = self.stride + 2
+        self.pos_begin = prefix_len
+        self.pos_end = desc.max_positions - tq
+        i32 = dict(dtype=torch.int32, device=device)
+        self.doc_tok_offset = torch.from_numpy(np.ascontiguousarray(doc_tok_offset, dtype=np.int64)).to(device)
+        self.doc_len = torch.from_numpy(np.ascontiguousarray(doc_len, dtype=np.int32)).to(device)
+        self.q_off = torch.arange(0, (self.batch + 1) * tq, tq, **i32)
+        self.cand = torch.arange(self.stride, **i32).repeat(self.batch, 1).contiguous()
+        self.n_cand = torch.full((self.batch,), self.stride, **i32)
+        self.keep_idx = torch.zeros((self.batch, self.stride), **i32)
+        self.n_keep = torch.zeros((self.batch,), **i32)
+        self.order = torch.zeros((self.batch, self.stride), **i32)
+        self.new_start = torch.zeros((self.batch, self.stride), **i32)
+        self.q_start = torch.zeros((self.batch,), **i32)
+        self.n_reuse = torch.zeros((self.batch,), **i32)
+        self.score = torch.zeros((self.batch, self.stride), dtype=torch.float32, device=device)
+        self.mass = torch.zeros((self.batch, self.seg_stride), dtype=torch.float32, device=device)
+        self.segs = torch.zeros((self.batch, self.seg_stride, 32), dtype=torch.uint8, device=device)
+        self.n_seg = torch.zeros((self.batch,), **i32)
+        self.dev_flag = torch.zeros((1,), **i32)
+        self.max_kv_tokens = int(prefix_len + doc_len.sum(axis=1).max() + tq)
+        self.ws_bytes = cf.cf_prefill_workspace_bytes(desc, self.batch, tq, self.seg_stride, self.max_kv_tokens)
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
+        self.n_alive = self.stride
+
+    # -- Alg. 2 init: every document is a candidate, placement order = retriever order
+    def allocate_initial(self, force_n_reuse: int = 0) -> None:
+        cf.cf_assign_positions(self.doc_len, self.cand, self.n_cand, self.batch, self.stride, self.pos_begin,
+                               self.pos_end, cf.CF_ALLOC_SORT, force_n_reuse, self.new_start, self.q_start,
+                               self.n_reuse, self.order, self.dev_flag)
+        self.gather(self.n_cand)
+
+    def gather(self, n_order: torch.Tensor) -> None:
+        cf.cf_gather_segments(self.doc_tok_offset, self.doc_len, self.order, n_order, self.new_start,
+                              self.q_start, self.q_off, self.batch, self.stride, self.prefix_len,
+                              self.doc_stored_start, self.q_stored_start, self.segs, self.n_seg, self.seg_stride,
+                              self.dev_flag)
+
+    # -- Alg. 2: layer_l on the re-positioned caches, S += s^l
+    def attention(self, q, k_self, v_self, k_store, v_store, out, accumulate: bool = True) -> None:
+        cf.cf_prefill_attention(self.desc, q, self.q_off, self.q_stored_start, self.q_start, k_store, v_store,
+                                self.n_store_tokens, k_self, v_self, self.segs, self.n_seg, self.seg_stride,
+                                self.batch, self.tq, self.max_kv_tokens, out, self.mass,
+                                self.score if accumulate else None, self.stride, self.workspace, self.ws_bytes,
+                                self.dev_flag)
+
+    # -- Alg. 2: ids_sort = argsort(S); ids = prun(ids_sort); then Sec. 2.5 re-allocation
+    def prune(self, keep: int, strategy: int = cf.CF_ALLOC_SORT, normalise_by_len: bool = True,
+              force_n_reuse: int = 0) -> None:
+        cf.cf_prune_topk(self.score, self.doc_len if normalise_by_len else None, self.cand, self.n_cand, keep,
+                         self.batch, self.stride, self.keep_idx, self.n_keep, self.dev_flag)
+        cf.cf_assign_positions(self.doc_len, self.keep_idx, self.n_keep, self.batch, self.stride, self.pos_begin,
+                               self.pos_end, strategy, force_n_reuse, self.new_start, self.q_start, self.n_reuse,
+                               self.order, self.dev_flag)
+        self.gather(self.n_keep)
+        # the survivors, in placement order, are the next candidates
+        self.cand, self.order = self.order, self.cand
+        self.n_cand, self.n_keep = self.n_keep, self.n_cand
+        self.n_alive = min(keep, self.n_alive)
+
+    def flags(self) -> int:
+        return int(self.dev_flag.item())

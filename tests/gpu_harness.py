@@ -1,0 +1,64 @@
+"""GPU-side glue for the parity tests: upload a synthetic workload, run the library through
+its C ABI (via the binding), fetch results, and compute the error metrics."""
+
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import cachefocus_oracle as orc
+from paper_2502_11101_amd import binding as cf
+from paper_2502_11101_amd import pipeline as pl
+from paper_2502_11101_amd import workloads as wl
+
+OUT_TOL = {"f32": 1e-4, "bf16": 2e-2, "f16": 2e-2}
+MASS_TOL = {"f32": 1e-5, "bf16": 1e-4, "f16": 1e-4}
+
+
+def desc_of(cfg: wl.Config, pairing=cf.CF_ROPE_HALF):
+    g = cfg.geometry
+    return cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions, pairing)
+
+
+def upload_layer(cfg: wl.Config, tensors: dict):
+    g = cfg.geometry
+    return {k: pl.to_device(v, g.dtype) for k, v in tensors.items()}
+
+
+def make_batch(cfg: wl.Config, st: wl.Structure, pairing=cf.CF_ROPE_HALF) -> pl.PrefillBatch:
+    off = st.doc_off[:-1][st.query_docs]                 # [batch, k]
+    lens = st.doc_lens[st.query_docs]
+    return pl.PrefillBatch(desc_of(cfg, pairing), off, lens, cfg.tq, cfg.prefix_len, cfg.doc_stored_start,
+                           st.n_store_tokens)
+
+
+def row_error(gpu: np.ndarray, ref: np.ndarray) -> float:
+    """max over (row, head) of ||gpu - ref||_inf / ||ref[row, head]||_inf."""
+    diff = np.abs(gpu.astype(np.float64) - ref).max(axis=-1)
+    norm = np.abs(ref).max(axis=-1)
+    return float((diff / norm).max())
+
+
+def rel_error(gpu: np.ndarray, ref: np.ndarray) -> float:
+    ref = np.asarray(ref, dtype=np.float64)
+    return float((np.abs(gpu.astype(np.float64) - ref) / np.maximum(np.abs(ref), 1e-300)).max())
+
+
+def device_segments(pb: pl.PrefillBatch, b: int):
+    """Query b's current segment table as oracle Segment tuples."""
+    n = int(pb.n_seg[b].item())
+    arr = cf.segments_from_device(pb.segs[b], n)
+    return [orc.Segment(int(r["tok_offset"]), int(r["len"]), int(r["stored_start"]), int(r["new_start"]),
+                        int(r["kind"]), int(r["doc"])) for r in arr]
+
+
+def oracle_on_device_segments(cfg: wl.Config, tensors: dict, pb: pl.PrefillBatch, b: int, pairing="half"):
+    """Run the oracle for query b on exactly the segment table the device holds."""
+    g = cfg.geometry
+    segs = device_segments(pb, b)
+    q_start = int(pb.q_start[b].item())
+    q = np.asarray(tensors["q"][b * cfg.tq:(b + 1) * cfg.tq], dtype=np.float64)
+    out, mass = orc.prefill_attention(q, pb.q_stored_start, q_start, tensors["k_store"], tensors["v_store"],
+                                      tensors["k_self"], tensors["v_self"], segs, g.n_kv_heads, g.rope_base,
+                                      pairing)
+    return segs, out, mass

@@ -1,0 +1,127 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol
+the header declares, and rejects bad host arguments before touching the device."""
+
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2502_11101_amd import binding as cf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "cachefocus.h")
+
+
+def _declared():
+    text = open(HEADER).read()
+    return sorted(set(re.findall(r"CF_API[^;(]*?\b(cf_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = cf.load()
+    names = _declared()
+    assert set(names) == set(cf.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert cf.cf_version() >= 100
+
+
+def test_struct_layouts_match_the_header():
+    assert C.sizeof(cf.cf_layer_desc) == 40
+    assert cf.SEGMENT_DTYPE.itemsize == 32
+    assert cf.SEGMENT_DTYPE.fields["len"][1] == 8 and cf.SEGMENT_DTYPE.fields["doc"][1] == 24
+
+
+def _desc(**kw):
+    args = dict(n_q_heads=8, n_kv_heads=2, head_dim=128, dtype="bf16", rope_base=1.0e4, max_positions=4096)
+    args.update(kw)
+    return cf.make_desc(**args)
+
+
+def _status(fn, *a, **k):
+    with pytest.raises(cf.CacheFocusError) as e:
+        fn(*a, **k)
+    return e.value.status, e.value.message
+
+
+FAKE = 0x1000  # never dereferenced: validation fails first
+
+
+def test_descriptor_validation():
+    for bad, code in [(_desc(n_q_heads=7), cf.CF_ERR_INVALID_ARG), (_desc(head_dim=100), cf.CF_ERR_UNSUPPORTED),
+                      (_desc(head_dim=512), cf.CF_ERR_UNSUPPORTED), (_desc(dtype=9), cf.CF_ERR_INVALID_ARG),
+                      (_desc(rope_base=0.5), cf.CF_ERR_INVALID_ARG), (_desc(max_positions=0), cf.CF_ERR_INVALID_ARG),
+                      (_desc(rope_pairing=5), cf.CF_ERR_INVALID_ARG)]:
+        st, msg = _status(cf.cf_reposition_keys, bad, FAKE, FAKE, FAKE, 1, 10, 1, stream=0)
+        assert st == code and msg
+        assert cf.cf_prefill_workspace_bytes(bad, 1, 8, 4, 100) == 0
+    assert cf.cf_prefill_workspace_bytes(_desc(), 1, 8, 4, 100) > 0
+    assert cf.cf_prefill_workspace_bytes(_desc(), 1, 8, 4, 100) % 256 == 0
+
+
+def test_reposition_argument_checks():
+    d = _desc()
+    assert _status(cf.cf_reposition_keys, d, None, FAKE, FAKE, 1, 10, 1, stream=0)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.cf_reposition_keys, d, FAKE + 4, FAKE, FAKE, 1, 10, 1, stream=0)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.cf_reposition_keys, d, FAKE, FAKE, FAKE, -1, 10, 1, stream=0)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.cf_reposition_keys, d, FAKE, FAKE, FAKE, 1, 10, 0, stream=0)[0] == cf.CF_ERR_INVALID_ARG
+    cf.cf_reposition_keys(d, None, None, None, 0, 0, 1, stream=0)      # empty table: nothing to do
+
+
+def test_prefill_argument_checks():
+    d = _desc()
+
+    def call(**kw):
+        a = dict(desc=d, q=FAKE, q_off=FAKE, q_stored_start=0, q_new_start=FAKE, k_store=FAKE, v_store=FAKE,
+                 n_store_tokens=100, k_self=FAKE, v_self=FAKE, segs=FAKE, n_seg=FAKE, seg_stride=4, batch=1,
+                 max_tq=8, max_kv_tokens=100, out=FAKE, mass=FAKE, score_accum=None, score_stride=0,
+                 workspace=0x10000, workspace_bytes=1 << 30, stream=0)
+        a.update(kw)
+        return _status(cf.cf_prefill_attention, **a)
+
+    assert call(q=None)[0] == cf.CF_ERR_INVALID_ARG
+    assert call(v_self=None)[0] == cf.CF_ERR_INVALID_ARG
+    assert call(k_store=None, v_store=None)[0] == cf.CF_ERR_INVALID_ARG
+    assert call(out=FAKE + 2)[0] == cf.CF_ERR_INVALID_ARG
+    assert call(max_tq=0)[0] == cf.CF_ERR_INVALID_ARG
+    assert call(seg_stride=0)[0] == cf.CF_ERR_INVALID_ARG
+    assert call(score_accum=FAKE, score_stride=0)[0] == cf.CF_ERR_INVALID_ARG
+    assert call(q_stored_start=4096)[0] == cf.CF_ERR_RANGE
+    assert call(workspace=None)[0] == cf.CF_ERR_WORKSPACE
+    assert call(workspace_bytes=16)[0] == cf.CF_ERR_WORKSPACE
+    assert call(workspace=0x10010)[0] == cf.CF_ERR_WORKSPACE
+    st, msg = call(workspace_bytes=16)
+    assert "workspace" in msg
+    # an empty batch is a no-op and needs no GPU
+    cf.cf_prefill_attention(d, None, None, 0, None, None, None, 0, None, None, None, None, 4, 0, 8, 0, None, None,
+                            None, 0, None, 0, stream=0)
+
+
+def test_prune_and_assign_argument_checks():
+    assert _status(cf.cf_prune_topk, FAKE, None, FAKE, FAKE, 5, 1, 4, FAKE + 64, FAKE, stream=0)[0] == cf.CF_ERR_INVALID_ARG  # keep > stride
+    assert _status(cf.cf_prune_topk, FAKE, None, FAKE, FAKE, -1, 1, 4, FAKE + 64, FAKE, stream=0)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.cf_prune_topk, None, None, FAKE, FAKE, 1, 1, 4, FAKE + 64, FAKE, stream=0)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.cf_prune_topk, FAKE, None, FAKE, FAKE, 1, 1, 4, FAKE, FAKE, stream=0)[0] == cf.CF_ERR_INVALID_ARG       # alias
+    assert _status(cf.cf_prune_topk, FAKE, None, FAKE, FAKE, 1, 1, 100000, FAKE + 64, FAKE, stream=0)[0] == cf.CF_ERR_INVALID_ARG
+
+    def assign(**kw):
+        a = dict(len_=FAKE, ranked=FAKE, n_ranked=FAKE, batch=1, stride=4, pos_begin=4, pos_end=100,
+                 strategy=cf.CF_ALLOC_SORT, force_n_reuse=0, new_start=FAKE, q_start=FAKE, n_reuse=FAKE,
+                 order=FAKE + 64, stream=0)
+        a.update(kw)
+        return _status(cf.cf_assign_positions, **a)
+
+    assert assign(pos_end=4)[0] == cf.CF_ERR_RANGE
+    assert assign(pos_begin=-1)[0] == cf.CF_ERR_RANGE
+    assert assign(strategy=7)[0] == cf.CF_ERR_INVALID_ARG
+    assert assign(force_n_reuse=-2)[0] == cf.CF_ERR_INVALID_ARG
+    assert assign(new_start=None)[0] == cf.CF_ERR_INVALID_ARG
+    assert assign(order=FAKE)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.cf_gather_segments, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, 4, 0, 0, 0, FAKE, FAKE, 1,
+                   stream=0)[0] == cf.CF_ERR_INVALID_ARG
+
+
+def test_last_error_is_set():
+    _status(cf.cf_prune_topk, FAKE, None, FAKE, FAKE, 9, 1, 4, FAKE + 64, FAKE, stream=0)
+    assert "keep" in cf.cf_last_error()

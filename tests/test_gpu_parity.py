@@ -1,0 +1,269 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.  Integer results (kept indices, positions, segment tables) must be bit-exact;
+attention outputs within 1e-4 (fp32) / 2e-2 (16-bit) in the row-normalised max error; masses
+within 1e-5 / 1e-4 relative."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import cachefocus_oracle as orc
+from paper_2502_11101_amd import binding as cf
+from paper_2502_11101_amd import pipeline as pl
+from paper_2502_11101_amd import workloads as wl
+from tests import gpu_harness as G
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+I32 = dict(dtype=torch.int32, device="cuda")
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ----------------------------------------------------------------------------- cf_reposition_keys
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("pairing", [cf.CF_ROPE_HALF, cf.CF_ROPE_INTERLEAVED])
+@pytest.mark.parametrize("hkv,d,base", [(4, 64, 1.0e4), (2, 128, 1.0e6)])
+def test_reposition_keys_matches_oracle(dtype, pairing, hkv, d, base):
+    _say(f"reposition dtype={dtype} pairing={pairing} hkv={hkv} d={d}")
+    rng = np.random.default_rng(21)
+    n_tok = 700
+    k = wl.round_to_dtype(rng.standard_normal((n_tok, hkv, d), dtype=np.float32), dtype)
+    segs = [orc.Segment(0, 33, 0, 0, 1, 0), orc.Segment(40, 161, 32, 1999, 1, 1),
+            orc.Segment(210, 1, 5, 30000 if base > 1e5 else 4000, 1, 2), orc.Segment(300, 0, 0, 9, 1, 3),
+            orc.Segment(320, 380, 32, 7, 1, 4)]
+    desc = cf.make_desc(hkv, hkv, d, dtype, base, 32768, pairing)
+    k_dev = pl.to_device(k, dtype)
+    out = torch.empty_like(k_dev)
+    out.copy_(k_dev)
+    seg_dev = cf.segments_to_device(cf.segments_array(segs))
+    flag = torch.zeros(1, **I32)
+    cf.cf_reposition_keys(desc, k_dev, out, seg_dev, len(segs), n_tok, 64, flag)
+    torch.cuda.synchronize()
+    ref = orc.reposition_keys(k, segs, base, "half" if pairing == cf.CF_ROPE_HALF else "interleaved")
+    got = out.float().cpu().numpy().astype(np.float64)
+    tol = {"f32": 2e-6, "bf16": 2.0 ** -8, "f16": 2.0 ** -10}[dtype]
+    assert np.max(np.abs(got - ref)) <= tol * max(1.0, np.abs(ref).max())
+    assert flag.item() == 0
+    # the zero-shift segment and all unlisted tokens are bit-identical
+    same = torch.ones(n_tok, dtype=torch.bool)
+    for s in segs[1:]:
+        same[s.tok_offset:s.tok_offset + s.len] = False
+    assert torch.equal(out.cpu()[same], k_dev.cpu()[same])
+    # in place, then back: rotation by +D then -D returns the input to within rounding
+    cf.cf_reposition_keys(desc, k_dev, k_dev, seg_dev, len(segs), n_tok, 64, flag)
+    assert torch.equal(k_dev, out)
+    back = [s._replace(stored_start=s.new_start, new_start=s.stored_start) for s in segs]
+    cf.cf_reposition_keys(desc, k_dev, k_dev, cf.segments_to_device(cf.segments_array(back)), len(back), n_tok,
+                          64, flag)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(k_dev.float().cpu().numpy() - k)) <= 2.5 * tol * max(1.0, np.abs(k).max())
+
+
+def test_reposition_flags_bad_segments_without_touching_memory():
+    desc = cf.make_desc(2, 2, 64, "bf16", 1.0e4, 4096)
+    k = torch.randn(50, 2, 64, device="cuda").to(torch.bfloat16)
+    ref = k.clone()
+    segs = [orc.Segment(40, 20, 0, 5, 1, 0), orc.Segment(-3, 5, 0, 5, 1, 1), orc.Segment(0, -1, 0, 5, 1, 2)]
+    flag = torch.zeros(1, **I32)
+    cf.cf_reposition_keys(desc, k, k, cf.segments_to_device(cf.segments_array(segs)), 3, 50, 32, flag)
+    torch.cuda.synchronize()
+    assert flag.item() == cf.CF_FLAG_BAD_SEGMENT
+    assert torch.equal(k, ref)
+
+
+# ----------------------------------------------------------------------------- cf_prune_topk
+def test_prune_topk_bit_exact_random_and_ties():
+    rng = np.random.default_rng(31)
+    batch, stride = 37, 50
+    score = (rng.integers(0, 12, size=(batch, stride)) / 8.0).astype(np.float32)     # many exact ties
+    score[::2] = rng.random((len(score[::2]), stride), dtype=np.float32) * 100
+    lens = rng.integers(100, 201, size=(batch, stride)).astype(np.int32)
+    n_cand = rng.integers(1, stride + 1, size=batch).astype(np.int32)
+    cand = np.stack([rng.permutation(stride) for _ in range(batch)]).astype(np.int32)
+    for use_len in (True, False):
+        for keep in (0, 1, 7, 50):
+            keep_idx = torch.full((batch, stride), -1, **I32)
+            n_keep = torch.zeros(batch, **I32)
+            flag = torch.zeros(1, **I32)
+            cf.cf_prune_topk(torch.from_numpy(score).cuda(), torch.from_numpy(lens).cuda() if use_len else None,
+                             torch.from_numpy(cand).cuda(), torch.from_numpy(n_cand).cuda(), keep, batch, stride,
+                             keep_idx, n_keep, flag)
+            torch.cuda.synchronize()
+            assert flag.item() == 0
+            ki, nk = keep_idx.cpu().numpy(), n_keep.cpu().numpy()
+            for b in range(batch):
+                c = cand[b, :n_cand[b]].tolist()
+                k = min(keep, len(c))
+                ref = orc.prune_topk(score[b], lens[b] if use_len else None, c, k)
+                assert nk[b] == k
+                assert ki[b, :k].tolist() == ref
+                assert np.all(ki[b, k:] == -1)
+
+
+def test_prune_topk_flags():
+    score = torch.tensor([[1.0, float("nan"), 2.0, 0.5]], device="cuda")
+    cand = torch.arange(4, **I32).reshape(1, 4)
+    n_cand = torch.tensor([4], **I32)
+    keep_idx = torch.full((1, 4), -1, **I32)
+    n_keep = torch.full((1,), 9, **I32)
+    flag = torch.zeros(1, **I32)
+    cf.cf_prune_topk(score, None, cand, n_cand, 2, 1, 4, keep_idx, n_keep, flag)
+    torch.cuda.synchronize()
+    assert flag.item() == cf.CF_FLAG_NONFINITE_SCORE and n_keep.item() == 0
+    flag.zero_()
+    cand[0, 1] = 77
+    cf.cf_prune_topk(torch.ones(1, 4, device="cuda"), None, cand, n_cand, 2, 1, 4, keep_idx, n_keep, flag)
+    torch.cuda.synchronize()
+    assert flag.item() == cf.CF_FLAG_BAD_INDEX and n_keep.item() == 0
+
+
+# ----------------------------------------------------------------------------- cf_assign_positions
+@pytest.mark.parametrize("strategy", [cf.CF_ALLOC_SORT, cf.CF_ALLOC_ALIGN])
+def test_assign_positions_bit_exact(strategy):
+    rng = np.random.default_rng(41)
+    batch, stride = 64, 40
+    lens = rng.integers(1, 201, size=(batch, stride)).astype(np.int32)
+    n_ranked = rng.integers(0, stride + 1, size=batch).astype(np.int32)
+    ranked = np.stack([rng.permutation(stride) for _ in range(batch)]).astype(np.int32)
+    for pos_begin, pos_end, force in [(32, 4048, 0), (0, 32704, 0), (32, 900, 0), (32, 4048, 5), (7, 300, 0),
+                                      (0, 150, 0)]:
+        new_start = torch.full((batch, stride), -7, **I32)
+        q_start = torch.full((batch,), -7, **I32)
+        n_reuse = torch.full((batch,), -7, **I32)
+        order = torch.full((batch, stride), -7, **I32)
+        flag = torch.zeros(1, **I32)
+        cf.cf_assign_positions(torch.from_numpy(lens).cuda(), torch.from_numpy(ranked).cuda(),
+                               torch.from_numpy(n_ranked).cuda(), batch, stride, pos_begin, pos_end, strategy,
+                               force, new_start, q_start, n_reuse, order, flag)
+        torch.cuda.synchronize()
+        ns, qs, nr, od = (x.cpu().numpy() for x in (new_start, q_start, n_reuse, order))
+        expect_flag = 0
+        for b in range(batch):
+            r = ranked[b, :n_ranked[b]].tolist()
+            try:
+                ref_ns, ref_q, ref_nr = orc.assign_positions(lens[b], r, pos_begin, pos_end, strategy, force)
+            except ValueError as e:
+                expect_flag |= cf.CF_FLAG_DOC_TOO_LONG if "longer" in str(e) else cf.CF_FLAG_POS_OVERFLOW
+                assert qs[b] == -7 and np.all(ns[b] == -7)          # untouched
+                continue
+            assert qs[b] == ref_q and nr[b] == ref_nr
+            for slot in range(stride):
+                assert ns[b, slot] == ref_ns.get(slot, -7)
+            ref_order = sorted(r) if strategy == cf.CF_ALLOC_ALIGN else r
+            assert od[b, :len(r)].tolist() == ref_order
+        assert flag.item() == expect_flag
+
+
+def test_assign_keep_only_lists_survivors():
+    lens = torch.full((1, 6), 10, **I32)
+    ranked = torch.tensor([[4, 1, 3, 0, 0, 0]], **I32)
+    new_start = torch.full((1, 6), 5, **I32)
+    q_start = torch.full((1,), 99, **I32)
+    n_reuse = torch.full((1,), 1, **I32)
+    order = torch.zeros((1, 6), **I32)
+    cf.cf_assign_positions(lens, ranked, torch.tensor([3], **I32), 1, 6, 0, 100, cf.CF_ALLOC_KEEP, 0, new_start,
+                           q_start, n_reuse, order)
+    torch.cuda.synchronize()
+    assert order[0, :3].tolist() == [1, 3, 4]
+    assert q_start.item() == 99 and torch.all(new_start == 5)
+
+
+# ----------------------------------------------------------------------------- generic attention path
+def _run_single_layer(cfg, pairing=cf.CF_ROPE_HALF, seed=None, check_prune=True):
+    st = wl.build_structure(cfg, seed=None if seed is None else 7000 + seed)
+    t = wl.build_layer(cfg, st, seed=seed)
+    g = cfg.geometry
+    pname = "half" if pairing == cf.CF_ROPE_HALF else "interleaved"
+    pb = G.make_batch(cfg, st, pairing)
+    dev = G.upload_layer(cfg, t)
+    out = torch.empty_like(dev["q"])
+    pb.allocate_initial()
+    pb.attention(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out)
+    torch.cuda.synchronize()
+    assert pb.flags() == 0
+    out_np = out.float().cpu().numpy()
+    mass_np = pb.mass.cpu().numpy()
+    score_np = pb.score.cpu().numpy()
+    worst_out = worst_mass = 0.0
+    for b in range(cfg.batch):
+        # positions and segment table: bit-exact against the oracle's own allocation
+        ref_segs, ref_q, _ = H.initial_segments(cfg, st, b)
+        segs = G.device_segments(pb, b)
+        assert segs == ref_segs and int(pb.q_start[b].item()) == ref_q
+        ref_out, ref_mass = H.oracle_query(cfg, st, t, b, ref_segs, ref_q, pairing=pname)
+        worst_out = max(worst_out, G.row_error(out_np[b * cfg.tq:(b + 1) * cfg.tq], ref_out))
+        worst_mass = max(worst_mass, G.rel_error(mass_np[b, :len(segs)], ref_mass))
+        ref_score = H.doc_scores(ref_segs, ref_mass, cfg.docs_per_query)
+        assert G.rel_error(score_np[b], ref_score) <= G.MASS_TOL[g.dtype]
+        assert mass_np[b, :len(segs)].sum() == pytest.approx(g.n_q_heads * cfg.tq, rel=1e-5)
+    _say(f"{cfg.name}: out err {worst_out:.3e}  mass err {worst_mass:.3e}")
+    assert worst_out <= G.OUT_TOL[g.dtype]
+    assert worst_mass <= G.MASS_TOL[g.dtype]
+    return cfg, st, t, pb, dev, out
+
+
+def test_tiny_fp32_configuration_end_to_end():
+    """Configuration 1: attention, mass, keep top-2, re-pack after the 4-token prefix."""
+    cfg, st, t, pb, dev, out = _run_single_layer(wl.CONFIGS["tiny_f32"])
+    # prune with the oracle's own scores fed to the device: indices must match exactly
+    ref_segs, ref_q, lens = H.initial_segments(cfg, st, 0)
+    _, ref_mass = H.oracle_query(cfg, st, t, 0, ref_segs, ref_q)
+    ref_score = H.doc_scores(ref_segs, ref_mass, cfg.docs_per_query).astype(np.float32)
+    ref_keep = orc.prune_topk(ref_score, lens, list(range(4)), cfg.keep)
+    pb.score.copy_(torch.from_numpy(ref_score).reshape(1, -1))
+    pb.prune(cfg.keep, cf.CF_ALLOC_SORT)
+    torch.cuda.synchronize()
+    assert pb.flags() == 0
+    assert pb.keep_idx[0, :cfg.keep].tolist() == ref_keep
+    assert set(st.planted[0].tolist()) <= set(ref_keep)
+    ref_ns, ref_qs, ref_nr = orc.assign_positions(lens, ref_keep, cfg.prefix_len, cfg.geometry.max_positions - cfg.tq)
+    assert pb.q_start.item() == ref_qs == 68
+    ns = pb.new_start.cpu().numpy()[0]
+    for slot, pos in ref_ns.items():
+        assert ns[slot] == pos
+    assert sorted(ref_ns.values()) == [4, 36]
+    segs = G.device_segments(pb, 0)
+    assert [s.kind for s in segs] == [cf.CF_SEG_PREFIX, cf.CF_SEG_DOC, cf.CF_SEG_DOC, cf.CF_SEG_SELF]
+    assert [s.doc for s in segs[1:3]] == ref_keep
+    # second layer on the pruned, re-packed set
+    pb.attention(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out, accumulate=False)
+    torch.cuda.synchronize()
+    _, ref_out, ref_mass2 = G.oracle_on_device_segments(cfg, t, pb, 0)
+    assert G.row_error(out.float().cpu().numpy(), ref_out) <= 1e-4
+    assert G.rel_error(pb.mass.cpu().numpy()[0, :4], ref_mass2) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype,pairing,d,hq,hkv", [("f32", cf.CF_ROPE_INTERLEAVED, 64, 4, 2),
+                                                    ("bf16", cf.CF_ROPE_INTERLEAVED, 128, 8, 2),
+                                                    ("f16", cf.CF_ROPE_HALF, 64, 6, 3),
+                                                    ("f32", cf.CF_ROPE_HALF, 256, 2, 1)])
+def test_generic_path_shapes(dtype, pairing, d, hq, hkv):
+    base = wl.CONFIGS["tiny_f32"]
+    cfg = wl.scaled(base, name=f"generic_{dtype}_{d}", geometry=wl.Geometry(hq, hkv, d, dtype, 1.0e6, 32768),
+                    n_store_docs=12, docs_per_query=4, batch=3, doc_len_range=(1, 150), tq=11, prefix_len=5,
+                    doc_stored_start=5, n_planted=1)
+    _run_single_layer(cfg, pairing, seed=55)
+
+
+def test_attention_flags_bad_table_entries():
+    cfg = wl.CONFIGS["tiny_f32"]
+    st = wl.build_structure(cfg)
+    t = wl.build_layer(cfg, st)
+    pb = G.make_batch(cfg, st)
+    dev = G.upload_layer(cfg, t)
+    out = torch.empty_like(dev["q"])
+    pb.allocate_initial()
+    segs = cf.segments_from_device(pb.segs[0], 6)
+    segs[2]["tok_offset"] = 10 ** 9          # far outside the store: must be skipped, not read
+    segs[3]["len"] = -5
+    pb.segs[0].copy_(cf.segments_to_device(segs).reshape(6, 32))
+    pb.attention(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out)
+    torch.cuda.synchronize()
+    assert pb.flags() & cf.CF_FLAG_BAD_SEGMENT
+    mass = pb.mass.cpu().numpy()[0]
+    assert mass[2] == 0 and mass[3] == 0
+    assert mass[:6].sum() == pytest.approx(cfg.geometry.n_q_heads * cfg.tq, rel=1e-5)
