@@ -61,6 +61,11 @@ class PrefillBatch:
         self.mass = torch.zeros((self.batch, self.seg_stride), dtype=torch.float32, device=device)
         self.segs = torch.zeros((self.batch, self.seg_stride, 32), dtype=torch.uint8, device=device)
         self.n_seg = torch.zeros((self.batch,), **i32)
+        # tables of the next layer, written by prune() and made current by advance()
+        self.next_segs = torch.zeros_like(self.segs)
+        self.next_n_seg = torch.zeros_like(self.n_seg)
+        self.next_new_start = torch.zeros_like(self.new_start)
+        self.next_q_start = torch.zeros_like(self.q_start)
         self.dev_flag = torch.zeros((1,), **i32)
         self.max_kv_tokens = int(prefix_len + doc_len.sum(axis=1).max() + tq)
         self.ws_bytes = cf.cf_prefill_workspace_bytes(desc, self.batch, tq, self.seg_stride, self.max_kv_tokens)
@@ -72,10 +77,7 @@ class PrefillBatch:
         cf.cf_assign_positions(self.doc_len, self.cand, self.n_cand, self.batch, self.stride, self.pos_begin,
                                self.pos_end, cf.CF_ALLOC_SORT, force_n_reuse, self.new_start, self.q_start,
                                self.n_reuse, self.order, self.dev_flag)
-        self.gather(self.n_cand)
-
-    def gather(self, n_order: torch.Tensor) -> None:
-        cf.cf_gather_segments(self.doc_tok_offset, self.doc_len, self.order, n_order, self.new_start,
+        cf.cf_gather_segments(self.doc_tok_offset, self.doc_len, self.order, self.n_cand, self.new_start,
                               self.q_start, self.q_off, self.batch, self.stride, self.prefix_len,
                               self.doc_stored_start, self.q_stored_start, self.segs, self.n_seg, self.seg_stride,
                               self.dev_flag)
@@ -88,19 +90,33 @@ class PrefillBatch:
                                 self.score if accumulate else None, self.stride, self.workspace, self.ws_bytes,
                                 self.dev_flag)
 
-    # -- Alg. 2: ids_sort = argsort(S); ids = prun(ids_sort); then Sec. 2.5 re-allocation
+    # -- Alg. 2: ids_sort = argsort(S); ids = prun(ids_sort); then Sec. 2.5 re-allocation.
+    # Writes the next layer's tables; the current ones stay valid until advance().
     def prune(self, keep: int, strategy: int = cf.CF_ALLOC_SORT, normalise_by_len: bool = True,
               force_n_reuse: int = 0) -> None:
         cf.cf_prune_topk(self.score, self.doc_len if normalise_by_len else None, self.cand, self.n_cand, keep,
                          self.batch, self.stride, self.keep_idx, self.n_keep, self.dev_flag)
+        if strategy == cf.CF_ALLOC_KEEP:
+            self.next_new_start.copy_(self.new_start)
+            self.next_q_start.copy_(self.q_start)
         cf.cf_assign_positions(self.doc_len, self.keep_idx, self.n_keep, self.batch, self.stride, self.pos_begin,
-                               self.pos_end, strategy, force_n_reuse, self.new_start, self.q_start, self.n_reuse,
-                               self.order, self.dev_flag)
-        self.gather(self.n_keep)
-        # the survivors, in placement order, are the next candidates
+                               self.pos_end, strategy, force_n_reuse, self.next_new_start, self.next_q_start,
+                               self.n_reuse, self.order, self.dev_flag)
+        cf.cf_gather_segments(self.doc_tok_offset, self.doc_len, self.order, self.n_keep, self.next_new_start,
+                              self.next_q_start, self.q_off, self.batch, self.stride, self.prefix_len,
+                              self.doc_stored_start, self.q_stored_start, self.next_segs, self.next_n_seg,
+                              self.seg_stride, self.dev_flag)
+        self._pending_keep = keep
+
+    # -- the survivors, in placement order, become the candidates of the following layers
+    def advance(self) -> None:
         self.cand, self.order = self.order, self.cand
         self.n_cand, self.n_keep = self.n_keep, self.n_cand
-        self.n_alive = min(keep, self.n_alive)
+        self.segs, self.next_segs = self.next_segs, self.segs
+        self.n_seg, self.next_n_seg = self.next_n_seg, self.n_seg
+        self.new_start, self.next_new_start = self.next_new_start, self.new_start
+        self.q_start, self.next_q_start = self.next_q_start, self.q_start
+        self.n_alive = min(self._pending_keep, self.n_alive)
 
     def flags(self) -> int:
         return int(self.dev_flag.item())

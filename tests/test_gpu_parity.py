@@ -216,6 +216,7 @@ def test_tiny_fp32_configuration_end_to_end():
     ref_keep = orc.prune_topk(ref_score, lens, list(range(4)), cfg.keep)
     pb.score.copy_(torch.from_numpy(ref_score).reshape(1, -1))
     pb.prune(cfg.keep, cf.CF_ALLOC_SORT)
+    pb.advance()
     torch.cuda.synchronize()
     assert pb.flags() == 0
     assert pb.keep_idx[0, :cfg.keep].tolist() == ref_keep
