@@ -173,7 +173,10 @@ def test_assign_keep_only_lists_survivors():
 
 
 # ----------------------------------------------------------------------------- generic attention path
-def _run_single_layer(cfg, pairing=cf.CF_ROPE_HALF, seed=None, check_prune=True):
+def _run_single_layer(cfg, pairing=cf.CF_ROPE_HALF, seed=None, mass_tol=None):
+    """mass_tol overrides the configuration-level mass tolerance for shapes with so few rows and
+    tokens that the 16-bit rounding of the rotated keys (about 2^-9 relative per probability) is
+    not averaged away."""
     st = wl.build_structure(cfg, seed=None if seed is None else 7000 + seed)
     t = wl.build_layer(cfg, st, seed=seed)
     g = cfg.geometry
@@ -189,6 +192,7 @@ def _run_single_layer(cfg, pairing=cf.CF_ROPE_HALF, seed=None, check_prune=True)
     mass_np = pb.mass.cpu().numpy()
     score_np = pb.score.cpu().numpy()
     worst_out = worst_mass = 0.0
+    mass_tol = G.MASS_TOL[g.dtype] if mass_tol is None else mass_tol
     for b in range(cfg.batch):
         # positions and segment table: bit-exact against the oracle's own allocation
         ref_segs, ref_q, _ = H.initial_segments(cfg, st, b)
@@ -198,11 +202,11 @@ def _run_single_layer(cfg, pairing=cf.CF_ROPE_HALF, seed=None, check_prune=True)
         worst_out = max(worst_out, G.row_error(out_np[b * cfg.tq:(b + 1) * cfg.tq], ref_out))
         worst_mass = max(worst_mass, G.rel_error(mass_np[b, :len(segs)], ref_mass))
         ref_score = H.doc_scores(ref_segs, ref_mass, cfg.docs_per_query)
-        assert G.rel_error(score_np[b], ref_score) <= G.MASS_TOL[g.dtype]
+        assert G.rel_error(score_np[b], ref_score) <= mass_tol
         assert mass_np[b, :len(segs)].sum() == pytest.approx(g.n_q_heads * cfg.tq, rel=1e-5)
     _say(f"{cfg.name}: out err {worst_out:.3e}  mass err {worst_mass:.3e}")
     assert worst_out <= G.OUT_TOL[g.dtype]
-    assert worst_mass <= G.MASS_TOL[g.dtype]
+    assert worst_mass <= mass_tol
     return cfg, st, t, pb, dev, out
 
 
@@ -268,3 +272,53 @@ def test_attention_flags_bad_table_entries():
     mass = pb.mass.cpu().numpy()[0]
     assert mass[2] == 0 and mass[3] == 0
     assert mass[:6].sum() == pytest.approx(cfg.geometry.n_q_heads * cfg.tq, rel=1e-5)
+
+
+# ----------------------------------------------------------------------------- 16-bit MFMA path
+def test_llama2_7b_layer_configuration():
+    """Configuration 2 (MHA, bf16, HBM-bound shape) at full size."""
+    _run_single_layer(wl.CONFIGS["llama2_7b_layer"])
+
+
+def test_qwen2_7b_layer_configuration():
+    """Configuration 3 (GQA 28/4, bf16, 50 ragged documents) at full size."""
+    _run_single_layer(wl.CONFIGS["qwen2_7b_layer"])
+
+
+def test_qwen2_1p5b_batch_reduced():
+    """Configuration 5's shape (fp16 GQA 12/2, ragged documents, batch of queries over a shared
+    store) with a smaller store and batch so the oracle finishes in seconds."""
+    cfg = wl.scaled(wl.CONFIGS["qwen2_1p5b_batch"], n_store_docs=300, batch=6)
+    _run_single_layer(cfg)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("hq,hkv,tq,docs,len_range,prefix", [
+    (4, 4, 1, 3, (1, 70), 0),          # single query row, no prefix
+    (8, 2, 5, 1, (33, 33), 7),         # one document, ragged everything
+    (6, 2, 17, 9, (1, 40), 3),         # stacked rows straddle the 64-row tile
+    (2, 2, 70, 4, (90, 130), 16),      # more rows than one tile in MHA
+])
+def test_mfma_path_edge_shapes(dtype, hq, hkv, tq, docs, len_range, prefix):
+    cfg = wl.scaled(wl.CONFIGS["tiny_f32"], name=f"edge_{dtype}_{hq}_{hkv}_{tq}",
+                    geometry=wl.Geometry(hq, hkv, 128, dtype, 1.0e6, 32768), n_store_docs=2 * docs,
+                    docs_per_query=docs, batch=2, doc_len_range=len_range, tq=tq, prefix_len=prefix,
+                    doc_stored_start=prefix, n_planted=1)
+    _run_single_layer(cfg, seed=77, mass_tol=2e-3)
+
+
+def test_mfma_path_is_deterministic():
+    cfg = wl.CONFIGS["llama2_7b_layer"]
+    st = wl.build_structure(cfg)
+    dev = G.upload_layer(cfg, wl.build_layer(cfg, st))
+    pb = G.make_batch(cfg, st)
+    pb.allocate_initial()
+    outs, masses = [], []
+    for _ in range(3):
+        out = torch.empty_like(dev["q"])
+        pb.attention(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out, accumulate=False)
+        torch.cuda.synchronize()
+        outs.append(out.clone())
+        masses.append(pb.mass.clone())
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    assert torch.equal(masses[0], masses[1]) and torch.equal(masses[0], masses[2])
