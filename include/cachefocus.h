@@ -234,6 +234,13 @@ CF_API cf_status cf_gather_segments(const int64_t* doc_tok_offset, const int32_t
 /* Thread-local text for the last non-OK status returned on this thread (static storage). */
 CF_API const char* cf_last_error(void);
 
+/* Profiling aid (not part of the method): restrict the kernels that later cf_prefill_attention
+ * calls on this thread launch on the 16-bit path, so that one of them can be timed alone with
+ * events.  Bit 0: the attention kernel proper (K/V streaming, re-rotation, MFMA, softmax);
+ * bit 1: the merge of the splits' partial outputs; bit 2: the per-segment mass reduction.
+ * Default 7 (all).  With a partial mask the call's outputs are not meaningful. */
+CF_API void cf_profile_phases(int32_t mask);
+
 /* Library version as major*10000 + minor*100 + patch. */
 CF_API int32_t cf_version(void);
 

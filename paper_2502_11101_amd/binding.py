@@ -27,7 +27,7 @@ CF_FLAG_BAD_SEGMENT, CF_FLAG_NONFINITE_SCORE, CF_FLAG_DOC_TOO_LONG, CF_FLAG_POS_
 DTYPE_CODE = {"f32": CF_F32, "bf16": CF_BF16, "f16": CF_F16}
 
 EXPORTS = ("cf_reposition_keys", "cf_prefill_workspace_bytes", "cf_prefill_attention", "cf_prune_topk",
-           "cf_assign_positions", "cf_gather_segments", "cf_last_error", "cf_version")
+           "cf_assign_positions", "cf_gather_segments", "cf_last_error", "cf_version", "cf_profile_phases")
 
 
 class cf_layer_desc(C.Structure):
@@ -65,6 +65,8 @@ def load() -> C.CDLL:
     lib.cf_last_error.argtypes = []
     lib.cf_version.restype = i32
     lib.cf_version.argtypes = []
+    lib.cf_profile_phases.restype = None
+    lib.cf_profile_phases.argtypes = [i32]
     lib.cf_reposition_keys.restype = i32
     lib.cf_reposition_keys.argtypes = [dp, vp, vp, vp, i32, i64, i32, vp, vp]
     lib.cf_prefill_workspace_bytes.restype = sz
@@ -134,6 +136,10 @@ def _check(status: int) -> None:
 
 def cf_version() -> int:
     return load().cf_version()
+
+
+def cf_profile_phases(mask: int) -> None:
+    load().cf_profile_phases(mask)
 
 
 def cf_last_error() -> str:

@@ -12,7 +12,10 @@ namespace cf {
 
 namespace {
 thread_local char g_err[512] = "";
+thread_local int g_phases = 7;
 }
+
+int profile_phases() { return g_phases; }
 
 void set_error(const char* fmt, ...) {
     va_list ap;
@@ -61,6 +64,8 @@ extern "C" {
 const char* cf_last_error(void) { return g_err; }
 
 int32_t cf_version(void) { return 100; }
+
+void cf_profile_phases(int32_t mask) { g_phases = mask & 7; }
 
 cf_status cf_reposition_keys(const cf_layer_desc* desc, const void* k_in, void* k_out, const cf_segment* segs,
                              int32_t n_seg, int64_t n_store_tokens, int32_t max_seg_len, int32_t* dev_flag,

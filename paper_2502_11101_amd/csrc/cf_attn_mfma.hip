@@ -1,21 +1,25 @@
 // 16-bit MFMA prefill attention for gfx950 (head_dim 128, half-split RoPE pairing).
 //
-// Work decomposition.  For one (query b, kv head, tile of 64 stacked query rows) — a "unit" —
-// the attended tokens are cut into blocks of 32 tokens that never straddle a segment.  The
-// block list of a unit is divided evenly over `nsplit` workgroups and, inside a workgroup,
-// over its 4 wavefronts; a wavefront is therefore an independent flash-attention worker over a
-// contiguous run of blocks ("sub-split") for all 64 rows of the tile:
-//   * K/V blocks are fetched with coalesced 16-byte loads into registers one block ahead,
-//   * the key block is rotated in registers by the segment's relative position shift (Eq. 5;
-//     cos/sin of the shift per 2-D slice, angle reduced in fp64) and rounded once to the storage
-//     type while it is staged into LDS — rotated keys never return to memory,
-//   * S^T = K Q^T and O^T += V^T P^T run on v_mfma_f32_32x32x16 (Q fragments live in registers;
-//     the transposed forms keep one query row per lane, so softmax statistics need one cross-lane
-//     exchange and rescaling needs none),
-//   * softmax is online in fp32 in the exp2 domain.
-// Per segment a wavefront leaves (running max, sum of exp2) per row; a second kernel merges the
-// partial outputs of the splits and turns those pairs into per-segment attention mass (the
-// document-wise score of Alg. 2) with fixed-order reductions.
+// Work decomposition.  The query rows that share a kv head (all rows of the G = Hq/Hkv heads of
+// the group, stacked: row m = g*tq + t) are cut into 16-row blocks.  A workgroup of 4 wavefronts
+// owns up to 4*NRB such blocks of one (query, kv head) — wavefront w the blocks [w*NRB, (w+1)*NRB)
+// — and a contiguous run of the attended tokens.  Tokens are counted in tiles of 64 that never
+// straddle a segment; the tile list of a (query, kv head) is divided evenly over `nsplit`
+// workgroups.  Per tile:
+//   * all 256 threads fetch the next K/V tile with coalesced 16-byte loads into registers while
+//     the current one is being consumed,
+//   * the key tile is rotated in registers by its segment's relative position shift (Eq. 5;
+//     cos/sin per 2-D slice from an fp64-reduced angle), rounded once to the storage type and
+//     staged into LDS — rotated keys never return to memory; V is staged transposed,
+//   * S^T = K Q^T and O^T += V^T P^T run on v_mfma_f32_16x16x32 with the Q fragments resident
+//     in registers; the transposed forms keep one query row per lane, so the online softmax
+//     (fp32, exp2 domain) needs two cross-lane exchanges per 32 tokens and the rescale none.
+// At the end of each segment a wavefront leaves (running max, sum of exp2) per row.
+//
+// A second kernel merges the splits' partial outputs and writes the output rows; a third reduces
+// the (max, sum) pairs to per-segment attention mass (the document-wise score of Alg. 2) in a
+// fixed order and adds it to the accumulated scores.  Results cross between the kernels at the
+// kernel boundaries: no fences, no atomics on the data path, bit-identical reruns.
 #include <cstdlib>
 
 #include "cf_common.h"
@@ -27,573 +31,638 @@ constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr int kD = 128;
 constexpr int kHalf = 64;
-constexpr int kBlk = 32;        // tokens per block
-constexpr int kRowTile = 64;    // stacked query rows per unit
-constexpr int kSK = 136;        // LDS row stride of a staged K block, elements (272 B)
-constexpr int kSV = 40;         // LDS row stride of a staged V^T block, elements (80 B)
-constexpr int kKBytes = kBlk * kSK * 2;
+constexpr int kTile = 64;       // tokens per tile
+constexpr int kSK = 136;        // LDS row stride of the staged K tile, elements (272 B)
+constexpr int kSV = 72;         // LDS row stride of the staged V^T tile, elements (144 B)
+constexpr int kKBytes = kTile * kSK * 2;
 constexpr int kVBytes = kD * kSV * 2;
-constexpr int kStageBytes = kKBytes + kVBytes;          // per wavefront
-constexpr int kMaxSegs = 512;
-constexpr int kORegs = 128;                             // fp32 accumulator registers per lane
+constexpr int kStageBytes = kKBytes + kVBytes;
+constexpr int kMaxSegs = 256;
+constexpr int kMaxSplit = 32;
+constexpr int kMassChunks = 16;     // mass workgroups per query (segments dealt round-robin)
+constexpr int kStatRows = 2048;     // rows whose (max, 1/sum) a mass workgroup holds at a time
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 struct Plan {
-    int rowtiles, units_per_b, units, nsplit, nsub, slots;
-    size_t off_counters, off_ml, off_opart, off_massml, off_massunit, total;
+    int nrb;            // 16-row blocks per wavefront (1..4)
+    int rows_wg;        // 64 * nrb
+    int n_rg;           // row groups per (query, kv head)
+    int blocks_rg;      // 16-row blocks per row group
+    int units_per_b, units, nsplit, slots, x_count, mass_chunks;
+    size_t off_ml, off_opart, off_massml, off_rowstat, total;
 };
 
 Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_stride, int64_t max_kv_tokens) {
     Plan p;
     const int group = n_q_heads / n_kv_heads;
-    p.rowtiles = (group * max_tq + kRowTile - 1) / kRowTile;
-    p.units_per_b = n_kv_heads * p.rowtiles;
+    const int row_blocks = (group * max_tq + 15) / 16;
+    p.n_rg = (row_blocks + 15) / 16;
+    p.blocks_rg = (row_blocks + p.n_rg - 1) / p.n_rg;
+    p.nrb = (p.blocks_rg + kWaves - 1) / kWaves;
+    p.rows_wg = 64 * p.nrb;
+    p.units_per_b = n_kv_heads * p.n_rg;
     p.units = batch * p.units_per_b;
-    const int64_t est_blocks = max_kv_tokens / kBlk + seg_stride;
-    int64_t ns = (256 + p.units - 1) / p.units;
-    const int64_t cap = est_blocks / kWaves > 1 ? est_blocks / kWaves : 1;
+    // enough workgroups to fill 256 CUs at the occupancy the register budget of this NRB allows
+    const int per_cu = p.nrb == 1 ? 2 : 1;
+    const int64_t est_tiles = max_kv_tokens / kTile + seg_stride;
+    int64_t ns = (256 * per_cu + p.units - 1) / p.units;
+    const int64_t cap = est_tiles / 2 > 1 ? est_tiles / 2 : 1;
     if (ns > cap) ns = cap;
-    if (ns > 64) ns = 64;
+    if (ns > kMaxSplit) ns = kMaxSplit;
+    if (const char* e = std::getenv("CF_NSPLIT")) ns = std::atoi(e);     // development knob
     if (ns < 1) ns = 1;
+    if (ns > kMaxSplit) ns = kMaxSplit;
     p.nsplit = (int)ns;
-    p.nsub = p.nsplit * kWaves;
-    p.slots = seg_stride + p.nsub;
+    p.slots = seg_stride + p.nsplit;
+    p.x_count = batch * n_kv_heads * p.nsplit;
+    p.mass_chunks = seg_stride < kMassChunks ? seg_stride : kMassChunks;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
-    p.off_counters = take((size_t)batch * 4);
-    p.off_ml = take((size_t)p.units * p.nsplit * kRowTile * sizeof(float2));
-    p.off_opart = take((size_t)p.units * p.nsplit * kORegs * kWave * sizeof(float));
-    p.off_massml = take((size_t)p.units * p.slots * kRowTile * sizeof(float2));
-    p.off_massunit = take((size_t)p.units * seg_stride * sizeof(float));
+    p.off_ml = take((size_t)p.units * p.nsplit * p.rows_wg * sizeof(float2));
+    p.off_opart = take((size_t)p.units * p.nsplit * p.rows_wg * kD * sizeof(float));
+    p.off_massml = take((size_t)p.units * p.slots * p.rows_wg * sizeof(float2));
+    p.off_rowstat = take((size_t)p.units * p.rows_wg * sizeof(float2));
     p.total = off;
+#ifdef CF_TRACE
+    p.total += (size_t)(p.x_count * p.n_rg + p.units * p.nrb * 4 + batch * p.mass_chunks) * 16 * 8;
+#endif
     return p;
 }
 
-// Per-query segment table in LDS, with the block prefix that defines the partition.
+#ifdef CF_TRACE
+#define CF_STAMP(k) do { if (threadIdx.x == 0) trace[(k)] = wall_clock64(); } while (0)
+#else
+#define CF_STAMP(k) do {} while (0)
+#endif
+
+// Per-query segment table in LDS with the tile prefix that defines the partition.
 struct SegTable {
-    int64_t tok[kMaxSegs];     // first token in its tensor
-    int32_t vis[kMaxSegs];     // visible tokens (0 for a rejected entry)
-    int32_t delta[kMaxSegs];   // relative shift: (new - stored) - (q_new - q_stored)
-    int32_t self[kMaxSegs];    // 1 for the causal own block
-    int32_t blk0[kMaxSegs + 1];// exclusive prefix of 32-token block counts
+    int64_t tok[kMaxSegs];      // first token in its tensor
+    int32_t vis[kMaxSegs];      // visible tokens (0 for a rejected entry)
+    int32_t delta[kMaxSegs];    // relative shift: (new - stored) - (q_new - q_stored)
+    int32_t self[kMaxSegs];     // 1 for the causal own block
+    int32_t tile0[kMaxSegs + 1];// exclusive prefix of tile counts
     int32_t n;
 };
 
-// Every workgroup that works on query b builds the same table (both kernels use this).
-__device__ void build_table(const AttnArgs& a, int b, SegTable* t) {
+// All threads of a workgroup call this; every workgroup of query b builds the same table.
+// The table entries are fetched for the whole stride at once, so that their loads do not wait
+// for the segment count.
+__device__ __forceinline__ void build_table(const AttnArgs& a, int b, SegTable* t, int tq_raw) {
+    const int tid = threadIdx.x;
+    cf_segment seg;
+    const bool in_stride = tid < a.seg_stride;        // seg_stride <= kMaxSegs == kThreads
+    if (in_stride) seg = a.segs[(int64_t)b * a.seg_stride + tid];
     int n = a.n_seg[b];
-    if (n < 0 || n > a.seg_stride) {
-        if (threadIdx.x == 0) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
-        n = n < 0 ? 0 : a.seg_stride;
-    }
-    const int q0 = a.q_off[b];
-    const int tq = min(a.q_off[b + 1] - q0, a.max_tq);
     const int64_t q_total = a.q_off[a.batch];
     const int qdelta = a.q_new_start[b] - a.q_stored_start;
-    for (int s = threadIdx.x; s < n; s += kThreads) {
-        const cf_segment seg = a.segs[(int64_t)b * a.seg_stride + s];
+    if (n < 0 || n > a.seg_stride) {
+        if (tid == 0) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
+        n = n < 0 ? 0 : a.seg_stride;
+    }
+    const int tq = min(tq_raw, a.max_tq);
+    if (in_stride && tid < n) {
         const bool self = seg.kind == CF_SEG_SELF;
         const int64_t limit = self ? q_total : a.n_store_tokens;
         const bool bad = seg.kind < 0 || seg.kind > CF_SEG_SELF || seg.len < 0 || seg.tok_offset < 0 ||
                          seg.tok_offset + seg.len > limit || (self && a.k_self == nullptr);
         if (bad) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
         const int vis = bad ? 0 : (self ? min(seg.len, tq) : seg.len);
-        t->tok[s] = seg.tok_offset;
-        t->vis[s] = vis;
-        t->delta[s] = seg.new_start - seg.stored_start - qdelta;
-        t->self[s] = self ? 1 : 0;
-        t->blk0[s + 1] = (vis + kBlk - 1) / kBlk;
+        t->tok[tid] = seg.tok_offset;
+        t->vis[tid] = vis;
+        t->delta[tid] = seg.new_start - seg.stored_start - qdelta;
+        t->self[tid] = self ? 1 : 0;
+        t->tile0[tid + 1] = (vis + kTile - 1) / kTile;
     }
-    if (threadIdx.x == 0) { t->n = n; t->blk0[0] = 0; }
+    if (tid == 0) { t->n = n; t->tile0[0] = 0; }
     __syncthreads();
-    if (threadIdx.x < kWave) {                       // inclusive scan by the first wavefront
+    if (tid < kWave) {                               // inclusive scan by the first wavefront
         int carry = 0;
         for (int c0 = 0; c0 < n; c0 += kWave) {
-            const int s = c0 + threadIdx.x;
-            int v = s < n ? t->blk0[s + 1] : 0;
+            const int s = c0 + tid;
+            int v = s < n ? t->tile0[s + 1] : 0;
 #pragma unroll
             for (int o = 1; o < kWave; o <<= 1) {
                 const int u = __shfl_up(v, o);
-                if ((int)threadIdx.x >= o) v += u;
+                if (tid >= o) v += u;
             }
-            if (s < n) t->blk0[s + 1] = v + carry;
+            if (s < n) t->tile0[s + 1] = v + carry;
             carry += __shfl(v, kWave - 1);
         }
     }
     __syncthreads();
 }
 
-// sub-split ss of a unit owns blocks [lo, hi) of its `total` blocks
-__device__ __forceinline__ void sub_range(int total, int nsplit, int ss, int* lo, int* hi) {
-    const int split = ss / kWaves, w = ss % kWaves;
-    const int b0 = (int)(((int64_t)total * split) / nsplit);
-    const int b1 = (int)(((int64_t)total * (split + 1)) / nsplit);
-    const int n = b1 - b0;
-    *lo = b0 + (n * w) / kWaves;
-    *hi = b0 + (n * (w + 1)) / kWaves;
-}
+// split i of a list of `total` tiles owns [total*i/nsplit, total*(i+1)/nsplit)
+__device__ __forceinline__ int split_begin(unsigned total, unsigned nsplit, unsigned i) { return (int)(total * i / nsplit); }
+// the split that owns tile x
+__device__ __forceinline__ int split_of(unsigned total, unsigned nsplit, unsigned x) { return (int)(((x + 1) * nsplit - 1) / total); }
 
 template <int DT> struct Mma;
 template <> struct Mma<CF_BF16> {
-    static __device__ __forceinline__ f32x16 run(uint4 a, uint4 b, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    static __device__ __forceinline__ f32x4 run(uint4 a, uint4 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
     }
-    static __device__ __forceinline__ float to_f(uint32_t bits) { return bf16_bits_to_float(bits); }
-    static __device__ __forceinline__ uint32_t from_f(float f) { return float_to_bf16_bits(f); }
+    static __device__ __forceinline__ float lo(uint32_t w) { return __uint_as_float(w << 16); }
+    static __device__ __forceinline__ float hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+    static __device__ __forceinline__ uint32_t pack(float x, float y) {
+        f32x2 v = {x, y};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    }
 };
 template <> struct Mma<CF_F16> {
-    static __device__ __forceinline__ f32x16 run(uint4 a, uint4 b, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    static __device__ __forceinline__ f32x4 run(uint4 a, uint4 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
     }
-    static __device__ __forceinline__ float to_f(uint32_t bits) { return f16_bits_to_float(bits); }
-    static __device__ __forceinline__ uint32_t from_f(float f) { return float_to_f16_bits(f); }
+    static __device__ __forceinline__ float lo(uint32_t w) { return (float)__builtin_bit_cast(f16x2, w)[0]; }
+    static __device__ __forceinline__ float hi(uint32_t w) { return (float)__builtin_bit_cast(f16x2, w)[1]; }
+    static __device__ __forceinline__ uint32_t pack(float x, float y) {
+        f32x2 v = {x, y};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+    }
 };
 
-template <int DT>
-__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-    return Mma<DT>::from_f(lo) | (Mma<DT>::from_f(hi) << 16);
-}
-
-struct BlockDesc {
+struct TileDesc {
     int seg;       // segment index
-    int tok0;      // first token of the block inside the segment
-    int ntok;      // valid tokens (1..32)
+    int tok0;      // first token of the tile inside the segment
+    int ntok;      // valid tokens (1..64)
 };
 
-template <int DT>
+template <int DT, int NRB>
 __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFreq freq, Plan p) {
     __shared__ SegTable tbl;
-    __shared__ __attribute__((aligned(16))) unsigned char stage_all[kWaves * kStageBytes];
-    __shared__ float2 ml_w[kWaves][kRowTile];
+    __shared__ __attribute__((aligned(16))) unsigned char stage[kStageBytes];
+    __shared__ float2 cs_lds[2][kHalf];
 
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
-    const int li = lane & 31, lg = lane >> 5;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const int li = lane & 15, lg = lane >> 4;
+#ifdef CF_TRACE
+    long long* trace = reinterpret_cast<long long*>(static_cast<char*>(a.workspace) + p.total) -
+                       (size_t)(p.x_count * p.n_rg + p.units * p.nrb * 4 + a.batch * p.mass_chunks) * 16 + (size_t)blockIdx.x * 16;
+#endif
+    CF_STAMP(0);
 
+    // block -> (row group, query, kv head, split); workgroups that read the same K/V tiles differ
+    // by a multiple of x_count
     const int bid = blockIdx.x;
-    const int split = bid % p.nsplit;
-    const int unit = bid / p.nsplit;
-    const int rowtile = unit % p.rowtiles;
-    const int hkv = (unit / p.rowtiles) % a.n_kv_heads;
-    const int b = unit / p.units_per_b;
-
-    if (bid == 0) {
-        int32_t* counters = reinterpret_cast<int32_t*>(static_cast<char*>(a.workspace) + p.off_counters);
-        for (int i = threadIdx.x; i < a.batch; i += kThreads) counters[i] = 0;
-    }
+    const int rg = bid / p.x_count;
+    const int x = bid - rg * p.x_count;
+    const int split = x % p.nsplit;
+    const int hkv = (x / p.nsplit) % a.n_kv_heads;
+    const int b = x / (p.nsplit * a.n_kv_heads);
+    const int unit = (b * a.n_kv_heads + hkv) * p.n_rg + rg;
 
     const int hq = a.n_q_heads;
     const int group = hq / a.n_kv_heads;
     const int q0 = a.q_off[b];
-    const int tq = min(a.q_off[b + 1] - q0, a.max_tq);
-    const int n_rows = group * tq;                 // stacked rows of this (b, kv head)
+    const int tq_raw = a.q_off[b + 1] - q0;
+    const double my_freq = freq.rev[tid & (kHalf - 1)];
+
+    build_table(a, b, &tbl, tq_raw);
+    CF_STAMP(1);
+
+    const int tq = min(tq_raw, a.max_tq);
+    const int n_rows = group * tq;
+    const unsigned total = (unsigned)tbl.tile0[tbl.n];
+    const int t_begin = split_begin(total, p.nsplit, split);
+    const int t_end = split_begin(total, p.nsplit, split + 1);
+
+    const int64_t kv_row = (int64_t)a.n_kv_heads * kD;
+    // staging: thread -> K items (tokens kt and kt+32, slices 8*kj..), V item (4 tokens 4*vq.., channels 8*vj..)
+    const int kt = tid >> 3, kj = tid & 7;
+    const int vq = tid >> 4, vj = tid & 15;
+    struct StageRegs { uint4 ka[2], kb[2], v[4]; };
+    StageRegs regs0, regs1;                          // two tiles in flight
+
+    auto describe = [&](int tile, int s) {
+        TileDesc d;
+        d.seg = s;
+        d.tok0 = (tile - tbl.tile0[s]) * kTile;
+        d.ntok = min(kTile, tbl.vis[s] - d.tok0);
+        return d;
+    };
+    auto locate = [&](int tile, int s) {             // first segment at or after s whose tiles reach past `tile`
+        while (tbl.tile0[s + 1] <= tile) ++s;
+        return s;
+    };
+    auto issue_loads = [&](const TileDesc& d, StageRegs& r) {
+        const bool self = tbl.self[d.seg] != 0;
+        const uint16_t* kb = static_cast<const uint16_t*>(self ? a.k_self : a.k_store);
+        const uint16_t* vb = static_cast<const uint16_t*>(self ? a.v_self : a.v_store);
+        const int64_t base = (tbl.tok[d.seg] + d.tok0) * kv_row + (int64_t)hkv * kD;
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int tok = kt + 32 * it;
+            if (tok < d.ntok) {
+                const uint16_t* pk = kb + base + tok * kv_row + 8 * kj;
+                r.ka[it] = *reinterpret_cast<const uint4*>(pk);
+                r.kb[it] = *reinterpret_cast<const uint4*>(pk + kHalf);
+            } else {
+                r.ka[it] = zero;
+                r.kb[it] = zero;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int tok = 4 * vq + i;
+            r.v[i] = tok < d.ntok ? *reinterpret_cast<const uint4*>(vb + base + tok * kv_row + 8 * vj) : zero;
+        }
+    };
+    int s_next = 0;
+    int next_tile = t_begin;                         // next tile whose loads have not been issued
+    auto fetch = [&](TileDesc& d, StageRegs& r) {    // ntok == 0 marks "no tile"
+        if (next_tile >= t_end) { d.ntok = 0; return; }
+        s_next = locate(next_tile, s_next);
+        d = describe(next_tile, s_next);
+        issue_loads(d, r);
+        ++next_tile;
+    };
+
+    // ---- the first two tiles' loads go out before anything else that touches memory
+    TileDesc d0, d1;
+    d0.seg = d1.seg = 0; d0.tok0 = d1.tok0 = 0; d0.ntok = d1.ntok = 0;
+    constexpr bool kDeep = NRB <= 2;                 // wider row tiles have no registers to spare for a second tile
+    fetch(d0, regs0);
+    if (kDeep) fetch(d1, regs1);
 
     // ---- Q fragments: row m = g*tq + t of the stack is q[q0 + t][hkv*group + g]
-    uint4 qf[2][8];
-    int trow[2];
+    uint4 qf[NRB][4];
+    int trow[NRB];
+    const int row_base = rg * p.blocks_rg * 16;
+    const int row_limit = min(n_rows, row_base + p.blocks_rg * 16);
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-        const int m = rowtile * kRowTile + rb * 32 + li;
-        const bool valid = m < n_rows;
+    for (int rb = 0; rb < NRB; ++rb) {
+        const int m = row_base + (wave * NRB + rb) * 16 + li;
+        const bool valid = m < row_limit;
         const int gi = valid ? m / tq : 0;
         const int t = valid ? m - gi * tq : 0;
         trow[rb] = valid ? t : 0x7fffffff;        // padding rows: nothing to mask, results unused
         const uint16_t* qp = static_cast<const uint16_t*>(a.q) + (((int64_t)q0 + t) * hq + hkv * group + gi) * kD + 8 * lg;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
-            qf[rb][kk] = valid ? *reinterpret_cast<const uint4*>(qp + 16 * kk) : make_uint4(0, 0, 0, 0);
+        for (int kk = 0; kk < 4; ++kk)
+            qf[rb][kk] = valid ? *reinterpret_cast<const uint4*>(qp + 32 * kk) : make_uint4(0, 0, 0, 0);
     }
 
-    build_table(a, b, &tbl);
-
-    const int total = tbl.blk0[tbl.n];
-    int wb0, wb1;
-    sub_range(total, p.nsplit, split * kWaves + wave, &wb0, &wb1);
-
-    unsigned char* stage = stage_all + wave * kStageBytes;
     uint16_t* k_lds = reinterpret_cast<uint16_t*>(stage);
     uint16_t* v_lds = reinterpret_cast<uint16_t*>(stage + kKBytes);
 
-    f32x16 acc[4][2];
+    f32x4 acc[NRB][8];
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int db = 0; db < 8; ++db) acc[rb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run[NRB], l_run[NRB], seg_l[NRB];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[db][rb][r] = 0.f;
-    float m_run[2] = {-INFINITY, -INFINITY};
-    float l_run[2] = {0.f, 0.f};
-    float seg_l[2] = {0.f, 0.f};
+    for (int rb = 0; rb < NRB; ++rb) { m_run[rb] = -INFINITY; l_run[rb] = 0.f; seg_l[rb] = 0.f; }
 
-    const int64_t kv_row = (int64_t)a.n_kv_heads * kD;
-    float2* massml = reinterpret_cast<float2*>(static_cast<char*>(a.workspace) + p.off_massml) +
-                     (int64_t)unit * p.slots * kRowTile;
-    const int ss = split * kWaves + wave;
+    char* ws = static_cast<char*>(a.workspace);
+    float2* massml = reinterpret_cast<float2*>(ws + p.off_massml) + (int64_t)unit * p.slots * p.rows_wg;
 
-    // staging registers (one block ahead)
-    uint4 kreg_a[4], kreg_b[4], vreg[2][4];
-    const int kj = lane & 7, ktr = lane >> 3;       // K: 8 lanes per token, 8 tokens per load
-    const int vj = lane & 15, vtg = lane >> 4;      // V: 16 lanes per token, 4 tokens per load
-
-    auto describe = [&](int blk, int s) {
-        BlockDesc d;
-        d.seg = s;
-        d.tok0 = (blk - tbl.blk0[s]) * kBlk;
-        d.ntok = min(kBlk, tbl.vis[s] - d.tok0);
-        return d;
-    };
-    auto locate = [&](int blk, int s) {             // first segment at or after s whose blocks reach past blk
-        while (tbl.blk0[s + 1] <= blk) ++s;
-        return s;
-    };
-    auto issue_loads = [&](const BlockDesc& d) {
-        const bool self = tbl.self[d.seg] != 0;
-        const uint16_t* kb = static_cast<const uint16_t*>(self ? a.k_self : a.k_store);
-        const uint16_t* vb = static_cast<const uint16_t*>(self ? a.v_self : a.v_store);
-        const int64_t base = (tbl.tok[d.seg] + d.tok0) * kv_row + (int64_t)hkv * kD;
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int tok = 8 * it + ktr;
-            if (tok < d.ntok) {
-                const uint16_t* pk = kb + base + tok * kv_row + 8 * kj;
-                kreg_a[it] = *reinterpret_cast<const uint4*>(pk);
-                kreg_b[it] = *reinterpret_cast<const uint4*>(pk + kHalf);
-            } else {
-                kreg_a[it] = make_uint4(0, 0, 0, 0);
-                kreg_b[it] = make_uint4(0, 0, 0, 0);
-            }
-        }
-#pragma unroll
-        for (int it = 0; it < 2; ++it)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int tok = 16 * it + 4 * vtg + r;
-                vreg[it][r] = tok < d.ntok ? *reinterpret_cast<const uint4*>(vb + base + tok * kv_row + 8 * vj)
-                                           : make_uint4(0, 0, 0, 0);
-            }
-    };
     auto emit = [&](int s) {                        // (running max, segment sum) per row for segment s
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            const float tot = seg_l[rb] + __shfl_xor(seg_l[rb], 32);
-            if (lg == 0) massml[(int64_t)(s + ss) * kRowTile + rb * 32 + li] = make_float2(m_run[rb], tot);
+        for (int rb = 0; rb < NRB; ++rb) {
+            float tot = seg_l[rb] + __shfl_xor(seg_l[rb], 16);
+            tot += __shfl_xor(tot, 32);
+            if (lg == 0) massml[(int64_t)(s + split) * p.rows_wg + (wave * NRB + rb) * 16 + li] = make_float2(m_run[rb], tot);
         }
     };
 
-    if (wb0 < wb1) {
-        int s_next = locate(wb0, 0);
-        BlockDesc nd = describe(wb0, s_next);
-        issue_loads(nd);
-        int cur_seg = -1;
-        int cur_delta = 0;
-        float cs_c[8], cs_s[8];
-        for (int blk = wb0; blk < wb1; ++blk) {
-            const BlockDesc cd = nd;
-            if (cd.seg != cur_seg) {
-                if (cur_seg >= 0) emit(cur_seg);
-                cur_seg = cd.seg;
-                seg_l[0] = seg_l[1] = 0.f;
-                cur_delta = tbl.delta[cur_seg];
-                if (cur_delta != 0) {
+    int cs_slot = 0;
+    int cur_seg = -1;
+    bool first = true;
+    if (d0.ntok > 0 && tid < kHalf) cs_lds[0][tid] = rope_cos_sin(tbl.delta[d0.seg], my_freq);
+
+    // One tile: stage `cur` from its registers, refill those registers with the tile after `nxt`,
+    // prepare the cos/sin table of `nxt`, then do the math of `cur` out of LDS.
+    auto step = [&](TileDesc& cur, StageRegs& r, const TileDesc& nxt) {
+        const TileDesc cd = cur;
+        if (cd.seg != cur_seg) {
+            if (cur_seg >= 0) emit(cur_seg);
+            cur_seg = cd.seg;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float2 w = rope_cos_sin(cur_delta, freq.rev[8 * kj + e]);
-                        cs_c[e] = w.x;
-                        cs_s[e] = w.y;
-                    }
-                }
-            }
-            // ---- stage K: rotate pairs (c, c + 64), round once, write [token][c]
+            for (int rb = 0; rb < NRB; ++rb) seg_l[rb] = 0.f;
+        }
+        const int cur_delta = tbl.delta[cd.seg];
+        __syncthreads();            // previous tile fully consumed; this tile's cos/sin table is visible
+        // ---- stage K: rotate pairs (c, c + 64), round once, write [token][c]
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                uint4 ra = kreg_a[it], rb4 = kreg_b[it];
-                if (cur_delta != 0) {
-                    uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb4.x, rb4.y, rb4.z, rb4.w};
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float a0 = Mma<DT>::to_f(wa[i] & 0xffffu), a1 = Mma<DT>::to_f(wa[i] >> 16);
-                        const float b0 = Mma<DT>::to_f(wb[i] & 0xffffu), b1 = Mma<DT>::to_f(wb[i] >> 16);
-                        const float c0 = cs_c[2 * i], s0 = cs_s[2 * i], c1 = cs_c[2 * i + 1], s1 = cs_s[2 * i + 1];
-                        wa[i] = pack2<DT>(a0 * c0 - b0 * s0, a1 * c1 - b1 * s1);
-                        wb[i] = pack2<DT>(a0 * s0 + b0 * c0, a1 * s1 + b1 * c1);
-                    }
-                    ra = make_uint4(wa[0], wa[1], wa[2], wa[3]);
-                    rb4 = make_uint4(wb[0], wb[1], wb[2], wb[3]);
-                }
-                uint16_t* dst = k_lds + (8 * it + ktr) * kSK + 8 * kj;
-                *reinterpret_cast<uint4*>(dst) = ra;
-                *reinterpret_cast<uint4*>(dst + kHalf) = rb4;
-            }
-            // ---- stage V transposed: [dv][token], tokens ordered so that each MFMA k-group is contiguous
-#pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const uint32_t x0[4] = {vreg[it][0].x, vreg[it][0].y, vreg[it][0].z, vreg[it][0].w};
-                const uint32_t x1[4] = {vreg[it][1].x, vreg[it][1].y, vreg[it][1].z, vreg[it][1].w};
-                const uint32_t x2[4] = {vreg[it][2].x, vreg[it][2].y, vreg[it][2].z, vreg[it][2].w};
-                const uint32_t x3[4] = {vreg[it][3].x, vreg[it][3].y, vreg[it][3].z, vreg[it][3].w};
-                // quad (4 consecutive tokens) index in the block: 4*it + vtg; its slot in the row
-                const int pos = (2 * it + (vtg & 1)) * 8 + (vtg >> 1) * 4;
+        for (int it = 0; it < 2; ++it) {
+            uint4 ra = r.ka[it], rb4 = r.kb[it];
+            if (cur_delta != 0) {
+                uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb4.x, rb4.y, rb4.z, rb4.w};
+                const float2* cs = cs_lds[cs_slot] + 8 * kj;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    uint2 lo, hi;
-                    lo.x = __builtin_amdgcn_perm(x1[i], x0[i], 0x05040100u);
-                    lo.y = __builtin_amdgcn_perm(x3[i], x2[i], 0x05040100u);
-                    hi.x = __builtin_amdgcn_perm(x1[i], x0[i], 0x07060302u);
-                    hi.y = __builtin_amdgcn_perm(x3[i], x2[i], 0x07060302u);
-                    *reinterpret_cast<uint2*>(v_lds + (8 * vj + 2 * i) * kSV + pos) = lo;
-                    *reinterpret_cast<uint2*>(v_lds + (8 * vj + 2 * i + 1) * kSV + pos) = hi;
+                    const float a0 = Mma<DT>::lo(wa[i]), a1 = Mma<DT>::hi(wa[i]);
+                    const float b0 = Mma<DT>::lo(wb[i]), b1 = Mma<DT>::hi(wb[i]);
+                    const float2 w0 = cs[2 * i], w1 = cs[2 * i + 1];
+                    wa[i] = Mma<DT>::pack(a0 * w0.x - b0 * w0.y, a1 * w1.x - b1 * w1.y);
+                    wb[i] = Mma<DT>::pack(a0 * w0.y + b0 * w0.x, a1 * w1.y + b1 * w1.x);
                 }
+                ra = make_uint4(wa[0], wa[1], wa[2], wa[3]);
+                rb4 = make_uint4(wb[0], wb[1], wb[2], wb[3]);
             }
-            // ---- next block's loads fly during this block's math
-            if (blk + 1 < wb1) {
-                s_next = locate(blk + 1, s_next);
-                nd = describe(blk + 1, s_next);
-                issue_loads(nd);
+            uint16_t* dst = k_lds + (kt + 32 * it) * kSK + 8 * kj;
+            *reinterpret_cast<uint4*>(dst) = ra;
+            *reinterpret_cast<uint4*>(dst + kHalf) = rb4;
+        }
+        // ---- stage V transposed: [channel][token]; inside each half of 32 tokens the order puts the
+        // 8 tokens of MFMA k-group g — {4g..4g+3} and {16+4g..16+4g+3} — side by side
+        {
+            const int tk = 4 * vq;                     // first token of this thread's quad
+            const int t32 = tk & 31;
+            const int pos = (tk >> 5) * 32 + ((t32 & 15) >> 2) * 8 + (t32 >> 4) * 4;
+            const uint32_t x0[4] = {r.v[0].x, r.v[0].y, r.v[0].z, r.v[0].w};
+            const uint32_t x1[4] = {r.v[1].x, r.v[1].y, r.v[1].z, r.v[1].w};
+            const uint32_t x2[4] = {r.v[2].x, r.v[2].y, r.v[2].z, r.v[2].w};
+            const uint32_t x3[4] = {r.v[3].x, r.v[3].y, r.v[3].z, r.v[3].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint2 lo, hi;
+                lo.x = __builtin_amdgcn_perm(x1[i], x0[i], 0x05040100u);
+                lo.y = __builtin_amdgcn_perm(x3[i], x2[i], 0x05040100u);
+                hi.x = __builtin_amdgcn_perm(x1[i], x0[i], 0x07060302u);
+                hi.y = __builtin_amdgcn_perm(x3[i], x2[i], 0x07060302u);
+                *reinterpret_cast<uint2*>(v_lds + (8 * vj + 2 * i) * kSV + pos) = lo;
+                *reinterpret_cast<uint2*>(v_lds + (8 * vj + 2 * i + 1) * kSV + pos) = hi;
             }
-            __builtin_amdgcn_wave_barrier();
+        }
+        // ---- these registers are free again: the tile after `nxt` starts loading now
+        fetch(cur, r);
+        if (nxt.ntok > 0 && nxt.seg != cd.seg) {
+            cs_slot ^= 1;
+            if (tid < kHalf) cs_lds[cs_slot][tid] = rope_cos_sin(tbl.delta[nxt.seg], my_freq);
+        }
+        __syncthreads();            // staged tile visible
+        if (first) { CF_STAMP(2); first = false; }
 
-            // ---- S^T = K Q^T : lane (li, lg) gets, for query row li, tokens 8*(r>>2) + 4*lg + (r&3)
-            f32x16 sc[2];
+        const bool causal = tbl.self[cd.seg] != 0;
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
+        for (int h2 = 0; h2 < 2; ++h2) {
+            const int nt = cd.ntok - 32 * h2;      // valid tokens of this half
+            if (nt <= 0) break;
+            // ---- S^T = K Q^T : lane (li, lg) gets, for query row li, tokens 32*h2 + 16*tb + 4*lg + r
+            f32x4 sc[NRB][2];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) sc[rb][r] = 0.f;
+            for (int rb = 0; rb < NRB; ++rb) { sc[rb][0] = f32x4{0.f, 0.f, 0.f, 0.f}; sc[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                const uint4 ka = *reinterpret_cast<const uint4*>(k_lds + li * kSK + 16 * kk + 8 * lg);
+            for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-                for (int rb = 0; rb < 2; ++rb) sc[rb] = Mma<DT>::run(ka, qf[rb][kk], sc[rb]);
-            }
-            // ---- online softmax (exp2 domain), fp32
-            const bool causal = tbl.self[cd.seg] != 0;
-            uint4 pfrag[2][2];
+                for (int kk = 0; kk < 4; ++kk) {
+                    const uint4 ka = *reinterpret_cast<const uint4*>(k_lds + (32 * h2 + 16 * tb + li) * kSK + 32 * kk + 8 * lg);
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
-                float x[16];
-                float mloc = -INFINITY;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int tk = 8 * (r >> 2) + 4 * lg + (r & 3);
-                    const bool ok = tk < cd.ntok && (!causal || cd.tok0 + tk <= trow[rb]);
-                    x[r] = ok ? sc[rb][r] * a.scale_log2e : -INFINITY;
-                    mloc = fmaxf(mloc, x[r]);
+                    for (int rb = 0; rb < NRB; ++rb) sc[rb][tb] = Mma<DT>::run(ka, qf[rb][kk], sc[rb][tb]);
                 }
+            // ---- online softmax (exp2 domain), fp32
+            const bool need_mask = causal || nt < 32;
+            uint4 pfrag[NRB];
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb) {
+                float xv[8];
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) xv[4 * tb + e] = sc[rb][tb][e];
+                if (need_mask) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int tk = 16 * (e >> 2) + 4 * lg + (e & 3);
+                        const bool ok = tk < nt && (!causal || cd.tok0 + 32 * h2 + tk <= trow[rb]);
+                        xv[e] = ok ? xv[e] : -INFINITY;
+                    }
+                }
+                float mloc = fmaxf(fmaxf(fmaxf(xv[0], xv[1]), fmaxf(xv[2], xv[3])), fmaxf(fmaxf(xv[4], xv[5]), fmaxf(xv[6], xv[7])));
+                mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
                 mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+                mloc *= a.scale_log2e;                       // scale > 0: max commutes with it
                 const float m_new = fmaxf(m_run[rb], mloc);
                 const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-                const float alpha = exp2f(m_run[rb] - m_safe);
+                const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_safe);
                 float lsum = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    x[r] = exp2f(x[r] - m_safe);
-                    lsum += x[r];
+                for (int e = 0; e < 8; ++e) {
+                    xv[e] = __builtin_amdgcn_exp2f(fmaf(xv[e], a.scale_log2e, -m_safe));
+                    lsum += xv[e];
                 }
                 l_run[rb] = l_run[rb] * alpha + lsum;
                 seg_l[rb] = seg_l[rb] * alpha + lsum;
                 m_run[rb] = m_new;
                 if (__any(alpha != 1.f)) {
 #pragma unroll
-                    for (int db = 0; db < 4; ++db)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) acc[db][rb][r] *= alpha;
+                    for (int db = 0; db < 8; ++db) acc[rb][db] *= alpha;
                 }
-                pfrag[rb][0] = make_uint4(pack2<DT>(x[0], x[1]), pack2<DT>(x[2], x[3]), pack2<DT>(x[4], x[5]), pack2<DT>(x[6], x[7]));
-                pfrag[rb][1] = make_uint4(pack2<DT>(x[8], x[9]), pack2<DT>(x[10], x[11]), pack2<DT>(x[12], x[13]), pack2<DT>(x[14], x[15]));
+                pfrag[rb] = make_uint4(Mma<DT>::pack(xv[0], xv[1]), Mma<DT>::pack(xv[2], xv[3]),
+                                       Mma<DT>::pack(xv[4], xv[5]), Mma<DT>::pack(xv[6], xv[7]));
             }
             // ---- O^T += V^T P^T
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int db = 0; db < 8; ++db) {
+                const uint4 va = *reinterpret_cast<const uint4*>(v_lds + (16 * db + li) * kSV + 32 * h2 + 8 * lg);
 #pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    const uint4 va = *reinterpret_cast<const uint4*>(v_lds + (32 * db + li) * kSV + (2 * h + lg) * 8);
-#pragma unroll
-                    for (int rb = 0; rb < 2; ++rb) acc[db][rb] = Mma<DT>::run(va, pfrag[rb][h], acc[db][rb]);
-                }
-            __builtin_amdgcn_wave_barrier();
+                for (int rb = 0; rb < NRB; ++rb) acc[rb][db] = Mma<DT>::run(va, pfrag[rb], acc[rb][db]);
+            }
         }
-        emit(cur_seg);
-    }
+    };
 
-    // ---- merge the 4 sub-splits of this workgroup (same rows, different tokens)
-    float l_tot[2];
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-        l_tot[rb] = l_run[rb] + __shfl_xor(l_run[rb], 32);
-        if (lg == 0) ml_w[wave][rb * 32 + li] = make_float2(m_run[rb], l_tot[rb]);
-    }
-    __syncthreads();
-    float mx[2], zz[2];
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-        const int row = rb * 32 + li;
-        float m = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) m = fmaxf(m, ml_w[w][row].x);
-        const float ms = m == -INFINITY ? 0.f : m;
-        float z = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) z += ml_w[w][row].y * exp2f(ml_w[w][row].x - ms);
-        mx[rb] = m;
-        zz[rb] = z;
-        const float f = exp2f(m_run[rb] - ms);
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[db][rb][r] *= f;
-    }
-    float* red = reinterpret_cast<float*>(stage_all);           // 2 slots of kORegs*64 floats (64 KB)
-    auto put = [&](int slot) {
-        float* dst = red + slot * kORegs * kWave + lane;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) dst[((db * 2 + rb) * 16 + r) * kWave] = acc[db][rb][r];
-    };
-    auto add = [&](int slot) {
-        const float* src = red + slot * kORegs * kWave + lane;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[db][rb][r] += src[((db * 2 + rb) * 16 + r) * kWave];
-    };
-    if (wave >= 2) put(wave - 2);
-    __syncthreads();
-    if (wave < 2) add(wave);
-    __syncthreads();
-    if (wave == 1) put(0);
-    __syncthreads();
-    if (wave == 0) {
-        add(0);
-        float* opart = reinterpret_cast<float*>(static_cast<char*>(a.workspace) + p.off_opart) +
-                       ((int64_t)unit * p.nsplit + split) * kORegs * kWave + lane;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) opart[((db * 2 + rb) * 16 + r) * kWave] = acc[db][rb][r];
-        float2* ml = reinterpret_cast<float2*>(static_cast<char*>(a.workspace) + p.off_ml) +
-                     ((int64_t)unit * p.nsplit + split) * kRowTile;
-        if (lg == 0) {
-            ml[li] = make_float2(mx[0], zz[0]);
-            ml[32 + li] = make_float2(mx[1], zz[1]);
+    if (kDeep) {
+        while (d0.ntok > 0) {
+            step(d0, regs0, d1);
+            if (d1.ntok <= 0) break;
+            step(d1, regs1, d0);
         }
+    } else {
+        while (d0.ntok > 0) step(d0, regs0, d0);      // `nxt` is read after the refill: the same object serves
     }
+    if (cur_seg >= 0) emit(cur_seg);
+    CF_STAMP(3);
+
+    // ---- partial results of this split: O^T in MFMA layout (one float4 per lane, row block and
+    // channel block) and (max, sum) per row
+    f32x4* opart = reinterpret_cast<f32x4*>(ws + p.off_opart) +
+                   (((int64_t)unit * p.nsplit + split) * p.rows_wg / 16 + wave * NRB) * 8 * kWave + lane;
+    float2* ml = reinterpret_cast<float2*>(ws + p.off_ml) + ((int64_t)unit * p.nsplit + split) * p.rows_wg;
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+#pragma unroll
+        for (int db = 0; db < 8; ++db) opart[(rb * 8 + db) * kWave] = acc[rb][db];
+        float tot = l_run[rb] + __shfl_xor(l_run[rb], 16);
+        tot += __shfl_xor(tot, 32);
+        if (lg == 0) ml[(wave * NRB + rb) * 16 + li] = make_float2(m_run[rb], tot);
+    }
+    CF_STAMP(4);
 }
 
-// One workgroup per unit: merges the splits' partial outputs, writes the output tile, reduces the
-// per-segment (max, sum) pairs over the tile's rows; the last unit of a query to finish adds the
-// units' masses in a fixed order.
+// Second kernel: one workgroup per (unit, 64-row pass, quarter of the output channels) merges the
+// splits' partial outputs, writes its output rows and leaves (max, 1/sum) per row for the mass kernel.
 template <int DT>
 __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan p) {
-    __shared__ SegTable tbl;
-    __shared__ float wgt[64][kRowTile];          // per split: exp2(m_split - M) / Z
-    __shared__ float row_m[kRowTile], row_iz[kRowTile];
-    __shared__ __attribute__((aligned(16))) uint16_t otile[kRowTile][kD + 8];
-    __shared__ int is_last;
+    __shared__ float2 mlw[kMaxSplit * 64];       // (m, l) per split and row, then the split's weight in .x
 
-    const int unit = blockIdx.x;
-    const int rowtile = unit % p.rowtiles;
-    const int hkv = (unit / p.rowtiles) % a.n_kv_heads;
-    const int b = unit / p.units_per_b;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const int li = lane & 15, lg = lane >> 4;
+    char* ws = static_cast<char*>(a.workspace);
     const int hq = a.n_q_heads, group = hq / a.n_kv_heads;
+#ifdef CF_TRACE
+    long long* trace = reinterpret_cast<long long*>(ws + p.total) -
+                       (size_t)(p.units * p.nrb * 4 + a.batch * p.mass_chunks) * 16 + (size_t)blockIdx.x * 16;
+#endif
+    CF_STAMP(0);
+    const int dbq = blockIdx.x & 3;
+    const int pass = (blockIdx.x >> 2) % p.nrb;
+    const int unit = blockIdx.x / (4 * p.nrb);
+    const int rg = unit % p.n_rg;
+    const int hkv = (unit / p.n_rg) % a.n_kv_heads;
+    const int b = unit / p.units_per_b;
     const int q0 = a.q_off[b];
     const int tq = min(a.q_off[b + 1] - q0, a.max_tq);
     const int n_rows = group * tq;
+    const int row_base = rg * p.blocks_rg * 16;
+    const int rows_here = min(p.blocks_rg * 16, n_rows - row_base);
+    const float2* ml = reinterpret_cast<const float2*>(ws + p.off_ml) + (int64_t)unit * p.nsplit * p.rows_wg + pass * 64;
+    const f32x4* opart = reinterpret_cast<const f32x4*>(ws + p.off_opart) + (int64_t)unit * p.nsplit * p.rows_wg * (kD / 4);
 
-    build_table(a, b, &tbl);
-
-    const float2* ml = reinterpret_cast<const float2*>(static_cast<const char*>(a.workspace) + p.off_ml) +
-                       (int64_t)unit * p.nsplit * kRowTile;
-    if (threadIdx.x < kRowTile) {
-        const int row = threadIdx.x;
+    for (int idx = tid; idx < p.nsplit * 64; idx += kThreads) mlw[idx] = ml[(idx >> 6) * p.rows_wg + (idx & 63)];
+    __syncthreads();
+    if (tid < 64) {
         float m = -INFINITY;
-        for (int s = 0; s < p.nsplit; ++s) m = fmaxf(m, ml[s * kRowTile + row].x);
+        for (int s = 0; s < p.nsplit; ++s) m = fmaxf(m, mlw[s * 64 + tid].x);
         const float ms = m == -INFINITY ? 0.f : m;
         float z = 0.f;
-        for (int s = 0; s < p.nsplit; ++s) z += ml[s * kRowTile + row].y * exp2f(ml[s * kRowTile + row].x - ms);
+        for (int s = 0; s < p.nsplit; ++s) z += mlw[s * 64 + tid].y * exp2f(mlw[s * 64 + tid].x - ms);
         const float iz = z > 0.f ? 1.f / z : 0.f;
-        for (int s = 0; s < p.nsplit; ++s) wgt[s][row] = exp2f(ml[s * kRowTile + row].x - ms) * iz;
-        row_m[row] = ms;
-        row_iz[row] = iz;
+        for (int s = 0; s < p.nsplit; ++s) mlw[s * 64 + tid].x = exp2f(mlw[s * 64 + tid].x - ms) * iz;
+        if (dbq == 0)
+            reinterpret_cast<float2*>(ws + p.off_rowstat)[(int64_t)unit * p.rows_wg + pass * 64 + tid] = make_float2(ms, iz);
     }
     __syncthreads();
+    const int blk = pass * kWaves + wave;                      // row block inside the workgroup tile
+    f32x4 o0 = f32x4{0.f, 0.f, 0.f, 0.f}, o1 = o0;
+    const f32x4* src = opart + ((int64_t)blk * 8 + 2 * dbq) * kWave + lane;
+    const int64_t split_stride = (int64_t)p.rows_wg / 16 * 8 * kWave;
+#pragma unroll 8
+    for (int s = 0; s < p.nsplit; ++s) {
+        const float w = mlw[s * 64 + wave * 16 + li].x;
+        const f32x4 v0 = src[s * split_stride], v1 = src[s * split_stride + kWave];
+        o0 += v0 * w;
+        o1 += v1 * w;
+    }
+    const int lrow = pass * 64 + wave * 16 + li;
+    if (lrow < rows_here) {
+        const int m2 = row_base + lrow;
+        const int gi = m2 / tq, t = m2 - gi * tq;
+        uint16_t* op = static_cast<uint16_t*>(a.out) + (((int64_t)q0 + t) * hq + hkv * group + gi) * kD + 32 * dbq + 4 * lg;
+        uint2 pk;
+        pk.x = Mma<DT>::pack(o0[0], o0[1]);
+        pk.y = Mma<DT>::pack(o0[2], o0[3]);
+        *reinterpret_cast<uint2*>(op) = pk;
+        pk.x = Mma<DT>::pack(o1[0], o1[1]);
+        pk.y = Mma<DT>::pack(o1[2], o1[3]);
+        *reinterpret_cast<uint2*>(op + 16) = pk;
+    }
+    CF_STAMP(1);
+}
 
-    // ---- output tile: element (reg, lane) of a partial is O^T[dv][row] of the MFMA layout
-    const float* opart = reinterpret_cast<const float*>(static_cast<const char*>(a.workspace) + p.off_opart) +
-                         (int64_t)unit * p.nsplit * kORegs * kWave;
-    for (int idx = threadIdx.x; idx < kORegs * kWave; idx += kThreads) {
-        const int reg = idx >> 6, ln = idx & 63;
-        const int db = reg >> 5, rb = (reg >> 4) & 1, r = reg & 15;
-        const int row = rb * 32 + (ln & 31);
-        const int dv = 32 * db + 8 * (r >> 2) + 4 * (ln >> 5) + (r & 3);
-        float v = 0.f;
-        for (int s = 0; s < p.nsplit; ++s) v += wgt[s][row] * opart[(int64_t)s * kORegs * kWave + idx];
-        otile[row][dv] = (uint16_t)Mma<DT>::from_f(v);
-    }
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < kRowTile * (kD / 8); idx += kThreads) {
-        const int row = idx / (kD / 8), c = idx % (kD / 8);
-        const int m = rowtile * kRowTile + row;
-        if (m < n_rows) {
-            const int gi = m / tq, t = m - gi * tq;
-            uint16_t* op = static_cast<uint16_t*>(a.out) + (((int64_t)q0 + t) * hq + hkv * group + gi) * kD + 8 * c;
-            *reinterpret_cast<uint4*>(op) = *reinterpret_cast<const uint4*>(&otile[row][8 * c]);
+// Third kernel: per-segment attention mass.  Workgroup (query b, chunk c) owns the segments
+// c, c + mass_chunks, ... and adds, over every row of every unit of the query and every split that
+// touched the segment, sum * exp2(max - row max) / row sum — in a fixed order — then S += mass.
+__global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p) {
+    __shared__ float2 stat[kStatRows];           // (max, 1/sum) per row of a group of units
+    __shared__ SegTable tbl;
+    __shared__ float red[kWaves];
+    __shared__ float segtot[kMaxSegs];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const char* ws = static_cast<const char*>(a.workspace);
+    const int group = a.n_q_heads / a.n_kv_heads;
+#ifdef CF_TRACE
+    long long* trace = reinterpret_cast<long long*>(static_cast<char*>(a.workspace) + p.total) -
+                       (size_t)(a.batch * p.mass_chunks) * 16 + (size_t)blockIdx.x * 16;
+#endif
+    CF_STAMP(0);
+    const int b = blockIdx.x / p.mass_chunks;
+    const int chunk = blockIdx.x % p.mass_chunks;
+    const int q0 = a.q_off[b];
+    const int tq_raw = a.q_off[b + 1] - q0;
+    const float2* rs_b = reinterpret_cast<const float2*>(ws + p.off_rowstat) + (int64_t)b * p.units_per_b * p.rows_wg;
+    const float2* mm_b = reinterpret_cast<const float2*>(ws + p.off_massml) + (int64_t)b * p.units_per_b * p.slots * p.rows_wg;
+    const int units_per_pass = kStatRows / p.rows_wg;            // rows_wg <= 256
+    // the first group's row statistics travel together with the table's loads
+    float2 pre[kStatRows / kThreads];
+    {
+        const int nu = min(units_per_pass, p.units_per_b);
+#pragma unroll
+        for (int j = 0; j < kStatRows / kThreads; ++j) {
+            const int idx = tid + j * kThreads;
+            pre[j] = idx < nu * p.rows_wg ? rs_b[idx] : make_float2(0.f, 0.f);
         }
     }
+    build_table(a, b, &tbl, tq_raw);
+    const int tq = min(tq_raw, a.max_tq);
+    const int n_rows = group * tq;
+    const unsigned total = (unsigned)tbl.tile0[tbl.n];
+    for (int i = tid; i < kMaxSegs; i += kThreads) segtot[i] = 0.f;
 
-    // ---- per-segment mass of this unit: wavefront w owns segments s = w, w+4, ...; lane = row
-    const float2* massml = reinterpret_cast<const float2*>(static_cast<const char*>(a.workspace) + p.off_massml) +
-                           (int64_t)unit * p.slots * kRowTile;
-    float* massunit = reinterpret_cast<float*>(static_cast<char*>(a.workspace) + p.off_massunit);
-    const int total = tbl.blk0[tbl.n];
-    const int row_valid = (rowtile * kRowTile + lane) < n_rows;
-    for (int s = wave; s < tbl.n; s += kWaves) {
-        const int bs = tbl.blk0[s], be = tbl.blk0[s + 1];
-        float accm = 0.f;
-        if (be > bs) {
-            for (int ss = 0; ss < p.nsub; ++ss) {
-                int lo, hi;
-                sub_range(total, p.nsplit, ss, &lo, &hi);
-                if (lo < be && hi > bs && lo < hi) {
-                    const float2 v = massml[(int64_t)(s + ss) * kRowTile + lane];
-                    const float c = row_valid ? v.y * exp2f(v.x - row_m[lane]) * row_iz[lane] : 0.f;
-                    accm += wave_sum(c);
+    for (int u0 = 0; u0 < p.units_per_b; u0 += units_per_pass) {
+        const int nu = min(units_per_pass, p.units_per_b - u0);
+        __syncthreads();
+        if (u0 == 0) {
+#pragma unroll
+            for (int j = 0; j < kStatRows / kThreads; ++j) stat[tid + j * kThreads] = pre[j];
+        } else {
+            for (int idx = tid; idx < nu * p.rows_wg; idx += kThreads) stat[idx] = rs_b[(int64_t)u0 * p.rows_wg + idx];
+        }
+        __syncthreads();
+        int k = 0;
+        for (int s = chunk; s < tbl.n; s += p.mass_chunks, ++k) {
+            const int ts = tbl.tile0[s], te = tbl.tile0[s + 1];
+            if (te <= ts) continue;
+            const int s0 = split_of(total, p.nsplit, ts), s1 = split_of(total, p.nsplit, te - 1);
+            float c = 0.f;
+            for (int idx = tid; idx < nu * p.rows_wg; idx += kThreads) {
+                const int ul = idx / p.rows_wg, r = idx % p.rows_wg;
+                const int rg = (u0 + ul) % p.n_rg;
+                const int rows_here = min(p.blocks_rg * 16, n_rows - rg * p.blocks_rg * 16);
+                if (r < rows_here) {
+                    const float2 st = stat[idx];
+                    const float2* src = mm_b + ((int64_t)(u0 + ul) * p.slots + s) * p.rows_wg + r;
+                    for (int sp = s0; sp <= s1; ++sp) {
+                        const float2 v = src[(int64_t)sp * p.rows_wg];
+                        c += v.y * exp2f(v.x - st.x) * st.y;
+                    }
                 }
             }
+            c = wave_sum(c);
+            __syncthreads();
+            if (lane == 0) red[wave] = c;
+            __syncthreads();
+            if (tid == 0) segtot[k] += (red[0] + red[1]) + (red[2] + red[3]);
         }
-        if (lane == 0) massunit[((int64_t)b * p.units_per_b + (unit % p.units_per_b)) * a.seg_stride + s] = accm;
-    }
-
-    // ---- last unit of query b sums the units in order
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int32_t* counters = reinterpret_cast<int32_t*>(static_cast<char*>(a.workspace) + p.off_counters);
-        is_last = atomicAdd(&counters[b], 1) == p.units_per_b - 1;
     }
     __syncthreads();
-    if (is_last) {
-        __threadfence();
-        for (int s = threadIdx.x; s < tbl.n; s += kThreads) {
-            float tot = 0.f;
-            for (int u = 0; u < p.units_per_b; ++u)
-                tot += __builtin_nontemporal_load(&massunit[((int64_t)b * p.units_per_b + u) * a.seg_stride + s]);
-            a.mass[(int64_t)b * a.seg_stride + s] = tot;
+    if (tid == 0) {
+        int k = 0;
+        for (int s = chunk; s < tbl.n; s += p.mass_chunks, ++k) {
+            const float seg_total = segtot[k];
+            a.mass[(int64_t)b * a.seg_stride + s] = seg_total;
             const int doc = a.segs[(int64_t)b * a.seg_stride + s].doc;
             if (a.score_accum && doc >= 0 && doc < a.score_stride)
-                atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], tot);
+                atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], seg_total);
         }
     }
+    CF_STAMP(1);
 }
 
 }  // namespace
@@ -614,17 +683,25 @@ size_t mfma_workspace_bytes(const cf_layer_desc* d, int32_t batch, int32_t max_t
 
 cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_t s) {
     if (!mfma_shape_ok(a.seg_stride)) return launch_attention_generic(a, f, s);
+    const int phases = profile_phases();
     const Plan p = make_plan(a.n_q_heads, a.n_kv_heads, a.batch, a.max_tq, a.seg_stride, a.max_kv_tokens);
-    const unsigned grid = (unsigned)(p.units * p.nsplit);
-    if (a.dtype == CF_BF16) {
-        hipLaunchKernelGGL((attn_mfma_kernel<CF_BF16>), dim3(grid), dim3(kThreads), 0, s, a, f, p);
-        CF_HIP(hipGetLastError());
-        hipLaunchKernelGGL((attn_combine_kernel<CF_BF16>), dim3(p.units), dim3(kThreads), 0, s, a, p);
-    } else {
-        hipLaunchKernelGGL((attn_mfma_kernel<CF_F16>), dim3(grid), dim3(kThreads), 0, s, a, f, p);
-        CF_HIP(hipGetLastError());
-        hipLaunchKernelGGL((attn_combine_kernel<CF_F16>), dim3(p.units), dim3(kThreads), 0, s, a, p);
-    }
+    const dim3 grid((unsigned)(p.x_count * p.n_rg)), block(kThreads);
+    const dim3 grid2((unsigned)(p.units * p.nrb * 4)), grid3((unsigned)(a.batch * p.mass_chunks));
+#define CF_LAUNCH(DT, N) hipLaunchKernelGGL((attn_mfma_kernel<DT, N>), grid, block, 0, s, a, f, p)
+#define CF_LAUNCH_DT(DT)                                   \
+    if (phases & 1) switch (p.nrb) {                       \
+        case 1: CF_LAUNCH(DT, 1); break;                   \
+        case 2: CF_LAUNCH(DT, 2); break;                   \
+        case 3: CF_LAUNCH(DT, 3); break;                   \
+        default: CF_LAUNCH(DT, 4); break;                  \
+    }                                                      \
+    CF_HIP(hipGetLastError());                             \
+    if (phases & 2) hipLaunchKernelGGL((attn_combine_kernel<DT>), grid2, block, 0, s, a, p);
+    if (a.dtype == CF_BF16) { CF_LAUNCH_DT(CF_BF16) } else { CF_LAUNCH_DT(CF_F16) }
+#undef CF_LAUNCH_DT
+#undef CF_LAUNCH
+    CF_HIP(hipGetLastError());
+    if (phases & 4) hipLaunchKernelGGL(attn_mass_kernel, grid3, block, 0, s, a, p);
     CF_HIP(hipGetLastError());
     return CF_OK;
 }

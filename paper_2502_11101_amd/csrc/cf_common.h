@@ -19,6 +19,7 @@ struct RopeFreq {
 };
 
 void set_error(const char* fmt, ...);
+int profile_phases();   // bit mask set by cf_profile_phases (thread-local, default: all)
 cf_status check_desc(const cf_layer_desc* d);
 void fill_rope_freq(const cf_layer_desc* d, RopeFreq* f);
 size_t elem_size(int32_t dtype);
