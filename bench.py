@@ -3,8 +3,9 @@
 
 A step is one pass of the whole hot path over one layer of the LLaMA-2-7B-shaped workload
 (32-token shared prefix + 10 cached documents x 160 tokens + a 48-token query, bf16):
-cf_prefill_attention (keys re-positioned on the fly, attention, per-document mass, S += mass),
-cf_prune_topk (keep 5), cf_assign_positions and cf_gather_segments for the next layer's table.
+one cf_prefill_layer call = cf_prefill_attention (keys re-positioned on the fly, attention,
+per-document mass, S += mass) + cf_prune_topk (keep 5) + cf_assign_positions + cf_gather_segments
+for the next layer's table.
 Steps cycle through distinct layer buffers whose total exceeds twice the 256 MB last-level
 cache, so every step streams its K/V from HBM.  Inputs are resident in HBM before timing.
 
@@ -120,8 +121,9 @@ def main() -> int:
 
     def step(i: int) -> None:
         L = layers[i % len(layers)]
-        pb.attention(L["q"], L["k_self"], L["v_self"], L["k_store"], L["v_store"], out)
-        pb.prune(cfg.keep, cf.CF_ALLOC_SORT)      # next layer's tables; this layer's stay in use
+        # attention + mass + S += mass + prune + allocation + next layer's table (this layer's table stays in use)
+        pb.layer(L["q"], L["k_self"], L["v_self"], L["k_store"], L["v_store"], out, keep=cfg.keep,
+                 strategy=cf.CF_ALLOC_SORT)
 
     for i in range(args.warmup):
         step(i)
@@ -174,7 +176,7 @@ def main() -> int:
         "config": {"workload": WORKLOAD, "batch": cfg.batch, "kv_tokens_per_step": kv_tokens,
                    "q_heads": g.n_q_heads, "kv_heads": g.n_kv_heads, "head_dim": g.head_dim, "tq": cfg.tq,
                    "docs": cfg.docs_per_query, "keep": cfg.keep, "layer_buffers": len(layers),
-                   "step": "prefill_attention + prune_topk + assign_positions + gather_segments"},
+                   "step": "cf_prefill_layer: attention + mass + prune_topk + assign_positions + gather_segments"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "kernel": "attn_mfma_kernel (first kernel of cf_prefill_attention)",

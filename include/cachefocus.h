@@ -231,6 +231,54 @@ CF_API cf_status cf_gather_segments(const int64_t* doc_tok_offset, const int32_t
                              cf_segment* segs, int32_t* n_seg, int32_t seg_stride,
                              int32_t* dev_flag, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * One whole layer of Alg. 2, Phase 1, in one call: the attention of cf_prefill_attention (with
+ * S += s^l into score_accum, which must be given) followed — when `prune` is not NULL — by the
+ * prune event of that layer: cf_prune_topk on the accumulated scores, cf_assign_positions for the
+ * survivors and cf_gather_segments into the NEXT layer's table.  Results are identical to the
+ * four separate calls; on the 16-bit path the mass reduction, ranking, allocation and table rebuild
+ * run in one kernel, so a layer costs three launches instead of six.
+ * The current table (segs / n_seg / q_new_start) is only read; the prune step writes next_segs,
+ * next_n_seg, new_start, q_start, which therefore must not alias the current ones.
+ * All pointers in cf_prune_step are device memory with the shapes given at the stand-alone calls
+ * (stride = document slots per query; next_segs has the same seg_stride as segs).
+ * With strategy CF_ALLOC_KEEP new_start / q_start are not written: hand in arrays that already
+ * hold the current positions.
+ */
+typedef struct cf_prune_step {
+    int32_t keep;              /* documents kept per query, 0 <= keep <= stride                    */
+    int32_t strategy;          /* cf_alloc_strategy                                                */
+    int32_t force_n_reuse;     /* 0 = Eq. 6                                                        */
+    int32_t normalise_by_len;  /* non-zero: rank by score/len                                      */
+    int32_t stride;
+    int32_t pos_begin, pos_end;
+    int32_t prefix_len, doc_stored_start;
+    int32_t reserved;          /* must be 0                                                        */
+    const int64_t* doc_tok_offset;  /* [batch*stride] */
+    const int32_t* doc_len;         /* [batch*stride] */
+    const int32_t* cand;            /* [batch*stride] current candidates                           */
+    const int32_t* n_cand;          /* [batch]                                                     */
+    int32_t* keep_idx;              /* [batch*stride] out: survivors, best first                   */
+    int32_t* n_keep;                /* [batch] out                                                 */
+    int32_t* new_start;             /* [batch*stride] out (survivors' entries)                     */
+    int32_t* q_start;               /* [batch] out                                                 */
+    int32_t* n_reuse;               /* [batch] out                                                 */
+    int32_t* order;                 /* [batch*stride] out: placement order = next candidates       */
+    cf_segment* next_segs;          /* [batch*seg_stride] out                                      */
+    int32_t* next_n_seg;            /* [batch] out                                                 */
+} cf_prune_step;
+
+CF_API cf_status cf_prefill_layer(const cf_layer_desc* desc,
+                                  const void* q, const int32_t* q_off, int32_t q_stored_start,
+                                  const int32_t* q_new_start,
+                                  const void* k_store, const void* v_store, int64_t n_store_tokens,
+                                  const void* k_self, const void* v_self,
+                                  const cf_segment* segs, const int32_t* n_seg, int32_t seg_stride,
+                                  int32_t batch, int32_t max_tq, int64_t max_kv_tokens,
+                                  void* out, float* mass, float* score_accum, int32_t score_stride,
+                                  void* workspace, size_t workspace_bytes,
+                                  const cf_prune_step* prune, int32_t* dev_flag, void* stream);
+
 /* Thread-local text for the last non-OK status returned on this thread (static storage). */
 CF_API const char* cf_last_error(void);
 

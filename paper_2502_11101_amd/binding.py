@@ -27,13 +27,24 @@ CF_FLAG_BAD_SEGMENT, CF_FLAG_NONFINITE_SCORE, CF_FLAG_DOC_TOO_LONG, CF_FLAG_POS_
 DTYPE_CODE = {"f32": CF_F32, "bf16": CF_BF16, "f16": CF_F16}
 
 EXPORTS = ("cf_reposition_keys", "cf_prefill_workspace_bytes", "cf_prefill_attention", "cf_prune_topk",
-           "cf_assign_positions", "cf_gather_segments", "cf_last_error", "cf_version", "cf_profile_phases")
+           "cf_assign_positions", "cf_gather_segments", "cf_last_error", "cf_version", "cf_profile_phases",
+           "cf_prefill_layer")
 
 
 class cf_layer_desc(C.Structure):
     _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("dtype", C.c_int32), ("rope_pairing", C.c_int32), ("max_positions", C.c_int32),
                 ("rope_base", C.c_double), ("softmax_scale", C.c_float), ("reserved", C.c_int32)]
+
+
+class cf_prune_step(C.Structure):
+    _fields_ = [("keep", C.c_int32), ("strategy", C.c_int32), ("force_n_reuse", C.c_int32),
+                ("normalise_by_len", C.c_int32), ("stride", C.c_int32), ("pos_begin", C.c_int32),
+                ("pos_end", C.c_int32), ("prefix_len", C.c_int32), ("doc_stored_start", C.c_int32),
+                ("reserved", C.c_int32),
+                ("doc_tok_offset", C.c_void_p), ("doc_len", C.c_void_p), ("cand", C.c_void_p), ("n_cand", C.c_void_p),
+                ("keep_idx", C.c_void_p), ("n_keep", C.c_void_p), ("new_start", C.c_void_p), ("q_start", C.c_void_p),
+                ("n_reuse", C.c_void_p), ("order", C.c_void_p), ("next_segs", C.c_void_p), ("next_n_seg", C.c_void_p)]
 
 
 SEGMENT_DTYPE = np.dtype([("tok_offset", "<i8"), ("len", "<i4"), ("stored_start", "<i4"),
@@ -74,6 +85,9 @@ def load() -> C.CDLL:
     lib.cf_prefill_attention.restype = i32
     lib.cf_prefill_attention.argtypes = [dp, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp, i32, i32, i32, i64,
                                          vp, vp, vp, i32, vp, sz, vp, vp]
+    lib.cf_prefill_layer.restype = i32
+    lib.cf_prefill_layer.argtypes = [dp, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp, i32, i32, i32, i64,
+                                     vp, vp, vp, i32, vp, sz, C.POINTER(cf_prune_step), vp, vp]
     lib.cf_prune_topk.restype = i32
     lib.cf_prune_topk.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.cf_assign_positions.restype = i32
@@ -165,6 +179,26 @@ def cf_prefill_attention(desc, q, q_off, q_stored_start: int, q_new_start, k_sto
         n_store_tokens, _ptr(k_self), _ptr(v_self), _ptr(segs), _ptr(n_seg), seg_stride, batch, max_tq,
         max_kv_tokens, _ptr(out), _ptr(mass), _ptr(score_accum), score_stride, _ptr(workspace), workspace_bytes,
         _ptr(dev_flag), _stream(stream)))
+
+
+def make_prune_step(keep: int, strategy: int, force_n_reuse: int, normalise_by_len: bool, stride: int, pos_begin: int,
+                    pos_end: int, prefix_len: int, doc_stored_start: int, doc_tok_offset, doc_len, cand, n_cand,
+                    keep_idx, n_keep, new_start, q_start, n_reuse, order, next_segs, next_n_seg) -> cf_prune_step:
+    return cf_prune_step(keep, strategy, force_n_reuse, 1 if normalise_by_len else 0, stride, pos_begin, pos_end,
+                         prefix_len, doc_stored_start, 0, _ptr(doc_tok_offset), _ptr(doc_len), _ptr(cand), _ptr(n_cand),
+                         _ptr(keep_idx), _ptr(n_keep), _ptr(new_start), _ptr(q_start), _ptr(n_reuse), _ptr(order),
+                         _ptr(next_segs), _ptr(next_n_seg))
+
+
+def cf_prefill_layer(desc, q, q_off, q_stored_start: int, q_new_start, k_store, v_store, n_store_tokens: int,
+                     k_self, v_self, segs, n_seg, seg_stride: int, batch: int, max_tq: int, max_kv_tokens: int, out,
+                     mass, score_accum, score_stride: int, workspace, workspace_bytes: int,
+                     prune: Optional[cf_prune_step] = None, dev_flag=None, stream=None) -> None:
+    _check(load().cf_prefill_layer(
+        C.byref(desc), _ptr(q), _ptr(q_off), q_stored_start, _ptr(q_new_start), _ptr(k_store), _ptr(v_store),
+        n_store_tokens, _ptr(k_self), _ptr(v_self), _ptr(segs), _ptr(n_seg), seg_stride, batch, max_tq,
+        max_kv_tokens, _ptr(out), _ptr(mass), _ptr(score_accum), score_stride, _ptr(workspace), workspace_bytes,
+        C.byref(prune) if prune is not None else None, _ptr(dev_flag), _stream(stream)))
 
 
 def cf_prune_topk(score, len_, cand, n_cand, keep: int, batch: int, stride: int, keep_idx, n_keep,

@@ -55,6 +55,18 @@ void fill_rope_freq(const cf_layer_desc* d, RopeFreq* f) {
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+cf_status launch_prune_step(const AttnArgs& a, const cf_prune_step* pr, hipStream_t s) {
+    cf_status st = launch_prune(a.score_accum, pr->normalise_by_len ? pr->doc_len : nullptr, pr->cand, pr->n_cand, pr->keep,
+                                a.batch, pr->stride, pr->keep_idx, pr->n_keep, a.dev_flag, s);
+    if (st != CF_OK) return st;
+    st = launch_assign(pr->doc_len, pr->keep_idx, pr->n_keep, a.batch, pr->stride, pr->pos_begin, pr->pos_end,
+                       pr->strategy, pr->force_n_reuse, pr->new_start, pr->q_start, pr->n_reuse, pr->order, a.dev_flag, s);
+    if (st != CF_OK) return st;
+    return launch_gather(pr->doc_tok_offset, pr->doc_len, pr->order, pr->n_keep, pr->new_start, pr->q_start, a.q_off,
+                         a.batch, pr->stride, pr->prefix_len, pr->doc_stored_start, a.q_stored_start, pr->next_segs,
+                         pr->next_n_seg, a.seg_stride, a.dev_flag, s);
+}
+
 }  // namespace cf
 
 using namespace cf;
@@ -93,13 +105,40 @@ size_t cf_prefill_workspace_bytes(const cf_layer_desc* desc, int32_t batch, int3
     return (n + 255) & ~(size_t)255;
 }
 
-cf_status cf_prefill_attention(const cf_layer_desc* desc, const void* q, const int32_t* q_off,
+static cf_status check_prune_step(const cf_prune_step* pr, int32_t seg_stride, const float* score_accum,
+                                  int32_t score_stride, const cf_segment* segs, const int32_t* n_seg,
+                                  const int32_t* q_new_start) {
+    CF_REQUIRE(score_accum != nullptr, CF_ERR_INVALID_ARG, "a prune step needs score_accum");
+    CF_REQUIRE(pr->stride >= 1 && pr->stride <= kMaxSelectStride, CF_ERR_INVALID_ARG, "stride must be in [1, %d]",
+               kMaxSelectStride);
+    CF_REQUIRE(score_stride == pr->stride, CF_ERR_INVALID_ARG, "score_stride must equal the prune step's stride");
+    CF_REQUIRE(pr->keep >= 0 && pr->keep <= pr->stride, CF_ERR_INVALID_ARG, "keep (%d) must be in [0, stride = %d]",
+               pr->keep, pr->stride);
+    CF_REQUIRE(pr->strategy == CF_ALLOC_KEEP || pr->strategy == CF_ALLOC_ALIGN || pr->strategy == CF_ALLOC_SORT,
+               CF_ERR_INVALID_ARG, "unknown strategy %d", pr->strategy);
+    CF_REQUIRE(pr->force_n_reuse >= 0 && pr->reserved == 0, CF_ERR_INVALID_ARG, "bad force_n_reuse / reserved");
+    CF_REQUIRE(pr->pos_begin >= 0 && pr->pos_end > pr->pos_begin, CF_ERR_RANGE,
+               "need 0 <= pos_begin < pos_end (got %d, %d)", pr->pos_begin, pr->pos_end);
+    CF_REQUIRE(pr->prefix_len >= 0 && pr->doc_stored_start >= 0, CF_ERR_RANGE, "negative prefix_len / doc_stored_start");
+    CF_REQUIRE(seg_stride >= 2, CF_ERR_INVALID_ARG, "seg_stride must be >= 2");
+    CF_REQUIRE(pr->doc_tok_offset && pr->doc_len && pr->cand && pr->n_cand && pr->keep_idx && pr->n_keep &&
+                   pr->new_start && pr->q_start && pr->n_reuse && pr->order && pr->next_segs && pr->next_n_seg,
+               CF_ERR_INVALID_ARG, "NULL pointer in the prune step");
+    CF_REQUIRE(pr->keep_idx != pr->cand && pr->order != pr->keep_idx && pr->order != pr->cand, CF_ERR_INVALID_ARG,
+               "keep_idx, order and cand must be distinct arrays");
+    CF_REQUIRE(pr->next_segs != segs && pr->next_n_seg != n_seg && pr->q_start != q_new_start, CF_ERR_INVALID_ARG,
+               "the next layer's tables must not alias the current ones");
+    return CF_OK;
+}
+
+static cf_status prefill_impl(const cf_layer_desc* desc, const void* q, const int32_t* q_off,
                                int32_t q_stored_start, const int32_t* q_new_start, const void* k_store,
                                const void* v_store, int64_t n_store_tokens, const void* k_self,
                                const void* v_self, const cf_segment* segs, const int32_t* n_seg,
                                int32_t seg_stride, int32_t batch, int32_t max_tq, int64_t max_kv_tokens,
                                void* out, float* mass, float* score_accum, int32_t score_stride,
-                               void* workspace, size_t workspace_bytes, int32_t* dev_flag, void* stream) {
+                               void* workspace, size_t workspace_bytes, const cf_prune_step* prune,
+                               int32_t* dev_flag, void* stream) {
     cf_status st = check_desc(desc);
     if (st != CF_OK) return st;
     CF_REQUIRE(batch >= 0, CF_ERR_INVALID_ARG, "batch is negative");
@@ -108,6 +147,10 @@ cf_status cf_prefill_attention(const cf_layer_desc* desc, const void* q, const i
     CF_REQUIRE(n_store_tokens >= 0 && max_kv_tokens >= 0, CF_ERR_INVALID_ARG, "negative token count");
     CF_REQUIRE(score_accum == nullptr || score_stride >= 1, CF_ERR_INVALID_ARG,
                "score_stride must be >= 1 when score_accum is given");
+    if (prune) {
+        st = check_prune_step(prune, seg_stride, score_accum, score_stride, segs, n_seg, q_new_start);
+        if (st != CF_OK) return st;
+    }
     if (batch == 0) return CF_OK;
     CF_REQUIRE(q && q_off && q_new_start && segs && n_seg && out && mass, CF_ERR_INVALID_ARG,
                "q, q_off, q_new_start, segs, n_seg, out and mass must not be NULL");
@@ -141,8 +184,35 @@ cf_status cf_prefill_attention(const cf_layer_desc* desc, const void* q, const i
     RopeFreq f;
     fill_rope_freq(desc, &f);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (mfma_path_supported(desc)) return launch_attention_mfma(a, f, s);
-    return launch_attention_generic(a, f, s);
+    if (mfma_path_supported(desc)) return launch_attention_mfma(a, f, s, prune);
+    st = launch_attention_generic(a, f, s);
+    if (st != CF_OK || !prune) return st;
+    return launch_prune_step(a, prune, s);
+}
+
+cf_status cf_prefill_attention(const cf_layer_desc* desc, const void* q, const int32_t* q_off,
+                               int32_t q_stored_start, const int32_t* q_new_start, const void* k_store,
+                               const void* v_store, int64_t n_store_tokens, const void* k_self,
+                               const void* v_self, const cf_segment* segs, const int32_t* n_seg,
+                               int32_t seg_stride, int32_t batch, int32_t max_tq, int64_t max_kv_tokens,
+                               void* out, float* mass, float* score_accum, int32_t score_stride,
+                               void* workspace, size_t workspace_bytes, int32_t* dev_flag, void* stream) {
+    return prefill_impl(desc, q, q_off, q_stored_start, q_new_start, k_store, v_store, n_store_tokens, k_self, v_self,
+                        segs, n_seg, seg_stride, batch, max_tq, max_kv_tokens, out, mass, score_accum, score_stride,
+                        workspace, workspace_bytes, nullptr, dev_flag, stream);
+}
+
+cf_status cf_prefill_layer(const cf_layer_desc* desc, const void* q, const int32_t* q_off, int32_t q_stored_start,
+                           const int32_t* q_new_start, const void* k_store, const void* v_store,
+                           int64_t n_store_tokens, const void* k_self, const void* v_self, const cf_segment* segs,
+                           const int32_t* n_seg, int32_t seg_stride, int32_t batch, int32_t max_tq,
+                           int64_t max_kv_tokens, void* out, float* mass, float* score_accum, int32_t score_stride,
+                           void* workspace, size_t workspace_bytes, const cf_prune_step* prune, int32_t* dev_flag,
+                           void* stream) {
+    CF_REQUIRE(score_accum != nullptr, CF_ERR_INVALID_ARG, "cf_prefill_layer needs score_accum");
+    return prefill_impl(desc, q, q_off, q_stored_start, q_new_start, k_store, v_store, n_store_tokens, k_self, v_self,
+                        segs, n_seg, seg_stride, batch, max_tq, max_kv_tokens, out, mass, score_accum, score_stride,
+                        workspace, workspace_bytes, prune, dev_flag, stream);
 }
 
 cf_status cf_prune_topk(const float* score, const int32_t* len, const int32_t* cand, const int32_t* n_cand,

@@ -23,6 +23,7 @@
 #include <cstdlib>
 
 #include "cf_common.h"
+#include "cf_select_dev.h"
 
 namespace cf {
 namespace {
@@ -50,11 +51,14 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 struct Plan {
+    int row_blocks;     // 16-row blocks of the stacked rows of one kv head
     int nrb;            // 16-row blocks per wavefront (1..4)
     int rows_wg;        // 64 * nrb
     int n_rg;           // row groups per (query, kv head)
     int blocks_rg;      // 16-row blocks per row group
     int units_per_b, units, nsplit, slots, x_count, mass_chunks;
+    int tile;           // tokens per tile: 64 (shared-tile kernel) or 32 (wavefront-private tiles)
+    int sub;            // sub-splits per workgroup: 4 when every wavefront streams its own tiles, else 1
     size_t off_ml, off_opart, off_massml, off_rowstat, total;
 };
 
@@ -62,24 +66,28 @@ Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_str
     Plan p;
     const int group = n_q_heads / n_kv_heads;
     const int row_blocks = (group * max_tq + 15) / 16;
+    p.row_blocks = row_blocks;
     p.n_rg = (row_blocks + 15) / 16;
     p.blocks_rg = (row_blocks + p.n_rg - 1) / p.n_rg;
     p.nrb = (p.blocks_rg + kWaves - 1) / kWaves;
     p.rows_wg = 64 * p.nrb;
     p.units_per_b = n_kv_heads * p.n_rg;
     p.units = batch * p.units_per_b;
-    // enough workgroups to fill 256 CUs at the occupancy the register budget of this NRB allows
-    const int per_cu = p.nrb == 1 ? 2 : 1;
-    const int64_t est_tiles = max_kv_tokens / kTile + seg_stride;
-    int64_t ns = (256 * per_cu + p.units - 1) / p.units;
-    const int64_t cap = est_tiles / 2 > 1 ? est_tiles / 2 : 1;
+    // Few stacked rows (MHA-like, HBM-bound): every wavefront holds all rows and streams its own
+    // 32-token tiles.  Many rows (GQA, MFMA-bound): the wavefronts share 64-token tiles.
+    const bool small_m = row_blocks <= 4 && seg_stride <= 64;
+    p.tile = small_m ? 32 : kTile;
+    p.sub = small_m ? kWaves : 1;
+    const int64_t est_tiles = max_kv_tokens / p.tile + seg_stride;
+    int64_t ns = (256 + p.units - 1) / p.units;         // one workgroup per CU and launch wave
+    const int64_t cap = est_tiles / (2 * p.sub) > 1 ? est_tiles / (2 * p.sub) : 1;
     if (ns > cap) ns = cap;
     if (ns > kMaxSplit) ns = kMaxSplit;
     if (const char* e = std::getenv("CF_NSPLIT")) ns = std::atoi(e);     // development knob
     if (ns < 1) ns = 1;
     if (ns > kMaxSplit) ns = kMaxSplit;
     p.nsplit = (int)ns;
-    p.slots = seg_stride + p.nsplit;
+    p.slots = seg_stride + p.nsplit * p.sub;
     p.x_count = batch * n_kv_heads * p.nsplit;
     p.mass_chunks = seg_stride < kMassChunks ? seg_stride : kMassChunks;
     size_t off = 0;
@@ -111,34 +119,49 @@ struct SegTable {
     int32_t n;
 };
 
-// All threads of a workgroup call this; every workgroup of query b builds the same table.
-// The table entries are fetched for the whole stride at once, so that their loads do not wait
-// for the segment count.
-__device__ __forceinline__ void build_table(const AttnArgs& a, int b, SegTable* t, int tq_raw) {
-    const int tid = threadIdx.x;
+// Per-query scalars and this thread's segment-table entry, fetched in one batch: the entry is
+// read for the whole stride so that its load does not wait for the segment count.
+struct QueryHead {
+    int q0, tq_raw, n_seg, qdelta;
+    int64_t q_total;
     cf_segment seg;
-    const bool in_stride = tid < a.seg_stride;        // seg_stride <= kMaxSegs == kThreads
-    if (in_stride) seg = a.segs[(int64_t)b * a.seg_stride + tid];
-    int n = a.n_seg[b];
-    const int64_t q_total = a.q_off[a.batch];
-    const int qdelta = a.q_new_start[b] - a.q_stored_start;
+};
+
+__device__ __forceinline__ QueryHead load_query_head(const AttnArgs& a, int b) {   // b: wave-uniform
+    QueryHead h;
+    if ((int)threadIdx.x < a.seg_stride) h.seg = a.segs[(int64_t)b * a.seg_stride + threadIdx.x];   // seg_stride <= kMaxSegs == kThreads
+    const int q0 = a.q_off[b], q1 = a.q_off[b + 1], qt = a.q_off[a.batch], n = a.n_seg[b], qn = a.q_new_start[b];
+    asm volatile("" ::"s"(q0), "s"(q1), "s"(qt), "s"(n), "s"(qn));    // all five scalar loads are out before any is used
+    h.q0 = q0;
+    h.tq_raw = q1 - q0;
+    h.q_total = qt;
+    h.n_seg = n;
+    h.qdelta = qn - a.q_stored_start;
+    return h;
+}
+
+// All threads of a workgroup call this; every workgroup of query b builds the same table.
+__device__ __forceinline__ void build_table(const AttnArgs& a, const QueryHead& h, SegTable* t, int tile_tokens) {
+    const int tid = threadIdx.x;
+    const cf_segment& seg = h.seg;
+    int n = h.n_seg;
     if (n < 0 || n > a.seg_stride) {
         if (tid == 0) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
         n = n < 0 ? 0 : a.seg_stride;
     }
-    const int tq = min(tq_raw, a.max_tq);
-    if (in_stride && tid < n) {
+    const int tq = min(h.tq_raw, a.max_tq);
+    if (tid < n) {
         const bool self = seg.kind == CF_SEG_SELF;
-        const int64_t limit = self ? q_total : a.n_store_tokens;
+        const int64_t limit = self ? h.q_total : a.n_store_tokens;
         const bool bad = seg.kind < 0 || seg.kind > CF_SEG_SELF || seg.len < 0 || seg.tok_offset < 0 ||
                          seg.tok_offset + seg.len > limit || (self && a.k_self == nullptr);
         if (bad) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
         const int vis = bad ? 0 : (self ? min(seg.len, tq) : seg.len);
         t->tok[tid] = seg.tok_offset;
         t->vis[tid] = vis;
-        t->delta[tid] = seg.new_start - seg.stored_start - qdelta;
+        t->delta[tid] = seg.new_start - seg.stored_start - h.qdelta;
         t->self[tid] = self ? 1 : 0;
-        t->tile0[tid + 1] = (vis + kTile - 1) / kTile;
+        t->tile0[tid + 1] = (vis + tile_tokens - 1) / tile_tokens;
     }
     if (tid == 0) { t->n = n; t->tile0[0] = 0; }
     __syncthreads();
@@ -209,6 +232,16 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
                        (size_t)(p.x_count * p.n_rg + p.units * p.nrb * 4 + a.batch * p.mass_chunks) * 16 + (size_t)blockIdx.x * 16;
 #endif
     CF_STAMP(0);
+    // Pull every pointer and scalar the streaming loop needs out of the kernel-argument segment
+    // now, in one batch of scalar loads, instead of one dependent round trip per first use.
+    {
+        const void *p0 = a.q, *p1 = a.q_off, *p2 = a.q_new_start, *p3 = a.k_store, *p4 = a.v_store, *p5 = a.k_self,
+                   *p6 = a.v_self, *p7 = a.segs, *p8 = a.n_seg, *p9 = a.workspace;
+        asm volatile("" ::"s"(p0), "s"(p1), "s"(p2), "s"(p3), "s"(p4), "s"(p5), "s"(p6), "s"(p7), "s"(p8), "s"(p9));
+        asm volatile("" ::"s"(a.n_store_tokens), "s"(a.seg_stride), "s"(a.batch), "s"(a.max_tq), "s"(a.n_q_heads),
+                     "s"(a.n_kv_heads), "s"(a.scale_log2e), "s"(a.q_stored_start), "s"(p.nsplit), "s"(p.slots),
+                     "s"(p.off_ml), "s"(p.off_opart), "s"(p.off_massml));
+    }
 
     // block -> (row group, query, kv head, split); workgroups that read the same K/V tiles differ
     // by a multiple of x_count
@@ -217,16 +250,16 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
     const int x = bid - rg * p.x_count;
     const int split = x % p.nsplit;
     const int hkv = (x / p.nsplit) % a.n_kv_heads;
-    const int b = x / (p.nsplit * a.n_kv_heads);
+    const int b = __builtin_amdgcn_readfirstlane(x / (p.nsplit * a.n_kv_heads));
     const int unit = (b * a.n_kv_heads + hkv) * p.n_rg + rg;
 
     const int hq = a.n_q_heads;
     const int group = hq / a.n_kv_heads;
-    const int q0 = a.q_off[b];
-    const int tq_raw = a.q_off[b + 1] - q0;
+    const QueryHead qh = load_query_head(a, b);
     const double my_freq = freq.rev[tid & (kHalf - 1)];
+    const int q0 = qh.q0, tq_raw = qh.tq_raw;
 
-    build_table(a, b, &tbl, tq_raw);
+    build_table(a, qh, &tbl, kTile);
     CF_STAMP(1);
 
     const int tq = min(tq_raw, a.max_tq);
@@ -274,7 +307,8 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int tok = 4 * vq + i;
-            r.v[i] = tok < d.ntok ? *reinterpret_cast<const uint4*>(vb + base + tok * kv_row + 8 * vj) : zero;
+            if (tok < d.ntok) r.v[i] = *reinterpret_cast<const uint4*>(vb + base + tok * kv_row + 8 * vj);
+            else r.v[i] = zero;
         }
     };
     int s_next = 0;
@@ -501,6 +535,422 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
     CF_STAMP(4);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Small-M variant (at most 64 stacked query rows per kv head and at most 64 segments per query:
+// MHA and short queries; HBM-bound).  Every wavefront holds all NRB 16-row blocks and is an
+// independent worker over its own run of 32-token tiles (sub-split):
+//   * the segment table lives in registers, one segment per lane (prefix by a wavefront scan,
+//     lookup by ballot), so the prologue has no workgroup barrier and no LDS round trips;
+//   * two tiles are in flight in registers; K is rotated and staged, V staged transposed, in the
+//     wavefront's private slice of LDS, so the streaming loop has no workgroup barrier either
+//     and every K/V byte is read from LDS once;
+//   * Q fragments are read from a shared LDS copy (they would not fit in registers next to two
+//     tiles in flight);
+//   * the four sub-splits of a workgroup are merged through LDS at the end, so one partial
+//     result per workgroup goes to memory.
+constexpr int kTileS = 32;
+constexpr int kSVs = 40;                               // LDS row stride of a staged 32-token V^T tile, elements
+constexpr int kKBytesS = kTileS * kSK * 2;             // 8704
+constexpr int kVBytesS = kD * kSVs * 2;                // 10240
+constexpr int kStageBytesS = kKBytesS + kVBytesS;      // per wavefront
+constexpr int kMaxSegsS = 64;
+
+// cos/sin of delta*theta from the hardware sine/cosine (argument in revolutions, reduced in fp64):
+// their absolute error is far below the rounding step of the 16-bit keys this feeds.
+__device__ __forceinline__ float2 rope_cos_sin_fast(int delta, double theta_rev) {
+    const double x = (double)delta * theta_rev;
+    const float fr = (float)(x - rint(x));
+    return make_float2(__builtin_amdgcn_cosf(fr), __builtin_amdgcn_sinf(fr));
+}
+
+template <int DT, int NRB>
+__global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFreq freq, Plan p) {
+    __shared__ __attribute__((aligned(16))) unsigned char stage_all[kWaves * kStageBytesS];
+    __shared__ __attribute__((aligned(16))) uint16_t q_lds[64 * kSK];
+    __shared__ __attribute__((aligned(16))) float2 cs_all[kWaves][kHalf];
+    __shared__ float2 ml_w[kWaves][64];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const int li = lane & 15, lg = lane >> 4;
+#ifdef CF_TRACE
+    long long* trace = reinterpret_cast<long long*>(static_cast<char*>(a.workspace) + p.total) -
+                       (size_t)(p.x_count * p.n_rg + p.units * p.nrb * 4 + a.batch * p.mass_chunks) * 16 + (size_t)blockIdx.x * 16;
+#endif
+    CF_STAMP(0);
+    // Pull every pointer and scalar the streaming loop needs out of the kernel-argument segment
+    // now, in one batch of scalar loads, instead of one dependent round trip per first use.
+    {
+        const void *p0 = a.q, *p1 = a.q_off, *p2 = a.q_new_start, *p3 = a.k_store, *p4 = a.v_store, *p5 = a.k_self,
+                   *p6 = a.v_self, *p7 = a.segs, *p8 = a.n_seg, *p9 = a.workspace;
+        asm volatile("" ::"s"(p0), "s"(p1), "s"(p2), "s"(p3), "s"(p4), "s"(p5), "s"(p6), "s"(p7), "s"(p8), "s"(p9));
+        asm volatile("" ::"s"(a.n_store_tokens), "s"(a.seg_stride), "s"(a.batch), "s"(a.max_tq), "s"(a.n_q_heads),
+                     "s"(a.n_kv_heads), "s"(a.scale_log2e), "s"(a.q_stored_start), "s"(p.nsplit), "s"(p.slots),
+                     "s"(p.off_ml), "s"(p.off_opart), "s"(p.off_massml));
+    }
+
+    const int bid = blockIdx.x;                      // n_rg == 1: unit = (query, kv head)
+    const int split = bid % p.nsplit;
+    const int unit = bid / p.nsplit;
+    const int hkv = unit % a.n_kv_heads;
+    const int b = __builtin_amdgcn_readfirstlane(unit / a.n_kv_heads);
+    const int hq = a.n_q_heads;
+    const int group = hq / a.n_kv_heads;
+
+    // ---- per-query scalars and the segment table: lane s of every wavefront holds segment s
+    cf_segment seg;
+    seg.tok_offset = 0; seg.len = 0; seg.stored_start = 0; seg.new_start = 0; seg.kind = CF_SEG_DOC; seg.doc = -1; seg.reserved = 0;
+    if (lane < a.seg_stride) seg = a.segs[(int64_t)b * a.seg_stride + lane];      // seg_stride <= 64
+    const int q0 = a.q_off[b], q1 = a.q_off[b + 1], n_raw = a.n_seg[b], qn = a.q_new_start[b];
+    const int64_t q_total = a.q_off[a.batch];
+    asm volatile("" ::"s"(q0), "s"(q1), "s"(n_raw), "s"(qn));
+    const double my_freq = freq.rev[lane];
+    const int tq = min(q1 - q0, a.max_tq);
+    const int n_rows = group * tq;
+    int n_seg = n_raw;
+    if (n_seg < 0 || n_seg > a.seg_stride) {
+        if (tid == 0) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
+        n_seg = n_seg < 0 ? 0 : a.seg_stride;
+    }
+    const bool t_self = seg.kind == CF_SEG_SELF;
+    int t_vis = 0;
+    if (lane < n_seg) {
+        const int64_t limit = t_self ? q_total : a.n_store_tokens;
+        const bool bad = seg.kind < 0 || seg.kind > CF_SEG_SELF || seg.len < 0 || seg.tok_offset < 0 ||
+                         seg.tok_offset + seg.len > limit || (t_self && a.k_self == nullptr);
+        if (bad && wave == 0) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
+        t_vis = bad ? 0 : (t_self ? min(seg.len, tq) : seg.len);
+    }
+    const int t_delta = seg.new_start - seg.stored_start - (qn - a.q_stored_start);
+    const int t_cnt = (t_vis + kTileS - 1) / kTileS;
+    int t_incl = t_cnt;                              // inclusive prefix of tile counts over the lanes
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int u = __shfl_up(t_incl, o);
+        if (lane >= o) t_incl += u;
+    }
+    const unsigned total = (unsigned)__builtin_amdgcn_readlane(t_incl, kWave - 1);
+    const int t_tok_lo = (int)(uint32_t)seg.tok_offset, t_tok_hi = (int)(seg.tok_offset >> 32);
+    CF_STAMP(1);
+
+    const unsigned nsub = (unsigned)(p.nsplit * kWaves);
+    const int ss = split * kWaves + wave;            // this wavefront's sub-split
+    const int t_begin = split_begin(total, nsub, ss);
+    const int t_end = split_begin(total, nsub, ss + 1);
+
+    const int64_t kv_row = (int64_t)a.n_kv_heads * kD;
+    // staging (per wavefront): K items (tokens kt + 8*it, slices 8*kj..), V items (quads vq + 4*it, channels 8*vj..)
+    const int kt = lane >> 3, kj = lane & 7;
+    const int vq = lane >> 4, vj = lane & 15;
+    struct StageRegs { uint4 ka[4], kb[4], v[2][4]; };
+    struct Tile { int seg, tok0, ntok, delta, self; };
+    StageRegs regs0, regs1;
+
+    int next_tile = t_begin;
+    auto fetch = [&](Tile& d, StageRegs& r) {        // ntok == 0 marks "no tile"
+        if (next_tile >= t_end) { d.ntok = 0; return; }
+        // the segment that owns this tile: first lane whose inclusive prefix exceeds it
+        const unsigned long long m = __ballot(t_incl > next_tile);
+        const int s = __builtin_ctzll(m);
+        const int incl = __builtin_amdgcn_readlane(t_incl, s), cnt = __builtin_amdgcn_readlane(t_cnt, s);
+        d.seg = s;
+        d.tok0 = (next_tile - (incl - cnt)) * kTileS;
+        d.ntok = min(kTileS, __builtin_amdgcn_readlane(t_vis, s) - d.tok0);
+        d.delta = __builtin_amdgcn_readlane(t_delta, s);
+        d.self = __builtin_amdgcn_readlane((int)t_self, s);
+        const int64_t tok = ((int64_t)__builtin_amdgcn_readlane(t_tok_hi, s) << 32) | (uint32_t)__builtin_amdgcn_readlane(t_tok_lo, s);
+        ++next_tile;
+        const uint16_t* kb = static_cast<const uint16_t*>(d.self ? a.k_self : a.k_store);
+        const uint16_t* vb = static_cast<const uint16_t*>(d.self ? a.v_self : a.v_store);
+        const int64_t base = (tok + d.tok0) * kv_row + (int64_t)hkv * kD;
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int t = kt + 8 * it;
+            if (t < d.ntok) {
+                const uint16_t* pk = kb + base + t * kv_row + 8 * kj;
+                r.ka[it] = *reinterpret_cast<const uint4*>(pk);
+                r.kb[it] = *reinterpret_cast<const uint4*>(pk + kHalf);
+            } else {
+                r.ka[it] = zero;
+                r.kb[it] = zero;
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < 2; ++it)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int t = 4 * (vq + 4 * it) + i;
+                if (t < d.ntok) r.v[it][i] = *reinterpret_cast<const uint4*>(vb + base + t * kv_row + 8 * vj);
+                else r.v[it][i] = zero;
+            }
+    };
+    Tile d0, d1;
+    d0.seg = d1.seg = 0; d0.tok0 = d1.tok0 = 0; d0.ntok = d1.ntok = 0; d0.delta = d1.delta = 0; d0.self = d1.self = 0;
+    constexpr bool kTwo = NRB <= 3;                  // 64 rows leave no registers for a second tile in flight
+    fetch(d0, regs0);                                // the loads go out before anything else
+    if (kTwo) fetch(d1, regs1);
+    CF_STAMP(5);
+
+    // ---- Q rows of this kv head into LDS: row m = g*tq + t of the stack is q[q0 + t][hkv*group + g]
+    {
+        const int row = tid >> 2, part = tid & 3;    // 64 rows x 4 quarters of 64 bytes
+        uint4 qv[4];
+        const bool valid = row < n_rows && row < NRB * 16;
+        const int gi = valid ? row / tq : 0;
+        const int t = valid ? row - gi * tq : 0;
+        const uint16_t* qp = static_cast<const uint16_t*>(a.q) + (((int64_t)q0 + t) * hq + hkv * group + gi) * kD + 32 * part;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qv[i] = valid ? *reinterpret_cast<const uint4*>(qp + 8 * i) : make_uint4(0, 0, 0, 0);
+        if (row < NRB * 16) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(q_lds + row * kSK + 32 * part + 8 * i) = qv[i];
+        }
+    }
+    int trow[NRB];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        const int m = rb * 16 + li;
+        trow[rb] = m < n_rows ? m % tq : 0x7fffffff;  // padding rows: nothing to mask, results unused
+    }
+
+    unsigned char* stage = stage_all + wave * kStageBytesS;
+    uint16_t* k_lds = reinterpret_cast<uint16_t*>(stage);
+    uint16_t* v_lds = reinterpret_cast<uint16_t*>(stage + kKBytesS);
+    float2* cs = cs_all[wave];
+
+    f32x4 acc[NRB][8];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int db = 0; db < 8; ++db) acc[rb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run[NRB], l_run[NRB], seg_l[NRB];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) { m_run[rb] = -INFINITY; l_run[rb] = 0.f; seg_l[rb] = 0.f; }
+
+    char* ws = static_cast<char*>(a.workspace);
+    float2* massml = reinterpret_cast<float2*>(ws + p.off_massml) + (int64_t)unit * p.slots * 64;
+    auto emit = [&](int s) {                        // (running max, segment sum) per row for segment s
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            float tot = seg_l[rb] + __shfl_xor(seg_l[rb], 16);
+            tot += __shfl_xor(tot, 32);
+            if (lg == 0) massml[(int64_t)(s + ss) * 64 + rb * 16 + li] = make_float2(m_run[rb], tot);
+        }
+    };
+    __syncthreads();                                 // Q rows are in LDS
+    CF_STAMP(6);
+
+    int cur_seg = -1;
+    bool first = true;
+    // One tile: rotate and stage `cur` from its registers, refill those registers with the tile after
+    // next, then do the math of `cur` out of LDS.
+    auto step = [&](Tile& cur, StageRegs& r) {
+        const Tile cd = cur;
+        if (cd.seg != cur_seg) {
+            if (cur_seg >= 0) emit(cur_seg);
+            cur_seg = cd.seg;
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb) seg_l[rb] = 0.f;
+            if (cd.delta != 0) {                       // lane m prepares cos/sin of slice m for the whole wavefront
+                __builtin_amdgcn_wave_barrier();
+                cs[lane] = rope_cos_sin_fast(cd.delta, my_freq);
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+        if (first) CF_STAMP(7);
+        // ---- stage K: rotate pairs (c, c + 64), round once, write [token][c]
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            uint4 ra = r.ka[it], rb4 = r.kb[it];
+            if (cd.delta != 0) {
+                uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb4.x, rb4.y, rb4.z, rb4.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float a0 = Mma<DT>::lo(wa[i]), a1 = Mma<DT>::hi(wa[i]);
+                    const float b0 = Mma<DT>::lo(wb[i]), b1 = Mma<DT>::hi(wb[i]);
+                    const float2 w0 = cs[8 * kj + 2 * i], w1 = cs[8 * kj + 2 * i + 1];
+                    wa[i] = Mma<DT>::pack(a0 * w0.x - b0 * w0.y, a1 * w1.x - b1 * w1.y);
+                    wb[i] = Mma<DT>::pack(a0 * w0.y + b0 * w0.x, a1 * w1.y + b1 * w1.x);
+                }
+                ra = make_uint4(wa[0], wa[1], wa[2], wa[3]);
+                rb4 = make_uint4(wb[0], wb[1], wb[2], wb[3]);
+            }
+            uint16_t* dst = k_lds + (kt + 8 * it) * kSK + 8 * kj;
+            *reinterpret_cast<uint4*>(dst) = ra;
+            *reinterpret_cast<uint4*>(dst + kHalf) = rb4;
+        }
+        // ---- stage V transposed: [channel][token]; the 8 tokens of MFMA k-group g — {4g..4g+3} and
+        // {16+4g..16+4g+3} — sit side by side
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int tk = 4 * (vq + 4 * it);
+            const int pos = ((tk & 15) >> 2) * 8 + (tk >> 4) * 4;
+            const uint32_t x0[4] = {r.v[it][0].x, r.v[it][0].y, r.v[it][0].z, r.v[it][0].w};
+            const uint32_t x1[4] = {r.v[it][1].x, r.v[it][1].y, r.v[it][1].z, r.v[it][1].w};
+            const uint32_t x2[4] = {r.v[it][2].x, r.v[it][2].y, r.v[it][2].z, r.v[it][2].w};
+            const uint32_t x3[4] = {r.v[it][3].x, r.v[it][3].y, r.v[it][3].z, r.v[it][3].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint2 lo, hi;
+                lo.x = __builtin_amdgcn_perm(x1[i], x0[i], 0x05040100u);
+                lo.y = __builtin_amdgcn_perm(x3[i], x2[i], 0x05040100u);
+                hi.x = __builtin_amdgcn_perm(x1[i], x0[i], 0x07060302u);
+                hi.y = __builtin_amdgcn_perm(x3[i], x2[i], 0x07060302u);
+                *reinterpret_cast<uint2*>(v_lds + (8 * vj + 2 * i) * kSVs + pos) = lo;
+                *reinterpret_cast<uint2*>(v_lds + (8 * vj + 2 * i + 1) * kSVs + pos) = hi;
+            }
+        }
+        fetch(cur, r);                               // these registers are free again
+        __builtin_amdgcn_wave_barrier();
+        if (first) { CF_STAMP(2); first = false; }
+
+        const bool causal = cd.self != 0;
+        const int nt = cd.ntok;
+        // ---- S^T = K Q^T : lane (li, lg) gets, for query row li, tokens 16*tb + 4*lg + r
+        f32x4 sc[NRB][2];
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) { sc[rb][0] = f32x4{0.f, 0.f, 0.f, 0.f}; sc[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const uint4 k0 = *reinterpret_cast<const uint4*>(k_lds + li * kSK + 32 * kk + 8 * lg);
+            const uint4 k1 = *reinterpret_cast<const uint4*>(k_lds + (16 + li) * kSK + 32 * kk + 8 * lg);
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb) {
+                const uint4 qv = *reinterpret_cast<const uint4*>(q_lds + (16 * rb + li) * kSK + 32 * kk + 8 * lg);
+                sc[rb][0] = Mma<DT>::run(k0, qv, sc[rb][0]);
+                sc[rb][1] = Mma<DT>::run(k1, qv, sc[rb][1]);
+            }
+        }
+        // ---- online softmax (exp2 domain), fp32
+        const bool need_mask = causal || nt < kTileS;
+        uint4 pfrag[NRB];
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            float xv[8];
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) xv[4 * tb + e] = sc[rb][tb][e];
+            if (need_mask) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int tk = 16 * (e >> 2) + 4 * lg + (e & 3);
+                    const bool ok = tk < nt && (!causal || cd.tok0 + tk <= trow[rb]);
+                    xv[e] = ok ? xv[e] : -INFINITY;
+                }
+            }
+            float mloc = fmaxf(fmaxf(fmaxf(xv[0], xv[1]), fmaxf(xv[2], xv[3])), fmaxf(fmaxf(xv[4], xv[5]), fmaxf(xv[6], xv[7])));
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+            mloc *= a.scale_log2e;                       // scale > 0: max commutes with it
+            const float m_old = m_run[rb];
+            const float m_new = fmaxf(m_old, mloc);
+            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_old - m_safe);
+            float lsum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                xv[e] = __builtin_amdgcn_exp2f(fmaf(xv[e], a.scale_log2e, -m_safe));
+                lsum += xv[e];
+            }
+            l_run[rb] = l_run[rb] * alpha + lsum;
+            seg_l[rb] = seg_l[rb] * alpha + lsum;
+            m_run[rb] = m_new;
+            if (__any(alpha != 1.f && m_old != -INFINITY)) {     // nothing accumulated yet: nothing to rescale
+#pragma unroll
+                for (int db = 0; db < 8; ++db) acc[rb][db] *= alpha;
+            }
+            pfrag[rb] = make_uint4(Mma<DT>::pack(xv[0], xv[1]), Mma<DT>::pack(xv[2], xv[3]),
+                                   Mma<DT>::pack(xv[4], xv[5]), Mma<DT>::pack(xv[6], xv[7]));
+        }
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+            const uint4 va = *reinterpret_cast<const uint4*>(v_lds + (16 * db + li) * kSVs + 8 * lg);
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb) acc[rb][db] = Mma<DT>::run(va, pfrag[rb], acc[rb][db]);
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+    if (kTwo) {
+        while (d0.ntok > 0) {
+            step(d0, regs0);
+            if (d1.ntok <= 0) break;
+            step(d1, regs1);
+        }
+    } else {
+        while (d0.ntok > 0) step(d0, regs0);
+    }
+    if (cur_seg >= 0) emit(cur_seg);
+    CF_STAMP(3);
+
+    // ---- merge the four sub-splits of this workgroup (same rows, different tokens) through LDS
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        float tot = l_run[rb] + __shfl_xor(l_run[rb], 16);
+        tot += __shfl_xor(tot, 32);
+        if (lg == 0) ml_w[wave][rb * 16 + li] = make_float2(m_run[rb], tot);
+    }
+    __syncthreads();                                 // also: every wavefront is done with its staging slice
+    float mx[NRB], zz[NRB];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        const int row = rb * 16 + li;
+        float m = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) m = fmaxf(m, ml_w[w][row].x);
+        const float ms = m == -INFINITY ? 0.f : m;
+        float z = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) z += ml_w[w][row].y * exp2f(ml_w[w][row].x - ms);
+        mx[rb] = m;
+        zz[rb] = z;
+        const float f = exp2f(m_run[rb] - ms);
+#pragma unroll
+        for (int db = 0; db < 8; ++db) acc[rb][db] *= f;
+    }
+    f32x4* red = reinterpret_cast<f32x4*>(stage_all);            // 2 slots of NRB*8*64 float4 (<= 64 KB)
+    auto put = [&](int slot) {
+        f32x4* dst = red + slot * NRB * 8 * kWave + lane;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+            for (int db = 0; db < 8; ++db) dst[(rb * 8 + db) * kWave] = acc[rb][db];
+    };
+    auto add = [&](int slot) {
+        const f32x4* src = red + slot * NRB * 8 * kWave + lane;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+            for (int db = 0; db < 8; ++db) acc[rb][db] += src[(rb * 8 + db) * kWave];
+    };
+    if (wave >= 2) put(wave - 2);
+    __syncthreads();
+    if (wave < 2) add(wave);
+    __syncthreads();
+    if (wave == 1) put(0);
+    __syncthreads();
+    if (wave == 0) {
+        add(0);
+        // partial result of this workgroup, same format as the shared-tile kernel with one row block per wavefront
+        f32x4* opart = reinterpret_cast<f32x4*>(ws + p.off_opart) + ((int64_t)unit * p.nsplit + split) * 4 * 8 * kWave + lane;
+        float2* ml = reinterpret_cast<float2*>(ws + p.off_ml) + ((int64_t)unit * p.nsplit + split) * 64;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+#pragma unroll
+            for (int db = 0; db < 8; ++db) opart[(rb * 8 + db) * kWave] = acc[rb][db];
+            if (lg == 0) ml[rb * 16 + li] = make_float2(mx[rb], zz[rb]);
+        }
+        if (NRB < 4 && lg == 0) {                    // row blocks that do not exist: neutral statistics
+#pragma unroll
+            for (int rb = NRB; rb < 4; ++rb) ml[rb * 16 + li] = make_float2(-INFINITY, 0.f);
+        }
+    }
+    CF_STAMP(4);
+}
+
 // Second kernel: one workgroup per (unit, 64-row pass, quarter of the output channels) merges the
 // splits' partial outputs, writes its output rows and leaves (max, 1/sum) per row for the mass kernel.
 template <int DT>
@@ -592,10 +1042,10 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p)
                        (size_t)(a.batch * p.mass_chunks) * 16 + (size_t)blockIdx.x * 16;
 #endif
     CF_STAMP(0);
-    const int b = blockIdx.x / p.mass_chunks;
+    const int b = __builtin_amdgcn_readfirstlane(blockIdx.x / p.mass_chunks);
     const int chunk = blockIdx.x % p.mass_chunks;
-    const int q0 = a.q_off[b];
-    const int tq_raw = a.q_off[b + 1] - q0;
+    const QueryHead qh = load_query_head(a, b);
+    const int tq_raw = qh.tq_raw;
     const float2* rs_b = reinterpret_cast<const float2*>(ws + p.off_rowstat) + (int64_t)b * p.units_per_b * p.rows_wg;
     const float2* mm_b = reinterpret_cast<const float2*>(ws + p.off_massml) + (int64_t)b * p.units_per_b * p.slots * p.rows_wg;
     const int units_per_pass = kStatRows / p.rows_wg;            // rows_wg <= 256
@@ -609,10 +1059,11 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p)
             pre[j] = idx < nu * p.rows_wg ? rs_b[idx] : make_float2(0.f, 0.f);
         }
     }
-    build_table(a, b, &tbl, tq_raw);
+    build_table(a, qh, &tbl, p.tile);
     const int tq = min(tq_raw, a.max_tq);
     const int n_rows = group * tq;
     const unsigned total = (unsigned)tbl.tile0[tbl.n];
+    const unsigned nsub = (unsigned)(p.nsplit * p.sub);
     for (int i = tid; i < kMaxSegs; i += kThreads) segtot[i] = 0.f;
 
     for (int u0 = 0; u0 < p.units_per_b; u0 += units_per_pass) {
@@ -629,17 +1080,19 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p)
         for (int s = chunk; s < tbl.n; s += p.mass_chunks, ++k) {
             const int ts = tbl.tile0[s], te = tbl.tile0[s + 1];
             if (te <= ts) continue;
-            const int s0 = split_of(total, p.nsplit, ts), s1 = split_of(total, p.nsplit, te - 1);
+            const int s0 = split_of(total, nsub, ts), s1 = split_of(total, nsub, te - 1);
             float c = 0.f;
-            for (int idx = tid; idx < nu * p.rows_wg; idx += kThreads) {
-                const int ul = idx / p.rows_wg, r = idx % p.rows_wg;
-                const int rg = (u0 + ul) % p.n_rg;
-                const int rows_here = min(p.blocks_rg * 16, n_rows - rg * p.blocks_rg * 16);
-                if (r < rows_here) {
-                    const float2 st = stat[idx];
-                    const float2* src = mm_b + ((int64_t)(u0 + ul) * p.slots + s) * p.rows_wg + r;
-                    for (int sp = s0; sp <= s1; ++sp) {
-                        const float2 v = src[(int64_t)sp * p.rows_wg];
+            for (int sp = s0; sp <= s1; ++sp) {
+                // a sub-split between the first and the last may own no tile at all (fewer tiles than
+                // sub-splits): its slot was not written by this call
+                if (split_begin(total, nsub, sp) >= split_begin(total, nsub, sp + 1)) continue;
+                for (int idx = tid; idx < nu * p.rows_wg; idx += kThreads) {
+                    const int ul = idx / p.rows_wg, r = idx % p.rows_wg;
+                    const int rg = (u0 + ul) % p.n_rg;
+                    const int rows_here = min(p.blocks_rg * 16, n_rows - rg * p.blocks_rg * 16);
+                    if (r < rows_here) {
+                        const float2 st = stat[idx];
+                        const float2 v = mm_b[((int64_t)(u0 + ul) * p.slots + s + sp) * p.rows_wg + r];
                         c += v.y * exp2f(v.x - st.x) * st.y;
                     }
                 }
@@ -665,6 +1118,127 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p)
     CF_STAMP(1);
 }
 
+// Fused layer epilogue (third kernel of cf_prefill_layer): one workgroup per query computes the
+// attention mass of every segment (wavefront w owns segments w, w + #wavefronts, ...; fixed
+// summation order), adds it to the accumulated scores, and — when a prune step is attached —
+// ranks the candidates, allocates the survivors' positions and writes the next layer's segment
+// table, i.e. Alg. 2's "S += s; ids_sort = argsort(S); ids = prun(ids_sort)" followed by the
+// allocation of Sec. 2.5, without leaving the GPU.
+constexpr int kEpiThreads = 1024;
+
+struct PruneArgs {
+    int32_t enabled, keep, strategy, force_n_reuse, normalise_by_len, stride, pos_begin, pos_end, prefix_len,
+        doc_stored_start;
+    const int64_t* doc_tok_offset;
+    const int32_t* doc_len;
+    const int32_t* cand;
+    const int32_t* n_cand;
+    int32_t* keep_idx;
+    int32_t* n_keep;
+    int32_t* new_start;
+    int32_t* q_start;
+    int32_t* n_reuse;
+    int32_t* order;
+    cf_segment* next_segs;
+    int32_t* next_n_seg;
+};
+
+__global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a, Plan p, PruneArgs pr) {
+    extern __shared__ unsigned char dyn_smem[];          // 3*stride words for the ranking / allocation
+    __shared__ float2 stat[kStatRows];
+    __shared__ SegTable tbl;
+    __shared__ float segtot[kMaxSegs];
+    __shared__ int s_int[4];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const int n_waves = kEpiThreads / kWave;
+    const char* ws = static_cast<const char*>(a.workspace);
+    const int group = a.n_q_heads / a.n_kv_heads;
+    const int b = __builtin_amdgcn_readfirstlane(blockIdx.x);
+    const QueryHead qh = load_query_head(a, b);
+    const float2* rs_b = reinterpret_cast<const float2*>(ws + p.off_rowstat) + (int64_t)b * p.units_per_b * p.rows_wg;
+    const float2* mm_b = reinterpret_cast<const float2*>(ws + p.off_massml) + (int64_t)b * p.units_per_b * p.slots * p.rows_wg;
+    const int units_per_pass = kStatRows / p.rows_wg;
+    float2 pre[kStatRows / kEpiThreads];
+    {
+        const int nu = min(units_per_pass, p.units_per_b);
+#pragma unroll
+        for (int j = 0; j < kStatRows / kEpiThreads; ++j) {
+            const int idx = tid + j * kEpiThreads;
+            pre[j] = idx < nu * p.rows_wg ? rs_b[idx] : make_float2(0.f, 0.f);
+        }
+    }
+    build_table(a, qh, &tbl, p.tile);
+    const int tq = min(qh.tq_raw, a.max_tq);
+    const int n_rows = group * tq;
+    const unsigned total = (unsigned)tbl.tile0[tbl.n];
+    const unsigned nsub = (unsigned)(p.nsplit * p.sub);
+    for (int i = tid; i < kMaxSegs; i += kEpiThreads) segtot[i] = 0.f;
+
+    for (int u0 = 0; u0 < p.units_per_b; u0 += units_per_pass) {
+        const int nu = min(units_per_pass, p.units_per_b - u0);
+        __syncthreads();
+        if (u0 == 0) {
+#pragma unroll
+            for (int j = 0; j < kStatRows / kEpiThreads; ++j) stat[tid + j * kEpiThreads] = pre[j];
+        } else {
+            for (int idx = tid; idx < nu * p.rows_wg; idx += kEpiThreads) stat[idx] = rs_b[(int64_t)u0 * p.rows_wg + idx];
+        }
+        __syncthreads();
+        for (int s = wave; s < tbl.n; s += n_waves) {
+            const int ts = tbl.tile0[s], te = tbl.tile0[s + 1];
+            if (te <= ts) continue;
+            const int s0 = split_of(total, nsub, ts), s1 = split_of(total, nsub, te - 1);
+            float c = 0.f;
+            for (int sp = s0; sp <= s1; ++sp) {
+                // a sub-split between the first and the last may own no tile at all (fewer tiles than
+                // sub-splits): its slot was not written by this call
+                if (split_begin(total, nsub, sp) >= split_begin(total, nsub, sp + 1)) continue;
+                for (int idx = lane; idx < nu * p.rows_wg; idx += kWave) {
+                    const int ul = idx / p.rows_wg, r = idx % p.rows_wg;
+                    const int rg = (u0 + ul) % p.n_rg;
+                    const int rows_here = min(p.blocks_rg * 16, n_rows - rg * p.blocks_rg * 16);
+                    if (r < rows_here) {
+                        const float2 st = stat[idx];
+                        const float2 v = mm_b[((int64_t)(u0 + ul) * p.slots + s + sp) * p.rows_wg + r];
+                        c += v.y * exp2f(v.x - st.x) * st.y;
+                    }
+                }
+            }
+            c = wave_sum(c);
+            if (lane == 0) segtot[s] += c;               // this wavefront is the only writer of segtot[s]
+        }
+    }
+    __syncthreads();
+    for (int s = tid; s < tbl.n; s += kEpiThreads) {
+        const float m = segtot[s];
+        a.mass[(int64_t)b * a.seg_stride + s] = m;
+        const int doc = a.segs[(int64_t)b * a.seg_stride + s].doc;
+        if (a.score_accum && doc >= 0 && doc < a.score_stride)
+            atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], m);
+    }
+    if (!pr.enabled) return;
+    __threadfence_block();
+    __syncthreads();
+    const int64_t off = (int64_t)b * pr.stride;
+    const int k = prune_topk_block(a.score_accum + (int64_t)b * a.score_stride, pr.normalise_by_len ? pr.doc_len + off : nullptr,
+                                   pr.cand + off, pr.n_cand[b], pr.keep, pr.stride, pr.keep_idx + off, a.dev_flag, dyn_smem,
+                                   &s_int[3]);
+    if (tid == 0) pr.n_keep[b] = k;
+    __threadfence_block();
+    __syncthreads();
+    assign_positions_block(pr.doc_len + off, pr.keep_idx + off, k, pr.stride, pr.pos_begin, pr.pos_end, pr.strategy,
+                           pr.force_n_reuse, pr.new_start + off, pr.q_start + b, pr.n_reuse + b, pr.order + off, a.dev_flag,
+                           dyn_smem, s_int);
+    __threadfence_block();
+    __syncthreads();
+    gather_segments_block(pr.doc_tok_offset + off, pr.doc_len + off, pr.order + off, k, pr.new_start + off, pr.q_start[b],
+                          qh.q0, qh.q0 + qh.tq_raw, pr.stride, pr.prefix_len, pr.doc_stored_start, a.q_stored_start,
+                          pr.next_segs + (int64_t)b * a.seg_stride, pr.next_n_seg + b, a.seg_stride, a.dev_flag);
+}
+
 }  // namespace
 
 bool mfma_path_supported(const cf_layer_desc* d) {
@@ -681,27 +1255,51 @@ size_t mfma_workspace_bytes(const cf_layer_desc* d, int32_t batch, int32_t max_t
     return p.total;
 }
 
-cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_t s) {
-    if (!mfma_shape_ok(a.seg_stride)) return launch_attention_generic(a, f, s);
+cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_t s, const cf_prune_step* prune) {
+    if (!mfma_shape_ok(a.seg_stride)) {
+        cf_status st = launch_attention_generic(a, f, s);
+        return st != CF_OK || !prune ? st : launch_prune_step(a, prune, s);
+    }
     const int phases = profile_phases();
     const Plan p = make_plan(a.n_q_heads, a.n_kv_heads, a.batch, a.max_tq, a.seg_stride, a.max_kv_tokens);
     const dim3 grid((unsigned)(p.x_count * p.n_rg)), block(kThreads);
     const dim3 grid2((unsigned)(p.units * p.nrb * 4)), grid3((unsigned)(a.batch * p.mass_chunks));
 #define CF_LAUNCH(DT, N) hipLaunchKernelGGL((attn_mfma_kernel<DT, N>), grid, block, 0, s, a, f, p)
+#define CF_LAUNCH_S(DT, N) hipLaunchKernelGGL((attn_small_kernel<DT, N>), grid, block, 0, s, a, f, p)
 #define CF_LAUNCH_DT(DT)                                   \
-    if (phases & 1) switch (p.nrb) {                       \
+    if ((phases & 1) && p.sub == 1) switch (p.nrb) {       \
         case 1: CF_LAUNCH(DT, 1); break;                   \
         case 2: CF_LAUNCH(DT, 2); break;                   \
         case 3: CF_LAUNCH(DT, 3); break;                   \
         default: CF_LAUNCH(DT, 4); break;                  \
     }                                                      \
+    if ((phases & 1) && p.sub != 1) switch (p.row_blocks) {\
+        case 1: CF_LAUNCH_S(DT, 1); break;                 \
+        case 2: CF_LAUNCH_S(DT, 2); break;                 \
+        case 3: CF_LAUNCH_S(DT, 3); break;                 \
+        default: CF_LAUNCH_S(DT, 4); break;                \
+    }                                                      \
     CF_HIP(hipGetLastError());                             \
     if (phases & 2) hipLaunchKernelGGL((attn_combine_kernel<DT>), grid2, block, 0, s, a, p);
     if (a.dtype == CF_BF16) { CF_LAUNCH_DT(CF_BF16) } else { CF_LAUNCH_DT(CF_F16) }
 #undef CF_LAUNCH_DT
+#undef CF_LAUNCH_S
 #undef CF_LAUNCH
     CF_HIP(hipGetLastError());
-    if (phases & 4) hipLaunchKernelGGL(attn_mass_kernel, grid3, block, 0, s, a, p);
+    if (prune) {
+        PruneArgs pr;
+        pr.enabled = 1; pr.keep = prune->keep; pr.strategy = prune->strategy; pr.force_n_reuse = prune->force_n_reuse;
+        pr.normalise_by_len = prune->normalise_by_len; pr.stride = prune->stride; pr.pos_begin = prune->pos_begin;
+        pr.pos_end = prune->pos_end; pr.prefix_len = prune->prefix_len; pr.doc_stored_start = prune->doc_stored_start;
+        pr.doc_tok_offset = prune->doc_tok_offset; pr.doc_len = prune->doc_len; pr.cand = prune->cand;
+        pr.n_cand = prune->n_cand; pr.keep_idx = prune->keep_idx; pr.n_keep = prune->n_keep;
+        pr.new_start = prune->new_start; pr.q_start = prune->q_start; pr.n_reuse = prune->n_reuse;
+        pr.order = prune->order; pr.next_segs = prune->next_segs; pr.next_n_seg = prune->next_n_seg;
+        if (phases & 4)
+            hipLaunchKernelGGL(layer_epilogue_kernel, dim3(a.batch), dim3(kEpiThreads), (size_t)prune->stride * 12, s, a, p, pr);
+    } else if (phases & 4) {
+        hipLaunchKernelGGL(attn_mass_kernel, grid3, block, 0, s, a, p);
+    }
     CF_HIP(hipGetLastError());
     return CF_OK;
 }

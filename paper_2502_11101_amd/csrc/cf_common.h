@@ -145,7 +145,9 @@ cf_status launch_attention_generic(const AttnArgs& a, const RopeFreq& f, hipStre
 bool mfma_path_supported(const cf_layer_desc* d);
 size_t mfma_workspace_bytes(const cf_layer_desc* d, int32_t batch, int32_t max_tq, int32_t seg_stride,
                             int64_t max_kv_tokens);
-cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_t s);
+cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_t s, const cf_prune_step* prune);
+// the three stand-alone launches of a prune step (ranking, allocation, table rebuild)
+cf_status launch_prune_step(const AttnArgs& a, const cf_prune_step* prune, hipStream_t s);
 
 cf_status launch_prune(const float* score, const int32_t* len, const int32_t* cand, const int32_t* n_cand,
                        int32_t keep, int32_t batch, int32_t stride, int32_t* keep_idx, int32_t* n_keep,

@@ -108,6 +108,25 @@ class PrefillBatch:
                               self.seg_stride, self.dev_flag)
         self._pending_keep = keep
 
+    # -- Alg. 2, one whole layer in one call: attention, S += s^l and, with `keep` given, the prune event
+    def layer(self, q, k_self, v_self, k_store, v_store, out, keep: Optional[int] = None,
+              strategy: int = cf.CF_ALLOC_SORT, normalise_by_len: bool = True, force_n_reuse: int = 0) -> None:
+        step = None
+        if keep is not None:
+            if strategy == cf.CF_ALLOC_KEEP:
+                self.next_new_start.copy_(self.new_start)
+                self.next_q_start.copy_(self.q_start)
+            step = cf.make_prune_step(keep, strategy, force_n_reuse, normalise_by_len, self.stride, self.pos_begin,
+                                      self.pos_end, self.prefix_len, self.doc_stored_start, self.doc_tok_offset,
+                                      self.doc_len, self.cand, self.n_cand, self.keep_idx, self.n_keep,
+                                      self.next_new_start, self.next_q_start, self.n_reuse, self.order,
+                                      self.next_segs, self.next_n_seg)
+            self._pending_keep = keep
+        cf.cf_prefill_layer(self.desc, q, self.q_off, self.q_stored_start, self.q_start, k_store, v_store,
+                            self.n_store_tokens, k_self, v_self, self.segs, self.n_seg, self.seg_stride, self.batch,
+                            self.tq, self.max_kv_tokens, out, self.mass, self.score, self.stride, self.workspace,
+                            self.ws_bytes, step, self.dev_flag)
+
     # -- the survivors, in placement order, become the candidates of the following layers
     def advance(self) -> None:
         self.cand, self.order = self.order, self.cand

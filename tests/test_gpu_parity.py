@@ -185,6 +185,7 @@ def _run_single_layer(cfg, pairing=cf.CF_ROPE_HALF, seed=None, mass_tol=None):
     dev = G.upload_layer(cfg, t)
     out = torch.empty_like(dev["q"])
     pb.allocate_initial()
+    pb.workspace.fill_(0xFF)          # the workspace is scratch: stale contents (here NaN patterns) must not matter
     pb.attention(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out)
     torch.cuda.synchronize()
     assert pb.flags() == 0
@@ -322,3 +323,103 @@ def test_mfma_path_is_deterministic():
         masses.append(pb.mass.clone())
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
     assert torch.equal(masses[0], masses[1]) and torch.equal(masses[0], masses[2])
+
+
+# ----------------------------------------------------------------------------- fused layer call
+@pytest.mark.parametrize("name", ["tiny_f32", "llama2_7b_layer", "qwen2_7b_layer"])
+@pytest.mark.parametrize("strategy", [cf.CF_ALLOC_SORT, cf.CF_ALLOC_ALIGN, cf.CF_ALLOC_KEEP])
+def test_fused_layer_equals_separate_calls(name, strategy):
+    """cf_prefill_layer = cf_prefill_attention + cf_prune_topk + cf_assign_positions + cf_gather_segments."""
+    cfg = wl.CONFIGS[name]
+    st = wl.build_structure(cfg)
+    t = wl.build_layer(cfg, st)
+    dev = G.upload_layer(cfg, t)
+    g = cfg.geometry
+    res = []
+    for fused in (False, True):
+        pb = G.make_batch(cfg, st)
+        out = torch.empty_like(dev["q"])
+        pb.allocate_initial()
+        if fused:
+            pb.layer(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out, keep=cfg.keep,
+                     strategy=strategy)
+        else:
+            pb.attention(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out)
+            pb.prune(cfg.keep, strategy)
+        torch.cuda.synchronize()
+        assert pb.flags() == 0
+        score = pb.score.cpu().numpy()
+        lens = st.doc_lens[st.query_docs[0]]
+        # the ranking must be exact for the scores this path itself produced
+        ref_keep = orc.prune_topk(score[0], lens, list(range(cfg.docs_per_query)), cfg.keep)
+        assert pb.keep_idx[0, :cfg.keep].tolist() == ref_keep
+        pb.advance()
+        res.append(dict(out=out.clone(), mass=pb.mass.cpu().numpy().copy(), score=score,
+                        segs=G.device_segments(pb, 0), q_start=int(pb.q_start[0].item()),
+                        cand=pb.cand[0, :cfg.keep].tolist()))
+    a, b = res
+    assert torch.equal(a["out"], b["out"])
+    n = cfg.docs_per_query + 2
+    assert G.rel_error(b["mass"][0, :n], a["mass"][0, :n]) < 2e-6
+    assert a["segs"] == b["segs"] and a["q_start"] == b["q_start"] and a["cand"] == b["cand"]
+    if strategy != cf.CF_ALLOC_KEEP:
+        lens = [int(x) for x in st.doc_lens[st.query_docs[0]]]
+        ref_ns, ref_q, _ = orc.assign_positions(lens, a["cand"] if strategy == cf.CF_ALLOC_SORT else sorted(a["cand"]),
+                                                cfg.prefix_len, g.max_positions - cfg.tq, cf.CF_ALLOC_SORT)
+        assert b["q_start"] == ref_q
+        assert {s.doc: s.new_start for s in b["segs"] if s.kind == cf.CF_SEG_DOC} == ref_ns
+
+
+def test_layer_stack_with_pruning_matches_oracle():
+    """A reduced layer stack in the LLaMA-2-7B geometry (the full one is 32 layers x 30 documents):
+    Alg. 2, Phase 1 on the GPU through cf_prefill_layer, checked against the oracle layer by layer on
+    the state the device holds.  Every cut must be exact for the scores the device accumulated, and
+    must agree with the oracle's own scores wherever those are not within 1e-3 of the cut (documents
+    closer than that to the boundary may legitimately fall either way in 16-bit arithmetic)."""
+    base = wl.CONFIGS["llama2_7b_stack"]
+    cfg = wl.scaled(base, n_store_docs=12, docs_per_query=12, n_planted=2, n_layers=6, prune_layers=(1, 3, 5))
+    g = cfg.geometry
+    st = wl.build_structure(cfg, seed=9100)
+    lens = [int(x) for x in st.doc_lens]
+    keeps, k = {}, cfg.docs_per_query
+    for layer in cfg.prune_layers:
+        k = orc.keep_fraction(k, cfg.keep_frac)
+        keeps[layer] = k
+    assert list(keeps.values()) == [8, 5, 3]
+    pb = G.make_batch(cfg, st)
+    pb.allocate_initial()
+    ref_score = np.zeros(cfg.docs_per_query)
+    alive = list(range(cfg.docs_per_query))
+    for layer in range(cfg.n_layers):
+        t = wl.build_layer(cfg, st, layer, seed=910000 + layer)
+        dev = G.upload_layer(cfg, t)
+        out = torch.empty_like(dev["q"])
+        segs, ref_out, ref_mass = G.oracle_on_device_segments(cfg, t, pb, 0)
+        assert sorted(s.doc for s in segs if s.kind == cf.CF_SEG_DOC) == sorted(alive)
+        pb.layer(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out, keep=keeps.get(layer),
+                 strategy=cf.CF_ALLOC_SORT)
+        torch.cuda.synchronize()
+        assert pb.flags() == 0
+        assert G.row_error(out.float().cpu().numpy(), ref_out) <= G.OUT_TOL[g.dtype]
+        assert G.rel_error(pb.mass.cpu().numpy()[0, :len(segs)], ref_mass) <= G.MASS_TOL[g.dtype]
+        ref_score += H.doc_scores(segs, ref_mass, cfg.docs_per_query)
+        dev_score = pb.score.cpu().numpy()[0]
+        assert G.rel_error(dev_score[alive], ref_score[alive]) <= G.MASS_TOL[g.dtype]
+        if layer in keeps:
+            keep = keeps[layer]
+            kept = pb.keep_idx[0, :keep].tolist()
+            assert int(pb.n_keep[0].item()) == keep
+            assert kept == orc.prune_topk(dev_score, lens, alive, keep)            # exact for its own scores
+            key = {i: ref_score[i] / lens[i] for i in alive}
+            cut = sorted(key.values(), reverse=True)[keep - 1]
+            for i in alive:
+                if key[i] > cut * (1 + 1e-3):
+                    assert i in kept
+                if key[i] < cut * (1 - 1e-3):
+                    assert i not in kept
+            ref_ns, ref_q, _ = orc.assign_positions(lens, kept, cfg.prefix_len, g.max_positions - cfg.tq)
+            pb.advance()
+            assert int(pb.q_start[0].item()) == ref_q
+            assert {s.doc: s.new_start for s in G.device_segments(pb, 0) if s.kind == cf.CF_SEG_DOC} == ref_ns
+            alive = kept
+    assert set(st.planted[0].tolist()) <= set(alive)
