@@ -41,7 +41,6 @@ constexpr int kStageBytes = kKBytes + kVBytes;
 constexpr int kMaxSegs = 256;
 constexpr int kMaxSplit = 32;
 constexpr int kMassChunks = 16;     // mass workgroups per query (segments dealt round-robin)
-constexpr int kStatRows = 2048;     // rows whose (max, 1/sum) a mass workgroup holds at a time
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -59,7 +58,7 @@ struct Plan {
     int units_per_b, units, nsplit, slots, x_count, mass_chunks;
     int tile;           // tokens per tile: 64 (shared-tile kernel) or 32 (wavefront-private tiles)
     int sub;            // sub-splits per workgroup: 4 when every wavefront streams its own tiles, else 1
-    size_t off_ml, off_opart, off_massml, off_rowstat, total;
+    size_t off_ml, off_opart, off_massml, off_masspart, total;
 };
 
 Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_stride, int64_t max_kv_tokens) {
@@ -95,7 +94,7 @@ Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_str
     p.off_ml = take((size_t)p.units * p.nsplit * p.rows_wg * sizeof(float2));
     p.off_opart = take((size_t)p.units * p.nsplit * p.rows_wg * kD * sizeof(float));
     p.off_massml = take((size_t)p.units * p.slots * p.rows_wg * sizeof(float2));
-    p.off_rowstat = take((size_t)p.units * p.rows_wg * sizeof(float2));
+    p.off_masspart = take((size_t)p.units * p.nrb * p.slots * sizeof(float));
     p.total = off;
 #ifdef CF_TRACE
     p.total += (size_t)(p.x_count * p.n_rg + p.units * p.nrb * 4 + batch * p.mass_chunks) * 16 * 8;
@@ -553,7 +552,6 @@ constexpr int kSVs = 40;                               // LDS row stride of a st
 constexpr int kKBytesS = kTileS * kSK * 2;             // 8704
 constexpr int kVBytesS = kD * kSVs * 2;                // 10240
 constexpr int kStageBytesS = kKBytesS + kVBytesS;      // per wavefront
-constexpr int kMaxSegsS = 64;
 
 // cos/sin of delta*theta from the hardware sine/cosine (argument in revolutions, reduced in fp64):
 // their absolute error is far below the rounding step of the 16-bit keys this feeds.
@@ -952,10 +950,13 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
 }
 
 // Second kernel: one workgroup per (unit, 64-row pass, quarter of the output channels) merges the
-// splits' partial outputs, writes its output rows and leaves (max, 1/sum) per row for the mass kernel.
+// splits' partial outputs and writes its output rows; the four workgroups of a (unit, pass) also share
+// the reduction, over the pass's 64 rows, of every (segment, sub-split) slot's (max, sum) pairs to
+// sum * exp2(max - row max) / row sum, which the mass kernel then only has to add up.
 template <int DT>
 __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan p) {
     __shared__ float2 mlw[kMaxSplit * 64];       // (m, l) per split and row, then the split's weight in .x
+    __shared__ float2 rstat[64];                 // (max, 1/sum) per row of this pass
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -992,8 +993,7 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
         for (int s = 0; s < p.nsplit; ++s) z += mlw[s * 64 + tid].y * exp2f(mlw[s * 64 + tid].x - ms);
         const float iz = z > 0.f ? 1.f / z : 0.f;
         for (int s = 0; s < p.nsplit; ++s) mlw[s * 64 + tid].x = exp2f(mlw[s * 64 + tid].x - ms) * iz;
-        if (dbq == 0)
-            reinterpret_cast<float2*>(ws + p.off_rowstat)[(int64_t)unit * p.rows_wg + pass * 64 + tid] = make_float2(ms, iz);
+        rstat[tid] = make_float2(ms, pass * 64 + tid < rows_here ? iz : 0.f);    // padding rows carry no mass
     }
     __syncthreads();
     const int blk = pass * kWaves + wave;                      // row block inside the workgroup tile
@@ -1020,23 +1020,56 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
         pk.y = Mma<DT>::pack(o1[2], o1[3]);
         *reinterpret_cast<uint2*>(op + 16) = pk;
     }
+    // slot partials: slot k = segment + sub-split; slots no sub-split wrote this call hold stale pairs and
+    // give meaningless numbers that the mass kernel never reads
+    {
+        const float2* massml = reinterpret_cast<const float2*>(ws + p.off_massml) + (int64_t)unit * p.slots * p.rows_wg + pass * 64 + lane;
+        float* masspart = reinterpret_cast<float*>(ws + p.off_masspart) + ((int64_t)unit * p.nrb + pass) * p.slots;
+        const float2 st = rstat[lane];
+        for (int k0 = dbq * kWaves + wave; k0 < p.slots; k0 += 4 * 4 * kWaves) {
+            float2 v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int k = k0 + j * 4 * kWaves;
+                v[j] = k < p.slots ? massml[(int64_t)k * p.rows_wg] : make_float2(0.f, 0.f);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int k = k0 + j * 4 * kWaves;
+                const float c = wave_sum(st.y > 0.f ? v[j].y * exp2f(v[j].x - st.x) * st.y : 0.f);
+                if (lane == 0 && k < p.slots) masspart[k] = c;
+            }
+        }
+    }
     CF_STAMP(1);
 }
 
-// Third kernel: per-segment attention mass.  Workgroup (query b, chunk c) owns the segments
-// c, c + mass_chunks, ... and adds, over every row of every unit of the query and every split that
-// touched the segment, sum * exp2(max - row max) / row sum — in a fixed order — then S += mass.
-__global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p) {
-    __shared__ float2 stat[kStatRows];           // (max, 1/sum) per row of a group of units
-    __shared__ SegTable tbl;
-    __shared__ float red[kWaves];
-    __shared__ float segtot[kMaxSegs];
+// Mass of segment s of query b: the slot partials of every (unit, pass) and every sub-split that
+// holds tiles of the segment, added by one wavefront in a fixed order.
+__device__ __forceinline__ float segment_mass(const Plan& p, const SegTable& tbl, const float* mp_b, int s, unsigned total,
+                                              unsigned nsub, int lane) {
+    const int ts = tbl.tile0[s], te = tbl.tile0[s + 1];
+    if (te <= ts) return 0.f;
+    const int s0 = split_of(total, nsub, ts), s1 = split_of(total, nsub, te - 1);
+    const int nparts = p.units_per_b * p.nrb;
+    float c = 0.f;
+    for (int sp = s0; sp <= s1; ++sp) {
+        // a sub-split between the first and the last may own no tile at all (fewer tiles than sub-splits):
+        // its slot was not written by this call
+        if (split_begin(total, nsub, sp) >= split_begin(total, nsub, sp + 1)) continue;
+        for (int part = lane; part < nparts; part += kWave) c += mp_b[(int64_t)part * p.slots + s + sp];
+    }
+    return wave_sum(c);
+}
 
+// Third kernel: per-segment attention mass.  Workgroup (query b, chunk c) owns the segments
+// c, c + mass_chunks, ..., one wavefront per segment; then S += mass.
+__global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p) {
+    __shared__ SegTable tbl;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
     const char* ws = static_cast<const char*>(a.workspace);
-    const int group = a.n_q_heads / a.n_kv_heads;
 #ifdef CF_TRACE
     long long* trace = reinterpret_cast<long long*>(static_cast<char*>(a.workspace) + p.total) -
                        (size_t)(a.batch * p.mass_chunks) * 16 + (size_t)blockIdx.x * 16;
@@ -1045,74 +1078,17 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p)
     const int b = __builtin_amdgcn_readfirstlane(blockIdx.x / p.mass_chunks);
     const int chunk = blockIdx.x % p.mass_chunks;
     const QueryHead qh = load_query_head(a, b);
-    const int tq_raw = qh.tq_raw;
-    const float2* rs_b = reinterpret_cast<const float2*>(ws + p.off_rowstat) + (int64_t)b * p.units_per_b * p.rows_wg;
-    const float2* mm_b = reinterpret_cast<const float2*>(ws + p.off_massml) + (int64_t)b * p.units_per_b * p.slots * p.rows_wg;
-    const int units_per_pass = kStatRows / p.rows_wg;            // rows_wg <= 256
-    // the first group's row statistics travel together with the table's loads
-    float2 pre[kStatRows / kThreads];
-    {
-        const int nu = min(units_per_pass, p.units_per_b);
-#pragma unroll
-        for (int j = 0; j < kStatRows / kThreads; ++j) {
-            const int idx = tid + j * kThreads;
-            pre[j] = idx < nu * p.rows_wg ? rs_b[idx] : make_float2(0.f, 0.f);
-        }
-    }
     build_table(a, qh, &tbl, p.tile);
-    const int tq = min(tq_raw, a.max_tq);
-    const int n_rows = group * tq;
     const unsigned total = (unsigned)tbl.tile0[tbl.n];
     const unsigned nsub = (unsigned)(p.nsplit * p.sub);
-    for (int i = tid; i < kMaxSegs; i += kThreads) segtot[i] = 0.f;
-
-    for (int u0 = 0; u0 < p.units_per_b; u0 += units_per_pass) {
-        const int nu = min(units_per_pass, p.units_per_b - u0);
-        __syncthreads();
-        if (u0 == 0) {
-#pragma unroll
-            for (int j = 0; j < kStatRows / kThreads; ++j) stat[tid + j * kThreads] = pre[j];
-        } else {
-            for (int idx = tid; idx < nu * p.rows_wg; idx += kThreads) stat[idx] = rs_b[(int64_t)u0 * p.rows_wg + idx];
-        }
-        __syncthreads();
-        int k = 0;
-        for (int s = chunk; s < tbl.n; s += p.mass_chunks, ++k) {
-            const int ts = tbl.tile0[s], te = tbl.tile0[s + 1];
-            if (te <= ts) continue;
-            const int s0 = split_of(total, nsub, ts), s1 = split_of(total, nsub, te - 1);
-            float c = 0.f;
-            for (int sp = s0; sp <= s1; ++sp) {
-                // a sub-split between the first and the last may own no tile at all (fewer tiles than
-                // sub-splits): its slot was not written by this call
-                if (split_begin(total, nsub, sp) >= split_begin(total, nsub, sp + 1)) continue;
-                for (int idx = tid; idx < nu * p.rows_wg; idx += kThreads) {
-                    const int ul = idx / p.rows_wg, r = idx % p.rows_wg;
-                    const int rg = (u0 + ul) % p.n_rg;
-                    const int rows_here = min(p.blocks_rg * 16, n_rows - rg * p.blocks_rg * 16);
-                    if (r < rows_here) {
-                        const float2 st = stat[idx];
-                        const float2 v = mm_b[((int64_t)(u0 + ul) * p.slots + s + sp) * p.rows_wg + r];
-                        c += v.y * exp2f(v.x - st.x) * st.y;
-                    }
-                }
-            }
-            c = wave_sum(c);
-            __syncthreads();
-            if (lane == 0) red[wave] = c;
-            __syncthreads();
-            if (tid == 0) segtot[k] += (red[0] + red[1]) + (red[2] + red[3]);
-        }
-    }
-    __syncthreads();
-    if (tid == 0) {
-        int k = 0;
-        for (int s = chunk; s < tbl.n; s += p.mass_chunks, ++k) {
-            const float seg_total = segtot[k];
-            a.mass[(int64_t)b * a.seg_stride + s] = seg_total;
+    const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * p.units_per_b * p.nrb * p.slots;
+    for (int s = chunk + p.mass_chunks * wave; s < tbl.n; s += p.mass_chunks * kWaves) {
+        const float m = segment_mass(p, tbl, mp_b, s, total, nsub, lane);
+        if (lane == 0) {
+            a.mass[(int64_t)b * a.seg_stride + s] = m;
             const int doc = a.segs[(int64_t)b * a.seg_stride + s].doc;
             if (a.score_accum && doc >= 0 && doc < a.score_stride)
-                atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], seg_total);
+                atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], m);
         }
     }
     CF_STAMP(1);
@@ -1145,9 +1121,7 @@ struct PruneArgs {
 
 __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a, Plan p, PruneArgs pr) {
     extern __shared__ unsigned char dyn_smem[];          // 3*stride words for the ranking / allocation
-    __shared__ float2 stat[kStatRows];
     __shared__ SegTable tbl;
-    __shared__ float segtot[kMaxSegs];
     __shared__ int s_int[4];
 
     const int tid = threadIdx.x;
@@ -1155,69 +1129,20 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
     const int wave = tid / kWave;
     const int n_waves = kEpiThreads / kWave;
     const char* ws = static_cast<const char*>(a.workspace);
-    const int group = a.n_q_heads / a.n_kv_heads;
     const int b = __builtin_amdgcn_readfirstlane(blockIdx.x);
     const QueryHead qh = load_query_head(a, b);
-    const float2* rs_b = reinterpret_cast<const float2*>(ws + p.off_rowstat) + (int64_t)b * p.units_per_b * p.rows_wg;
-    const float2* mm_b = reinterpret_cast<const float2*>(ws + p.off_massml) + (int64_t)b * p.units_per_b * p.slots * p.rows_wg;
-    const int units_per_pass = kStatRows / p.rows_wg;
-    float2 pre[kStatRows / kEpiThreads];
-    {
-        const int nu = min(units_per_pass, p.units_per_b);
-#pragma unroll
-        for (int j = 0; j < kStatRows / kEpiThreads; ++j) {
-            const int idx = tid + j * kEpiThreads;
-            pre[j] = idx < nu * p.rows_wg ? rs_b[idx] : make_float2(0.f, 0.f);
-        }
-    }
     build_table(a, qh, &tbl, p.tile);
-    const int tq = min(qh.tq_raw, a.max_tq);
-    const int n_rows = group * tq;
     const unsigned total = (unsigned)tbl.tile0[tbl.n];
     const unsigned nsub = (unsigned)(p.nsplit * p.sub);
-    for (int i = tid; i < kMaxSegs; i += kEpiThreads) segtot[i] = 0.f;
-
-    for (int u0 = 0; u0 < p.units_per_b; u0 += units_per_pass) {
-        const int nu = min(units_per_pass, p.units_per_b - u0);
-        __syncthreads();
-        if (u0 == 0) {
-#pragma unroll
-            for (int j = 0; j < kStatRows / kEpiThreads; ++j) stat[tid + j * kEpiThreads] = pre[j];
-        } else {
-            for (int idx = tid; idx < nu * p.rows_wg; idx += kEpiThreads) stat[idx] = rs_b[(int64_t)u0 * p.rows_wg + idx];
+    const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * p.units_per_b * p.nrb * p.slots;
+    for (int s = wave; s < tbl.n; s += n_waves) {
+        const float m = segment_mass(p, tbl, mp_b, s, total, nsub, lane);
+        if (lane == 0) {
+            a.mass[(int64_t)b * a.seg_stride + s] = m;
+            const int doc = a.segs[(int64_t)b * a.seg_stride + s].doc;
+            if (a.score_accum && doc >= 0 && doc < a.score_stride)
+                atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], m);
         }
-        __syncthreads();
-        for (int s = wave; s < tbl.n; s += n_waves) {
-            const int ts = tbl.tile0[s], te = tbl.tile0[s + 1];
-            if (te <= ts) continue;
-            const int s0 = split_of(total, nsub, ts), s1 = split_of(total, nsub, te - 1);
-            float c = 0.f;
-            for (int sp = s0; sp <= s1; ++sp) {
-                // a sub-split between the first and the last may own no tile at all (fewer tiles than
-                // sub-splits): its slot was not written by this call
-                if (split_begin(total, nsub, sp) >= split_begin(total, nsub, sp + 1)) continue;
-                for (int idx = lane; idx < nu * p.rows_wg; idx += kWave) {
-                    const int ul = idx / p.rows_wg, r = idx % p.rows_wg;
-                    const int rg = (u0 + ul) % p.n_rg;
-                    const int rows_here = min(p.blocks_rg * 16, n_rows - rg * p.blocks_rg * 16);
-                    if (r < rows_here) {
-                        const float2 st = stat[idx];
-                        const float2 v = mm_b[((int64_t)(u0 + ul) * p.slots + s + sp) * p.rows_wg + r];
-                        c += v.y * exp2f(v.x - st.x) * st.y;
-                    }
-                }
-            }
-            c = wave_sum(c);
-            if (lane == 0) segtot[s] += c;               // this wavefront is the only writer of segtot[s]
-        }
-    }
-    __syncthreads();
-    for (int s = tid; s < tbl.n; s += kEpiThreads) {
-        const float m = segtot[s];
-        a.mass[(int64_t)b * a.seg_stride + s] = m;
-        const int doc = a.segs[(int64_t)b * a.seg_stride + s].doc;
-        if (a.score_accum && doc >= 0 && doc < a.score_stride)
-            atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], m);
     }
     if (!pr.enabled) return;
     __threadfence_block();
