@@ -563,14 +563,15 @@ __device__ __forceinline__ float2 rope_cos_sin_fast(int delta, double theta_rev)
 
 template <int DT, int NRB>
 __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFreq freq, Plan p) {
-    __shared__ __attribute__((aligned(16))) unsigned char stage_all[kWaves * kStageBytesS];
+    constexpr int kMergeBytes = 4 * 3 * NRB * 2 * kWave * 16;      // the end-of-kernel reduce-scatter reuses the staging area
+    __shared__ __attribute__((aligned(16))) unsigned char stage_all[kWaves * kStageBytesS > kMergeBytes ? kWaves * kStageBytesS : kMergeBytes];
     __shared__ __attribute__((aligned(16))) uint16_t q_lds[64 * kSK];
     __shared__ __attribute__((aligned(16))) float2 cs_all[kWaves][kHalf];
     __shared__ float2 ml_w[kWaves][64];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
-    const int wave = tid / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int li = lane & 15, lg = lane >> 4;
 #ifdef CF_TRACE
     long long* trace = reinterpret_cast<long long*>(static_cast<char*>(a.workspace) + p.total) -
@@ -582,8 +583,8 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
     {
         const void *p0 = a.q, *p1 = a.q_off, *p2 = a.q_new_start, *p3 = a.k_store, *p4 = a.v_store, *p5 = a.k_self,
                    *p6 = a.v_self, *p7 = a.segs, *p8 = a.n_seg, *p9 = a.workspace;
-        asm volatile("" ::"s"(p0), "s"(p1), "s"(p2), "s"(p3), "s"(p4), "s"(p5), "s"(p6), "s"(p7), "s"(p8), "s"(p9));
-        asm volatile("" ::"s"(a.n_store_tokens), "s"(a.seg_stride), "s"(a.batch), "s"(a.max_tq), "s"(a.n_q_heads),
+        asm volatile("" ::"s"(p0), "s"(p1), "s"(p2), "s"(p3), "s"(p4), "s"(p5), "s"(p6), "s"(p7), "s"(p8), "s"(p9),
+                     "s"(a.n_store_tokens), "s"(a.seg_stride), "s"(a.batch), "s"(a.max_tq), "s"(a.n_q_heads),
                      "s"(a.n_kv_heads), "s"(a.scale_log2e), "s"(a.q_stored_start), "s"(p.nsplit), "s"(p.slots),
                      "s"(p.off_ml), "s"(p.off_opart), "s"(p.off_massml));
     }
@@ -687,6 +688,9 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
     Tile d0, d1;
     d0.seg = d1.seg = 0; d0.tok0 = d1.tok0 = 0; d0.ntok = d1.ntok = 0; d0.delta = d1.delta = 0; d0.self = d1.self = 0;
     constexpr bool kTwo = NRB <= 3;                  // 64 rows leave no registers for a second tile in flight
+#ifdef CF_EXP_NOLOADS
+    next_tile = t_end;
+#endif
     fetch(d0, regs0);                                // the loads go out before anything else
     if (kTwo) fetch(d1, regs1);
     CF_STAMP(5);
@@ -758,6 +762,13 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
             }
         }
         if (first) CF_STAMP(7);
+#ifdef CF_EXP_NOSTAGE
+        { uint32_t x = 0;
+          for (int it = 0; it < 4; ++it) x ^= r.ka[it].x ^ r.kb[it].y;
+          for (int it = 0; it < 2; ++it) for (int i = 0; i < 4; ++i) x ^= r.v[it][i].z;
+          if (x == 0x12345u) m_run[0] = 1.f;
+          fetch(cur, r); return; }
+#endif
         // ---- stage K: rotate pairs (c, c + 64), round once, write [token][c]
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
@@ -803,6 +814,9 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
         fetch(cur, r);                               // these registers are free again
         __builtin_amdgcn_wave_barrier();
         if (first) { CF_STAMP(2); first = false; }
+#ifdef CF_EXP_NOCOMPUTE
+        return;
+#endif
 
         const bool causal = cd.self != 0;
         const int nt = cd.ntok;
@@ -909,42 +923,39 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
 #pragma unroll
         for (int db = 0; db < 8; ++db) acc[rb][db] *= f;
     }
-    f32x4* red = reinterpret_cast<f32x4*>(stage_all);            // 2 slots of NRB*8*64 float4 (<= 64 KB)
-    auto put = [&](int slot) {
-        f32x4* dst = red + slot * NRB * 8 * kWave + lane;
+    // Reduce-scatter: item j = (row block, channel block) belongs to wavefront j % 4; every wavefront parks
+    // the items it does not own in LDS, one barrier, then each owner adds the three parked copies to its
+    // own (fixed order) and stores its items — the partial result of this workgroup, same format as the
+    // shared-tile kernel with one row block per wavefront.
+    f32x4* red = reinterpret_cast<f32x4*>(stage_all);
+    constexpr int kOwn = NRB * 2;                    // items per owner
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb)
+    for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-            for (int db = 0; db < 8; ++db) dst[(rb * 8 + db) * kWave] = acc[rb][db];
-    };
-    auto add = [&](int slot) {
-        const f32x4* src = red + slot * NRB * 8 * kWave + lane;
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-            for (int db = 0; db < 8; ++db) acc[rb][db] += src[(rb * 8 + db) * kWave];
-    };
-    if (wave >= 2) put(wave - 2);
+        for (int db = 0; db < 8; ++db) {
+            const int j = rb * 8 + db, o = j & 3;
+            if (o != wave) red[(((o * 3 + ((wave - o - 1) & 3)) * kOwn) + (j >> 2)) * kWave + lane] = acc[rb][db];
+        }
     __syncthreads();
-    if (wave < 2) add(wave);
-    __syncthreads();
-    if (wave == 1) put(0);
-    __syncthreads();
-    if (wave == 0) {
-        add(0);
-        // partial result of this workgroup, same format as the shared-tile kernel with one row block per wavefront
-        f32x4* opart = reinterpret_cast<f32x4*>(ws + p.off_opart) + ((int64_t)unit * p.nsplit + split) * 4 * 8 * kWave + lane;
+    f32x4* opart = reinterpret_cast<f32x4*>(ws + p.off_opart) + ((int64_t)unit * p.nsplit + split) * 4 * 8 * kWave + lane;
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+            const int j = rb * 8 + db;
+            if ((j & 3) == wave) {
+                f32x4 v = acc[rb][db];
+#pragma unroll
+                for (int r = 0; r < 3; ++r) v += red[(((wave * 3 + r) * kOwn) + (j >> 2)) * kWave + lane];
+                opart[j * kWave] = v;
+            }
+        }
+    if (wave == 0 && lg == 0) {
         float2* ml = reinterpret_cast<float2*>(ws + p.off_ml) + ((int64_t)unit * p.nsplit + split) * 64;
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) {
+        for (int rb = 0; rb < NRB; ++rb) ml[rb * 16 + li] = make_float2(mx[rb], zz[rb]);
 #pragma unroll
-            for (int db = 0; db < 8; ++db) opart[(rb * 8 + db) * kWave] = acc[rb][db];
-            if (lg == 0) ml[rb * 16 + li] = make_float2(mx[rb], zz[rb]);
-        }
-        if (NRB < 4 && lg == 0) {                    // row blocks that do not exist: neutral statistics
-#pragma unroll
-            for (int rb = NRB; rb < 4; ++rb) ml[rb * 16 + li] = make_float2(-INFINITY, 0.f);
-        }
+        for (int rb = NRB; rb < 4; ++rb) ml[rb * 16 + li] = make_float2(-INFINITY, 0.f);   // row blocks that do not exist
     }
     CF_STAMP(4);
 }
