@@ -29,6 +29,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel on this workload, from the FETCH_SIZE and WRITE_SIZE counter runs
+# summarised in profiles/attn_small_kernel_llama2_7b_layer.md (scaled by a 1 GiB copy kernel: x2.000 and x1.000)
+TRAFFIC_BYTES_PER_LAUNCH = 31_220_900 + 6_815_744
 WORKLOAD = "llama2_7b_layer"
 
 
@@ -86,6 +89,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--layers", type=int, default=24, help="distinct layer buffers cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only 10 elementwise copies of 1 GiB (read 1 GiB + write 1 GiB each): the known-size "
+                         "kernel that scales the HBM byte counters of a profiler run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -100,6 +106,15 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"launches": 10, "read_bytes": src.numel() * 4,
+                                               "write_bytes": dst.numel() * 4}}))
+        return 0
     cf.load()
 
     cfg = wl.CONFIGS[WORKLOAD]
@@ -178,8 +193,8 @@ def main() -> int:
                    "docs": cfg.docs_per_query, "keep": cfg.keep, "layer_buffers": len(layers),
                    "step": "cf_prefill_layer: attention + mass + prune_topk + assign_positions + gather_segments"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "attn_mfma_kernel (first kernel of cf_prefill_attention)",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                     "kernel": "attn_small_kernel<bf16,3> (first kernel of cf_prefill_layer / cf_prefill_attention)",
                      "ms_per_launch": kernel_ms, "algorithmic_bytes_per_launch": kv_tokens * bytes_per_token,
                      "ms_per_call_all_kernels": attn_ms},
     }

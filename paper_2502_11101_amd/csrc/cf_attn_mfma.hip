@@ -82,7 +82,9 @@ Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_str
     const int64_t cap = est_tiles / (2 * p.sub) > 1 ? est_tiles / (2 * p.sub) : 1;
     if (ns > cap) ns = cap;
     if (ns > kMaxSplit) ns = kMaxSplit;
-    if (const char* e = std::getenv("CF_NSPLIT")) ns = std::atoi(e);     // development knob
+#ifdef CF_DEV
+    if (const char* e = std::getenv("CF_NSPLIT")) ns = std::atoi(e);
+#endif
     if (ns < 1) ns = 1;
     if (ns > kMaxSplit) ns = kMaxSplit;
     p.nsplit = (int)ns;

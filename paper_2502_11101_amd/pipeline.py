@@ -69,7 +69,7 @@ class PrefillBatch:
         self.dev_flag = torch.zeros((1,), **i32)
         self.max_kv_tokens = int(prefix_len + doc_len.sum(axis=1).max() + tq)
         self.ws_bytes = cf.cf_prefill_workspace_bytes(desc, self.batch, tq, self.seg_stride, self.max_kv_tokens)
-        self.workspace = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=device)   # zeroed once, see header
+        self.workspace = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=device)   # contents are scratch
         self.n_alive = self.stride
 
     # -- Alg. 2 init: every document is a candidate, placement order = retriever order
