@@ -542,18 +542,22 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
 // independent worker over its own run of 32-token tiles (sub-split):
 //   * the segment table lives in registers, one segment per lane (prefix by a wavefront scan,
 //     lookup by ballot), so the prologue has no workgroup barrier and no LDS round trips;
-//   * two tiles are in flight in registers; K is rotated and staged, V staged transposed, in the
-//     wavefront's private slice of LDS, so the streaming loop has no workgroup barrier either
-//     and every K/V byte is read from LDS once;
-//   * Q fragments are read from a shared LDS copy (they would not fit in registers next to two
-//     tiles in flight);
+//   * K never touches LDS: a lane loads its key fragments straight in the MFMA operand layout
+//     (token = lane & 15 (+16), eight consecutive channels per 32-channel block), where the two
+//     halves (c, c + 64) of every RoPE pair sit in the same lane, and rotates them in registers;
+//   * V goes from memory to LDS without passing through registers (global_load_lds, 16 bytes per
+//     lane), row-major with a 32-byte XOR swizzle, and is read back as the V^T operand with the
+//     transposing LDS read (ds_read_b64_tr_b16), so no lane does any work to transpose it;
+//   * two tiles are in flight per wavefront (K in registers, V in a ring of three LDS slots); the
+//     streaming loop has no workgroup barrier;
+//   * Q fragments are read from a shared LDS copy;
 //   * the four sub-splits of a workgroup are merged through LDS at the end, so one partial
 //     result per workgroup goes to memory.
 constexpr int kTileS = 32;
-constexpr int kSVs = 40;                               // LDS row stride of a staged 32-token V^T tile, elements
-constexpr int kKBytesS = kTileS * kSK * 2;             // 8704
-constexpr int kVBytesS = kD * kSVs * 2;                // 10240
-constexpr int kStageBytesS = kKBytesS + kVBytesS;      // per wavefront
+constexpr int kVSlots = 3;                             // V tiles per wavefront in LDS
+constexpr int kVTileBytes = kTileS * kD * 2;           // 8192
+
+typedef short short4v __attribute__((ext_vector_type(4)));
 
 // cos/sin of delta*theta from the hardware sine/cosine (argument in revolutions, reduced in fp64):
 // their absolute error is far below the rounding step of the 16-bit keys this feeds.
@@ -565,8 +569,9 @@ __device__ __forceinline__ float2 rope_cos_sin_fast(int delta, double theta_rev)
 
 template <int DT, int NRB>
 __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFreq freq, Plan p) {
-    constexpr int kMergeBytes = 4 * 3 * NRB * 2 * kWave * 16;      // the end-of-kernel reduce-scatter reuses the staging area
-    __shared__ __attribute__((aligned(16))) unsigned char stage_all[kWaves * kStageBytesS > kMergeBytes ? kWaves * kStageBytesS : kMergeBytes];
+    constexpr int kMergeBytes = 4 * 3 * NRB * 2 * kWave * 16;      // the end-of-kernel reduce-scatter reuses the V ring
+    constexpr int kRingBytes = kWaves * kVSlots * kVTileBytes;
+    __shared__ __attribute__((aligned(16))) unsigned char v_all[kRingBytes > kMergeBytes ? kRingBytes : kMergeBytes];
     __shared__ __attribute__((aligned(16))) uint16_t q_lds[64 * kSK];
     __shared__ __attribute__((aligned(16))) float2 cs_all[kWaves][kHalf];
     __shared__ float2 ml_w[kWaves][64];
@@ -575,11 +580,6 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int li = lane & 15, lg = lane >> 4;
-#ifdef CF_TRACE
-    long long* trace = reinterpret_cast<long long*>(static_cast<char*>(a.workspace) + p.total) -
-                       (size_t)(p.x_count * p.n_rg + p.units * p.nrb * 4 + a.batch * p.mass_chunks) * 16 + (size_t)blockIdx.x * 16;
-#endif
-    CF_STAMP(0);
     // Pull every pointer and scalar the streaming loop needs out of the kernel-argument segment
     // now, in one batch of scalar loads, instead of one dependent round trip per first use.
     {
@@ -633,7 +633,6 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
     }
     const unsigned total = (unsigned)__builtin_amdgcn_readlane(t_incl, kWave - 1);
     const int t_tok_lo = (int)(uint32_t)seg.tok_offset, t_tok_hi = (int)(seg.tok_offset >> 32);
-    CF_STAMP(1);
 
     const unsigned nsub = (unsigned)(p.nsplit * kWaves);
     const int ss = split * kWaves + wave;            // this wavefront's sub-split
@@ -641,15 +640,15 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
     const int t_end = split_begin(total, nsub, ss + 1);
 
     const int64_t kv_row = (int64_t)a.n_kv_heads * kD;
-    // staging (per wavefront): K items (tokens kt + 8*it, slices 8*kj..), V items (quads vq + 4*it, channels 8*vj..)
-    const int kt = lane >> 3, kj = lane & 7;
-    const int vq = lane >> 4, vj = lane & 15;
-    struct StageRegs { uint4 ka[4], kb[4], v[2][4]; };
-    struct Tile { int seg, tok0, ntok, delta, self; };
-    StageRegs regs0, regs1;
+    const uint32_t row_bytes = (uint32_t)a.n_kv_heads * (kD * 2);      // between consecutive tokens of one head
+    struct KRegs { uint4 f[2][4]; };                 // [token li + 16*h][channels 32*kk + 8*lg ..]
+    struct Tile { int seg, tok0, ntok, delta, self, slot; };
+    KRegs regs0, regs1;
+    unsigned char* v_wave = v_all + wave * (kVSlots * kVTileBytes);
 
     int next_tile = t_begin;
-    auto fetch = [&](Tile& d, StageRegs& r) {        // ntok == 0 marks "no tile"
+    int next_slot = 0;
+    auto fetch = [&](Tile& d, KRegs& r) {            // ntok == 0 marks "no tile"
         if (next_tile >= t_end) { d.ntok = 0; return; }
         // the segment that owns this tile: first lane whose inclusive prefix exceeds it
         const unsigned long long m = __ballot(t_incl > next_tile);
@@ -660,42 +659,38 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
         d.ntok = min(kTileS, __builtin_amdgcn_readlane(t_vis, s) - d.tok0);
         d.delta = __builtin_amdgcn_readlane(t_delta, s);
         d.self = __builtin_amdgcn_readlane((int)t_self, s);
+        d.slot = next_slot;
         const int64_t tok = ((int64_t)__builtin_amdgcn_readlane(t_tok_hi, s) << 32) | (uint32_t)__builtin_amdgcn_readlane(t_tok_lo, s);
         ++next_tile;
-        const uint16_t* kb = static_cast<const uint16_t*>(d.self ? a.k_self : a.k_store);
-        const uint16_t* vb = static_cast<const uint16_t*>(d.self ? a.v_self : a.v_store);
-        const int64_t base = (tok + d.tok0) * kv_row + (int64_t)hkv * kD;
-        const uint4 zero = make_uint4(0, 0, 0, 0);
+        next_slot = next_slot == kVSlots - 1 ? 0 : next_slot + 1;
+        const int64_t base = ((tok + d.tok0) * kv_row + (int64_t)hkv * kD) * 2;
+        const char* kb = static_cast<const char*>(d.self ? a.k_self : a.k_store) + base;
+        const char* vb = static_cast<const char*>(d.self ? a.v_self : a.v_store) + base;
+        // Rows past the end of a ragged tile re-read its last row: always in bounds, and their scores
+        // are masked out below.
+        const int last = d.ntok - 1;
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int t = kt + 8 * it;
-            if (t < d.ntok) {
-                const uint16_t* pk = kb + base + t * kv_row + 8 * kj;
-                r.ka[it] = *reinterpret_cast<const uint4*>(pk);
-                r.kb[it] = *reinterpret_cast<const uint4*>(pk + kHalf);
-            } else {
-                r.ka[it] = zero;
-                r.kb[it] = zero;
-            }
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t off = (uint32_t)min(li + 16 * h, last) * row_bytes + lg * 16;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) r.f[h][kk] = *reinterpret_cast<const uint4*>(kb + off + 64 * kk);
         }
+        // V: instruction n drops rows 4n..4n+3 (16 lanes of 16 bytes each) at byte n*1024 of the slot;
+        // the lane at LDS chunk c' of row t fetches memory chunk c' ^ 2*(t & 7)
+        unsigned char* slot = v_wave + d.slot * kVTileBytes;
 #pragma unroll
-        for (int it = 0; it < 2; ++it)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int t = 4 * (vq + 4 * it) + i;
-                if (t < d.ntok) r.v[it][i] = *reinterpret_cast<const uint4*>(vb + base + t * kv_row + 8 * vj);
-                else r.v[it][i] = zero;
-            }
+        for (int n = 0; n < 8; ++n) {
+            const int t = 4 * n + (lane >> 4);
+            const int c = (lane & 15) ^ (2 * (t & 7));
+            const uint32_t off = (uint32_t)min(t, last) * row_bytes + 16 * c;
+            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(vb + off),
+                                             (uint32_t __attribute__((address_space(3)))*)(slot + n * 1024), 16, 0, 0);
+        }
     };
     Tile d0, d1;
-    d0.seg = d1.seg = 0; d0.tok0 = d1.tok0 = 0; d0.ntok = d1.ntok = 0; d0.delta = d1.delta = 0; d0.self = d1.self = 0;
-    constexpr bool kTwo = NRB <= 3;                  // 64 rows leave no registers for a second tile in flight
-#ifdef CF_EXP_NOLOADS
-    next_tile = t_end;
-#endif
+    d0.seg = d1.seg = 0; d0.tok0 = d1.tok0 = 0; d0.ntok = d1.ntok = 0; d0.delta = d1.delta = 0; d0.self = d1.self = 0; d0.slot = d1.slot = 0;
     fetch(d0, regs0);                                // the loads go out before anything else
-    if (kTwo) fetch(d1, regs1);
-    CF_STAMP(5);
+    fetch(d1, regs1);
 
     // ---- Q rows of this kv head into LDS: row m = g*tq + t of the stack is q[q0 + t][hkv*group + g]
     {
@@ -719,10 +714,16 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
         trow[rb] = m < n_rows ? m % tq : 0x7fffffff;  // padding rows: nothing to mask, results unused
     }
 
-    unsigned char* stage = stage_all + wave * kStageBytesS;
-    uint16_t* k_lds = reinterpret_cast<uint16_t*>(stage);
-    uint16_t* v_lds = reinterpret_cast<uint16_t*>(stage + kKBytesS);
     float2* cs = cs_all[wave];
+    float2 csr[2][8];                                // cos/sin of this lane's 16 pair slices, current segment
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) csr[kk][e] = make_float2(1.f, 0.f);
+    // transposing V reads: lane 16*lg + s addresses row 4*lg + s/4 (+16), 8 bytes at channel 16*db + 4*(s&3)
+    const int tr_row = 4 * lg + (li >> 2);
+    const uint32_t tr_base = (uint32_t)tr_row * 256 + 8 * (li & 3);
+    const uint32_t tr_x = (uint32_t)(tr_row & 7) * 32;
 
     f32x4 acc[NRB][8];
 #pragma unroll
@@ -744,13 +745,11 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
         }
     };
     __syncthreads();                                 // Q rows are in LDS
-    CF_STAMP(6);
 
     int cur_seg = -1;
-    bool first = true;
-    // One tile: rotate and stage `cur` from its registers, refill those registers with the tile after
-    // next, then do the math of `cur` out of LDS.
-    auto step = [&](Tile& cur, StageRegs& r) {
+    // One tile: rotate `cur` in its registers, S^T = K Q^T, refill the registers with the tile after
+    // next, softmax, O^T += V^T P^T out of the tile's LDS slot.
+    auto step = [&](Tile& cur, KRegs& r) {
         const Tile cd = cur;
         if (cd.seg != cur_seg) {
             if (cur_seg >= 0) emit(cur_seg);
@@ -761,65 +760,36 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
                 __builtin_amdgcn_wave_barrier();
                 cs[lane] = rope_cos_sin_fast(cd.delta, my_freq);
                 __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                    for (int e = 0; e < 8; e += 2) {
+                        const float4 w = *reinterpret_cast<const float4*>(&cs[32 * kk + 8 * lg + e]);
+                        csr[kk][e] = make_float2(w.x, w.y);
+                        csr[kk][e + 1] = make_float2(w.z, w.w);
+                    }
             }
         }
-        if (first) CF_STAMP(7);
-#ifdef CF_EXP_NOSTAGE
-        { uint32_t x = 0;
-          for (int it = 0; it < 4; ++it) x ^= r.ka[it].x ^ r.kb[it].y;
-          for (int it = 0; it < 2; ++it) for (int i = 0; i < 4; ++i) x ^= r.v[it][i].z;
-          if (x == 0x12345u) m_run[0] = 1.f;
-          fetch(cur, r); return; }
-#endif
-        // ---- stage K: rotate pairs (c, c + 64), round once, write [token][c]
+        // ---- rotate pairs (c, c + 64): channel blocks kk and kk + 2 of the same lane; round once
+        if (cd.delta != 0) {
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            uint4 ra = r.ka[it], rb4 = r.kb[it];
-            if (cd.delta != 0) {
-                uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb4.x, rb4.y, rb4.z, rb4.w};
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float a0 = Mma<DT>::lo(wa[i]), a1 = Mma<DT>::hi(wa[i]);
-                    const float b0 = Mma<DT>::lo(wb[i]), b1 = Mma<DT>::hi(wb[i]);
-                    const float2 w0 = cs[8 * kj + 2 * i], w1 = cs[8 * kj + 2 * i + 1];
-                    wa[i] = Mma<DT>::pack(a0 * w0.x - b0 * w0.y, a1 * w1.x - b1 * w1.y);
-                    wb[i] = Mma<DT>::pack(a0 * w0.y + b0 * w0.x, a1 * w1.y + b1 * w1.x);
+                for (int kk = 0; kk < 2; ++kk) {
+                    uint32_t wa[4] = {r.f[h][kk].x, r.f[h][kk].y, r.f[h][kk].z, r.f[h][kk].w};
+                    uint32_t wb[4] = {r.f[h][kk + 2].x, r.f[h][kk + 2].y, r.f[h][kk + 2].z, r.f[h][kk + 2].w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float a0 = Mma<DT>::lo(wa[i]), a1 = Mma<DT>::hi(wa[i]);
+                        const float b0 = Mma<DT>::lo(wb[i]), b1 = Mma<DT>::hi(wb[i]);
+                        const float2 w0 = csr[kk][2 * i], w1 = csr[kk][2 * i + 1];
+                        wa[i] = Mma<DT>::pack(a0 * w0.x - b0 * w0.y, a1 * w1.x - b1 * w1.y);
+                        wb[i] = Mma<DT>::pack(a0 * w0.y + b0 * w0.x, a1 * w1.y + b1 * w1.x);
+                    }
+                    r.f[h][kk] = make_uint4(wa[0], wa[1], wa[2], wa[3]);
+                    r.f[h][kk + 2] = make_uint4(wb[0], wb[1], wb[2], wb[3]);
                 }
-                ra = make_uint4(wa[0], wa[1], wa[2], wa[3]);
-                rb4 = make_uint4(wb[0], wb[1], wb[2], wb[3]);
-            }
-            uint16_t* dst = k_lds + (kt + 8 * it) * kSK + 8 * kj;
-            *reinterpret_cast<uint4*>(dst) = ra;
-            *reinterpret_cast<uint4*>(dst + kHalf) = rb4;
         }
-        // ---- stage V transposed: [channel][token]; the 8 tokens of MFMA k-group g — {4g..4g+3} and
-        // {16+4g..16+4g+3} — sit side by side
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int tk = 4 * (vq + 4 * it);
-            const int pos = ((tk & 15) >> 2) * 8 + (tk >> 4) * 4;
-            const uint32_t x0[4] = {r.v[it][0].x, r.v[it][0].y, r.v[it][0].z, r.v[it][0].w};
-            const uint32_t x1[4] = {r.v[it][1].x, r.v[it][1].y, r.v[it][1].z, r.v[it][1].w};
-            const uint32_t x2[4] = {r.v[it][2].x, r.v[it][2].y, r.v[it][2].z, r.v[it][2].w};
-            const uint32_t x3[4] = {r.v[it][3].x, r.v[it][3].y, r.v[it][3].z, r.v[it][3].w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                uint2 lo, hi;
-                lo.x = __builtin_amdgcn_perm(x1[i], x0[i], 0x05040100u);
-                lo.y = __builtin_amdgcn_perm(x3[i], x2[i], 0x05040100u);
-                hi.x = __builtin_amdgcn_perm(x1[i], x0[i], 0x07060302u);
-                hi.y = __builtin_amdgcn_perm(x3[i], x2[i], 0x07060302u);
-                *reinterpret_cast<uint2*>(v_lds + (8 * vj + 2 * i) * kSVs + pos) = lo;
-                *reinterpret_cast<uint2*>(v_lds + (8 * vj + 2 * i + 1) * kSVs + pos) = hi;
-            }
-        }
-        fetch(cur, r);                               // these registers are free again
-        __builtin_amdgcn_wave_barrier();
-        if (first) { CF_STAMP(2); first = false; }
-#ifdef CF_EXP_NOCOMPUTE
-        return;
-#endif
-
         const bool causal = cd.self != 0;
         const int nt = cd.ntok;
         // ---- S^T = K Q^T : lane (li, lg) gets, for query row li, tokens 16*tb + 4*lg + r
@@ -828,15 +798,15 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
         for (int rb = 0; rb < NRB; ++rb) { sc[rb][0] = f32x4{0.f, 0.f, 0.f, 0.f}; sc[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            const uint4 k0 = *reinterpret_cast<const uint4*>(k_lds + li * kSK + 32 * kk + 8 * lg);
-            const uint4 k1 = *reinterpret_cast<const uint4*>(k_lds + (16 + li) * kSK + 32 * kk + 8 * lg);
 #pragma unroll
             for (int rb = 0; rb < NRB; ++rb) {
                 const uint4 qv = *reinterpret_cast<const uint4*>(q_lds + (16 * rb + li) * kSK + 32 * kk + 8 * lg);
-                sc[rb][0] = Mma<DT>::run(k0, qv, sc[rb][0]);
-                sc[rb][1] = Mma<DT>::run(k1, qv, sc[rb][1]);
+                sc[rb][0] = Mma<DT>::run(r.f[0][kk], qv, sc[rb][0]);
+                sc[rb][1] = Mma<DT>::run(r.f[1][kk], qv, sc[rb][1]);
             }
         }
+        const unsigned char* vt = v_wave + cd.slot * kVTileBytes;
+        fetch(cur, r);                               // these registers are free again
         // ---- online softmax (exp2 domain), fp32
         const bool need_mask = causal || nt < kTileS;
         uint4 pfrag[NRB];
@@ -879,26 +849,24 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
             pfrag[rb] = make_uint4(Mma<DT>::pack(xv[0], xv[1]), Mma<DT>::pack(xv[2], xv[3]),
                                    Mma<DT>::pack(xv[4], xv[5]), Mma<DT>::pack(xv[6], xv[7]));
         }
-        // ---- O^T += V^T P^T
+        // ---- O^T += V^T P^T; V^T fragments by transposing reads of the row-major slot
 #pragma unroll
         for (int db = 0; db < 8; ++db) {
-            const uint4 va = *reinterpret_cast<const uint4*>(v_lds + (16 * db + li) * kSVs + 8 * lg);
+            const unsigned char* src = vt + tr_base + ((uint32_t)(32 * db) ^ tr_x);
+            const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(src));
+            const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(src + 16 * 256));
+            const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+            const uint4 va = make_uint4(l2.x, l2.y, h2.x, h2.y);
 #pragma unroll
             for (int rb = 0; rb < NRB; ++rb) acc[rb][db] = Mma<DT>::run(va, pfrag[rb], acc[rb][db]);
         }
-        __builtin_amdgcn_wave_barrier();
     };
-    if (kTwo) {
-        while (d0.ntok > 0) {
-            step(d0, regs0);
-            if (d1.ntok <= 0) break;
-            step(d1, regs1);
-        }
-    } else {
-        while (d0.ntok > 0) step(d0, regs0);
+    while (d0.ntok > 0) {
+        step(d0, regs0);
+        if (d1.ntok <= 0) break;
+        step(d1, regs1);
     }
     if (cur_seg >= 0) emit(cur_seg);
-    CF_STAMP(3);
 
     // ---- merge the four sub-splits of this workgroup (same rows, different tokens) through LDS
 #pragma unroll
@@ -907,7 +875,7 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
         tot += __shfl_xor(tot, 32);
         if (lg == 0) ml_w[wave][rb * 16 + li] = make_float2(m_run[rb], tot);
     }
-    __syncthreads();                                 // also: every wavefront is done with its staging slice
+    __syncthreads();                                 // also: every wavefront is done with its V slots
     float mx[NRB], zz[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
@@ -929,7 +897,7 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
     // the items it does not own in LDS, one barrier, then each owner adds the three parked copies to its
     // own (fixed order) and stores its items — the partial result of this workgroup, same format as the
     // shared-tile kernel with one row block per wavefront.
-    f32x4* red = reinterpret_cast<f32x4*>(stage_all);
+    f32x4* red = reinterpret_cast<f32x4*>(v_all);
     constexpr int kOwn = NRB * 2;                    // items per owner
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb)
@@ -959,7 +927,6 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
 #pragma unroll
         for (int rb = NRB; rb < 4; ++rb) ml[rb * 16 + li] = make_float2(-INFINITY, 0.f);   // row blocks that do not exist
     }
-    CF_STAMP(4);
 }
 
 // Second kernel: one workgroup per (unit, 64-row pass, quarter of the output channels) merges the
