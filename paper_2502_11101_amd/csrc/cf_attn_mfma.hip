@@ -21,6 +21,7 @@
 // fixed order and adds it to the accumulated scores.  Results cross between the kernels at the
 // kernel boundaries: no fences, no atomics on the data path, bit-identical reruns.
 #include <cstdlib>
+#include <type_traits>
 
 #include "cf_common.h"
 #include "cf_select_dev.h"
@@ -545,17 +546,18 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
 //   * K never touches LDS: a lane loads its key fragments straight in the MFMA operand layout
 //     (token = lane & 15 (+16), eight consecutive channels per 32-channel block), where the two
 //     halves (c, c + 64) of every RoPE pair sit in the same lane, and rotates them in registers;
-//   * V goes from memory to LDS without passing through registers (global_load_lds, 16 bytes per
-//     lane), row-major with a 32-byte XOR swizzle, and is read back as the V^T operand with the
-//     transposing LDS read (ds_read_b64_tr_b16), so no lane does any work to transpose it;
-//   * two tiles are in flight per wavefront (K in registers, V in a ring of three LDS slots); the
-//     streaming loop has no workgroup barrier;
+//   * V is copied as loaded (16 bytes per lane, row-major with a 32-byte XOR swizzle) into the
+//     wavefront's own LDS tile and read back as the V^T operand with the transposing LDS read
+//     (ds_read_b64_tr_b16), so no lane does any work to transpose it;
+//   * two tiles are in flight per wavefront, in registers, and every step issues a fixed number of
+//     loads, so the wait for one tile never covers a later one; the streaming loop has no
+//     workgroup barrier;
 //   * Q fragments are read from a shared LDS copy;
 //   * the four sub-splits of a workgroup are merged through LDS at the end, so one partial
 //     result per workgroup goes to memory.
 constexpr int kTileS = 32;
-constexpr int kVSlots = 3;                             // V tiles per wavefront in LDS
 constexpr int kVTileBytes = kTileS * kD * 2;           // 8192
+constexpr float kRescaleSlack = 8.f;                   // log2 of the largest probability kept relative to the running reference
 
 typedef short short4v __attribute__((ext_vector_type(4)));
 
@@ -569,9 +571,9 @@ __device__ __forceinline__ float2 rope_cos_sin_fast(int delta, double theta_rev)
 
 template <int DT, int NRB>
 __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFreq freq, Plan p) {
-    constexpr int kMergeBytes = 4 * 3 * NRB * 2 * kWave * 16;      // the end-of-kernel reduce-scatter reuses the V ring
-    constexpr int kRingBytes = kWaves * kVSlots * kVTileBytes;
-    __shared__ __attribute__((aligned(16))) unsigned char v_all[kRingBytes > kMergeBytes ? kRingBytes : kMergeBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char v_all[kWaves * kVTileBytes];   // one V tile per wavefront
+    constexpr int kPassRb = NRB <= 3 ? NRB : 2;      // row blocks merged per pass of the end-of-kernel reduce-scatter
+    __shared__ __attribute__((aligned(16))) unsigned char red_all[4 * 3 * kPassRb * 2 * kWave * 16];
     __shared__ __attribute__((aligned(16))) uint16_t q_lds[64 * kSK];
     __shared__ __attribute__((aligned(16))) float2 cs_all[kWaves][kHalf];
     __shared__ float2 ml_w[kWaves][64];
@@ -639,73 +641,101 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
     const int t_begin = split_begin(total, nsub, ss);
     const int t_end = split_begin(total, nsub, ss + 1);
 
-    const int64_t kv_row = (int64_t)a.n_kv_heads * kD;
-    const uint32_t row_bytes = (uint32_t)a.n_kv_heads * (kD * 2);      // between consecutive tokens of one head
-    struct KRegs { uint4 f[2][4]; };                 // [token li + 16*h][channels 32*kk + 8*lg ..]
-    struct Tile { int seg, tok0, ntok, delta, self, slot; };
-    KRegs regs0, regs1;
-    unsigned char* v_wave = v_all + wave * (kVSlots * kVTileBytes);
-
-    int next_tile = t_begin;
-    int next_slot = 0;
-    auto fetch = [&](Tile& d, KRegs& r) {            // ntok == 0 marks "no tile"
-        if (next_tile >= t_end) { d.ntok = 0; return; }
-        // the segment that owns this tile: first lane whose inclusive prefix exceeds it
-        const unsigned long long m = __ballot(t_incl > next_tile);
-        const int s = __builtin_ctzll(m);
-        const int incl = __builtin_amdgcn_readlane(t_incl, s), cnt = __builtin_amdgcn_readlane(t_cnt, s);
-        d.seg = s;
-        d.tok0 = (next_tile - (incl - cnt)) * kTileS;
-        d.ntok = min(kTileS, __builtin_amdgcn_readlane(t_vis, s) - d.tok0);
-        d.delta = __builtin_amdgcn_readlane(t_delta, s);
-        d.self = __builtin_amdgcn_readlane((int)t_self, s);
-        d.slot = next_slot;
-        const int64_t tok = ((int64_t)__builtin_amdgcn_readlane(t_tok_hi, s) << 32) | (uint32_t)__builtin_amdgcn_readlane(t_tok_lo, s);
-        ++next_tile;
-        next_slot = next_slot == kVSlots - 1 ? 0 : next_slot + 1;
-        const int64_t base = ((tok + d.tok0) * kv_row + (int64_t)hkv * kD) * 2;
-        const char* kb = static_cast<const char*>(d.self ? a.k_self : a.k_store) + base;
-        const char* vb = static_cast<const char*>(d.self ? a.v_self : a.v_store) + base;
-        // Rows past the end of a ragged tile re-read its last row: always in bounds, and their scores
-        // are masked out below.
-        const int last = d.ntok - 1;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t off = (uint32_t)min(li + 16 * h, last) * row_bytes + lg * 16;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) r.f[h][kk] = *reinterpret_cast<const uint4*>(kb + off + 64 * kk);
-        }
-        // V: instruction n drops rows 4n..4n+3 (16 lanes of 16 bytes each) at byte n*1024 of the slot;
-        // the lane at LDS chunk c' of row t fetches memory chunk c' ^ 2*(t & 7)
-        unsigned char* slot = v_wave + d.slot * kVTileBytes;
-#pragma unroll
-        for (int n = 0; n < 8; ++n) {
-            const int t = 4 * n + (lane >> 4);
-            const int c = (lane & 15) ^ (2 * (t & 7));
-            const uint32_t off = (uint32_t)min(t, last) * row_bytes + 16 * c;
-            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(vb + off),
-                                             (uint32_t __attribute__((address_space(3)))*)(slot + n * 1024), 16, 0, 0);
-        }
-    };
-    Tile d0, d1;
-    d0.seg = d1.seg = 0; d0.tok0 = d1.tok0 = 0; d0.ntok = d1.ntok = 0; d0.delta = d1.delta = 0; d0.self = d1.self = 0; d0.slot = d1.slot = 0;
-    fetch(d0, regs0);                                // the loads go out before anything else
-    fetch(d1, regs1);
-
-    // ---- Q rows of this kv head into LDS: row m = g*tq + t of the stack is q[q0 + t][hkv*group + g]
+    // ---- Q rows of this kv head: row m = g*tq + t of the stack is q[q0 + t][hkv*group + g].  Their loads go
+    // out first: loads return in order, so the LDS copy below then waits for them and not for the tiles.
+    uint4 qv[4];
+    const int q_row = tid >> 2, q_part = tid & 3;    // 64 rows x 4 quarters of 64 bytes
     {
-        const int row = tid >> 2, part = tid & 3;    // 64 rows x 4 quarters of 64 bytes
-        uint4 qv[4];
-        const bool valid = row < n_rows && row < NRB * 16;
-        const int gi = valid ? row / tq : 0;
-        const int t = valid ? row - gi * tq : 0;
-        const uint16_t* qp = static_cast<const uint16_t*>(a.q) + (((int64_t)q0 + t) * hq + hkv * group + gi) * kD + 32 * part;
+        const bool valid = q_row < n_rows && q_row < NRB * 16;
+        const int gi = valid ? q_row / tq : 0;
+        const int t = valid ? q_row - gi * tq : 0;
+        const uint16_t* qp = static_cast<const uint16_t*>(a.q) + (((int64_t)q0 + t) * hq + hkv * group + gi) * kD + 32 * q_part;
 #pragma unroll
         for (int i = 0; i < 4; ++i) qv[i] = valid ? *reinterpret_cast<const uint4*>(qp + 8 * i) : make_uint4(0, 0, 0, 0);
-        if (row < NRB * 16) {
+    }
+    const int64_t kv_row = (int64_t)a.n_kv_heads * kD;
+    const uint32_t row_bytes = (uint32_t)a.n_kv_heads * (kD * 2);      // between consecutive tokens of one head
+    // One tile in registers: K in the MFMA operand layout ([token li + 16*h][channels 32*kk + 8*lg ..]) and
+    // V as loaded (instruction n: row 4n + (lane >> 4), 16-byte chunk lane & 15).
+    struct TileRegs { uint4 f[2][4]; uint4 v[8]; };
+    struct Tile { int seg, tok0, ntok, delta, self; int64_t base; };
+    TileRegs regs0, regs1;
+    unsigned char* const v_lds = v_all + wave * kVTileBytes;
+
+    // byte offsets of this lane's loads inside a whole tile (K: rows li, li + 16; V: rows (lane >> 4) + 4n)
+    uint32_t k_off[2];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(q_lds + row * kSK + 32 * part + 8 * i) = qv[i];
+    for (int h = 0; h < 2; ++h) k_off[h] = (uint32_t)(li + 16 * h) * row_bytes + lg * 16;
+    const uint32_t v_off = (uint32_t)(lane >> 4) * row_bytes + 16 * (lane & 15);
+
+    int next_tile = t_begin;
+    // Every step issues the same sixteen loads whether or not a tile is left (without one they re-read the
+    // first bytes of the workspace), so the number of loads in flight at any point of the loop is fixed
+    // and waiting for one tile's data never means waiting for a later tile's.
+    auto describe = [&](Tile& d) {                   // ntok == 0 marks "no tile"
+        if (next_tile < t_end) {
+            // the segment that owns this tile: first lane whose inclusive prefix exceeds it
+            const unsigned long long m = __ballot(t_incl > next_tile);
+            const int s = __builtin_ctzll(m);
+            const int incl = __builtin_amdgcn_readlane(t_incl, s), cnt = __builtin_amdgcn_readlane(t_cnt, s);
+            d.seg = s;
+            d.tok0 = (next_tile - (incl - cnt)) * kTileS;
+            d.ntok = min(kTileS, __builtin_amdgcn_readlane(t_vis, s) - d.tok0);
+            d.delta = __builtin_amdgcn_readlane(t_delta, s);
+            d.self = __builtin_amdgcn_readlane((int)t_self, s);
+            const int64_t tok = ((int64_t)__builtin_amdgcn_readlane(t_tok_hi, s) << 32) | (uint32_t)__builtin_amdgcn_readlane(t_tok_lo, s);
+            d.base = ((tok + d.tok0) * kv_row + (int64_t)hkv * kD) * 2;
+            ++next_tile;
+        } else {
+            d.seg = 0; d.tok0 = 0; d.ntok = 0; d.delta = 0; d.self = 0; d.base = 0;
         }
+    };
+    // Rows past the end of a ragged tile re-read its last row: always in bounds, and their scores are
+    // masked out below.
+    auto fetch_k = [&](const Tile& d, TileRegs& r) {
+        const char* kb = static_cast<const char*>(a.workspace);
+        uint32_t ko[2] = {0, 0};
+        if (d.ntok == kTileS) {
+            ko[0] = k_off[0];
+            ko[1] = k_off[1];
+        } else if (d.ntok > 0) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) ko[h] = (uint32_t)min(li + 16 * h, d.ntok - 1) * row_bytes + lg * 16;
+        }
+        if (d.ntok > 0) kb = static_cast<const char*>(d.self ? a.k_self : a.k_store) + d.base;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) r.f[h][kk] = *reinterpret_cast<const uint4*>(kb + ko[h] + 64 * kk);
+    };
+    auto fetch_v = [&](const Tile& d, TileRegs& r) {
+        const char* vb = static_cast<const char*>(a.workspace);
+        uint32_t vo[8];
+        if (d.ntok == kTileS) {
+#pragma unroll
+            for (int n = 0; n < 8; ++n) vo[n] = v_off + (uint32_t)n * (4 * row_bytes);
+        } else if (d.ntok > 0) {
+#pragma unroll
+            for (int n = 0; n < 8; ++n) vo[n] = (uint32_t)min(4 * n + (lane >> 4), d.ntok - 1) * row_bytes + 16 * (lane & 15);
+        } else {
+#pragma unroll
+            for (int n = 0; n < 8; ++n) vo[n] = 0;
+        }
+        if (d.ntok > 0) vb = static_cast<const char*>(d.self ? a.v_self : a.v_store) + d.base;
+#pragma unroll
+        for (int n = 0; n < 8; ++n) r.v[n] = *reinterpret_cast<const uint4*>(vb + vo[n]);
+    };
+    Tile d0, d1;
+    describe(d0);
+    fetch_k(d0, regs0);
+    fetch_v(d0, regs0);
+    describe(d1);
+    fetch_k(d1, regs1);
+    fetch_v(d1, regs1);
+
+    if (q_row < NRB * 16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(q_lds + q_row * kSK + 32 * q_part + 8 * i) = qv[i];
     }
     int trow[NRB];
 #pragma unroll
@@ -715,15 +745,18 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
     }
 
     float2* cs = cs_all[wave];
-    float2 csr[2][8];                                // cos/sin of this lane's 16 pair slices, current segment
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) csr[kk][e] = make_float2(1.f, 0.f);
     // transposing V reads: lane 16*lg + s addresses row 4*lg + s/4 (+16), 8 bytes at channel 16*db + 4*(s&3)
     const int tr_row = 4 * lg + (li >> 2);
     const uint32_t tr_base = (uint32_t)tr_row * 256 + 8 * (li & 3);
     const uint32_t tr_x = (uint32_t)(tr_row & 7) * 32;
+    // V staging: row-major [token][256 bytes], the 16-byte chunk c of row t at chunk c ^ 2*(t & 7) (a
+    // 32-byte XOR swizzle: the transposing reads of one pass then fall on distinct banks)
+    uint32_t vw_off[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int t = 4 * h + (lane >> 4);
+        vw_off[h] = (uint32_t)t * 256 + 16 * ((lane & 15) ^ (2 * (t & 7)));
+    }
 
     f32x4 acc[NRB][8];
 #pragma unroll
@@ -747,9 +780,9 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
     __syncthreads();                                 // Q rows are in LDS
 
     int cur_seg = -1;
-    // One tile: rotate `cur` in its registers, S^T = K Q^T, refill the registers with the tile after
-    // next, softmax, O^T += V^T P^T out of the tile's LDS slot.
-    auto step = [&](Tile& cur, KRegs& r) {
+    // One tile: rotate `cur` in its registers, S^T = K Q^T, refill the K registers with the tile after
+    // next, softmax, V registers to LDS and refilled, O^T += V^T P^T by transposing LDS reads.
+    auto step = [&](Tile& cur, TileRegs& r) {
         const Tile cd = cur;
         if (cd.seg != cur_seg) {
             if (cur_seg >= 0) emit(cur_seg);
@@ -760,35 +793,31 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
                 __builtin_amdgcn_wave_barrier();
                 cs[lane] = rope_cos_sin_fast(cd.delta, my_freq);
                 __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-                    for (int e = 0; e < 8; e += 2) {
-                        const float4 w = *reinterpret_cast<const float4*>(&cs[32 * kk + 8 * lg + e]);
-                        csr[kk][e] = make_float2(w.x, w.y);
-                        csr[kk][e + 1] = make_float2(w.z, w.w);
-                    }
             }
         }
         // ---- rotate pairs (c, c + 64): channel blocks kk and kk + 2 of the same lane; round once
         if (cd.delta != 0) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int kk = 0; kk < 2; ++kk) {
+                float4 w[4];                         // (cos, sin) of slices 32*kk + 8*lg + 2i, + 2i + 1
 #pragma unroll
-                for (int kk = 0; kk < 2; ++kk) {
+                for (int i = 0; i < 4; ++i) w[i] = *reinterpret_cast<const float4*>(&cs[32 * kk + 8 * lg + 2 * i]);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
                     uint32_t wa[4] = {r.f[h][kk].x, r.f[h][kk].y, r.f[h][kk].z, r.f[h][kk].w};
                     uint32_t wb[4] = {r.f[h][kk + 2].x, r.f[h][kk + 2].y, r.f[h][kk + 2].z, r.f[h][kk + 2].w};
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const float a0 = Mma<DT>::lo(wa[i]), a1 = Mma<DT>::hi(wa[i]);
                         const float b0 = Mma<DT>::lo(wb[i]), b1 = Mma<DT>::hi(wb[i]);
-                        const float2 w0 = csr[kk][2 * i], w1 = csr[kk][2 * i + 1];
+                        const float2 w0 = make_float2(w[i].x, w[i].y), w1 = make_float2(w[i].z, w[i].w);
                         wa[i] = Mma<DT>::pack(a0 * w0.x - b0 * w0.y, a1 * w1.x - b1 * w1.y);
                         wb[i] = Mma<DT>::pack(a0 * w0.y + b0 * w0.x, a1 * w1.y + b1 * w1.x);
                     }
                     r.f[h][kk] = make_uint4(wa[0], wa[1], wa[2], wa[3]);
                     r.f[h][kk + 2] = make_uint4(wb[0], wb[1], wb[2], wb[3]);
                 }
+            }
         }
         const bool causal = cd.self != 0;
         const int nt = cd.ntok;
@@ -805,8 +834,9 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
                 sc[rb][1] = Mma<DT>::run(r.f[1][kk], qv, sc[rb][1]);
             }
         }
-        const unsigned char* vt = v_wave + cd.slot * kVTileBytes;
-        fetch(cur, r);                               // these registers are free again
+        Tile nx;
+        describe(nx);
+        fetch_k(nx, r);                              // the K registers are free again
         // ---- online softmax (exp2 domain), fp32
         const bool need_mask = causal || nt < kTileS;
         uint4 pfrag[NRB];
@@ -825,34 +855,48 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
                     xv[e] = ok ? xv[e] : -INFINITY;
                 }
             }
+            // The running reference m_run is a stale row maximum: it only moves when some score of the
+            // row exceeds it by more than 8 (in the exp2 domain), so probabilities stay below 2^8 and the
+            // accumulators are rescaled a handful of times per row instead of once per tile.  Every sum
+            // kept beside it (l_run, seg_l, acc) is relative to the same reference, so the results are
+            // those of the exact maximum.
             float mloc = fmaxf(fmaxf(fmaxf(xv[0], xv[1]), fmaxf(xv[2], xv[3])), fmaxf(fmaxf(xv[4], xv[5]), fmaxf(xv[6], xv[7])));
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
             mloc *= a.scale_log2e;                       // scale > 0: max commutes with it
-            const float m_old = m_run[rb];
-            const float m_new = fmaxf(m_old, mloc);
-            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_old - m_safe);
+            if (__any(mloc > m_run[rb] + kRescaleSlack)) {
+                mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+                mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+                const float m_old = m_run[rb];
+                const float m_new = fmaxf(m_old, mloc);
+                const float alpha = __builtin_amdgcn_exp2f(m_old - (m_new == -INFINITY ? 0.f : m_new));
+                l_run[rb] *= alpha;
+                seg_l[rb] *= alpha;
+                m_run[rb] = m_new;
+                if (__any(alpha != 1.f && m_old != -INFINITY)) {     // nothing accumulated yet: nothing to rescale
+#pragma unroll
+                    for (int db = 0; db < 8; ++db) acc[rb][db] *= alpha;
+                }
+            }
+            const float m_safe = m_run[rb] == -INFINITY ? 0.f : m_run[rb];
             float lsum = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 xv[e] = __builtin_amdgcn_exp2f(fmaf(xv[e], a.scale_log2e, -m_safe));
                 lsum += xv[e];
             }
-            l_run[rb] = l_run[rb] * alpha + lsum;
-            seg_l[rb] = seg_l[rb] * alpha + lsum;
-            m_run[rb] = m_new;
-            if (__any(alpha != 1.f && m_old != -INFINITY)) {     // nothing accumulated yet: nothing to rescale
-#pragma unroll
-                for (int db = 0; db < 8; ++db) acc[rb][db] *= alpha;
-            }
+            l_run[rb] += lsum;
+            seg_l[rb] += lsum;
             pfrag[rb] = make_uint4(Mma<DT>::pack(xv[0], xv[1]), Mma<DT>::pack(xv[2], xv[3]),
                                    Mma<DT>::pack(xv[4], xv[5]), Mma<DT>::pack(xv[6], xv[7]));
         }
-        // ---- O^T += V^T P^T; V^T fragments by transposing reads of the row-major slot
+        // ---- V to LDS (the wavefront's own tile buffer; its previous contents were read by the last step)
+#pragma unroll
+        for (int n = 0; n < 8; ++n) *reinterpret_cast<uint4*>(v_lds + (n >> 1) * 2048 + vw_off[n & 1]) = r.v[n];
+        fetch_v(nx, r);                              // the V registers are free again
+        cur = nx;
+        // ---- O^T += V^T P^T; V^T fragments by transposing reads of the row-major tile
 #pragma unroll
         for (int db = 0; db < 8; ++db) {
-            const unsigned char* src = vt + tr_base + ((uint32_t)(32 * db) ^ tr_x);
+            const unsigned char* src = v_lds + tr_base + ((uint32_t)(32 * db) ^ tr_x);
             const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(src));
             const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(src + 16 * 256));
             const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
@@ -875,7 +919,7 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
         tot += __shfl_xor(tot, 32);
         if (lg == 0) ml_w[wave][rb * 16 + li] = make_float2(m_run[rb], tot);
     }
-    __syncthreads();                                 // also: every wavefront is done with its V slots
+    __syncthreads();
     float mx[NRB], zz[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
@@ -886,40 +930,62 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
         const float ms = m == -INFINITY ? 0.f : m;
         float z = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) z += ml_w[w][row].y * exp2f(ml_w[w][row].x - ms);
+        for (int w = 0; w < kWaves; ++w) z += ml_w[w][row].y * __builtin_amdgcn_exp2f(ml_w[w][row].x - ms);
         mx[rb] = m;
         zz[rb] = z;
-        const float f = exp2f(m_run[rb] - ms);
+        const float f = __builtin_amdgcn_exp2f(m_run[rb] - ms);
 #pragma unroll
         for (int db = 0; db < 8; ++db) acc[rb][db] *= f;
     }
-    // Reduce-scatter: item j = (row block, channel block) belongs to wavefront j % 4; every wavefront parks
-    // the items it does not own in LDS, one barrier, then each owner adds the three parked copies to its
-    // own (fixed order) and stores its items — the partial result of this workgroup, same format as the
-    // shared-tile kernel with one row block per wavefront.
-    f32x4* red = reinterpret_cast<f32x4*>(v_all);
-    constexpr int kOwn = NRB * 2;                    // items per owner
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-        for (int db = 0; db < 8; ++db) {
-            const int j = rb * 8 + db, o = j & 3;
-            if (o != wave) red[(((o * 3 + ((wave - o - 1) & 3)) * kOwn) + (j >> 2)) * kWave + lane] = acc[rb][db];
-        }
-    __syncthreads();
+    // Reduce-scatter, kPassRb row blocks per pass: item j = (row block, channel block) of the pass belongs
+    // to wavefront j % 4; every wavefront parks the items it does not own in LDS, one barrier, then each
+    // owner adds the three parked copies to its own (fixed order) and stores its items — the partial
+    // result of this workgroup, same format as the shared-tile kernel with one row block per wavefront.
+    f32x4* red = reinterpret_cast<f32x4*>(red_all);
+    constexpr int kOwn = kPassRb * 2;                // items per owner and pass
     f32x4* opart = reinterpret_cast<f32x4*>(ws + p.off_opart) + ((int64_t)unit * p.nsplit + split) * 4 * 8 * kWave + lane;
+    auto park = [&](auto w_, int rb0) {              // specialised per wavefront: straight-line code
+        constexpr int W = decltype(w_)::value;
 #pragma unroll
-    for (int rb = 0; rb < NRB; ++rb)
+        for (int r = 0; r < kPassRb; ++r)
 #pragma unroll
-        for (int db = 0; db < 8; ++db) {
-            const int j = rb * 8 + db;
-            if ((j & 3) == wave) {
-                f32x4 v = acc[rb][db];
-#pragma unroll
-                for (int r = 0; r < 3; ++r) v += red[(((wave * 3 + r) * kOwn) + (j >> 2)) * kWave + lane];
-                opart[j * kWave] = v;
+            for (int db = 0; db < 8; ++db) {
+                const int j = r * 8 + db, o = j & 3;
+                if (o != W) red[(((o * 3 + ((W - o - 1) & 3)) * kOwn) + (j >> 2)) * kWave + lane] = acc[rb0 + r][db];
             }
+    };
+    auto gather = [&](auto w_, int rb0) {
+        constexpr int W = decltype(w_)::value;
+#pragma unroll
+        for (int r = 0; r < kPassRb; ++r)
+#pragma unroll
+            for (int db = 0; db < 8; ++db) {
+                const int j = r * 8 + db;
+                if ((j & 3) == W) {
+                    f32x4 v = acc[rb0 + r][db];
+#pragma unroll
+                    for (int c = 0; c < 3; ++c) v += red[(((W * 3 + c) * kOwn) + (j >> 2)) * kWave + lane];
+                    opart[((rb0 + r) * 8 + db) * kWave] = v;
+                }
+            }
+    };
+#pragma unroll
+    for (int rb0 = 0; rb0 < NRB; rb0 += kPassRb) {
+        if (rb0 > 0) __syncthreads();                // the previous pass has been read
+        switch (wave) {
+            case 0: park(std::integral_constant<int, 0>{}, rb0); break;
+            case 1: park(std::integral_constant<int, 1>{}, rb0); break;
+            case 2: park(std::integral_constant<int, 2>{}, rb0); break;
+            default: park(std::integral_constant<int, 3>{}, rb0); break;
         }
+        __syncthreads();
+        switch (wave) {
+            case 0: gather(std::integral_constant<int, 0>{}, rb0); break;
+            case 1: gather(std::integral_constant<int, 1>{}, rb0); break;
+            case 2: gather(std::integral_constant<int, 2>{}, rb0); break;
+            default: gather(std::integral_constant<int, 3>{}, rb0); break;
+        }
+    }
     if (wave == 0 && lg == 0) {
         float2* ml = reinterpret_cast<float2*>(ws + p.off_ml) + ((int64_t)unit * p.nsplit + split) * 64;
 #pragma unroll
