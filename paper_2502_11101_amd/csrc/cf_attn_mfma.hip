@@ -99,17 +99,9 @@ Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_str
     p.off_massml = take((size_t)p.units * p.slots * p.rows_wg * sizeof(float2));
     p.off_masspart = take((size_t)p.units * p.nrb * p.slots * sizeof(float));
     p.total = off;
-#ifdef CF_TRACE
-    p.total += (size_t)(p.x_count * p.n_rg + p.units * p.nrb * 4 + batch * p.mass_chunks) * 16 * 8;
-#endif
     return p;
 }
 
-#ifdef CF_TRACE
-#define CF_STAMP(k) do { if (threadIdx.x == 0) trace[(k)] = wall_clock64(); } while (0)
-#else
-#define CF_STAMP(k) do {} while (0)
-#endif
 
 // Per-query segment table in LDS with the tile prefix that defines the partition.
 struct SegTable {
@@ -117,6 +109,7 @@ struct SegTable {
     int32_t vis[kMaxSegs];      // visible tokens (0 for a rejected entry)
     int32_t delta[kMaxSegs];    // relative shift: (new - stored) - (q_new - q_stored)
     int32_t self[kMaxSegs];     // 1 for the causal own block
+    int32_t doc[kMaxSegs];      // document slot of the entry (-1: none)
     int32_t tile0[kMaxSegs + 1];// exclusive prefix of tile counts
     int32_t n;
 };
@@ -163,6 +156,7 @@ __device__ __forceinline__ void build_table(const AttnArgs& a, const QueryHead& 
         t->vis[tid] = vis;
         t->delta[tid] = seg.new_start - seg.stored_start - h.qdelta;
         t->self[tid] = self ? 1 : 0;
+        t->doc[tid] = seg.doc;
         t->tile0[tid + 1] = (vis + tile_tokens - 1) / tile_tokens;
     }
     if (tid == 0) { t->n = n; t->tile0[0] = 0; }
@@ -229,11 +223,6 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
     const int li = lane & 15, lg = lane >> 4;
-#ifdef CF_TRACE
-    long long* trace = reinterpret_cast<long long*>(static_cast<char*>(a.workspace) + p.total) -
-                       (size_t)(p.x_count * p.n_rg + p.units * p.nrb * 4 + a.batch * p.mass_chunks) * 16 + (size_t)blockIdx.x * 16;
-#endif
-    CF_STAMP(0);
     // Pull every pointer and scalar the streaming loop needs out of the kernel-argument segment
     // now, in one batch of scalar loads, instead of one dependent round trip per first use.
     {
@@ -262,7 +251,6 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
     const int q0 = qh.q0, tq_raw = qh.tq_raw;
 
     build_table(a, qh, &tbl, kTile);
-    CF_STAMP(1);
 
     const int tq = min(tq_raw, a.max_tq);
     const int n_rows = group * tq;
@@ -374,7 +362,6 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
 
     int cs_slot = 0;
     int cur_seg = -1;
-    bool first = true;
     if (d0.ntok > 0 && tid < kHalf) cs_lds[0][tid] = rope_cos_sin(tbl.delta[d0.seg], my_freq);
 
     // One tile: stage `cur` from its registers, refill those registers with the tile after `nxt`,
@@ -439,7 +426,6 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
             if (tid < kHalf) cs_lds[cs_slot][tid] = rope_cos_sin(tbl.delta[nxt.seg], my_freq);
         }
         __syncthreads();            // staged tile visible
-        if (first) { CF_STAMP(2); first = false; }
 
         const bool causal = tbl.self[cd.seg] != 0;
 #pragma unroll
@@ -519,7 +505,6 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
         while (d0.ntok > 0) step(d0, regs0, d0);      // `nxt` is read after the refill: the same object serves
     }
     if (cur_seg >= 0) emit(cur_seg);
-    CF_STAMP(3);
 
     // ---- partial results of this split: O^T in MFMA layout (one float4 per lane, row block and
     // channel block) and (max, sum) per row
@@ -534,7 +519,6 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
         tot += __shfl_xor(tot, 32);
         if (lg == 0) ml[(wave * NRB + rb) * 16 + li] = make_float2(m_run[rb], tot);
     }
-    CF_STAMP(4);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -995,14 +979,15 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
     }
 }
 
-// Second kernel: one workgroup per (unit, 64-row pass, quarter of the output channels) merges the
-// splits' partial outputs and writes its output rows; the four workgroups of a (unit, pass) also share
+// Second kernel: one workgroup per (unit, 64-row pass, eighth of the output channels) merges the
+// splits' partial outputs and writes its output rows; the eight workgroups of a (unit, pass) also share
 // the reduction, over the pass's 64 rows, of every (segment, sub-split) slot's (max, sum) pairs to
 // sum * exp2(max - row max) / row sum, which the mass kernel then only has to add up.
 template <int DT>
 __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan p) {
     __shared__ float2 mlw[kMaxSplit * 64];       // (m, l) per split and row, then the split's weight in .x
     __shared__ float2 rstat[64];                 // (max, 1/sum) per row of this pass
+    constexpr int kPre = 8;                      // splits whose partial outputs are fetched before the statistics are ready
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -1010,26 +995,37 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     const int li = lane & 15, lg = lane >> 4;
     char* ws = static_cast<char*>(a.workspace);
     const int hq = a.n_q_heads, group = hq / a.n_kv_heads;
-#ifdef CF_TRACE
-    long long* trace = reinterpret_cast<long long*>(ws + p.total) -
-                       (size_t)(p.units * p.nrb * 4 + a.batch * p.mass_chunks) * 16 + (size_t)blockIdx.x * 16;
-#endif
-    CF_STAMP(0);
-    const int dbq = blockIdx.x & 3;
-    const int pass = (blockIdx.x >> 2) % p.nrb;
-    const int unit = blockIdx.x / (4 * p.nrb);
+    const int dbq = blockIdx.x & 7;
+    const int pass = (blockIdx.x >> 3) % p.nrb;
+    const int unit = blockIdx.x / (8 * p.nrb);
     const int rg = unit % p.n_rg;
     const int hkv = (unit / p.n_rg) % a.n_kv_heads;
     const int b = unit / p.units_per_b;
-    const int q0 = a.q_off[b];
-    const int tq = min(a.q_off[b + 1] - q0, a.max_tq);
+    const int q0 = a.q_off[b], q1 = a.q_off[b + 1];
+    const float2* ml = reinterpret_cast<const float2*>(ws + p.off_ml) + (int64_t)unit * p.nsplit * p.rows_wg + pass * 64;
+    const f32x4* opart = reinterpret_cast<const f32x4*>(ws + p.off_opart) + (int64_t)unit * p.nsplit * p.rows_wg * (kD / 4);
+    const int blk = pass * kWaves + wave;                      // row block inside the workgroup tile
+    const f32x4* src = opart + ((int64_t)blk * 8 + dbq) * kWave + lane;
+    const int64_t split_stride = (int64_t)p.rows_wg / 16 * 8 * kWave;
+    const float2* massml = reinterpret_cast<const float2*>(ws + p.off_massml) + (int64_t)unit * p.slots * p.rows_wg + pass * 64 + lane;
+    const int k_first = dbq * kWaves + wave, k_step = 8 * kWaves;
+
+    // Everything this workgroup reads is requested up front — row statistics, partial outputs of the
+    // first splits, the first slot statistics — so the three round trips to memory overlap.
+    for (int idx = tid; idx < p.nsplit * 64; idx += kThreads) mlw[idx] = ml[(idx >> 6) * p.rows_wg + (idx & 63)];
+    f32x4 pre[kPre];
+#pragma unroll
+    for (int s = 0; s < kPre; ++s) pre[s] = s < p.nsplit ? src[s * split_stride] : f32x4{0.f, 0.f, 0.f, 0.f};
+    float2 sv[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int k = k_first + j * k_step;
+        sv[j] = k < p.slots ? massml[(int64_t)k * p.rows_wg] : make_float2(0.f, 0.f);
+    }
+    const int tq = min(q1 - q0, a.max_tq);
     const int n_rows = group * tq;
     const int row_base = rg * p.blocks_rg * 16;
     const int rows_here = min(p.blocks_rg * 16, n_rows - row_base);
-    const float2* ml = reinterpret_cast<const float2*>(ws + p.off_ml) + (int64_t)unit * p.nsplit * p.rows_wg + pass * 64;
-    const f32x4* opart = reinterpret_cast<const f32x4*>(ws + p.off_opart) + (int64_t)unit * p.nsplit * p.rows_wg * (kD / 4);
-
-    for (int idx = tid; idx < p.nsplit * 64; idx += kThreads) mlw[idx] = ml[(idx >> 6) * p.rows_wg + (idx & 63)];
     __syncthreads();
     if (tid < 64) {
         float m = -INFINITY;
@@ -1042,52 +1038,34 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
         rstat[tid] = make_float2(ms, pass * 64 + tid < rows_here ? iz : 0.f);    // padding rows carry no mass
     }
     __syncthreads();
-    const int blk = pass * kWaves + wave;                      // row block inside the workgroup tile
-    f32x4 o0 = f32x4{0.f, 0.f, 0.f, 0.f}, o1 = o0;
-    const f32x4* src = opart + ((int64_t)blk * 8 + 2 * dbq) * kWave + lane;
-    const int64_t split_stride = (int64_t)p.rows_wg / 16 * 8 * kWave;
-#pragma unroll 8
-    for (int s = 0; s < p.nsplit; ++s) {
-        const float w = mlw[s * 64 + wave * 16 + li].x;
-        const f32x4 v0 = src[s * split_stride], v1 = src[s * split_stride + kWave];
-        o0 += v0 * w;
-        o1 += v1 * w;
-    }
+    f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < kPre; ++s)
+        if (s < p.nsplit) o += pre[s] * mlw[s * 64 + wave * 16 + li].x;
+    for (int s = kPre; s < p.nsplit; ++s) o += src[s * split_stride] * mlw[s * 64 + wave * 16 + li].x;
     const int lrow = pass * 64 + wave * 16 + li;
     if (lrow < rows_here) {
         const int m2 = row_base + lrow;
         const int gi = m2 / tq, t = m2 - gi * tq;
-        uint16_t* op = static_cast<uint16_t*>(a.out) + (((int64_t)q0 + t) * hq + hkv * group + gi) * kD + 32 * dbq + 4 * lg;
+        uint16_t* op = static_cast<uint16_t*>(a.out) + (((int64_t)q0 + t) * hq + hkv * group + gi) * kD + 16 * dbq + 4 * lg;
         uint2 pk;
-        pk.x = Mma<DT>::pack(o0[0], o0[1]);
-        pk.y = Mma<DT>::pack(o0[2], o0[3]);
+        pk.x = Mma<DT>::pack(o[0], o[1]);
+        pk.y = Mma<DT>::pack(o[2], o[3]);
         *reinterpret_cast<uint2*>(op) = pk;
-        pk.x = Mma<DT>::pack(o1[0], o1[1]);
-        pk.y = Mma<DT>::pack(o1[2], o1[3]);
-        *reinterpret_cast<uint2*>(op + 16) = pk;
     }
     // slot partials: slot k = segment + sub-split; slots no sub-split wrote this call hold stale pairs and
     // give meaningless numbers that the mass kernel never reads
     {
-        const float2* massml = reinterpret_cast<const float2*>(ws + p.off_massml) + (int64_t)unit * p.slots * p.rows_wg + pass * 64 + lane;
         float* masspart = reinterpret_cast<float*>(ws + p.off_masspart) + ((int64_t)unit * p.nrb + pass) * p.slots;
         const float2 st = rstat[lane];
-        for (int k0 = dbq * kWaves + wave; k0 < p.slots; k0 += 4 * 4 * kWaves) {
-            float2 v[4];
+        auto reduce = [&](int k, float2 v) {
+            const float c = wave_sum(st.y > 0.f ? v.y * exp2f(v.x - st.x) * st.y : 0.f);
+            if (lane == 0 && k < p.slots) masspart[k] = c;
+        };
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int k = k0 + j * 4 * kWaves;
-                v[j] = k < p.slots ? massml[(int64_t)k * p.rows_wg] : make_float2(0.f, 0.f);
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int k = k0 + j * 4 * kWaves;
-                const float c = wave_sum(st.y > 0.f ? v[j].y * exp2f(v[j].x - st.x) * st.y : 0.f);
-                if (lane == 0 && k < p.slots) masspart[k] = c;
-            }
-        }
+        for (int j = 0; j < 2; ++j) reduce(k_first + j * k_step, sv[j]);
+        for (int k = k_first + 2 * k_step; k < p.slots; k += k_step) reduce(k, massml[(int64_t)k * p.rows_wg]);
     }
-    CF_STAMP(1);
 }
 
 // Mass of segment s of query b: the slot partials of every (unit, pass) and every sub-split that
@@ -1116,11 +1094,6 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p)
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
     const char* ws = static_cast<const char*>(a.workspace);
-#ifdef CF_TRACE
-    long long* trace = reinterpret_cast<long long*>(static_cast<char*>(a.workspace) + p.total) -
-                       (size_t)(a.batch * p.mass_chunks) * 16 + (size_t)blockIdx.x * 16;
-#endif
-    CF_STAMP(0);
     const int b = __builtin_amdgcn_readfirstlane(blockIdx.x / p.mass_chunks);
     const int chunk = blockIdx.x % p.mass_chunks;
     const QueryHead qh = load_query_head(a, b);
@@ -1137,7 +1110,6 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p)
                 atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], m);
         }
     }
-    CF_STAMP(1);
 }
 
 // Fused layer epilogue (third kernel of cf_prefill_layer): one workgroup per query computes the
@@ -1165,49 +1137,77 @@ struct PruneArgs {
     int32_t* next_n_seg;
 };
 
+// Every per-document row of the query (scores, lengths, candidates, offsets, positions) and the slot
+// partial masses are fetched into LDS in one batch at the start: the ranking, the allocation and the
+// table rebuild then run out of LDS with workgroup barriers between them instead of a round trip
+// through memory per stage, and the results are written back at the end.
+// Dynamic LDS: 44*stride + 4*parts*slots bytes; larger problems take the stand-alone kernels.
 __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a, Plan p, PruneArgs pr) {
-    extern __shared__ unsigned char dyn_smem[];          // 3*stride words for the ranking / allocation
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
     __shared__ SegTable tbl;
-    __shared__ int s_int[4];
+    __shared__ int s_int[6];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
     const int n_waves = kEpiThreads / kWave;
+    const int stride = pr.stride;
+    int64_t* l_tok = reinterpret_cast<int64_t*>(dyn_smem);
+    unsigned char* scratch = dyn_smem + (size_t)8 * stride;            // 3*stride words for ranking / allocation
+    float* l_score = reinterpret_cast<float*>(scratch + (size_t)12 * stride);
+    int32_t* l_len = reinterpret_cast<int32_t*>(l_score + stride);
+    int32_t* l_cand = l_len + stride;
+    int32_t* l_keep = l_cand + stride;
+    int32_t* l_start = l_keep + stride;
+    int32_t* l_order = l_start + stride;
+    float* l_part = reinterpret_cast<float*>(l_order + stride);
+
     const char* ws = static_cast<const char*>(a.workspace);
     const int b = __builtin_amdgcn_readfirstlane(blockIdx.x);
+    const int64_t off = (int64_t)b * stride;
+    const int nparts = p.units_per_b * p.nrb;
+    const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * nparts * p.slots;
     const QueryHead qh = load_query_head(a, b);
-    build_table(a, qh, &tbl, p.tile);
+    const int n_cand = pr.n_cand[b];
+    if (tid == 0) { s_int[4] = pr.q_start[b]; s_int[5] = pr.n_reuse[b]; }
+    for (int i = tid; i < stride; i += kEpiThreads) {
+        l_tok[i] = pr.doc_tok_offset[off + i];
+        l_len[i] = pr.doc_len[off + i];
+        l_cand[i] = pr.cand[off + i];
+        l_score[i] = a.score_accum[off + i];
+        l_start[i] = pr.new_start[off + i];
+        l_order[i] = pr.order[off + i];
+    }
+    for (int i = tid; i < nparts * p.slots; i += kEpiThreads) l_part[i] = mp_b[i];
+    build_table(a, qh, &tbl, p.tile);                // its barriers also publish the rows above
     const unsigned total = (unsigned)tbl.tile0[tbl.n];
     const unsigned nsub = (unsigned)(p.nsplit * p.sub);
-    const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * p.units_per_b * p.nrb * p.slots;
     for (int s = wave; s < tbl.n; s += n_waves) {
-        const float m = segment_mass(p, tbl, mp_b, s, total, nsub, lane);
+        const float m = segment_mass(p, tbl, l_part, s, total, nsub, lane);
         if (lane == 0) {
             a.mass[(int64_t)b * a.seg_stride + s] = m;
-            const int doc = a.segs[(int64_t)b * a.seg_stride + s].doc;
-            if (a.score_accum && doc >= 0 && doc < a.score_stride)
-                atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], m);
+            const int doc = tbl.doc[s];
+            if (doc >= 0 && doc < stride) atomicAdd(&l_score[doc], m);
         }
     }
-    if (!pr.enabled) return;
-    __threadfence_block();
     __syncthreads();
-    const int64_t off = (int64_t)b * pr.stride;
-    const int k = prune_topk_block(a.score_accum + (int64_t)b * a.score_stride, pr.normalise_by_len ? pr.doc_len + off : nullptr,
-                                   pr.cand + off, pr.n_cand[b], pr.keep, pr.stride, pr.keep_idx + off, a.dev_flag, dyn_smem,
-                                   &s_int[3]);
+    for (int i = tid; i < stride; i += kEpiThreads) a.score_accum[off + i] = l_score[i];
+    const int k = prune_topk_block(l_score, pr.normalise_by_len ? l_len : nullptr, l_cand, n_cand, pr.keep, stride, l_keep,
+                                   a.dev_flag, scratch, &s_int[3]);
     if (tid == 0) pr.n_keep[b] = k;
-    __threadfence_block();
     __syncthreads();
-    assign_positions_block(pr.doc_len + off, pr.keep_idx + off, k, pr.stride, pr.pos_begin, pr.pos_end, pr.strategy,
-                           pr.force_n_reuse, pr.new_start + off, pr.q_start + b, pr.n_reuse + b, pr.order + off, a.dev_flag,
-                           dyn_smem, s_int);
-    __threadfence_block();
+    assign_positions_block(l_len, l_keep, k, stride, pr.pos_begin, pr.pos_end, pr.strategy, pr.force_n_reuse, l_start,
+                           &s_int[4], &s_int[5], l_order, a.dev_flag, scratch, s_int);
     __syncthreads();
-    gather_segments_block(pr.doc_tok_offset + off, pr.doc_len + off, pr.order + off, k, pr.new_start + off, pr.q_start[b],
-                          qh.q0, qh.q0 + qh.tq_raw, pr.stride, pr.prefix_len, pr.doc_stored_start, a.q_stored_start,
-                          pr.next_segs + (int64_t)b * a.seg_stride, pr.next_n_seg + b, a.seg_stride, a.dev_flag);
+    gather_segments_block(l_tok, l_len, l_order, k, l_start, s_int[4], qh.q0, qh.q0 + qh.tq_raw, stride, pr.prefix_len,
+                          pr.doc_stored_start, a.q_stored_start, pr.next_segs + (int64_t)b * a.seg_stride,
+                          pr.next_n_seg + b, a.seg_stride, a.dev_flag);
+    for (int i = tid; i < stride; i += kEpiThreads) {
+        if (i < k) pr.keep_idx[off + i] = l_keep[i];
+        pr.new_start[off + i] = l_start[i];
+        pr.order[off + i] = l_order[i];
+    }
+    if (tid == 0) { pr.q_start[b] = s_int[4]; pr.n_reuse[b] = s_int[5]; }
 }
 
 }  // namespace
@@ -1234,7 +1234,7 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
     const int phases = profile_phases();
     const Plan p = make_plan(a.n_q_heads, a.n_kv_heads, a.batch, a.max_tq, a.seg_stride, a.max_kv_tokens);
     const dim3 grid((unsigned)(p.x_count * p.n_rg)), block(kThreads);
-    const dim3 grid2((unsigned)(p.units * p.nrb * 4)), grid3((unsigned)(a.batch * p.mass_chunks));
+    const dim3 grid2((unsigned)(p.units * p.nrb * 8)), grid3((unsigned)(a.batch * p.mass_chunks));
 #define CF_LAUNCH(DT, N) hipLaunchKernelGGL((attn_mfma_kernel<DT, N>), grid, block, 0, s, a, f, p)
 #define CF_LAUNCH_S(DT, N) hipLaunchKernelGGL((attn_small_kernel<DT, N>), grid, block, 0, s, a, f, p)
 #define CF_LAUNCH_DT(DT)                                   \
@@ -1266,8 +1266,15 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
         pr.n_cand = prune->n_cand; pr.keep_idx = prune->keep_idx; pr.n_keep = prune->n_keep;
         pr.new_start = prune->new_start; pr.q_start = prune->q_start; pr.n_reuse = prune->n_reuse;
         pr.order = prune->order; pr.next_segs = prune->next_segs; pr.next_n_seg = prune->next_n_seg;
-        if (phases & 4)
-            hipLaunchKernelGGL(layer_epilogue_kernel, dim3(a.batch), dim3(kEpiThreads), (size_t)prune->stride * 12, s, a, p, pr);
+        const size_t lds_rows = (size_t)44 * prune->stride + (size_t)4 * p.units_per_b * p.nrb * p.slots;
+        if (!(phases & 4)) {
+        } else if (lds_rows <= 60 * 1024) {          // every per-document row and the slot partials fit LDS
+            hipLaunchKernelGGL(layer_epilogue_kernel, dim3(a.batch), dim3(kEpiThreads), lds_rows, s, a, p, pr);
+        } else {
+            hipLaunchKernelGGL(attn_mass_kernel, grid3, block, 0, s, a, p);
+            CF_HIP(hipGetLastError());
+            return launch_prune_step(a, prune, s);
+        }
     } else if (phases & 4) {
         hipLaunchKernelGGL(attn_mass_kernel, grid3, block, 0, s, a, p);
     }
