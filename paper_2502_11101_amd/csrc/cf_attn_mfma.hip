@@ -41,7 +41,6 @@ constexpr int kVBytes = kD * kSV * 2;
 constexpr int kStageBytes = kKBytes + kVBytes;
 constexpr int kMaxSegs = 256;
 constexpr int kMaxSplit = 32;
-constexpr int kMassChunks = 16;     // mass workgroups per query (segments dealt round-robin)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -56,7 +55,7 @@ struct Plan {
     int rows_wg;        // 64 * nrb
     int n_rg;           // row groups per (query, kv head)
     int blocks_rg;      // 16-row blocks per row group
-    int units_per_b, units, nsplit, slots, x_count, mass_chunks;
+    int units_per_b, units, nsplit, slots, x_count;
     int tile;           // tokens per tile: 64 (shared-tile kernel) or 32 (wavefront-private tiles)
     int sub;            // sub-splits per workgroup: 4 when every wavefront streams its own tiles, else 1
     size_t off_ml, off_opart, off_massml, off_masspart, total;
@@ -91,7 +90,6 @@ Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_str
     p.nsplit = (int)ns;
     p.slots = seg_stride + p.nsplit * p.sub;
     p.x_count = batch * n_kv_heads * p.nsplit;
-    p.mass_chunks = seg_stride < kMassChunks ? seg_stride : kMassChunks;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
     p.off_ml = take((size_t)p.units * p.nsplit * p.rows_wg * sizeof(float2));
@@ -768,6 +766,18 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
     // next, softmax, V registers to LDS and refilled, O^T += V^T P^T by transposing LDS reads.
     auto step = [&](Tile& cur, TileRegs& r) {
         const Tile cd = cur;
+        const bool live = cd.ntok > 0;               // without a tile only the (fixed number of) loads are issued
+        const bool causal = cd.self != 0;
+        const int nt = cd.ntok;
+        f32x4 sc[NRB][2];
+        uint4 pfrag[NRB];
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            sc[rb][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+            sc[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+            pfrag[rb] = make_uint4(0, 0, 0, 0);
+        }
+        if (live) {
         if (cd.seg != cur_seg) {
             if (cur_seg >= 0) emit(cur_seg);
             cur_seg = cd.seg;
@@ -803,12 +813,7 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
                 }
             }
         }
-        const bool causal = cd.self != 0;
-        const int nt = cd.ntok;
         // ---- S^T = K Q^T : lane (li, lg) gets, for query row li, tokens 16*tb + 4*lg + r
-        f32x4 sc[NRB][2];
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) { sc[rb][0] = f32x4{0.f, 0.f, 0.f, 0.f}; sc[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
 #pragma unroll
@@ -818,12 +823,13 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
                 sc[rb][1] = Mma<DT>::run(r.f[1][kk], qv, sc[rb][1]);
             }
         }
+        }
         Tile nx;
         describe(nx);
         fetch_k(nx, r);                              // the K registers are free again
+        if (live) {
         // ---- online softmax (exp2 domain), fp32
         const bool need_mask = causal || nt < kTileS;
-        uint4 pfrag[NRB];
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
             float xv[8];
@@ -875,9 +881,11 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
         // ---- V to LDS (the wavefront's own tile buffer; its previous contents were read by the last step)
 #pragma unroll
         for (int n = 0; n < 8; ++n) *reinterpret_cast<uint4*>(v_lds + (n >> 1) * 2048 + vw_off[n & 1]) = r.v[n];
+        }
         fetch_v(nx, r);                              // the V registers are free again
         cur = nx;
         // ---- O^T += V^T P^T; V^T fragments by transposing reads of the row-major tile
+        if (live) {
 #pragma unroll
         for (int db = 0; db < 8; ++db) {
             const unsigned char* src = v_lds + tr_base + ((uint32_t)(32 * db) ^ tr_x);
@@ -888,12 +896,14 @@ __global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFr
 #pragma unroll
             for (int rb = 0; rb < NRB; ++rb) acc[rb][db] = Mma<DT>::run(va, pfrag[rb], acc[rb][db]);
         }
+        }
     };
-    while (d0.ntok > 0) {
+    // Steps come in pairs and the exit test sits at the end only: every path round the loop issues the
+    // same loads.  A wavefront with an odd number of tiles runs one step without a tile.
+    do {
         step(d0, regs0);
-        if (d1.ntok <= 0) break;
         step(d1, regs1);
-    }
+    } while (d0.ntok > 0);
     if (cur_seg >= 0) emit(cur_seg);
 
     // ---- merge the four sub-splits of this workgroup (same rows, different tokens) through LDS
@@ -1068,53 +1078,83 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     }
 }
 
-// Mass of segment s of query b: the slot partials of every (unit, pass) and every sub-split that
-// holds tiles of the segment, added by one wavefront in a fixed order.
-__device__ __forceinline__ float segment_mass(const Plan& p, const SegTable& tbl, const float* mp_b, int s, unsigned total,
-                                              unsigned nsub, int lane) {
-    const int ts = tbl.tile0[s], te = tbl.tile0[s + 1];
-    if (te <= ts) return 0.f;
-    const int s0 = split_of(total, nsub, ts), s1 = split_of(total, nsub, te - 1);
-    const int nparts = p.units_per_b * p.nrb;
-    float c = 0.f;
-    for (int sp = s0; sp <= s1; ++sp) {
-        // a sub-split between the first and the last may own no tile at all (fewer tiles than sub-splits):
-        // its slot was not written by this call
-        if (split_begin(total, nsub, sp) >= split_begin(total, nsub, sp + 1)) continue;
-        for (int part = lane; part < nparts; part += kWave) c += mp_b[(int64_t)part * p.slots + s + sp];
-    }
-    return wave_sum(c);
-}
+// Per-segment attention mass of one query, by the whole workgroup, in a fixed order: first every
+// slot's partials are added over the (unit, pass) parts, then a segment adds the slots of the
+// sub-splits that hold its tiles.  A sub-split between a segment's first and last may own no tile at
+// all (fewer tiles than sub-splits): its slot was not written by this call and is skipped.
+// `parts`: [nparts][slots] floats, in LDS (stage == nullptr) or in memory (stage: kMassStage floats of LDS).
+// `on_mass(s, m)` is called once per segment.  Both forms add in the same order.
+struct MassScratch {
+    float colsum[kMaxSegs + kMaxSplit * kWaves];
+    int32_t sub_begin[kMaxSplit * kWaves + 1];
+};
+constexpr int kMassStage = 4096;            // floats of partials staged per round by the stand-alone mass kernel
 
-// Third kernel: per-segment attention mass.  Workgroup (query b, chunk c) owns the segments
-// c, c + mass_chunks, ..., one wavefront per segment; then S += mass.
-__global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p) {
-    __shared__ SegTable tbl;
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1);
-    const int wave = tid / kWave;
-    const char* ws = static_cast<const char*>(a.workspace);
-    const int b = __builtin_amdgcn_readfirstlane(blockIdx.x / p.mass_chunks);
-    const int chunk = blockIdx.x % p.mass_chunks;
-    const QueryHead qh = load_query_head(a, b);
-    build_table(a, qh, &tbl, p.tile);
+template <class F>
+__device__ __forceinline__ void segment_masses_block(const Plan& p, const SegTable& tbl, const float* parts, float* stage,
+                                                     MassScratch* ms, F on_mass) {
+    const int tid = threadIdx.x, nthr = blockDim.x;
     const unsigned total = (unsigned)tbl.tile0[tbl.n];
     const unsigned nsub = (unsigned)(p.nsplit * p.sub);
-    const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * p.units_per_b * p.nrb * p.slots;
-    for (int s = chunk + p.mass_chunks * wave; s < tbl.n; s += p.mass_chunks * kWaves) {
-        const float m = segment_mass(p, tbl, mp_b, s, total, nsub, lane);
-        if (lane == 0) {
-            a.mass[(int64_t)b * a.seg_stride + s] = m;
-            const int doc = a.segs[(int64_t)b * a.seg_stride + s].doc;
-            if (a.score_accum && doc >= 0 && doc < a.score_stride)
-                atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], m);
+    const int nparts = p.units_per_b * p.nrb;
+    if (stage == nullptr) {                          // partials already in LDS
+        for (int k = tid; k < p.slots; k += nthr) {
+            float c = 0.f;
+            for (int part = 0; part < nparts; ++part) c += parts[(int64_t)part * p.slots + k];
+            ms->colsum[k] = c;
         }
+    } else {                                         // partials in memory: whole rows through LDS, many loads in flight
+        const int rows = max(1, kMassStage / p.slots);   // slots <= kMassStage
+        float c[2] = {0.f, 0.f};                     // this thread's columns tid, tid + nthr (slots <= 2 * nthr)
+        for (int r0 = 0; r0 < nparts; r0 += rows) {
+            const int nr = min(rows, nparts - r0);
+            __syncthreads();
+            for (int i = tid; i < nr * p.slots; i += nthr) stage[i] = parts[(int64_t)r0 * p.slots + i];
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int k = tid + j * nthr;
+                if (k < p.slots)
+                    for (int r = 0; r < nr; ++r) c[j] += stage[r * p.slots + k];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (tid + j * nthr < p.slots) ms->colsum[tid + j * nthr] = c[j];
     }
+    for (int sp = tid; sp <= (int)nsub; sp += nthr) ms->sub_begin[sp] = split_begin(total, nsub, sp);
+    __syncthreads();
+    for (int s = tid; s < tbl.n; s += nthr) {
+        const int ts = tbl.tile0[s], te = tbl.tile0[s + 1];
+        float m = 0.f;
+        if (te > ts) {
+            const int s0 = split_of(total, nsub, ts), s1 = split_of(total, nsub, te - 1);
+            for (int sp = s0; sp <= s1; ++sp)
+                if (ms->sub_begin[sp] < ms->sub_begin[sp + 1]) m += ms->colsum[s + sp];
+        }
+        on_mass(s, m);
+    }
+}
+
+// Third kernel: per-segment attention mass, one workgroup per query; then S += mass.
+__global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p) {
+    __shared__ SegTable tbl;
+    __shared__ MassScratch ms;
+    __shared__ float stage[kMassStage];
+    const char* ws = static_cast<const char*>(a.workspace);
+    const int b = __builtin_amdgcn_readfirstlane(blockIdx.x);
+    const QueryHead qh = load_query_head(a, b);
+    build_table(a, qh, &tbl, p.tile);
+    const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * p.units_per_b * p.nrb * p.slots;
+    segment_masses_block(p, tbl, mp_b, stage, &ms, [&](int s, float m) {
+        a.mass[(int64_t)b * a.seg_stride + s] = m;
+        const int doc = tbl.doc[s];
+        if (a.score_accum && doc >= 0 && doc < a.score_stride) atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], m);
+    });
 }
 
 // Fused layer epilogue (third kernel of cf_prefill_layer): one workgroup per query computes the
-// attention mass of every segment (wavefront w owns segments w, w + #wavefronts, ...; fixed
-// summation order), adds it to the accumulated scores, and — when a prune step is attached —
+// attention mass of every segment (fixed summation order), adds it to the accumulated scores, and — when a prune step is attached —
 // ranks the candidates, allocates the survivors' positions and writes the next layer's segment
 // table, i.e. Alg. 2's "S += s; ids_sort = argsort(S); ids = prun(ids_sort)" followed by the
 // allocation of Sec. 2.5, without leaving the GPU.
@@ -1145,12 +1185,10 @@ struct PruneArgs {
 __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a, Plan p, PruneArgs pr) {
     extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
     __shared__ SegTable tbl;
+    __shared__ MassScratch ms;
     __shared__ int s_int[6];
 
     const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1);
-    const int wave = tid / kWave;
-    const int n_waves = kEpiThreads / kWave;
     const int stride = pr.stride;
     int64_t* l_tok = reinterpret_cast<int64_t*>(dyn_smem);
     unsigned char* scratch = dyn_smem + (size_t)8 * stride;            // 3*stride words for ranking / allocation
@@ -1167,6 +1205,9 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
     const int64_t off = (int64_t)b * stride;
     const int nparts = p.units_per_b * p.nrb;
     const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * nparts * p.slots;
+#if defined(CF_EPI_LEVEL) && CF_EPI_LEVEL <= 0
+    if (a.batch > 0) return;
+#endif
     const QueryHead qh = load_query_head(a, b);
     const int n_cand = pr.n_cand[b];
     if (tid == 0) { s_int[4] = pr.q_start[b]; s_int[5] = pr.n_reuse[b]; }
@@ -1180,24 +1221,31 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
     }
     for (int i = tid; i < nparts * p.slots; i += kEpiThreads) l_part[i] = mp_b[i];
     build_table(a, qh, &tbl, p.tile);                // its barriers also publish the rows above
-    const unsigned total = (unsigned)tbl.tile0[tbl.n];
-    const unsigned nsub = (unsigned)(p.nsplit * p.sub);
-    for (int s = wave; s < tbl.n; s += n_waves) {
-        const float m = segment_mass(p, tbl, l_part, s, total, nsub, lane);
-        if (lane == 0) {
-            a.mass[(int64_t)b * a.seg_stride + s] = m;
-            const int doc = tbl.doc[s];
-            if (doc >= 0 && doc < stride) atomicAdd(&l_score[doc], m);
-        }
-    }
+#if defined(CF_EPI_LEVEL) && CF_EPI_LEVEL <= 1
+    if (a.batch > 0) return;
+#endif
+    segment_masses_block(p, tbl, l_part, nullptr, &ms, [&](int s, float m) {
+        a.mass[(int64_t)b * a.seg_stride + s] = m;
+        const int doc = tbl.doc[s];
+        if (doc >= 0 && doc < stride) atomicAdd(&l_score[doc], m);
+    });
     __syncthreads();
+#if defined(CF_EPI_LEVEL) && CF_EPI_LEVEL <= 2
+    if (a.batch > 0) return;
+#endif
     for (int i = tid; i < stride; i += kEpiThreads) a.score_accum[off + i] = l_score[i];
     const int k = prune_topk_block(l_score, pr.normalise_by_len ? l_len : nullptr, l_cand, n_cand, pr.keep, stride, l_keep,
                                    a.dev_flag, scratch, &s_int[3]);
     if (tid == 0) pr.n_keep[b] = k;
+#if defined(CF_EPI_LEVEL) && CF_EPI_LEVEL <= 3
+    if (a.batch > 0) return;
+#endif
     __syncthreads();
     assign_positions_block(l_len, l_keep, k, stride, pr.pos_begin, pr.pos_end, pr.strategy, pr.force_n_reuse, l_start,
                            &s_int[4], &s_int[5], l_order, a.dev_flag, scratch, s_int);
+#if defined(CF_EPI_LEVEL) && CF_EPI_LEVEL <= 4
+    if (a.batch > 0) return;
+#endif
     __syncthreads();
     gather_segments_block(l_tok, l_len, l_order, k, l_start, s_int[4], qh.q0, qh.q0 + qh.tq_raw, stride, pr.prefix_len,
                           pr.doc_stored_start, a.q_stored_start, pr.next_segs + (int64_t)b * a.seg_stride,
@@ -1234,7 +1282,7 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
     const int phases = profile_phases();
     const Plan p = make_plan(a.n_q_heads, a.n_kv_heads, a.batch, a.max_tq, a.seg_stride, a.max_kv_tokens);
     const dim3 grid((unsigned)(p.x_count * p.n_rg)), block(kThreads);
-    const dim3 grid2((unsigned)(p.units * p.nrb * 8)), grid3((unsigned)(a.batch * p.mass_chunks));
+    const dim3 grid2((unsigned)(p.units * p.nrb * 8)), grid3((unsigned)a.batch);
 #define CF_LAUNCH(DT, N) hipLaunchKernelGGL((attn_mfma_kernel<DT, N>), grid, block, 0, s, a, f, p)
 #define CF_LAUNCH_S(DT, N) hipLaunchKernelGGL((attn_small_kernel<DT, N>), grid, block, 0, s, a, f, p)
 #define CF_LAUNCH_DT(DT)                                   \
