@@ -194,7 +194,7 @@ def main() -> int:
                    "step": "cf_prefill_layer: attention + mass + prune_topk + assign_positions + gather_segments"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
-                     "kernel": "attn_small_kernel<bf16,3> (first kernel of cf_prefill_layer / cf_prefill_attention)",
+                     "kernel": "attn_tile_kernel<bf16,1,32> (first kernel of cf_prefill_layer / cf_prefill_attention)",
                      "ms_per_launch": kernel_ms, "algorithmic_bytes_per_launch": kv_tokens * bytes_per_token,
                      "ms_per_call_all_kernels": attn_ms},
     }

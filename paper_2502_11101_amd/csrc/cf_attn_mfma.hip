@@ -3,18 +3,19 @@
 // Work decomposition.  The query rows that share a kv head (all rows of the G = Hq/Hkv heads of
 // the group, stacked: row m = g*tq + t) are cut into 16-row blocks.  A workgroup of 4 wavefronts
 // owns up to 4*NRB such blocks of one (query, kv head) — wavefront w the blocks [w*NRB, (w+1)*NRB)
-// — and a contiguous run of the attended tokens.  Tokens are counted in tiles of 64 that never
+// — and a contiguous run of the attended tokens.  Tokens are counted in tiles (32 tokens when the
+// stacked rows fit one workgroup pass of 64 — MHA, short queries: HBM-bound —, else 64) that never
 // straddle a segment; the tile list of a (query, kv head) is divided evenly over `nsplit`
 // workgroups.  Per tile:
-//   * all 256 threads fetch the next K/V tile with coalesced 16-byte loads into registers while
-//     the current one is being consumed,
+//   * all 256 threads fetch the tile two ahead with coalesced 16-byte loads into registers,
 //   * the key tile is rotated in registers by its segment's relative position shift (Eq. 5;
 //     cos/sin per 2-D slice from an fp64-reduced angle), rounded once to the storage type and
-//     staged into LDS — rotated keys never return to memory; V is staged transposed,
+//     staged into LDS — rotated keys never return to memory; V is staged as loaded,
 //   * S^T = K Q^T and O^T += V^T P^T run on v_mfma_f32_16x16x32 with the Q fragments resident
-//     in registers; the transposed forms keep one query row per lane, so the online softmax
-//     (fp32, exp2 domain) needs two cross-lane exchanges per 32 tokens and the rescale none.
-// At the end of each segment a wavefront leaves (running max, sum of exp2) per row.
+//     in registers and the V^T fragments read with transposing LDS reads; the transposed forms keep
+//     one query row per lane, so the online softmax (fp32, exp2 domain) needs no cross-lane exchange
+//     except when its reference maximum moves.
+// At the end of each segment a wavefront leaves (reference maximum, sum of exp2) per row.
 //
 // A second kernel merges the splits' partial outputs and writes the output rows; a third reduces
 // the (max, sum) pairs to per-segment attention mass (the document-wise score of Alg. 2) in a
@@ -33,12 +34,7 @@ constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr int kD = 128;
 constexpr int kHalf = 64;
-constexpr int kTile = 64;       // tokens per tile
 constexpr int kSK = 136;        // LDS row stride of the staged K tile, elements (272 B)
-constexpr int kSV = 72;         // LDS row stride of the staged V^T tile, elements (144 B)
-constexpr int kKBytes = kTile * kSK * 2;
-constexpr int kVBytes = kD * kSV * 2;
-constexpr int kStageBytes = kKBytes + kVBytes;
 constexpr int kMaxSegs = 256;
 constexpr int kMaxSplit = 32;
 
@@ -56,8 +52,7 @@ struct Plan {
     int n_rg;           // row groups per (query, kv head)
     int blocks_rg;      // 16-row blocks per row group
     int units_per_b, units, nsplit, slots, x_count;
-    int tile;           // tokens per tile: 64 (shared-tile kernel) or 32 (wavefront-private tiles)
-    int sub;            // sub-splits per workgroup: 4 when every wavefront streams its own tiles, else 1
+    int tile;           // tokens per tile: 32 or 64
     size_t off_ml, off_opart, off_massml, off_masspart, total;
 };
 
@@ -72,14 +67,12 @@ Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_str
     p.rows_wg = 64 * p.nrb;
     p.units_per_b = n_kv_heads * p.n_rg;
     p.units = batch * p.units_per_b;
-    // Few stacked rows (MHA-like, HBM-bound): every wavefront holds all rows and streams its own
-    // 32-token tiles.  Many rows (GQA, MFMA-bound): the wavefronts share 64-token tiles.
-    const bool small_m = row_blocks <= 4 && seg_stride <= 64;
-    p.tile = small_m ? 32 : kTile;
-    p.sub = small_m ? kWaves : 1;
+    // Few stacked rows (MHA-like, HBM-bound): small tiles, so that ragged segment ends waste little and
+    // a split still holds several tiles.  Many rows (GQA, MFMA-bound): 64-token tiles.
+    p.tile = row_blocks <= 4 ? 32 : 64;
     const int64_t est_tiles = max_kv_tokens / p.tile + seg_stride;
     int64_t ns = (256 + p.units - 1) / p.units;         // one workgroup per CU and launch wave
-    const int64_t cap = est_tiles / (2 * p.sub) > 1 ? est_tiles / (2 * p.sub) : 1;
+    const int64_t cap = est_tiles / 2 > 1 ? est_tiles / 2 : 1;
     if (ns > cap) ns = cap;
     if (ns > kMaxSplit) ns = kMaxSplit;
 #ifdef CF_DEV
@@ -88,7 +81,7 @@ Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_str
     if (ns < 1) ns = 1;
     if (ns > kMaxSplit) ns = kMaxSplit;
     p.nsplit = (int)ns;
-    p.slots = seg_stride + p.nsplit * p.sub;
+    p.slots = seg_stride + p.nsplit;
     p.x_count = batch * n_kv_heads * p.nsplit;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
@@ -205,29 +198,49 @@ template <> struct Mma<CF_F16> {
     }
 };
 
-struct TileDesc {
-    int seg;       // segment index
-    int tok0;      // first token of the tile inside the segment
-    int ntok;      // valid tokens (1..64)
-};
+constexpr float kRescaleSlack = 8.f;                   // log2 of the largest probability kept relative to the running reference
 
-template <int DT, int NRB>
-__global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFreq freq, Plan p) {
+typedef short short4v __attribute__((ext_vector_type(4)));
+
+// cos/sin of delta*theta from the hardware sine/cosine (argument in revolutions, reduced in fp64):
+// their absolute error is far below the rounding step of the 16-bit keys this feeds.
+__device__ __forceinline__ float2 rope_cos_sin_fast(int delta, double theta_rev) {
+    const double x = (double)delta * theta_rev;
+    const float fr = (float)(x - rint(x));
+    return make_float2(__builtin_amdgcn_cosf(fr), __builtin_amdgcn_sinf(fr));
+}
+
+// ---------------------------------------------------------------------------------------------
+// The attention kernel: the four wavefronts of a workgroup stream the same TILE-token tiles and own
+// different query rows (wavefront w the 16-row blocks [w*NRB, (w+1)*NRB)), so there is nothing to
+// merge inside a workgroup.  Per tile:
+//   * every thread's K/V loads for the tile two ahead are in flight in registers (a fixed number of
+//     loads per step, so the wait for one tile never covers a later one);
+//   * staging: a thread rotates the pairs (c, c + 64) of its 16-byte key chunks (Eq. 5) and writes
+//     them [token][channel] to one of two LDS tile buffers; V chunks are copied as loaded, row-major
+//     with a 32-byte XOR swizzle; one workgroup barrier per tile;
+//   * S^T = K Q^T from LDS key fragments and register-resident Q fragments, online softmax with a
+//     stale maximum, O^T += V^T P^T with V^T fragments from transposing LDS reads.
+template <int DT, int NRB, int TILE>
+__global__ __launch_bounds__(kThreads) void attn_tile_kernel(AttnArgs a, RopeFreq freq, Plan p) {
+    constexpr int kKTile = TILE * kSK * 2;           // bytes, padded rows
+    constexpr int kVTile = TILE * kD * 2;
+    constexpr int kKItems = TILE / 32;               // (row, chunk pair) items per thread
+    constexpr int kVItems = TILE / 16;               // (row, chunk) items per thread
     __shared__ SegTable tbl;
-    __shared__ __attribute__((aligned(16))) unsigned char stage[kStageBytes];
-    __shared__ float2 cs_lds[2][kHalf];
+    __shared__ __attribute__((aligned(16))) unsigned char k_buf[2][kKTile];
+    __shared__ __attribute__((aligned(16))) unsigned char v_buf[2][kVTile];
+    __shared__ __attribute__((aligned(16))) float2 cs_lds[2][kHalf];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
-    const int wave = tid / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int li = lane & 15, lg = lane >> 4;
-    // Pull every pointer and scalar the streaming loop needs out of the kernel-argument segment
-    // now, in one batch of scalar loads, instead of one dependent round trip per first use.
     {
         const void *p0 = a.q, *p1 = a.q_off, *p2 = a.q_new_start, *p3 = a.k_store, *p4 = a.v_store, *p5 = a.k_self,
                    *p6 = a.v_self, *p7 = a.segs, *p8 = a.n_seg, *p9 = a.workspace;
-        asm volatile("" ::"s"(p0), "s"(p1), "s"(p2), "s"(p3), "s"(p4), "s"(p5), "s"(p6), "s"(p7), "s"(p8), "s"(p9));
-        asm volatile("" ::"s"(a.n_store_tokens), "s"(a.seg_stride), "s"(a.batch), "s"(a.max_tq), "s"(a.n_q_heads),
+        asm volatile("" ::"s"(p0), "s"(p1), "s"(p2), "s"(p3), "s"(p4), "s"(p5), "s"(p6), "s"(p7), "s"(p8), "s"(p9),
+                     "s"(a.n_store_tokens), "s"(a.seg_stride), "s"(a.batch), "s"(a.max_tq), "s"(a.n_q_heads),
                      "s"(a.n_kv_heads), "s"(a.scale_log2e), "s"(a.q_stored_start), "s"(p.nsplit), "s"(p.slots),
                      "s"(p.off_ml), "s"(p.off_opart), "s"(p.off_massml));
     }
@@ -246,96 +259,81 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
     const int group = hq / a.n_kv_heads;
     const QueryHead qh = load_query_head(a, b);
     const double my_freq = freq.rev[tid & (kHalf - 1)];
-    const int q0 = qh.q0, tq_raw = qh.tq_raw;
-
-    build_table(a, qh, &tbl, kTile);
-
-    const int tq = min(tq_raw, a.max_tq);
+    const int q0 = qh.q0;
+    const int tq = min(qh.tq_raw, a.max_tq);
     const int n_rows = group * tq;
-    const unsigned total = (unsigned)tbl.tile0[tbl.n];
-    const int t_begin = split_begin(total, p.nsplit, split);
-    const int t_end = split_begin(total, p.nsplit, split + 1);
 
-    const int64_t kv_row = (int64_t)a.n_kv_heads * kD;
-    // staging: thread -> K items (tokens kt and kt+32, slices 8*kj..), V item (4 tokens 4*vq.., channels 8*vj..)
-    const int kt = tid >> 3, kj = tid & 7;
-    const int vq = tid >> 4, vj = tid & 15;
-    struct StageRegs { uint4 ka[2], kb[2], v[4]; };
-    StageRegs regs0, regs1;                          // two tiles in flight
-
-    auto describe = [&](int tile, int s) {
-        TileDesc d;
-        d.seg = s;
-        d.tok0 = (tile - tbl.tile0[s]) * kTile;
-        d.ntok = min(kTile, tbl.vis[s] - d.tok0);
-        return d;
-    };
-    auto locate = [&](int tile, int s) {             // first segment at or after s whose tiles reach past `tile`
-        while (tbl.tile0[s + 1] <= tile) ++s;
-        return s;
-    };
-    auto issue_loads = [&](const TileDesc& d, StageRegs& r) {
-        const bool self = tbl.self[d.seg] != 0;
-        const uint16_t* kb = static_cast<const uint16_t*>(self ? a.k_self : a.k_store);
-        const uint16_t* vb = static_cast<const uint16_t*>(self ? a.v_self : a.v_store);
-        const int64_t base = (tbl.tok[d.seg] + d.tok0) * kv_row + (int64_t)hkv * kD;
-        const uint4 zero = make_uint4(0, 0, 0, 0);
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int tok = kt + 32 * it;
-            if (tok < d.ntok) {
-                const uint16_t* pk = kb + base + tok * kv_row + 8 * kj;
-                r.ka[it] = *reinterpret_cast<const uint4*>(pk);
-                r.kb[it] = *reinterpret_cast<const uint4*>(pk + kHalf);
-            } else {
-                r.ka[it] = zero;
-                r.kb[it] = zero;
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int tok = 4 * vq + i;
-            if (tok < d.ntok) r.v[i] = *reinterpret_cast<const uint4*>(vb + base + tok * kv_row + 8 * vj);
-            else r.v[i] = zero;
-        }
-    };
-    int s_next = 0;
-    int next_tile = t_begin;                         // next tile whose loads have not been issued
-    auto fetch = [&](TileDesc& d, StageRegs& r) {    // ntok == 0 marks "no tile"
-        if (next_tile >= t_end) { d.ntok = 0; return; }
-        s_next = locate(next_tile, s_next);
-        d = describe(next_tile, s_next);
-        issue_loads(d, r);
-        ++next_tile;
-    };
-
-    // ---- the first two tiles' loads go out before anything else that touches memory
-    TileDesc d0, d1;
-    d0.seg = d1.seg = 0; d0.tok0 = d1.tok0 = 0; d0.ntok = d1.ntok = 0;
-    constexpr bool kDeep = NRB <= 2;                 // wider row tiles have no registers to spare for a second tile
-    fetch(d0, regs0);
-    if (kDeep) fetch(d1, regs1);
-
-    // ---- Q fragments: row m = g*tq + t of the stack is q[q0 + t][hkv*group + g]
+    // ---- Q fragments first (loads return in order): row m = g*tq + t of the stack is q[q0 + t][hkv*group + g]
     uint4 qf[NRB][4];
     int trow[NRB];
     const int row_base = rg * p.blocks_rg * 16;
     const int row_limit = min(n_rows, row_base + p.blocks_rg * 16);
+    const bool has_rows = row_base + wave * NRB * 16 < row_limit;        // wavefront-uniform
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
         const int m = row_base + (wave * NRB + rb) * 16 + li;
         const bool valid = m < row_limit;
         const int gi = valid ? m / tq : 0;
         const int t = valid ? m - gi * tq : 0;
-        trow[rb] = valid ? t : 0x7fffffff;        // padding rows: nothing to mask, results unused
+        trow[rb] = valid ? t : 0x7fffffff;            // padding rows: nothing to mask, results unused
         const uint16_t* qp = static_cast<const uint16_t*>(a.q) + (((int64_t)q0 + t) * hq + hkv * group + gi) * kD + 8 * lg;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
             qf[rb][kk] = valid ? *reinterpret_cast<const uint4*>(qp + 32 * kk) : make_uint4(0, 0, 0, 0);
     }
 
-    uint16_t* k_lds = reinterpret_cast<uint16_t*>(stage);
-    uint16_t* v_lds = reinterpret_cast<uint16_t*>(stage + kKBytes);
+    build_table(a, qh, &tbl, TILE);
+    const unsigned total = (unsigned)tbl.tile0[tbl.n];
+    const int t_begin = split_begin(total, p.nsplit, split);
+    const int t_end = split_begin(total, p.nsplit, split + 1);
+
+    const int64_t kv_row = (int64_t)a.n_kv_heads * kD;
+    const uint32_t row_bytes = (uint32_t)a.n_kv_heads * (kD * 2);
+    // staging items: K (row kr + 32*it, chunks kj and kj + 8), V (row vr + 16*it, chunk vc)
+    const int kr = tid >> 3, kj = tid & 7;
+    const int vr = tid >> 4, vc = tid & 15;
+    struct StageRegs { uint4 ka[kKItems], kb[kKItems], v[kVItems]; };
+    struct Tile { int seg, tok0, ntok, delta, self; };
+    StageRegs regs0, regs1;
+
+    int s_next = 0;
+    int next_tile = t_begin;
+    // Every call issues the same loads whether or not a tile is left (without one they re-read the first
+    // bytes of the workspace), so the number of loads in flight at any point of the loop is fixed.
+    auto fetch = [&](Tile& d, StageRegs& r) {        // ntok == 0 marks "no tile"
+        const char *kb = static_cast<const char*>(a.workspace), *vb = kb;
+        int last = -1;
+        if (next_tile < t_end) {
+            while (tbl.tile0[s_next + 1] <= next_tile) ++s_next;
+            d.seg = s_next;
+            d.tok0 = (next_tile - tbl.tile0[s_next]) * TILE;
+            d.ntok = min(TILE, tbl.vis[s_next] - d.tok0);
+            d.delta = tbl.delta[s_next];
+            d.self = tbl.self[s_next];
+            ++next_tile;
+            const int64_t base = ((tbl.tok[s_next] + d.tok0) * kv_row + (int64_t)hkv * kD) * 2;
+            kb = static_cast<const char*>(d.self ? a.k_self : a.k_store) + base;
+            vb = static_cast<const char*>(d.self ? a.v_self : a.v_store) + base;
+            last = d.ntok - 1;
+        } else {
+            d.seg = 0; d.tok0 = 0; d.ntok = 0; d.delta = 0; d.self = 0;
+        }
+        // rows past the end of a ragged tile re-read its last row (in bounds; their scores are masked)
+#pragma unroll
+        for (int it = 0; it < kKItems; ++it) {
+            const uint32_t off = last < 0 ? 0u : (uint32_t)min(kr + 32 * it, last) * row_bytes + 16 * kj;
+            r.ka[it] = *reinterpret_cast<const uint4*>(kb + off);
+            r.kb[it] = *reinterpret_cast<const uint4*>(kb + off + (last < 0 ? 0 : 128));
+        }
+#pragma unroll
+        for (int it = 0; it < kVItems; ++it) {
+            const uint32_t off = last < 0 ? 0u : (uint32_t)min(vr + 16 * it, last) * row_bytes + 16 * vc;
+            r.v[it] = *reinterpret_cast<const uint4*>(vb + off);
+        }
+    };
+    Tile d0, d1;
+    fetch(d0, regs0);
+    fetch(d1, regs1);
 
     f32x4 acc[NRB][8];
 #pragma unroll
@@ -348,8 +346,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
 
     char* ws = static_cast<char*>(a.workspace);
     float2* massml = reinterpret_cast<float2*>(ws + p.off_massml) + (int64_t)unit * p.slots * p.rows_wg;
-
-    auto emit = [&](int s) {                        // (running max, segment sum) per row for segment s
+    auto emit = [&](int s) {                        // (running reference, segment sum) per row for segment s
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
             float tot = seg_l[rb] + __shfl_xor(seg_l[rb], 16);
@@ -358,76 +355,66 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
         }
     };
 
+    // V staging offsets (row-major [token][256 bytes]; chunk c of row t at chunk c ^ 2*(t & 7)) and the
+    // transposing reads: lane 16*lg + s addresses row 4*lg + s/4 (+16), 8 bytes at channel 16*db + 4*(s&3)
+    const uint32_t vw_off = (uint32_t)vr * 256 + 16 * (vc ^ (2 * (vr & 7)));    // rows vr + 16*it keep (t & 7)
+    const int tr_row = 4 * lg + (li >> 2);
+    const uint32_t tr_base = (uint32_t)tr_row * 256 + 8 * (li & 3);
+    const uint32_t tr_x = (uint32_t)(tr_row & 7) * 32;
+
     int cs_slot = 0;
     int cur_seg = -1;
-    if (d0.ntok > 0 && tid < kHalf) cs_lds[0][tid] = rope_cos_sin(tbl.delta[d0.seg], my_freq);
+    if (d0.ntok > 0 && d0.delta != 0 && tid < kHalf) cs_lds[0][tid] = rope_cos_sin_fast(d0.delta, my_freq);
+    __syncthreads();
 
-    // One tile: stage `cur` from its registers, refill those registers with the tile after `nxt`,
-    // prepare the cos/sin table of `nxt`, then do the math of `cur` out of LDS.
-    auto step = [&](TileDesc& cur, StageRegs& r, const TileDesc& nxt) {
-        const TileDesc cd = cur;
+    // Stage tile `cur` from its registers into buffer `buf`, refill the registers with the tile after
+    // `nxt`, prepare the cos/sin table of `nxt`; after the barrier, the math of `cur`.
+    auto step = [&](Tile& cur, StageRegs& r, const Tile& nxt, int buf) {
+        const Tile cd = cur;
+        const bool live = cd.ntok > 0;
+        uint16_t* k_lds = reinterpret_cast<uint16_t*>(k_buf[buf]);
+        unsigned char* v_lds = v_buf[buf];
+        if (live) {
+#pragma unroll
+            for (int it = 0; it < kKItems; ++it) {
+                uint4 ra = r.ka[it], rb4 = r.kb[it];
+                if (cd.delta != 0) {
+                    uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb4.x, rb4.y, rb4.z, rb4.w};
+                    const float4* cs = reinterpret_cast<const float4*>(cs_lds[cs_slot] + 8 * kj);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float4 w = cs[i];          // (cos, sin) of slices 8*kj + 2i, + 2i + 1
+                        const float a0 = Mma<DT>::lo(wa[i]), a1 = Mma<DT>::hi(wa[i]);
+                        const float b0 = Mma<DT>::lo(wb[i]), b1 = Mma<DT>::hi(wb[i]);
+                        wa[i] = Mma<DT>::pack(a0 * w.x - b0 * w.y, a1 * w.z - b1 * w.w);
+                        wb[i] = Mma<DT>::pack(a0 * w.y + b0 * w.x, a1 * w.w + b1 * w.z);
+                    }
+                    ra = make_uint4(wa[0], wa[1], wa[2], wa[3]);
+                    rb4 = make_uint4(wb[0], wb[1], wb[2], wb[3]);
+                }
+                uint16_t* dst = k_lds + (kr + 32 * it) * kSK + 8 * kj;
+                *reinterpret_cast<uint4*>(dst) = ra;
+                *reinterpret_cast<uint4*>(dst + kHalf) = rb4;
+            }
+#pragma unroll
+            for (int it = 0; it < kVItems; ++it) *reinterpret_cast<uint4*>(v_lds + it * 16 * 256 + vw_off) = r.v[it];
+        }
+        fetch(cur, r);                               // the registers are free again
+        if (nxt.ntok > 0 && nxt.seg != cd.seg && nxt.delta != 0) {
+            cs_slot ^= 1;
+            if (tid < kHalf) cs_lds[cs_slot][tid] = rope_cos_sin_fast(nxt.delta, my_freq);
+        }
+        __syncthreads();            // tile `cur` is staged; every wavefront is done with the other buffer
+        if (!live || !has_rows) return;
         if (cd.seg != cur_seg) {
             if (cur_seg >= 0) emit(cur_seg);
             cur_seg = cd.seg;
 #pragma unroll
             for (int rb = 0; rb < NRB; ++rb) seg_l[rb] = 0.f;
         }
-        const int cur_delta = tbl.delta[cd.seg];
-        __syncthreads();            // previous tile fully consumed; this tile's cos/sin table is visible
-        // ---- stage K: rotate pairs (c, c + 64), round once, write [token][c]
+        const bool causal = cd.self != 0;
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            uint4 ra = r.ka[it], rb4 = r.kb[it];
-            if (cur_delta != 0) {
-                uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb4.x, rb4.y, rb4.z, rb4.w};
-                const float2* cs = cs_lds[cs_slot] + 8 * kj;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float a0 = Mma<DT>::lo(wa[i]), a1 = Mma<DT>::hi(wa[i]);
-                    const float b0 = Mma<DT>::lo(wb[i]), b1 = Mma<DT>::hi(wb[i]);
-                    const float2 w0 = cs[2 * i], w1 = cs[2 * i + 1];
-                    wa[i] = Mma<DT>::pack(a0 * w0.x - b0 * w0.y, a1 * w1.x - b1 * w1.y);
-                    wb[i] = Mma<DT>::pack(a0 * w0.y + b0 * w0.x, a1 * w1.y + b1 * w1.x);
-                }
-                ra = make_uint4(wa[0], wa[1], wa[2], wa[3]);
-                rb4 = make_uint4(wb[0], wb[1], wb[2], wb[3]);
-            }
-            uint16_t* dst = k_lds + (kt + 32 * it) * kSK + 8 * kj;
-            *reinterpret_cast<uint4*>(dst) = ra;
-            *reinterpret_cast<uint4*>(dst + kHalf) = rb4;
-        }
-        // ---- stage V transposed: [channel][token]; inside each half of 32 tokens the order puts the
-        // 8 tokens of MFMA k-group g — {4g..4g+3} and {16+4g..16+4g+3} — side by side
-        {
-            const int tk = 4 * vq;                     // first token of this thread's quad
-            const int t32 = tk & 31;
-            const int pos = (tk >> 5) * 32 + ((t32 & 15) >> 2) * 8 + (t32 >> 4) * 4;
-            const uint32_t x0[4] = {r.v[0].x, r.v[0].y, r.v[0].z, r.v[0].w};
-            const uint32_t x1[4] = {r.v[1].x, r.v[1].y, r.v[1].z, r.v[1].w};
-            const uint32_t x2[4] = {r.v[2].x, r.v[2].y, r.v[2].z, r.v[2].w};
-            const uint32_t x3[4] = {r.v[3].x, r.v[3].y, r.v[3].z, r.v[3].w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                uint2 lo, hi;
-                lo.x = __builtin_amdgcn_perm(x1[i], x0[i], 0x05040100u);
-                lo.y = __builtin_amdgcn_perm(x3[i], x2[i], 0x05040100u);
-                hi.x = __builtin_amdgcn_perm(x1[i], x0[i], 0x07060302u);
-                hi.y = __builtin_amdgcn_perm(x3[i], x2[i], 0x07060302u);
-                *reinterpret_cast<uint2*>(v_lds + (8 * vj + 2 * i) * kSV + pos) = lo;
-                *reinterpret_cast<uint2*>(v_lds + (8 * vj + 2 * i + 1) * kSV + pos) = hi;
-            }
-        }
-        // ---- these registers are free again: the tile after `nxt` starts loading now
-        fetch(cur, r);
-        if (nxt.ntok > 0 && nxt.seg != cd.seg) {
-            cs_slot ^= 1;
-            if (tid < kHalf) cs_lds[cs_slot][tid] = rope_cos_sin(tbl.delta[nxt.seg], my_freq);
-        }
-        __syncthreads();            // staged tile visible
-
-        const bool causal = tbl.self[cd.seg] != 0;
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
+        for (int h2 = 0; h2 < TILE / 32; ++h2) {
             const int nt = cd.ntok - 32 * h2;      // valid tokens of this half
             if (nt <= 0) break;
             // ---- S^T = K Q^T : lane (li, lg) gets, for query row li, tokens 32*h2 + 16*tb + 4*lg + r
@@ -442,7 +429,7 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
 #pragma unroll
                     for (int rb = 0; rb < NRB; ++rb) sc[rb][tb] = Mma<DT>::run(ka, qf[rb][kk], sc[rb][tb]);
                 }
-            // ---- online softmax (exp2 domain), fp32
+            // ---- online softmax (exp2 domain), fp32, against a stale row maximum (see kRescaleSlack)
             const bool need_mask = causal || nt < 32;
             uint4 pfrag[NRB];
 #pragma unroll
@@ -461,51 +448,56 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
                     }
                 }
                 float mloc = fmaxf(fmaxf(fmaxf(xv[0], xv[1]), fmaxf(xv[2], xv[3])), fmaxf(fmaxf(xv[4], xv[5]), fmaxf(xv[6], xv[7])));
-                mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-                mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
                 mloc *= a.scale_log2e;                       // scale > 0: max commutes with it
-                const float m_new = fmaxf(m_run[rb], mloc);
-                const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-                const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - m_safe);
+                if (__any(mloc > m_run[rb] + kRescaleSlack)) {
+                    mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+                    mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+                    const float m_old = m_run[rb];
+                    const float m_new = fmaxf(m_old, mloc);
+                    const float alpha = __builtin_amdgcn_exp2f(m_old - (m_new == -INFINITY ? 0.f : m_new));
+                    l_run[rb] *= alpha;
+                    seg_l[rb] *= alpha;
+                    m_run[rb] = m_new;
+                    if (__any(alpha != 1.f && m_old != -INFINITY)) {     // nothing accumulated yet: nothing to rescale
+#pragma unroll
+                        for (int db = 0; db < 8; ++db) acc[rb][db] *= alpha;
+                    }
+                }
+                const float m_safe = m_run[rb] == -INFINITY ? 0.f : m_run[rb];
                 float lsum = 0.f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     xv[e] = __builtin_amdgcn_exp2f(fmaf(xv[e], a.scale_log2e, -m_safe));
                     lsum += xv[e];
                 }
-                l_run[rb] = l_run[rb] * alpha + lsum;
-                seg_l[rb] = seg_l[rb] * alpha + lsum;
-                m_run[rb] = m_new;
-                if (__any(alpha != 1.f)) {
-#pragma unroll
-                    for (int db = 0; db < 8; ++db) acc[rb][db] *= alpha;
-                }
+                l_run[rb] += lsum;
+                seg_l[rb] += lsum;
                 pfrag[rb] = make_uint4(Mma<DT>::pack(xv[0], xv[1]), Mma<DT>::pack(xv[2], xv[3]),
                                        Mma<DT>::pack(xv[4], xv[5]), Mma<DT>::pack(xv[6], xv[7]));
             }
-            // ---- O^T += V^T P^T
+            // ---- O^T += V^T P^T; V^T fragments by transposing reads of the row-major tile
 #pragma unroll
             for (int db = 0; db < 8; ++db) {
-                const uint4 va = *reinterpret_cast<const uint4*>(v_lds + (16 * db + li) * kSV + 32 * h2 + 8 * lg);
+                const unsigned char* src = v_lds + h2 * 32 * 256 + tr_base + ((uint32_t)(32 * db) ^ tr_x);
+                const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(src));
+                const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(src + 16 * 256));
+                const uint2 l2 = __builtin_bit_cast(uint2, lo), h2v = __builtin_bit_cast(uint2, hi);
+                const uint4 va = make_uint4(l2.x, l2.y, h2v.x, h2v.y);
 #pragma unroll
                 for (int rb = 0; rb < NRB; ++rb) acc[rb][db] = Mma<DT>::run(va, pfrag[rb], acc[rb][db]);
             }
         }
     };
-
-    if (kDeep) {
-        while (d0.ntok > 0) {
-            step(d0, regs0, d1);
-            if (d1.ntok <= 0) break;
-            step(d1, regs1, d0);
-        }
-    } else {
-        while (d0.ntok > 0) step(d0, regs0, d0);      // `nxt` is read after the refill: the same object serves
-    }
+    // Steps come in pairs and the exit test sits at the end only: every path round the loop issues the
+    // same loads and meets the same barriers.
+    do {
+        step(d0, regs0, d1, 0);
+        step(d1, regs1, d0, 1);
+    } while (d0.ntok > 0);
     if (cur_seg >= 0) emit(cur_seg);
 
     // ---- partial results of this split: O^T in MFMA layout (one float4 per lane, row block and
-    // channel block) and (max, sum) per row
+    // channel block) and (reference, sum) per row
     f32x4* opart = reinterpret_cast<f32x4*>(ws + p.off_opart) +
                    (((int64_t)unit * p.nsplit + split) * p.rows_wg / 16 + wave * NRB) * 8 * kWave + lane;
     float2* ml = reinterpret_cast<float2*>(ws + p.off_ml) + ((int64_t)unit * p.nsplit + split) * p.rows_wg;
@@ -519,479 +511,9 @@ __global__ __launch_bounds__(kThreads) void attn_mfma_kernel(AttnArgs a, RopeFre
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Small-M variant (at most 64 stacked query rows per kv head and at most 64 segments per query:
-// MHA and short queries; HBM-bound).  Every wavefront holds all NRB 16-row blocks and is an
-// independent worker over its own run of 32-token tiles (sub-split):
-//   * the segment table lives in registers, one segment per lane (prefix by a wavefront scan,
-//     lookup by ballot), so the prologue has no workgroup barrier and no LDS round trips;
-//   * K never touches LDS: a lane loads its key fragments straight in the MFMA operand layout
-//     (token = lane & 15 (+16), eight consecutive channels per 32-channel block), where the two
-//     halves (c, c + 64) of every RoPE pair sit in the same lane, and rotates them in registers;
-//   * V is copied as loaded (16 bytes per lane, row-major with a 32-byte XOR swizzle) into the
-//     wavefront's own LDS tile and read back as the V^T operand with the transposing LDS read
-//     (ds_read_b64_tr_b16), so no lane does any work to transpose it;
-//   * two tiles are in flight per wavefront, in registers, and every step issues a fixed number of
-//     loads, so the wait for one tile never covers a later one; the streaming loop has no
-//     workgroup barrier;
-//   * Q fragments are read from a shared LDS copy;
-//   * the four sub-splits of a workgroup are merged through LDS at the end, so one partial
-//     result per workgroup goes to memory.
-constexpr int kTileS = 32;
-constexpr int kVTileBytes = kTileS * kD * 2;           // 8192
-constexpr float kRescaleSlack = 8.f;                   // log2 of the largest probability kept relative to the running reference
-
-typedef short short4v __attribute__((ext_vector_type(4)));
-
-// cos/sin of delta*theta from the hardware sine/cosine (argument in revolutions, reduced in fp64):
-// their absolute error is far below the rounding step of the 16-bit keys this feeds.
-__device__ __forceinline__ float2 rope_cos_sin_fast(int delta, double theta_rev) {
-    const double x = (double)delta * theta_rev;
-    const float fr = (float)(x - rint(x));
-    return make_float2(__builtin_amdgcn_cosf(fr), __builtin_amdgcn_sinf(fr));
-}
-
-template <int DT, int NRB>
-__global__ __launch_bounds__(kThreads) void attn_small_kernel(AttnArgs a, RopeFreq freq, Plan p) {
-    __shared__ __attribute__((aligned(16))) unsigned char v_all[kWaves * kVTileBytes];   // one V tile per wavefront
-    constexpr int kPassRb = NRB <= 3 ? NRB : 2;      // row blocks merged per pass of the end-of-kernel reduce-scatter
-    __shared__ __attribute__((aligned(16))) unsigned char red_all[4 * 3 * kPassRb * 2 * kWave * 16];
-    __shared__ __attribute__((aligned(16))) uint16_t q_lds[64 * kSK];
-    __shared__ __attribute__((aligned(16))) float2 cs_all[kWaves][kHalf];
-    __shared__ float2 ml_w[kWaves][64];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-    const int li = lane & 15, lg = lane >> 4;
-    // Pull every pointer and scalar the streaming loop needs out of the kernel-argument segment
-    // now, in one batch of scalar loads, instead of one dependent round trip per first use.
-    {
-        const void *p0 = a.q, *p1 = a.q_off, *p2 = a.q_new_start, *p3 = a.k_store, *p4 = a.v_store, *p5 = a.k_self,
-                   *p6 = a.v_self, *p7 = a.segs, *p8 = a.n_seg, *p9 = a.workspace;
-        asm volatile("" ::"s"(p0), "s"(p1), "s"(p2), "s"(p3), "s"(p4), "s"(p5), "s"(p6), "s"(p7), "s"(p8), "s"(p9),
-                     "s"(a.n_store_tokens), "s"(a.seg_stride), "s"(a.batch), "s"(a.max_tq), "s"(a.n_q_heads),
-                     "s"(a.n_kv_heads), "s"(a.scale_log2e), "s"(a.q_stored_start), "s"(p.nsplit), "s"(p.slots),
-                     "s"(p.off_ml), "s"(p.off_opart), "s"(p.off_massml));
-    }
-
-    const int bid = blockIdx.x;                      // n_rg == 1: unit = (query, kv head)
-    const int split = bid % p.nsplit;
-    const int unit = bid / p.nsplit;
-    const int hkv = unit % a.n_kv_heads;
-    const int b = __builtin_amdgcn_readfirstlane(unit / a.n_kv_heads);
-    const int hq = a.n_q_heads;
-    const int group = hq / a.n_kv_heads;
-
-    // ---- per-query scalars and the segment table: lane s of every wavefront holds segment s
-    cf_segment seg;
-    seg.tok_offset = 0; seg.len = 0; seg.stored_start = 0; seg.new_start = 0; seg.kind = CF_SEG_DOC; seg.doc = -1; seg.reserved = 0;
-    if (lane < a.seg_stride) seg = a.segs[(int64_t)b * a.seg_stride + lane];      // seg_stride <= 64
-    const int q0 = a.q_off[b], q1 = a.q_off[b + 1], n_raw = a.n_seg[b], qn = a.q_new_start[b];
-    const int64_t q_total = a.q_off[a.batch];
-    asm volatile("" ::"s"(q0), "s"(q1), "s"(n_raw), "s"(qn));
-    const double my_freq = freq.rev[lane];
-    const int tq = min(q1 - q0, a.max_tq);
-    const int n_rows = group * tq;
-    int n_seg = n_raw;
-    if (n_seg < 0 || n_seg > a.seg_stride) {
-        if (tid == 0) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
-        n_seg = n_seg < 0 ? 0 : a.seg_stride;
-    }
-    const bool t_self = seg.kind == CF_SEG_SELF;
-    int t_vis = 0;
-    if (lane < n_seg) {
-        const int64_t limit = t_self ? q_total : a.n_store_tokens;
-        const bool bad = seg.kind < 0 || seg.kind > CF_SEG_SELF || seg.len < 0 || seg.tok_offset < 0 ||
-                         seg.tok_offset + seg.len > limit || (t_self && a.k_self == nullptr);
-        if (bad && wave == 0) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
-        t_vis = bad ? 0 : (t_self ? min(seg.len, tq) : seg.len);
-    }
-    const int t_delta = seg.new_start - seg.stored_start - (qn - a.q_stored_start);
-    const int t_cnt = (t_vis + kTileS - 1) / kTileS;
-    int t_incl = t_cnt;                              // inclusive prefix of tile counts over the lanes
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        const int u = __shfl_up(t_incl, o);
-        if (lane >= o) t_incl += u;
-    }
-    const unsigned total = (unsigned)__builtin_amdgcn_readlane(t_incl, kWave - 1);
-    const int t_tok_lo = (int)(uint32_t)seg.tok_offset, t_tok_hi = (int)(seg.tok_offset >> 32);
-
-    const unsigned nsub = (unsigned)(p.nsplit * kWaves);
-    const int ss = split * kWaves + wave;            // this wavefront's sub-split
-    const int t_begin = split_begin(total, nsub, ss);
-    const int t_end = split_begin(total, nsub, ss + 1);
-
-    // ---- Q rows of this kv head: row m = g*tq + t of the stack is q[q0 + t][hkv*group + g].  Their loads go
-    // out first: loads return in order, so the LDS copy below then waits for them and not for the tiles.
-    uint4 qv[4];
-    const int q_row = tid >> 2, q_part = tid & 3;    // 64 rows x 4 quarters of 64 bytes
-    {
-        const bool valid = q_row < n_rows && q_row < NRB * 16;
-        const int gi = valid ? q_row / tq : 0;
-        const int t = valid ? q_row - gi * tq : 0;
-        const uint16_t* qp = static_cast<const uint16_t*>(a.q) + (((int64_t)q0 + t) * hq + hkv * group + gi) * kD + 32 * q_part;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) qv[i] = valid ? *reinterpret_cast<const uint4*>(qp + 8 * i) : make_uint4(0, 0, 0, 0);
-    }
-    const int64_t kv_row = (int64_t)a.n_kv_heads * kD;
-    const uint32_t row_bytes = (uint32_t)a.n_kv_heads * (kD * 2);      // between consecutive tokens of one head
-    // One tile in registers: K in the MFMA operand layout ([token li + 16*h][channels 32*kk + 8*lg ..]) and
-    // V as loaded (instruction n: row 4n + (lane >> 4), 16-byte chunk lane & 15).
-    struct TileRegs { uint4 f[2][4]; uint4 v[8]; };
-    struct Tile { int seg, tok0, ntok, delta, self; int64_t base; };
-    TileRegs regs0, regs1;
-    unsigned char* const v_lds = v_all + wave * kVTileBytes;
-
-    // byte offsets of this lane's loads inside a whole tile (K: rows li, li + 16; V: rows (lane >> 4) + 4n)
-    uint32_t k_off[2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) k_off[h] = (uint32_t)(li + 16 * h) * row_bytes + lg * 16;
-    const uint32_t v_off = (uint32_t)(lane >> 4) * row_bytes + 16 * (lane & 15);
-
-    int next_tile = t_begin;
-    // Every step issues the same sixteen loads whether or not a tile is left (without one they re-read the
-    // first bytes of the workspace), so the number of loads in flight at any point of the loop is fixed
-    // and waiting for one tile's data never means waiting for a later tile's.
-    auto describe = [&](Tile& d) {                   // ntok == 0 marks "no tile"
-        if (next_tile < t_end) {
-            // the segment that owns this tile: first lane whose inclusive prefix exceeds it
-            const unsigned long long m = __ballot(t_incl > next_tile);
-            const int s = __builtin_ctzll(m);
-            const int incl = __builtin_amdgcn_readlane(t_incl, s), cnt = __builtin_amdgcn_readlane(t_cnt, s);
-            d.seg = s;
-            d.tok0 = (next_tile - (incl - cnt)) * kTileS;
-            d.ntok = min(kTileS, __builtin_amdgcn_readlane(t_vis, s) - d.tok0);
-            d.delta = __builtin_amdgcn_readlane(t_delta, s);
-            d.self = __builtin_amdgcn_readlane((int)t_self, s);
-            const int64_t tok = ((int64_t)__builtin_amdgcn_readlane(t_tok_hi, s) << 32) | (uint32_t)__builtin_amdgcn_readlane(t_tok_lo, s);
-            d.base = ((tok + d.tok0) * kv_row + (int64_t)hkv * kD) * 2;
-            ++next_tile;
-        } else {
-            d.seg = 0; d.tok0 = 0; d.ntok = 0; d.delta = 0; d.self = 0; d.base = 0;
-        }
-    };
-    // Rows past the end of a ragged tile re-read its last row: always in bounds, and their scores are
-    // masked out below.
-    auto fetch_k = [&](const Tile& d, TileRegs& r) {
-        const char* kb = static_cast<const char*>(a.workspace);
-        uint32_t ko[2] = {0, 0};
-        if (d.ntok == kTileS) {
-            ko[0] = k_off[0];
-            ko[1] = k_off[1];
-        } else if (d.ntok > 0) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) ko[h] = (uint32_t)min(li + 16 * h, d.ntok - 1) * row_bytes + lg * 16;
-        }
-        if (d.ntok > 0) kb = static_cast<const char*>(d.self ? a.k_self : a.k_store) + d.base;
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) r.f[h][kk] = *reinterpret_cast<const uint4*>(kb + ko[h] + 64 * kk);
-    };
-    auto fetch_v = [&](const Tile& d, TileRegs& r) {
-        const char* vb = static_cast<const char*>(a.workspace);
-        uint32_t vo[8];
-        if (d.ntok == kTileS) {
-#pragma unroll
-            for (int n = 0; n < 8; ++n) vo[n] = v_off + (uint32_t)n * (4 * row_bytes);
-        } else if (d.ntok > 0) {
-#pragma unroll
-            for (int n = 0; n < 8; ++n) vo[n] = (uint32_t)min(4 * n + (lane >> 4), d.ntok - 1) * row_bytes + 16 * (lane & 15);
-        } else {
-#pragma unroll
-            for (int n = 0; n < 8; ++n) vo[n] = 0;
-        }
-        if (d.ntok > 0) vb = static_cast<const char*>(d.self ? a.v_self : a.v_store) + d.base;
-#pragma unroll
-        for (int n = 0; n < 8; ++n) r.v[n] = *reinterpret_cast<const uint4*>(vb + vo[n]);
-    };
-    Tile d0, d1;
-    describe(d0);
-    fetch_k(d0, regs0);
-    fetch_v(d0, regs0);
-    describe(d1);
-    fetch_k(d1, regs1);
-    fetch_v(d1, regs1);
-
-    if (q_row < NRB * 16) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(q_lds + q_row * kSK + 32 * q_part + 8 * i) = qv[i];
-    }
-    int trow[NRB];
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        const int m = rb * 16 + li;
-        trow[rb] = m < n_rows ? m % tq : 0x7fffffff;  // padding rows: nothing to mask, results unused
-    }
-
-    float2* cs = cs_all[wave];
-    // transposing V reads: lane 16*lg + s addresses row 4*lg + s/4 (+16), 8 bytes at channel 16*db + 4*(s&3)
-    const int tr_row = 4 * lg + (li >> 2);
-    const uint32_t tr_base = (uint32_t)tr_row * 256 + 8 * (li & 3);
-    const uint32_t tr_x = (uint32_t)(tr_row & 7) * 32;
-    // V staging: row-major [token][256 bytes], the 16-byte chunk c of row t at chunk c ^ 2*(t & 7) (a
-    // 32-byte XOR swizzle: the transposing reads of one pass then fall on distinct banks)
-    uint32_t vw_off[2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int t = 4 * h + (lane >> 4);
-        vw_off[h] = (uint32_t)t * 256 + 16 * ((lane & 15) ^ (2 * (t & 7)));
-    }
-
-    f32x4 acc[NRB][8];
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-        for (int db = 0; db < 8; ++db) acc[rb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run[NRB], l_run[NRB], seg_l[NRB];
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) { m_run[rb] = -INFINITY; l_run[rb] = 0.f; seg_l[rb] = 0.f; }
-
-    char* ws = static_cast<char*>(a.workspace);
-    float2* massml = reinterpret_cast<float2*>(ws + p.off_massml) + (int64_t)unit * p.slots * 64;
-    auto emit = [&](int s) {                        // (running max, segment sum) per row for segment s
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) {
-            float tot = seg_l[rb] + __shfl_xor(seg_l[rb], 16);
-            tot += __shfl_xor(tot, 32);
-            if (lg == 0) massml[(int64_t)(s + ss) * 64 + rb * 16 + li] = make_float2(m_run[rb], tot);
-        }
-    };
-    __syncthreads();                                 // Q rows are in LDS
-
-    int cur_seg = -1;
-    // One tile: rotate `cur` in its registers, S^T = K Q^T, refill the K registers with the tile after
-    // next, softmax, V registers to LDS and refilled, O^T += V^T P^T by transposing LDS reads.
-    auto step = [&](Tile& cur, TileRegs& r) {
-        const Tile cd = cur;
-        const bool live = cd.ntok > 0;               // without a tile only the (fixed number of) loads are issued
-        const bool causal = cd.self != 0;
-        const int nt = cd.ntok;
-        f32x4 sc[NRB][2];
-        uint4 pfrag[NRB];
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) {
-            sc[rb][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-            sc[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-            pfrag[rb] = make_uint4(0, 0, 0, 0);
-        }
-        if (live) {
-        if (cd.seg != cur_seg) {
-            if (cur_seg >= 0) emit(cur_seg);
-            cur_seg = cd.seg;
-#pragma unroll
-            for (int rb = 0; rb < NRB; ++rb) seg_l[rb] = 0.f;
-            if (cd.delta != 0) {                       // lane m prepares cos/sin of slice m for the whole wavefront
-                __builtin_amdgcn_wave_barrier();
-                cs[lane] = rope_cos_sin_fast(cd.delta, my_freq);
-                __builtin_amdgcn_wave_barrier();
-            }
-        }
-        // ---- rotate pairs (c, c + 64): channel blocks kk and kk + 2 of the same lane; round once
-        if (cd.delta != 0) {
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                float4 w[4];                         // (cos, sin) of slices 32*kk + 8*lg + 2i, + 2i + 1
-#pragma unroll
-                for (int i = 0; i < 4; ++i) w[i] = *reinterpret_cast<const float4*>(&cs[32 * kk + 8 * lg + 2 * i]);
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    uint32_t wa[4] = {r.f[h][kk].x, r.f[h][kk].y, r.f[h][kk].z, r.f[h][kk].w};
-                    uint32_t wb[4] = {r.f[h][kk + 2].x, r.f[h][kk + 2].y, r.f[h][kk + 2].z, r.f[h][kk + 2].w};
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float a0 = Mma<DT>::lo(wa[i]), a1 = Mma<DT>::hi(wa[i]);
-                        const float b0 = Mma<DT>::lo(wb[i]), b1 = Mma<DT>::hi(wb[i]);
-                        const float2 w0 = make_float2(w[i].x, w[i].y), w1 = make_float2(w[i].z, w[i].w);
-                        wa[i] = Mma<DT>::pack(a0 * w0.x - b0 * w0.y, a1 * w1.x - b1 * w1.y);
-                        wb[i] = Mma<DT>::pack(a0 * w0.y + b0 * w0.x, a1 * w1.y + b1 * w1.x);
-                    }
-                    r.f[h][kk] = make_uint4(wa[0], wa[1], wa[2], wa[3]);
-                    r.f[h][kk + 2] = make_uint4(wb[0], wb[1], wb[2], wb[3]);
-                }
-            }
-        }
-        // ---- S^T = K Q^T : lane (li, lg) gets, for query row li, tokens 16*tb + 4*lg + r
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-#pragma unroll
-            for (int rb = 0; rb < NRB; ++rb) {
-                const uint4 qv = *reinterpret_cast<const uint4*>(q_lds + (16 * rb + li) * kSK + 32 * kk + 8 * lg);
-                sc[rb][0] = Mma<DT>::run(r.f[0][kk], qv, sc[rb][0]);
-                sc[rb][1] = Mma<DT>::run(r.f[1][kk], qv, sc[rb][1]);
-            }
-        }
-        }
-        Tile nx;
-        describe(nx);
-        fetch_k(nx, r);                              // the K registers are free again
-        if (live) {
-        // ---- online softmax (exp2 domain), fp32
-        const bool need_mask = causal || nt < kTileS;
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) {
-            float xv[8];
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) xv[4 * tb + e] = sc[rb][tb][e];
-            if (need_mask) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int tk = 16 * (e >> 2) + 4 * lg + (e & 3);
-                    const bool ok = tk < nt && (!causal || cd.tok0 + tk <= trow[rb]);
-                    xv[e] = ok ? xv[e] : -INFINITY;
-                }
-            }
-            // The running reference m_run is a stale row maximum: it only moves when some score of the
-            // row exceeds it by more than 8 (in the exp2 domain), so probabilities stay below 2^8 and the
-            // accumulators are rescaled a handful of times per row instead of once per tile.  Every sum
-            // kept beside it (l_run, seg_l, acc) is relative to the same reference, so the results are
-            // those of the exact maximum.
-            float mloc = fmaxf(fmaxf(fmaxf(xv[0], xv[1]), fmaxf(xv[2], xv[3])), fmaxf(fmaxf(xv[4], xv[5]), fmaxf(xv[6], xv[7])));
-            mloc *= a.scale_log2e;                       // scale > 0: max commutes with it
-            if (__any(mloc > m_run[rb] + kRescaleSlack)) {
-                mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-                mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-                const float m_old = m_run[rb];
-                const float m_new = fmaxf(m_old, mloc);
-                const float alpha = __builtin_amdgcn_exp2f(m_old - (m_new == -INFINITY ? 0.f : m_new));
-                l_run[rb] *= alpha;
-                seg_l[rb] *= alpha;
-                m_run[rb] = m_new;
-                if (__any(alpha != 1.f && m_old != -INFINITY)) {     // nothing accumulated yet: nothing to rescale
-#pragma unroll
-                    for (int db = 0; db < 8; ++db) acc[rb][db] *= alpha;
-                }
-            }
-            const float m_safe = m_run[rb] == -INFINITY ? 0.f : m_run[rb];
-            float lsum = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                xv[e] = __builtin_amdgcn_exp2f(fmaf(xv[e], a.scale_log2e, -m_safe));
-                lsum += xv[e];
-            }
-            l_run[rb] += lsum;
-            seg_l[rb] += lsum;
-            pfrag[rb] = make_uint4(Mma<DT>::pack(xv[0], xv[1]), Mma<DT>::pack(xv[2], xv[3]),
-                                   Mma<DT>::pack(xv[4], xv[5]), Mma<DT>::pack(xv[6], xv[7]));
-        }
-        // ---- V to LDS (the wavefront's own tile buffer; its previous contents were read by the last step)
-#pragma unroll
-        for (int n = 0; n < 8; ++n) *reinterpret_cast<uint4*>(v_lds + (n >> 1) * 2048 + vw_off[n & 1]) = r.v[n];
-        }
-        fetch_v(nx, r);                              // the V registers are free again
-        cur = nx;
-        // ---- O^T += V^T P^T; V^T fragments by transposing reads of the row-major tile
-        if (live) {
-#pragma unroll
-        for (int db = 0; db < 8; ++db) {
-            const unsigned char* src = v_lds + tr_base + ((uint32_t)(32 * db) ^ tr_x);
-            const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(src));
-            const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(src + 16 * 256));
-            const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
-            const uint4 va = make_uint4(l2.x, l2.y, h2.x, h2.y);
-#pragma unroll
-            for (int rb = 0; rb < NRB; ++rb) acc[rb][db] = Mma<DT>::run(va, pfrag[rb], acc[rb][db]);
-        }
-        }
-    };
-    // Steps come in pairs and the exit test sits at the end only: every path round the loop issues the
-    // same loads.  A wavefront with an odd number of tiles runs one step without a tile.
-    do {
-        step(d0, regs0);
-        step(d1, regs1);
-    } while (d0.ntok > 0);
-    if (cur_seg >= 0) emit(cur_seg);
-
-    // ---- merge the four sub-splits of this workgroup (same rows, different tokens) through LDS
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        float tot = l_run[rb] + __shfl_xor(l_run[rb], 16);
-        tot += __shfl_xor(tot, 32);
-        if (lg == 0) ml_w[wave][rb * 16 + li] = make_float2(m_run[rb], tot);
-    }
-    __syncthreads();
-    float mx[NRB], zz[NRB];
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        const int row = rb * 16 + li;
-        float m = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) m = fmaxf(m, ml_w[w][row].x);
-        const float ms = m == -INFINITY ? 0.f : m;
-        float z = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) z += ml_w[w][row].y * __builtin_amdgcn_exp2f(ml_w[w][row].x - ms);
-        mx[rb] = m;
-        zz[rb] = z;
-        const float f = __builtin_amdgcn_exp2f(m_run[rb] - ms);
-#pragma unroll
-        for (int db = 0; db < 8; ++db) acc[rb][db] *= f;
-    }
-    // Reduce-scatter, kPassRb row blocks per pass: item j = (row block, channel block) of the pass belongs
-    // to wavefront j % 4; every wavefront parks the items it does not own in LDS, one barrier, then each
-    // owner adds the three parked copies to its own (fixed order) and stores its items — the partial
-    // result of this workgroup, same format as the shared-tile kernel with one row block per wavefront.
-    f32x4* red = reinterpret_cast<f32x4*>(red_all);
-    constexpr int kOwn = kPassRb * 2;                // items per owner and pass
-    f32x4* opart = reinterpret_cast<f32x4*>(ws + p.off_opart) + ((int64_t)unit * p.nsplit + split) * 4 * 8 * kWave + lane;
-    auto park = [&](auto w_, int rb0) {              // specialised per wavefront: straight-line code
-        constexpr int W = decltype(w_)::value;
-#pragma unroll
-        for (int r = 0; r < kPassRb; ++r)
-#pragma unroll
-            for (int db = 0; db < 8; ++db) {
-                const int j = r * 8 + db, o = j & 3;
-                if (o != W) red[(((o * 3 + ((W - o - 1) & 3)) * kOwn) + (j >> 2)) * kWave + lane] = acc[rb0 + r][db];
-            }
-    };
-    auto gather = [&](auto w_, int rb0) {
-        constexpr int W = decltype(w_)::value;
-#pragma unroll
-        for (int r = 0; r < kPassRb; ++r)
-#pragma unroll
-            for (int db = 0; db < 8; ++db) {
-                const int j = r * 8 + db;
-                if ((j & 3) == W) {
-                    f32x4 v = acc[rb0 + r][db];
-#pragma unroll
-                    for (int c = 0; c < 3; ++c) v += red[(((W * 3 + c) * kOwn) + (j >> 2)) * kWave + lane];
-                    opart[((rb0 + r) * 8 + db) * kWave] = v;
-                }
-            }
-    };
-#pragma unroll
-    for (int rb0 = 0; rb0 < NRB; rb0 += kPassRb) {
-        if (rb0 > 0) __syncthreads();                // the previous pass has been read
-        switch (wave) {
-            case 0: park(std::integral_constant<int, 0>{}, rb0); break;
-            case 1: park(std::integral_constant<int, 1>{}, rb0); break;
-            case 2: park(std::integral_constant<int, 2>{}, rb0); break;
-            default: park(std::integral_constant<int, 3>{}, rb0); break;
-        }
-        __syncthreads();
-        switch (wave) {
-            case 0: gather(std::integral_constant<int, 0>{}, rb0); break;
-            case 1: gather(std::integral_constant<int, 1>{}, rb0); break;
-            case 2: gather(std::integral_constant<int, 2>{}, rb0); break;
-            default: gather(std::integral_constant<int, 3>{}, rb0); break;
-        }
-    }
-    if (wave == 0 && lg == 0) {
-        float2* ml = reinterpret_cast<float2*>(ws + p.off_ml) + ((int64_t)unit * p.nsplit + split) * 64;
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) ml[rb * 16 + li] = make_float2(mx[rb], zz[rb]);
-#pragma unroll
-        for (int rb = NRB; rb < 4; ++rb) ml[rb * 16 + li] = make_float2(-INFINITY, 0.f);   // row blocks that do not exist
-    }
-}
-
 // Second kernel: one workgroup per (unit, 64-row pass, eighth of the output channels) merges the
 // splits' partial outputs and writes its output rows; the eight workgroups of a (unit, pass) also share
-// the reduction, over the pass's 64 rows, of every (segment, sub-split) slot's (max, sum) pairs to
+// the reduction, over the pass's 64 rows, of every (segment, split) slot's (max, sum) pairs to
 // sum * exp2(max - row max) / row sum, which the mass kernel then only has to add up.
 template <int DT>
 __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan p) {
@@ -1063,7 +585,7 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
         pk.y = Mma<DT>::pack(o[2], o[3]);
         *reinterpret_cast<uint2*>(op) = pk;
     }
-    // slot partials: slot k = segment + sub-split; slots no sub-split wrote this call hold stale pairs and
+    // slot partials: slot k = segment + split; slots no split wrote this call hold stale pairs and
     // give meaningless numbers that the mass kernel never reads
     {
         float* masspart = reinterpret_cast<float*>(ws + p.off_masspart) + ((int64_t)unit * p.nrb + pass) * p.slots;
@@ -1080,13 +602,13 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
 
 // Per-segment attention mass of one query, by the whole workgroup, in a fixed order: first every
 // slot's partials are added over the (unit, pass) parts, then a segment adds the slots of the
-// sub-splits that hold its tiles.  A sub-split between a segment's first and last may own no tile at
-// all (fewer tiles than sub-splits): its slot was not written by this call and is skipped.
+// splits that hold its tiles.  A split between a segment's first and last may own no tile at
+// all (fewer tiles than splits): its slot was not written by this call and is skipped.
 // `parts`: [nparts][slots] floats, in LDS (stage == nullptr) or in memory (stage: kMassStage floats of LDS).
 // `on_mass(s, m)` is called once per segment.  Both forms add in the same order.
 struct MassScratch {
-    float colsum[kMaxSegs + kMaxSplit * kWaves];
-    int32_t sub_begin[kMaxSplit * kWaves + 1];
+    float colsum[kMaxSegs + kMaxSplit];
+    int32_t sub_begin[kMaxSplit + 1];
 };
 constexpr int kMassStage = 4096;            // floats of partials staged per round by the stand-alone mass kernel
 
@@ -1095,7 +617,7 @@ __device__ __forceinline__ void segment_masses_block(const Plan& p, const SegTab
                                                      MassScratch* ms, F on_mass) {
     const int tid = threadIdx.x, nthr = blockDim.x;
     const unsigned total = (unsigned)tbl.tile0[tbl.n];
-    const unsigned nsub = (unsigned)(p.nsplit * p.sub);
+    const unsigned nsub = (unsigned)p.nsplit;
     const int nparts = p.units_per_b * p.nrb;
     if (stage == nullptr) {                          // partials already in LDS
         for (int k = tid; k < p.slots; k += nthr) {
@@ -1205,9 +727,6 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
     const int64_t off = (int64_t)b * stride;
     const int nparts = p.units_per_b * p.nrb;
     const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * nparts * p.slots;
-#if defined(CF_EPI_LEVEL) && CF_EPI_LEVEL <= 0
-    if (a.batch > 0) return;
-#endif
     const QueryHead qh = load_query_head(a, b);
     const int n_cand = pr.n_cand[b];
     if (tid == 0) { s_int[4] = pr.q_start[b]; s_int[5] = pr.n_reuse[b]; }
@@ -1221,31 +740,19 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
     }
     for (int i = tid; i < nparts * p.slots; i += kEpiThreads) l_part[i] = mp_b[i];
     build_table(a, qh, &tbl, p.tile);                // its barriers also publish the rows above
-#if defined(CF_EPI_LEVEL) && CF_EPI_LEVEL <= 1
-    if (a.batch > 0) return;
-#endif
     segment_masses_block(p, tbl, l_part, nullptr, &ms, [&](int s, float m) {
         a.mass[(int64_t)b * a.seg_stride + s] = m;
         const int doc = tbl.doc[s];
         if (doc >= 0 && doc < stride) atomicAdd(&l_score[doc], m);
     });
     __syncthreads();
-#if defined(CF_EPI_LEVEL) && CF_EPI_LEVEL <= 2
-    if (a.batch > 0) return;
-#endif
     for (int i = tid; i < stride; i += kEpiThreads) a.score_accum[off + i] = l_score[i];
     const int k = prune_topk_block(l_score, pr.normalise_by_len ? l_len : nullptr, l_cand, n_cand, pr.keep, stride, l_keep,
                                    a.dev_flag, scratch, &s_int[3]);
     if (tid == 0) pr.n_keep[b] = k;
-#if defined(CF_EPI_LEVEL) && CF_EPI_LEVEL <= 3
-    if (a.batch > 0) return;
-#endif
     __syncthreads();
     assign_positions_block(l_len, l_keep, k, stride, pr.pos_begin, pr.pos_end, pr.strategy, pr.force_n_reuse, l_start,
                            &s_int[4], &s_int[5], l_order, a.dev_flag, scratch, s_int);
-#if defined(CF_EPI_LEVEL) && CF_EPI_LEVEL <= 4
-    if (a.batch > 0) return;
-#endif
     __syncthreads();
     gather_segments_block(l_tok, l_len, l_order, k, l_start, s_int[4], qh.q0, qh.q0 + qh.tq_raw, stride, pr.prefix_len,
                           pr.doc_stored_start, a.q_stored_start, pr.next_segs + (int64_t)b * a.seg_stride,
@@ -1283,26 +790,22 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
     const Plan p = make_plan(a.n_q_heads, a.n_kv_heads, a.batch, a.max_tq, a.seg_stride, a.max_kv_tokens);
     const dim3 grid((unsigned)(p.x_count * p.n_rg)), block(kThreads);
     const dim3 grid2((unsigned)(p.units * p.nrb * 8)), grid3((unsigned)a.batch);
-#define CF_LAUNCH(DT, N) hipLaunchKernelGGL((attn_mfma_kernel<DT, N>), grid, block, 0, s, a, f, p)
-#define CF_LAUNCH_S(DT, N) hipLaunchKernelGGL((attn_small_kernel<DT, N>), grid, block, 0, s, a, f, p)
+#define CF_LAUNCH(DT, N)                                                                             \
+    do {                                                                                             \
+        if (p.tile == 32) hipLaunchKernelGGL((attn_tile_kernel<DT, N, 32>), grid, block, 0, s, a, f, p); \
+        else hipLaunchKernelGGL((attn_tile_kernel<DT, N, 64>), grid, block, 0, s, a, f, p);          \
+    } while (0)
 #define CF_LAUNCH_DT(DT)                                   \
-    if ((phases & 1) && p.sub == 1) switch (p.nrb) {       \
+    if (phases & 1) switch (p.nrb) {                       \
         case 1: CF_LAUNCH(DT, 1); break;                   \
         case 2: CF_LAUNCH(DT, 2); break;                   \
         case 3: CF_LAUNCH(DT, 3); break;                   \
         default: CF_LAUNCH(DT, 4); break;                  \
     }                                                      \
-    if ((phases & 1) && p.sub != 1) switch (p.row_blocks) {\
-        case 1: CF_LAUNCH_S(DT, 1); break;                 \
-        case 2: CF_LAUNCH_S(DT, 2); break;                 \
-        case 3: CF_LAUNCH_S(DT, 3); break;                 \
-        default: CF_LAUNCH_S(DT, 4); break;                \
-    }                                                      \
     CF_HIP(hipGetLastError());                             \
     if (phases & 2) hipLaunchKernelGGL((attn_combine_kernel<DT>), grid2, block, 0, s, a, p);
     if (a.dtype == CF_BF16) { CF_LAUNCH_DT(CF_BF16) } else { CF_LAUNCH_DT(CF_F16) }
 #undef CF_LAUNCH_DT
-#undef CF_LAUNCH_S
 #undef CF_LAUNCH
     CF_HIP(hipGetLastError());
     if (prune) {
