@@ -2,7 +2,8 @@
 """Benchmark of the re-positioned cached-KV prefill path on one MI355X.
 
 A step is one pass of the whole hot path over one layer of the LLaMA-2-7B-shaped workload
-(32-token shared prefix + 10 cached documents x 160 tokens + a 48-token query, bf16):
+(32-token shared prefix + 10 cached documents x 160 tokens + a 48-token query, bf16; the cache store
+head-major, [kv head][token][d], unless --store-layout token):
 one cf_prefill_layer call = cf_prefill_attention (keys re-positioned on the fly, attention,
 per-document mass, S += mass) + cf_prune_topk (keep 5) + cf_assign_positions + cf_gather_segments
 for the next layer's table.
@@ -89,6 +90,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--layers", type=int, default=24, help="distinct layer buffers cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--store-layout", choices=["head", "token"], default="head",
+                    help="layout of the cache store: head-major [kv head][token][d] (default, the layout the "
+                         "store is meant to be kept in) or token-major [token][kv head][d]")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only 10 elementwise copies of 1 GiB (read 1 GiB + write 1 GiB each): the known-size "
                          "kernel that scales the HBM byte counters of a profiler run")
@@ -120,14 +124,17 @@ def main() -> int:
     cfg = wl.CONFIGS[WORKLOAD]
     g = cfg.geometry
     st = wl.build_structure(cfg)
-    desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions)
+    ts, hs = pl.store_strides(st.n_store_tokens, g.n_kv_heads, g.head_dim, args.store_layout)
+    desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions,
+                        store_token_stride=ts, store_head_stride=hs)
     off = st.doc_off[:-1][st.query_docs]
     lens = st.doc_lens[st.query_docs]
     pb = pl.PrefillBatch(desc, off, lens, cfg.tq, cfg.prefix_len, cfg.doc_stored_start, st.n_store_tokens)
     layers = []
     for layer in range(args.layers):
         t = wl.build_layer(cfg, st, layer)
-        layers.append({k: pl.to_device(v, g.dtype) for k, v in t.items()})
+        layers.append({k: (pl.store_to_device(v, g.dtype, args.store_layout) if k in ("k_store", "v_store")
+                           else pl.to_device(v, g.dtype)) for k, v in t.items()})
     out = torch.empty_like(layers[0]["q"])
     pb.allocate_initial()
     torch.cuda.synchronize()
@@ -191,6 +198,7 @@ def main() -> int:
         "config": {"workload": WORKLOAD, "batch": cfg.batch, "kv_tokens_per_step": kv_tokens,
                    "q_heads": g.n_q_heads, "kv_heads": g.n_kv_heads, "head_dim": g.head_dim, "tq": cfg.tq,
                    "docs": cfg.docs_per_query, "keep": cfg.keep, "layer_buffers": len(layers),
+                   "store_layout": args.store_layout,
                    "step": "cf_prefill_layer: attention + mass + prune_topk + assign_positions + gather_segments"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,

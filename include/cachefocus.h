@@ -87,6 +87,14 @@ typedef struct cf_layer_desc {
     double  rope_base;       /* theta_m = rope_base^(-2m/head_dim)                                  */
     float   softmax_scale;   /* 0 => 1/sqrt(head_dim) (Eq. 1)                                       */
     int32_t reserved;        /* must be 0                                                           */
+    /* Layout of the cache store (k_store, v_store; k_in, k_out of cf_reposition_keys), in elements:
+     * channel c of kv head h of token t sits at t*store_token_stride + h*store_head_stride + c.
+     * Both 0: token-major [token][n_kv_heads][head_dim].  Head-major [n_kv_heads][tokens][head_dim]
+     * (token stride head_dim, head stride tokens*head_dim) makes every (head, document) run
+     * contiguous, which is what the streaming kernels read fastest.  Both must be multiples of 8 and
+     * at least head_dim.  q, out, k_self and v_self are always token-major. */
+    int64_t store_token_stride;
+    int64_t store_head_stride;
 } cf_layer_desc;
 
 /* One run of cached tokens attended by a query (device-resident table entry, 32 bytes).

@@ -34,7 +34,8 @@ EXPORTS = ("cf_reposition_keys", "cf_prefill_workspace_bytes", "cf_prefill_atten
 class cf_layer_desc(C.Structure):
     _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("dtype", C.c_int32), ("rope_pairing", C.c_int32), ("max_positions", C.c_int32),
-                ("rope_base", C.c_double), ("softmax_scale", C.c_float), ("reserved", C.c_int32)]
+                ("rope_base", C.c_double), ("softmax_scale", C.c_float), ("reserved", C.c_int32),
+                ("store_token_stride", C.c_int64), ("store_head_stride", C.c_int64)]
 
 
 class cf_prune_step(C.Structure):
@@ -99,10 +100,12 @@ def load() -> C.CDLL:
 
 
 def make_desc(n_q_heads: int, n_kv_heads: int, head_dim: int, dtype, rope_base: float, max_positions: int,
-              rope_pairing: int = CF_ROPE_HALF, softmax_scale: float = 0.0) -> cf_layer_desc:
+              rope_pairing: int = CF_ROPE_HALF, softmax_scale: float = 0.0, store_token_stride: int = 0,
+              store_head_stride: int = 0) -> cf_layer_desc:
+    """Strides (elements) describe the cache store; 0, 0 is token-major [token][kv head][head_dim]."""
     code = DTYPE_CODE[dtype] if isinstance(dtype, str) else int(dtype)
     return cf_layer_desc(n_q_heads, n_kv_heads, head_dim, code, rope_pairing, max_positions, float(rope_base),
-                         float(softmax_scale), 0)
+                         float(softmax_scale), 0, int(store_token_stride), int(store_head_stride))
 
 
 def segments_array(segments: Sequence) -> np.ndarray:

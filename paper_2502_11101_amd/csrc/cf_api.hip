@@ -43,6 +43,13 @@ cf_status check_desc(const cf_layer_desc* d) {
     CF_REQUIRE(std::isfinite(d->softmax_scale) && d->softmax_scale >= 0.f, CF_ERR_INVALID_ARG,
                "softmax_scale must be >= 0");
     CF_REQUIRE(d->reserved == 0, CF_ERR_INVALID_ARG, "desc.reserved must be 0");
+    if (d->store_token_stride != 0 || d->store_head_stride != 0) {
+        CF_REQUIRE(d->store_token_stride >= d->head_dim && d->store_head_stride >= d->head_dim, CF_ERR_INVALID_ARG,
+                   "store strides must both be 0 or both at least head_dim");
+        CF_REQUIRE(d->store_token_stride % 8 == 0 && d->store_head_stride % 8 == 0, CF_ERR_INVALID_ARG,
+                   "store strides must be multiples of 8 elements");
+        CF_REQUIRE(d->store_token_stride <= (1 << 24), CF_ERR_UNSUPPORTED, "store_token_stride above 2^24 elements");
+    }
     return CF_OK;
 }
 
@@ -181,6 +188,8 @@ static cf_status prefill_impl(const cf_layer_desc* desc, const void* q, const in
     a.dtype = desc->dtype; a.pairing = desc->rope_pairing;
     const double scale = desc->softmax_scale > 0.f ? (double)desc->softmax_scale : 1.0 / std::sqrt((double)desc->head_dim);
     a.scale_log2e = (float)(scale * 1.4426950408889634073599246810019);
+    a.store_ts = store_token_stride(desc);
+    a.store_hs = store_head_stride(desc);
     RopeFreq f;
     fill_rope_freq(desc, &f);
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -97,12 +97,14 @@ __global__ __launch_bounds__(kThreads) void attn_rows_kernel(AttnArgs a, RopeFre
             __builtin_amdgcn_wave_barrier();
             const T* kb = static_cast<const T*>(self ? a.k_self : a.k_store);
             const T* vb = static_cast<const T*>(self ? a.v_self : a.v_store);
+            const int64_t tok_stride = self ? kv_row : a.store_ts;       // the own block is always token-major
+            const int64_t head_off = (int64_t)kvh * (self ? d : a.store_hs);
             for (int tok0 = 0; tok0 < vis; tok0 += kWave) {
                 const int tok = tok0 + lane;
                 const bool valid = tok < vis;
                 float sc = -INFINITY;
                 if (valid) {
-                    const int64_t kbase = (seg.tok_offset + tok) * kv_row + (int64_t)kvh * d;
+                    const int64_t kbase = (seg.tok_offset + tok) * tok_stride + head_off;
                     float acc = 0.f;
                     for (int j = 0; j < half / 8; ++j) {
                         float x[8], y[8];
@@ -146,7 +148,7 @@ __global__ __launch_bounds__(kThreads) void attn_rows_kernel(AttnArgs a, RopeFre
                 const int cnt = min(kWave, vis - tok0);
                 for (int jj = 0; jj < cnt; ++jj) {
                     const float pj = __shfl(p, jj);
-                    const T* vp = vb + (seg.tok_offset + tok0 + jj) * kv_row + (int64_t)kvh * d;
+                    const T* vp = vb + (seg.tok_offset + tok0 + jj) * tok_stride + head_off;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int c = lane + kWave * i;

@@ -288,7 +288,6 @@ __global__ __launch_bounds__(kThreads) void attn_tile_kernel(AttnArgs a, RopeFre
     const int t_end = split_begin(total, p.nsplit, split + 1);
 
     const int64_t kv_row = (int64_t)a.n_kv_heads * kD;
-    const uint32_t row_bytes = (uint32_t)a.n_kv_heads * (kD * 2);
     // staging items: K (row kr + 32*it, chunks kj and kj + 8), V (row vr + 16*it, chunk vc)
     const int kr = tid >> 3, kj = tid & 7;
     const int vr = tid >> 4, vc = tid & 15;
@@ -296,24 +295,45 @@ __global__ __launch_bounds__(kThreads) void attn_tile_kernel(AttnArgs a, RopeFre
     struct Tile { int seg, tok0, ntok, delta, self; };
     StageRegs regs0, regs1;
 
-    int s_next = 0;
     int next_tile = t_begin;
+    // the segment of the tile fetched last, cached in scalars: most tiles continue their predecessor's segment
+    int c_seg = -1, c_first = 0, c_end = 0, c_vis = 0, c_delta = 0, c_self = 0;
+    int64_t c_tok = 0;
     // Every call issues the same loads whether or not a tile is left (without one they re-read the first
     // bytes of the workspace), so the number of loads in flight at any point of the loop is fixed.
     auto fetch = [&](Tile& d, StageRegs& r) {        // ntok == 0 marks "no tile"
         const char *kb = static_cast<const char*>(a.workspace), *vb = kb;
         int last = -1;
+        uint32_t row_bytes = 0;                      // between consecutive tokens of this head
         if (next_tile < t_end) {
-            while (tbl.tile0[s_next + 1] <= next_tile) ++s_next;
-            d.seg = s_next;
-            d.tok0 = (next_tile - tbl.tile0[s_next]) * TILE;
-            d.ntok = min(TILE, tbl.vis[s_next] - d.tok0);
-            d.delta = tbl.delta[s_next];
-            d.self = tbl.self[s_next];
+            if (next_tile >= c_end) {
+                // the first segment whose tiles reach past this one: every lane tests one entry per round
+                int s = 0;
+                for (int s0 = c_seg < 0 ? 0 : (c_seg & ~(kWave - 1));; s0 += kWave) {
+                    const int idx = s0 + lane;
+                    const unsigned long long hit = __ballot(idx < tbl.n && tbl.tile0[idx + 1] > next_tile);
+                    if (hit) { s = s0 + __builtin_ctzll(hit); break; }
+                }
+                c_seg = s;
+                c_first = tbl.tile0[s];
+                c_end = tbl.tile0[s + 1];
+                c_vis = tbl.vis[s];
+                c_delta = tbl.delta[s];
+                c_self = tbl.self[s];
+                c_tok = tbl.tok[s];
+            }
+            d.seg = c_seg;
+            d.tok0 = (next_tile - c_first) * TILE;
+            d.ntok = min(TILE, c_vis - d.tok0);
+            d.delta = c_delta;
+            d.self = c_self;
             ++next_tile;
-            const int64_t base = ((tbl.tok[s_next] + d.tok0) * kv_row + (int64_t)hkv * kD) * 2;
+            // the own block is always token-major; the store has its own strides
+            const int64_t tok_stride = d.self ? kv_row : a.store_ts;
+            const int64_t base = ((c_tok + d.tok0) * tok_stride + (int64_t)hkv * (d.self ? kD : a.store_hs)) * 2;
             kb = static_cast<const char*>(d.self ? a.k_self : a.k_store) + base;
             vb = static_cast<const char*>(d.self ? a.v_self : a.v_store) + base;
+            row_bytes = (uint32_t)tok_stride * 2;
             last = d.ntok - 1;
         } else {
             d.seg = 0; d.tok0 = 0; d.ntok = 0; d.delta = 0; d.self = 0;

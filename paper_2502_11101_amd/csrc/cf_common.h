@@ -137,7 +137,13 @@ struct AttnArgs {
     int32_t* dev_flag;
     int32_t n_q_heads, n_kv_heads, head_dim, dtype, pairing;
     float scale_log2e;   // softmax scale times log2(e)
+    int64_t store_ts, store_hs;   // element strides of the cache store between tokens / kv heads
 };
+
+inline int64_t store_token_stride(const cf_layer_desc* d) {
+    return d->store_token_stride ? d->store_token_stride : (int64_t)d->n_kv_heads * d->head_dim;
+}
+inline int64_t store_head_stride(const cf_layer_desc* d) { return d->store_head_stride ? d->store_head_stride : d->head_dim; }
 
 size_t generic_workspace_bytes(const cf_layer_desc* d, int32_t batch, int32_t max_tq, int32_t seg_stride);
 cf_status launch_attention_generic(const AttnArgs& a, const RopeFreq& f, hipStream_t s);

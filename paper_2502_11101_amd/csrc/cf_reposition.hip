@@ -60,7 +60,8 @@ template <> struct Vec8<CF_F16> : Vec8Half<CF_F16> {};
 template <int DT, int PAIRING>
 __global__ __launch_bounds__(kThreads) void reposition_kernel(
     const void* k_in, void* k_out, const cf_segment* __restrict__ segs,
-    int64_t n_store_tokens, int n_kv_heads, int head_dim, RopeFreq freq, int32_t* dev_flag) {
+    int64_t n_store_tokens, int n_kv_heads, int head_dim, int64_t tok_stride, int64_t head_stride, RopeFreq freq,
+    int32_t* dev_flag) {
     __shared__ float2 cs[kMaxHalf];
     const cf_segment seg = segs[blockIdx.x];
     const int half = head_dim >> 1;
@@ -74,7 +75,6 @@ __global__ __launch_bounds__(kThreads) void reposition_kernel(
 
     const int items_per_head = half / 8;                 // head_dim % 16 == 0 checked on the host
     const int items_per_tok = n_kv_heads * items_per_head;
-    const int64_t row_elems = (int64_t)n_kv_heads * head_dim;
     for (int tok0 = blockIdx.y * kTokPerBlock; tok0 < seg.len; tok0 += gridDim.y * kTokPerBlock) {
         const int ntok = min(kTokPerBlock, seg.len - tok0);
         const int n_items = ntok * items_per_tok;
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(kThreads) void reposition_kernel(
             const int r = it - tok * items_per_tok;
             const int head = r / items_per_head;
             const int j = r - head * items_per_head;
-            const int64_t base = (seg.tok_offset + tok0 + tok) * row_elems + (int64_t)head * head_dim;
+            const int64_t base = (seg.tok_offset + tok0 + tok) * tok_stride + (int64_t)head * head_stride;
             float a[8], b[8];
             if (PAIRING == CF_ROPE_HALF) {
                 Vec8<DT>::load(k_in, base + 8 * j, a);
@@ -136,10 +136,12 @@ cf_status launch_dt(const cf_layer_desc* d, const RopeFreq& f, const void* k_in,
     dim3 grid(n_seg, sweeps);
     if (d->rope_pairing == CF_ROPE_HALF)
         hipLaunchKernelGGL((reposition_kernel<DT, CF_ROPE_HALF>), grid, dim3(kThreads), 0, s, k_in, k_out,
-                           segs, n_store_tokens, d->n_kv_heads, d->head_dim, f, dev_flag);
+                           segs, n_store_tokens, d->n_kv_heads, d->head_dim, store_token_stride(d), store_head_stride(d), f,
+                           dev_flag);
     else
         hipLaunchKernelGGL((reposition_kernel<DT, CF_ROPE_INTERLEAVED>), grid, dim3(kThreads), 0, s, k_in,
-                           k_out, segs, n_store_tokens, d->n_kv_heads, d->head_dim, f, dev_flag);
+                           k_out, segs, n_store_tokens, d->n_kv_heads, d->head_dim, store_token_stride(d),
+                           store_head_stride(d), f, dev_flag);
     CF_HIP(hipGetLastError());
     return CF_OK;
 }

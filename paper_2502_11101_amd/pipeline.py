@@ -24,6 +24,28 @@ def to_device(x: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
     return t.to(device=device, dtype=TORCH_DTYPE[dtype])
 
 
+def store_strides(n_store_tokens: int, n_kv_heads: int, head_dim: int, layout: str, pad_tokens: int = 0):
+    """(store_token_stride, store_head_stride) in elements for a cache store laid out "token"-major
+    [token][kv head][head_dim] or "head"-major [kv head][token (+ pad_tokens unused rows)][head_dim]."""
+    if layout == "token":
+        return n_kv_heads * head_dim, head_dim
+    if layout == "head":
+        return head_dim, (n_store_tokens + pad_tokens) * head_dim
+    raise ValueError(f"unknown store layout {layout!r}")
+
+
+def store_to_device(x: np.ndarray, dtype: str, layout: str, pad_tokens: int = 0, device="cuda") -> torch.Tensor:
+    """Upload a [token][kv head][head_dim] array of the cache store in the given layout."""
+    if layout == "token":
+        return to_device(x, dtype, device)
+    t = to_device(np.ascontiguousarray(x.transpose(1, 0, 2)), dtype, device)
+    if pad_tokens:
+        padded = torch.zeros((t.shape[0], t.shape[1] + pad_tokens, t.shape[2]), dtype=t.dtype, device=device)
+        padded[:, :t.shape[1]].copy_(t)
+        return padded
+    return t
+
+
 class PrefillBatch:
     """Device tables of ``batch`` queries, each with up to ``stride`` candidate documents.
 

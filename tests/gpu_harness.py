@@ -15,21 +15,30 @@ OUT_TOL = {"f32": 1e-4, "bf16": 2e-2, "f16": 2e-2}
 MASS_TOL = {"f32": 1e-5, "bf16": 1e-4, "f16": 1e-4}
 
 
-def desc_of(cfg: wl.Config, pairing=cf.CF_ROPE_HALF):
+# store layouts exercised by the tests: token-major, head-major, head-major with unused rows per head
+LAYOUTS = {"token": ("token", 0), "head": ("head", 0), "head_padded": ("head", 5)}
+
+
+def desc_of(cfg: wl.Config, pairing=cf.CF_ROPE_HALF, layout="token", n_store_tokens=0):
     g = cfg.geometry
-    return cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions, pairing)
+    kind, pad = LAYOUTS[layout]
+    ts, hs = (0, 0) if layout == "token" else pl.store_strides(n_store_tokens, g.n_kv_heads, g.head_dim, kind, pad)
+    return cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions, pairing,
+                        store_token_stride=ts, store_head_stride=hs)
 
 
-def upload_layer(cfg: wl.Config, tensors: dict):
+def upload_layer(cfg: wl.Config, tensors: dict, layout="token"):
     g = cfg.geometry
-    return {k: pl.to_device(v, g.dtype) for k, v in tensors.items()}
+    kind, pad = LAYOUTS[layout]
+    return {k: (pl.store_to_device(v, g.dtype, kind, pad) if k in ("k_store", "v_store") else pl.to_device(v, g.dtype))
+            for k, v in tensors.items()}
 
 
-def make_batch(cfg: wl.Config, st: wl.Structure, pairing=cf.CF_ROPE_HALF) -> pl.PrefillBatch:
+def make_batch(cfg: wl.Config, st: wl.Structure, pairing=cf.CF_ROPE_HALF, layout="token") -> pl.PrefillBatch:
     off = st.doc_off[:-1][st.query_docs]                 # [batch, k]
     lens = st.doc_lens[st.query_docs]
-    return pl.PrefillBatch(desc_of(cfg, pairing), off, lens, cfg.tq, cfg.prefix_len, cfg.doc_stored_start,
-                           st.n_store_tokens)
+    return pl.PrefillBatch(desc_of(cfg, pairing, layout, st.n_store_tokens), off, lens, cfg.tq, cfg.prefix_len,
+                           cfg.doc_stored_start, st.n_store_tokens)
 
 
 def row_error(gpu: np.ndarray, ref: np.ndarray) -> float:

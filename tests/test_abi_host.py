@@ -28,7 +28,7 @@ def test_library_loads_and_exports_every_declared_symbol():
 
 
 def test_struct_layouts_match_the_header():
-    assert C.sizeof(cf.cf_layer_desc) == 40
+    assert C.sizeof(cf.cf_layer_desc) == 56
     assert cf.SEGMENT_DTYPE.itemsize == 32
     assert cf.SEGMENT_DTYPE.fields["len"][1] == 8 and cf.SEGMENT_DTYPE.fields["doc"][1] == 24
 
@@ -52,11 +52,16 @@ def test_descriptor_validation():
     for bad, code in [(_desc(n_q_heads=7), cf.CF_ERR_INVALID_ARG), (_desc(head_dim=100), cf.CF_ERR_UNSUPPORTED),
                       (_desc(head_dim=512), cf.CF_ERR_UNSUPPORTED), (_desc(dtype=9), cf.CF_ERR_INVALID_ARG),
                       (_desc(rope_base=0.5), cf.CF_ERR_INVALID_ARG), (_desc(max_positions=0), cf.CF_ERR_INVALID_ARG),
-                      (_desc(rope_pairing=5), cf.CF_ERR_INVALID_ARG)]:
+                      (_desc(rope_pairing=5), cf.CF_ERR_INVALID_ARG),
+                      (_desc(store_token_stride=128), cf.CF_ERR_INVALID_ARG),          # one stride without the other
+                      (_desc(store_token_stride=128, store_head_stride=64), cf.CF_ERR_INVALID_ARG),   # below head_dim
+                      (_desc(store_token_stride=132, store_head_stride=1280), cf.CF_ERR_INVALID_ARG),  # not 16-byte rows
+                      (_desc(store_token_stride=1 << 25, store_head_stride=128), cf.CF_ERR_UNSUPPORTED)]:
         st, msg = _status(cf.cf_reposition_keys, bad, FAKE, FAKE, FAKE, 1, 10, 1, stream=0)
         assert st == code and msg
         assert cf.cf_prefill_workspace_bytes(bad, 1, 8, 4, 100) == 0
     assert cf.cf_prefill_workspace_bytes(_desc(), 1, 8, 4, 100) > 0
+    assert cf.cf_prefill_workspace_bytes(_desc(store_token_stride=128, store_head_stride=128 * 1000), 1, 8, 4, 100) > 0
     assert cf.cf_prefill_workspace_bytes(_desc(), 1, 8, 4, 100) % 256 == 0
 
 

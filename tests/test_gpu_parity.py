@@ -63,6 +63,29 @@ def test_reposition_keys_matches_oracle(dtype, pairing, hkv, d, base):
     assert np.max(np.abs(k_dev.float().cpu().numpy() - k)) <= 2.5 * tol * max(1.0, np.abs(k).max())
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_reposition_keys_head_major_store(dtype):
+    """The same call on a head-major store [kv head][token + unused rows][head_dim]."""
+    _say(f"reposition head-major dtype={dtype}")
+    rng = np.random.default_rng(22)
+    n_tok, hkv, d, base, pad = 500, 3, 128, 1.0e4, 7
+    k = wl.round_to_dtype(rng.standard_normal((n_tok, hkv, d), dtype=np.float32), dtype)
+    segs = [orc.Segment(0, 40, 0, 0, 1, 0), orc.Segment(40, 161, 32, 1999, 1, 1), orc.Segment(260, 240, 32, 7, 1, 2)]
+    ts, hs = pl.store_strides(n_tok, hkv, d, "head", pad)
+    desc = cf.make_desc(hkv, hkv, d, dtype, base, 32768, store_token_stride=ts, store_head_stride=hs)
+    k_dev = pl.store_to_device(k, dtype, "head", pad)
+    k_dev[:, n_tok:] = 3.0                      # the unused rows must stay untouched
+    out = k_dev.clone()
+    flag = torch.zeros(1, **I32)
+    cf.cf_reposition_keys(desc, k_dev, out, cf.segments_to_device(cf.segments_array(segs)), len(segs), n_tok, 64, flag)
+    torch.cuda.synchronize()
+    ref = orc.reposition_keys(k, segs, base, "half")
+    got = out[:, :n_tok].float().cpu().numpy().astype(np.float64).transpose(1, 0, 2)
+    tol = {"f32": 2e-6, "bf16": 2.0 ** -8}[dtype]
+    assert np.max(np.abs(got - ref)) <= tol * max(1.0, np.abs(ref).max())
+    assert flag.item() == 0 and torch.all(out[:, n_tok:] == 3.0)
+
+
 def test_reposition_flags_bad_segments_without_touching_memory():
     desc = cf.make_desc(2, 2, 64, "bf16", 1.0e4, 4096)
     k = torch.randn(50, 2, 64, device="cuda").to(torch.bfloat16)
@@ -173,7 +196,7 @@ def test_assign_keep_only_lists_survivors():
 
 
 # ----------------------------------------------------------------------------- generic attention path
-def _run_single_layer(cfg, pairing=cf.CF_ROPE_HALF, seed=None, mass_tol=None):
+def _run_single_layer(cfg, pairing=cf.CF_ROPE_HALF, seed=None, mass_tol=None, layout="token"):
     """mass_tol overrides the configuration-level mass tolerance for shapes with so few rows and
     tokens that the 16-bit rounding of the rotated keys (about 2^-9 relative per probability) is
     not averaged away."""
@@ -181,8 +204,8 @@ def _run_single_layer(cfg, pairing=cf.CF_ROPE_HALF, seed=None, mass_tol=None):
     t = wl.build_layer(cfg, st, seed=seed)
     g = cfg.geometry
     pname = "half" if pairing == cf.CF_ROPE_HALF else "interleaved"
-    pb = G.make_batch(cfg, st, pairing)
-    dev = G.upload_layer(cfg, t)
+    pb = G.make_batch(cfg, st, pairing, layout)
+    dev = G.upload_layer(cfg, t, layout)
     out = torch.empty_like(dev["q"])
     pb.allocate_initial()
     pb.workspace.fill_(0xFF)          # the workspace is scratch: stale contents (here NaN patterns) must not matter
@@ -205,7 +228,7 @@ def _run_single_layer(cfg, pairing=cf.CF_ROPE_HALF, seed=None, mass_tol=None):
         ref_score = H.doc_scores(ref_segs, ref_mass, cfg.docs_per_query)
         assert G.rel_error(score_np[b], ref_score) <= mass_tol
         assert mass_np[b, :len(segs)].sum() == pytest.approx(g.n_q_heads * cfg.tq, rel=1e-5)
-    _say(f"{cfg.name}: out err {worst_out:.3e}  mass err {worst_mass:.3e}")
+    _say(f"{cfg.name} [{layout}]: out err {worst_out:.3e}  mass err {worst_mass:.3e}")
     assert worst_out <= G.OUT_TOL[g.dtype]
     assert worst_mass <= mass_tol
     return cfg, st, t, pb, dev, out
@@ -243,16 +266,17 @@ def test_tiny_fp32_configuration_end_to_end():
     assert G.rel_error(pb.mass.cpu().numpy()[0, :4], ref_mass2) <= 1e-5
 
 
+@pytest.mark.parametrize("layout", ["token", "head_padded"])
 @pytest.mark.parametrize("dtype,pairing,d,hq,hkv", [("f32", cf.CF_ROPE_INTERLEAVED, 64, 4, 2),
                                                     ("bf16", cf.CF_ROPE_INTERLEAVED, 128, 8, 2),
                                                     ("f16", cf.CF_ROPE_HALF, 64, 6, 3),
                                                     ("f32", cf.CF_ROPE_HALF, 256, 2, 1)])
-def test_generic_path_shapes(dtype, pairing, d, hq, hkv):
+def test_generic_path_shapes(dtype, pairing, d, hq, hkv, layout):
     base = wl.CONFIGS["tiny_f32"]
     cfg = wl.scaled(base, name=f"generic_{dtype}_{d}", geometry=wl.Geometry(hq, hkv, d, dtype, 1.0e6, 32768),
                     n_store_docs=12, docs_per_query=4, batch=3, doc_len_range=(1, 150), tq=11, prefix_len=5,
                     doc_stored_start=5, n_planted=1)
-    _run_single_layer(cfg, pairing, seed=55)
+    _run_single_layer(cfg, pairing, seed=55, layout=layout)
 
 
 def test_attention_flags_bad_table_entries():
@@ -276,14 +300,16 @@ def test_attention_flags_bad_table_entries():
 
 
 # ----------------------------------------------------------------------------- 16-bit MFMA path
-def test_llama2_7b_layer_configuration():
-    """Configuration 2 (MHA, bf16, HBM-bound shape) at full size."""
-    _run_single_layer(wl.CONFIGS["llama2_7b_layer"])
+@pytest.mark.parametrize("layout", ["token", "head"])
+def test_llama2_7b_layer_configuration(layout):
+    """Configuration 2 (MHA, bf16, HBM-bound shape) at full size; head-major is the layout bench.py times."""
+    _run_single_layer(wl.CONFIGS["llama2_7b_layer"], layout=layout)
 
 
-def test_qwen2_7b_layer_configuration():
+@pytest.mark.parametrize("layout", ["token", "head"])
+def test_qwen2_7b_layer_configuration(layout):
     """Configuration 3 (GQA 28/4, bf16, 50 ragged documents) at full size."""
-    _run_single_layer(wl.CONFIGS["qwen2_7b_layer"])
+    _run_single_layer(wl.CONFIGS["qwen2_7b_layer"], layout=layout)
 
 
 def test_qwen2_1p5b_batch_reduced():
@@ -293,19 +319,19 @@ def test_qwen2_1p5b_batch_reduced():
     _run_single_layer(cfg)
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("dtype,layout", [("bf16", "token"), ("f16", "token"), ("bf16", "head_padded")])
 @pytest.mark.parametrize("hq,hkv,tq,docs,len_range,prefix", [
     (4, 4, 1, 3, (1, 70), 0),          # single query row, no prefix
     (8, 2, 5, 1, (33, 33), 7),         # one document, ragged everything
     (6, 2, 17, 9, (1, 40), 3),         # stacked rows straddle the 64-row tile
     (2, 2, 70, 4, (90, 130), 16),      # more rows than one tile in MHA
 ])
-def test_mfma_path_edge_shapes(dtype, hq, hkv, tq, docs, len_range, prefix):
+def test_mfma_path_edge_shapes(dtype, layout, hq, hkv, tq, docs, len_range, prefix):
     cfg = wl.scaled(wl.CONFIGS["tiny_f32"], name=f"edge_{dtype}_{hq}_{hkv}_{tq}",
                     geometry=wl.Geometry(hq, hkv, 128, dtype, 1.0e6, 32768), n_store_docs=2 * docs,
                     docs_per_query=docs, batch=2, doc_len_range=len_range, tq=tq, prefix_len=prefix,
                     doc_stored_start=prefix, n_planted=1)
-    _run_single_layer(cfg, seed=77, mass_tol=2e-3)
+    _run_single_layer(cfg, seed=77, mass_tol=2e-3, layout=layout)
 
 
 def test_mfma_path_is_deterministic():
