@@ -53,6 +53,7 @@ struct Plan {
     int blocks_rg;      // 16-row blocks per row group
     int units_per_b, units, nsplit, slots, x_count;
     int tile;           // tokens per tile: 32 or 64
+    int groups;         // groups of four wavefronts per workgroup (each streams its own run of tiles): 1 or 2
     size_t off_ml, off_opart, off_massml, off_masspart, total;
 };
 
@@ -70,9 +71,12 @@ Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_str
     // Few stacked rows (MHA-like, HBM-bound): small tiles, so that ragged segment ends waste little and
     // a split still holds several tiles.  Many rows (GQA, MFMA-bound): 64-token tiles.
     p.tile = row_blocks <= 4 ? 32 : 64;
+    // The small-row kernel is light on registers: two groups of four wavefronts per workgroup run two
+    // tiles at a time on one CU and hide each other's LDS and barrier waits.
+    p.groups = row_blocks <= 4 ? 2 : 1;
     const int64_t est_tiles = max_kv_tokens / p.tile + seg_stride;
     int64_t ns = (256 + p.units - 1) / p.units;         // one workgroup per CU and launch wave
-    const int64_t cap = est_tiles / 2 > 1 ? est_tiles / 2 : 1;
+    const int64_t cap = est_tiles / (2 * p.groups) > 1 ? est_tiles / (2 * p.groups) : 1;
     if (ns > cap) ns = cap;
     if (ns > kMaxSplit) ns = kMaxSplit;
 #ifdef CF_DEV
@@ -81,7 +85,7 @@ Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_str
     if (ns < 1) ns = 1;
     if (ns > kMaxSplit) ns = kMaxSplit;
     p.nsplit = (int)ns;
-    p.slots = seg_stride + p.nsplit;
+    p.slots = seg_stride + p.nsplit * p.groups;
     p.x_count = batch * n_kv_heads * p.nsplit;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
@@ -221,20 +225,22 @@ __device__ __forceinline__ float2 rope_cos_sin_fast(int delta, double theta_rev)
 //     with a 32-byte XOR swizzle; one workgroup barrier per tile;
 //   * S^T = K Q^T from LDS key fragments and register-resident Q fragments, online softmax with a
 //     stale maximum, O^T += V^T P^T with V^T fragments from transposing LDS reads.
-template <int DT, int NRB, int TILE>
-__global__ __launch_bounds__(kThreads) void attn_tile_kernel(AttnArgs a, RopeFreq freq, Plan p) {
+template <int DT, int NRB, int TILE, int GROUPS>
+__global__ __launch_bounds__(kThreads * GROUPS) void attn_tile_kernel(AttnArgs a, RopeFreq freq, Plan p) {
+    static_assert(GROUPS == 1 || (GROUPS == 2 && NRB == 1 && TILE == 32), "two groups: one row block per wavefront, 32-token tiles");
     constexpr int kKTile = TILE * kSK * 2;           // bytes, padded rows
     constexpr int kVTile = TILE * kD * 2;
     constexpr int kKItems = TILE / 32;               // (row, chunk pair) items per thread
     constexpr int kVItems = TILE / 16;               // (row, chunk) items per thread
     __shared__ SegTable tbl;
-    __shared__ __attribute__((aligned(16))) unsigned char k_buf[2][kKTile];
-    __shared__ __attribute__((aligned(16))) unsigned char v_buf[2][kVTile];
-    __shared__ __attribute__((aligned(16))) float2 cs_lds[2][kHalf];
+    __shared__ __attribute__((aligned(16))) unsigned char k_buf[GROUPS][2][kKTile];
+    __shared__ __attribute__((aligned(16))) unsigned char v_buf[GROUPS][2][kVTile];
+    __shared__ __attribute__((aligned(16))) float2 cs_lds[GROUPS][2][kHalf];
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & (kThreads - 1);    // thread, wavefront: inside the group of four wavefronts
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int grp = GROUPS == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x / kThreads);
     const int li = lane & 15, lg = lane >> 4;
     {
         const void *p0 = a.q, *p1 = a.q_off, *p2 = a.q_new_start, *p3 = a.k_store, *p4 = a.v_store, *p5 = a.k_self,
@@ -284,8 +290,15 @@ __global__ __launch_bounds__(kThreads) void attn_tile_kernel(AttnArgs a, RopeFre
 
     build_table(a, qh, &tbl, TILE);
     const unsigned total = (unsigned)tbl.tile0[tbl.n];
-    const int t_begin = split_begin(total, p.nsplit, split);
-    const int t_end = split_begin(total, p.nsplit, split + 1);
+    // a group streams a contiguous run of the workgroup's tiles of its own (sub-split `ss`)
+    const unsigned nsub = (unsigned)(p.nsplit * GROUPS);
+    const int ss = split * GROUPS + grp;
+    const int t_begin = split_begin(total, nsub, ss);
+    const int t_end = split_begin(total, nsub, ss + 1);
+    int most_tiles = 0;                              // workgroup-uniform: the longest run among the groups
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g)
+        most_tiles = max(most_tiles, split_begin(total, nsub, split * GROUPS + g + 1) - split_begin(total, nsub, split * GROUPS + g));
 
     const int64_t kv_row = (int64_t)a.n_kv_heads * kD;
     // staging items: K (row kr + 32*it, chunks kj and kj + 8), V (row vr + 16*it, chunk vc)
@@ -371,7 +384,7 @@ __global__ __launch_bounds__(kThreads) void attn_tile_kernel(AttnArgs a, RopeFre
         for (int rb = 0; rb < NRB; ++rb) {
             float tot = seg_l[rb] + __shfl_xor(seg_l[rb], 16);
             tot += __shfl_xor(tot, 32);
-            if (lg == 0) massml[(int64_t)(s + split) * p.rows_wg + (wave * NRB + rb) * 16 + li] = make_float2(m_run[rb], tot);
+            if (lg == 0) massml[(int64_t)(s + ss) * p.rows_wg + (wave * NRB + rb) * 16 + li] = make_float2(m_run[rb], tot);
         }
     };
 
@@ -384,7 +397,7 @@ __global__ __launch_bounds__(kThreads) void attn_tile_kernel(AttnArgs a, RopeFre
 
     int cs_slot = 0;
     int cur_seg = -1;
-    if (d0.ntok > 0 && d0.delta != 0 && tid < kHalf) cs_lds[0][tid] = rope_cos_sin_fast(d0.delta, my_freq);
+    if (d0.ntok > 0 && d0.delta != 0 && tid < kHalf) cs_lds[grp][0][tid] = rope_cos_sin_fast(d0.delta, my_freq);
     __syncthreads();
 
     // Stage tile `cur` from its registers into buffer `buf`, refill the registers with the tile after
@@ -392,15 +405,15 @@ __global__ __launch_bounds__(kThreads) void attn_tile_kernel(AttnArgs a, RopeFre
     auto step = [&](Tile& cur, StageRegs& r, const Tile& nxt, int buf) {
         const Tile cd = cur;
         const bool live = cd.ntok > 0;
-        uint16_t* k_lds = reinterpret_cast<uint16_t*>(k_buf[buf]);
-        unsigned char* v_lds = v_buf[buf];
+        uint16_t* k_lds = reinterpret_cast<uint16_t*>(k_buf[grp][buf]);
+        unsigned char* v_lds = v_buf[grp][buf];
         if (live) {
 #pragma unroll
             for (int it = 0; it < kKItems; ++it) {
                 uint4 ra = r.ka[it], rb4 = r.kb[it];
                 if (cd.delta != 0) {
                     uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb4.x, rb4.y, rb4.z, rb4.w};
-                    const float4* cs = reinterpret_cast<const float4*>(cs_lds[cs_slot] + 8 * kj);
+                    const float4* cs = reinterpret_cast<const float4*>(cs_lds[grp][cs_slot] + 8 * kj);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const float4 w = cs[i];          // (cos, sin) of slices 8*kj + 2i, + 2i + 1
@@ -422,7 +435,7 @@ __global__ __launch_bounds__(kThreads) void attn_tile_kernel(AttnArgs a, RopeFre
         fetch(cur, r);                               // the registers are free again
         if (nxt.ntok > 0 && nxt.seg != cd.seg && nxt.delta != 0) {
             cs_slot ^= 1;
-            if (tid < kHalf) cs_lds[cs_slot][tid] = rope_cos_sin_fast(nxt.delta, my_freq);
+            if (tid < kHalf) cs_lds[grp][cs_slot][tid] = rope_cos_sin_fast(nxt.delta, my_freq);
         }
         __syncthreads();            // tile `cur` is staged; every wavefront is done with the other buffer
         if (!live || !has_rows) return;
@@ -508,13 +521,42 @@ __global__ __launch_bounds__(kThreads) void attn_tile_kernel(AttnArgs a, RopeFre
             }
         }
     };
-    // Steps come in pairs and the exit test sits at the end only: every path round the loop issues the
-    // same loads and meets the same barriers.
-    do {
+    // Steps come in pairs and the trip count is the workgroup's: every path round the loop issues the
+    // same loads and meets the same barriers.  A group with fewer tiles runs steps without one.
+    for (int it = 0; it < most_tiles; it += 2) {
         step(d0, regs0, d1, 0);
         step(d1, regs1, d0, 1);
-    } while (d0.ntok > 0);
+    }
     if (cur_seg >= 0) emit(cur_seg);
+
+    float l_row[NRB];                                // row sums (each lane holds those of its own tokens so far)
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        l_row[rb] = l_run[rb] + __shfl_xor(l_run[rb], 16);
+        l_row[rb] += __shfl_xor(l_row[rb], 32);
+    }
+    if (GROUPS == 2) {
+        // the second group hands its rows' results (same rows, other tokens) to the first through the tile
+        // buffers, which nobody reads any more
+        f32x4* red = reinterpret_cast<f32x4*>(&k_buf[0][0][0]);                    // 4 wavefronts x 8 x 64 lanes
+        float2* red_ml = reinterpret_cast<float2*>(&v_buf[0][0][0]);               // 4 wavefronts x 16 rows
+        __syncthreads();
+        if (grp == 1) {
+#pragma unroll
+            for (int db = 0; db < 8; ++db) red[(wave * 8 + db) * kWave + lane] = acc[0][db];
+            if (lg == 0) red_ml[wave * 16 + li] = make_float2(m_run[0], l_row[0]);
+        }
+        __syncthreads();
+        if (grp == 1) return;
+        const float2 o = red_ml[wave * 16 + li];
+        const float m = fmaxf(m_run[0], o.x);
+        const float ms = m == -INFINITY ? 0.f : m;
+        const float f0 = __builtin_amdgcn_exp2f(m_run[0] - ms), f1 = __builtin_amdgcn_exp2f(o.x - ms);
+#pragma unroll
+        for (int db = 0; db < 8; ++db) acc[0][db] = acc[0][db] * f0 + red[(wave * 8 + db) * kWave + lane] * f1;
+        l_row[0] = l_row[0] * f0 + o.y * f1;
+        m_run[0] = m;
+    }
 
     // ---- partial results of this split: O^T in MFMA layout (one float4 per lane, row block and
     // channel block) and (reference, sum) per row
@@ -525,9 +567,7 @@ __global__ __launch_bounds__(kThreads) void attn_tile_kernel(AttnArgs a, RopeFre
     for (int rb = 0; rb < NRB; ++rb) {
 #pragma unroll
         for (int db = 0; db < 8; ++db) opart[(rb * 8 + db) * kWave] = acc[rb][db];
-        float tot = l_run[rb] + __shfl_xor(l_run[rb], 16);
-        tot += __shfl_xor(tot, 32);
-        if (lg == 0) ml[(wave * NRB + rb) * 16 + li] = make_float2(m_run[rb], tot);
+        if (lg == 0) ml[(wave * NRB + rb) * 16 + li] = make_float2(m_run[rb], l_row[rb]);
     }
 }
 
@@ -627,8 +667,8 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
 // `parts`: [nparts][slots] floats, in LDS (stage == nullptr) or in memory (stage: kMassStage floats of LDS).
 // `on_mass(s, m)` is called once per segment.  Both forms add in the same order.
 struct MassScratch {
-    float colsum[kMaxSegs + kMaxSplit];
-    int32_t sub_begin[kMaxSplit + 1];
+    float colsum[kMaxSegs + 2 * kMaxSplit];
+    int32_t sub_begin[2 * kMaxSplit + 1];
 };
 constexpr int kMassStage = 4096;            // floats of partials staged per round by the stand-alone mass kernel
 
@@ -637,7 +677,7 @@ __device__ __forceinline__ void segment_masses_block(const Plan& p, const SegTab
                                                      MassScratch* ms, F on_mass) {
     const int tid = threadIdx.x, nthr = blockDim.x;
     const unsigned total = (unsigned)tbl.tile0[tbl.n];
-    const unsigned nsub = (unsigned)p.nsplit;
+    const unsigned nsub = (unsigned)(p.nsplit * p.groups);
     const int nparts = p.units_per_b * p.nrb;
     if (stage == nullptr) {                          // partials already in LDS
         for (int k = tid; k < p.slots; k += nthr) {
@@ -812,8 +852,9 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
     const dim3 grid2((unsigned)(p.units * p.nrb * 8)), grid3((unsigned)a.batch);
 #define CF_LAUNCH(DT, N)                                                                             \
     do {                                                                                             \
-        if (p.tile == 32) hipLaunchKernelGGL((attn_tile_kernel<DT, N, 32>), grid, block, 0, s, a, f, p); \
-        else hipLaunchKernelGGL((attn_tile_kernel<DT, N, 64>), grid, block, 0, s, a, f, p);          \
+        if (p.groups == 2) hipLaunchKernelGGL((attn_tile_kernel<DT, 1, 32, 2>), grid, dim3(2 * kThreads), 0, s, a, f, p); \
+        else if (p.tile == 32) hipLaunchKernelGGL((attn_tile_kernel<DT, N, 32, 1>), grid, block, 0, s, a, f, p); \
+        else hipLaunchKernelGGL((attn_tile_kernel<DT, N, 64, 1>), grid, block, 0, s, a, f, p);       \
     } while (0)
 #define CF_LAUNCH_DT(DT)                                   \
     if (phases & 1) switch (p.nrb) {                       \
