@@ -806,18 +806,37 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
         if (doc >= 0 && doc < stride) atomicAdd(&l_score[doc], m);
     });
     __syncthreads();
-    for (int i = tid; i < stride; i += kEpiThreads) a.score_accum[off + i] = l_score[i];
-    const int k = prune_topk_block(l_score, pr.normalise_by_len ? l_len : nullptr, l_cand, n_cand, pr.keep, stride, l_keep,
-                                   a.dev_flag, scratch, &s_int[3]);
-    if (tid == 0) pr.n_keep[b] = k;
-    __syncthreads();
-    assign_positions_block(l_len, l_keep, k, stride, pr.pos_begin, pr.pos_end, pr.strategy, pr.force_n_reuse, l_start,
-                           &s_int[4], &s_int[5], l_order, a.dev_flag, scratch, s_int);
-    __syncthreads();
-    gather_segments_block(l_tok, l_len, l_order, k, l_start, s_int[4], qh.q0, qh.q0 + qh.tq_raw, stride, pr.prefix_len,
-                          pr.doc_stored_start, a.q_stored_start, pr.next_segs + (int64_t)b * a.seg_stride,
-                          pr.next_n_seg + b, a.seg_stride, a.dev_flag);
-    for (int i = tid; i < stride; i += kEpiThreads) {
+    // With few candidates one wavefront finishes alone: the others leave, and the barriers of the stages
+    // below (which only wait for wavefronts that are still running) cost nothing.
+    const int nthr = n_cand <= 2 * kWave ? kWave : kEpiThreads;
+    if (tid >= nthr) return;
+    for (int i = tid; i < stride; i += nthr) a.score_accum[off + i] = l_score[i];
+    int k = min(pr.keep, n_cand);
+    bool done = false;
+    if (n_cand <= kWave) {                               // the usual case: everything in one wavefront's registers
+        SelectWaveArgs sw;
+        sw.score = l_score; sw.len = l_len; sw.cand = l_cand; sw.tok = l_tok; sw.keep_idx = l_keep; sw.new_start = l_start;
+        sw.order = l_order; sw.n = n_cand; sw.keep = pr.keep; sw.stride = stride; sw.normalise_by_len = pr.normalise_by_len;
+        sw.strategy = pr.strategy; sw.force_n_reuse = pr.force_n_reuse; sw.pos_begin = pr.pos_begin; sw.pos_end = pr.pos_end;
+        sw.prefix_len = pr.prefix_len; sw.doc_stored_start = pr.doc_stored_start; sw.q_stored_start = a.q_stored_start;
+        sw.q_lo = qh.q0; sw.q_hi = qh.q0 + qh.tq_raw; sw.seg_stride = a.seg_stride;
+        done = select_wave64(sw, pr.n_keep + b, &s_int[4], &s_int[5], pr.next_segs + (int64_t)b * a.seg_stride,
+                             pr.next_n_seg + b);
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (!done) {
+        k = prune_topk_block(l_score, pr.normalise_by_len ? l_len : nullptr, l_cand, n_cand, pr.keep, stride, l_keep,
+                             a.dev_flag, scratch, &s_int[3], nthr);
+        if (tid == 0) pr.n_keep[b] = k;
+        __syncthreads();
+        assign_positions_block(l_len, l_keep, k, stride, pr.pos_begin, pr.pos_end, pr.strategy, pr.force_n_reuse, l_start,
+                               &s_int[4], &s_int[5], l_order, a.dev_flag, scratch, s_int, nthr);
+        __syncthreads();
+        gather_segments_block(l_tok, l_len, l_order, k, l_start, s_int[4], qh.q0, qh.q0 + qh.tq_raw, stride, pr.prefix_len,
+                              pr.doc_stored_start, a.q_stored_start, pr.next_segs + (int64_t)b * a.seg_stride,
+                              pr.next_n_seg + b, a.seg_stride, a.dev_flag, nthr);
+    }
+    for (int i = tid; i < stride; i += nthr) {
         if (i < k) pr.keep_idx[off + i] = l_keep[i];
         pr.new_start[off + i] = l_start[i];
         pr.order[off + i] = l_order[i];

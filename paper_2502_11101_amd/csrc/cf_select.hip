@@ -20,7 +20,7 @@ __global__ __launch_bounds__(kThreads) void prune_topk_kernel(
     const int b = blockIdx.x;
     const int64_t off = (int64_t)b * stride;
     const int k = prune_topk_block(score + off, len ? len + off : nullptr, cand + off, n_cand[b], keep, stride,
-                                   keep_idx + off, dev_flag, smem, &s_bad);
+                                   keep_idx + off, dev_flag, smem, &s_bad, kThreads);
     if (threadIdx.x == 0) n_keep[b] = k;
 }
 
@@ -35,7 +35,7 @@ __global__ __launch_bounds__(kThreads) void assign_positions_kernel(
     const int64_t off = (int64_t)b * stride;
     assign_positions_block(len + off, ranked + off, n_ranked[b], stride, pos_begin, pos_end, strategy, force_n_reuse,
                            new_start ? new_start + off : nullptr, q_start ? q_start + b : nullptr,
-                           n_reuse ? n_reuse + b : nullptr, order + off, dev_flag, smem, s_int);
+                           n_reuse ? n_reuse + b : nullptr, order + off, dev_flag, smem, s_int, kThreads);
 }
 
 __global__ __launch_bounds__(kThreads) void gather_segments_kernel(
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(kThreads) void gather_segments_kernel(
     const int64_t off = (int64_t)b * stride;
     gather_segments_block(doc_tok_offset + off, len + off, order + off, n_order[b], new_start + off, q_start[b], q_off[b],
                           q_off[b + 1], stride, prefix_len, doc_stored_start, q_stored_start,
-                          segs + (int64_t)b * seg_stride, n_seg + b, seg_stride, dev_flag);
+                          segs + (int64_t)b * seg_stride, n_seg + b, seg_stride, dev_flag, kThreads);
 }
 
 }  // namespace

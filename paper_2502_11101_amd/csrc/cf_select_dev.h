@@ -21,15 +21,19 @@ __device__ __forceinline__ bool ranks_before(float sa, int la, int ia, int pa, f
     return pa < pb;
 }
 
-// smem: 3*stride 32-bit words.  All threads of the workgroup must call; returns the number kept
-// (0 after a flagged error).  score/len/cand/keep_idx point at this query's rows.
+// The three functions below are called by the first `nthr` threads of a workgroup, all of them, and by
+// no others; when the workgroup's other wavefronts have exited, nthr is one wavefront and the barriers
+// inside cost nothing.
+//
+// smem: 3*stride 32-bit words.  Returns the number kept (0 after a flagged error).
+// score/len/cand/keep_idx point at this query's rows.
 __device__ inline int prune_topk_block(const float* score, const int32_t* len, const int32_t* cand, int n, int keep,
                                        int stride, int32_t* keep_idx, int32_t* dev_flag, unsigned char* smem,
-                                       int* s_bad) {
+                                       int* s_bad, int nthr) {
     float* s_score = reinterpret_cast<float*>(smem);
     int32_t* s_len = reinterpret_cast<int32_t*>(s_score + stride);
     int32_t* s_idx = s_len + stride;
-    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int tid = threadIdx.x;
     if (tid == 0) *s_bad = 0;
     __syncthreads();
     if (n < 0 || n > stride) {
@@ -71,18 +75,17 @@ __device__ inline int prune_topk_block(const float* score, const int32_t* len, c
     return k;
 }
 
-// smem: 3*stride 32-bit words; s_int: 3 ints of LDS.  All threads must call.  Pointers are this
-// query's rows; q_start / n_reuse point at this query's entries.  Returns false (outputs
-// untouched) after a flagged error.
+// smem: 3*stride 32-bit words; s_int: 3 ints of LDS.  Pointers are this query's rows; q_start /
+// n_reuse point at this query's entries.  Returns false (outputs untouched) after a flagged error.
 __device__ inline bool assign_positions_block(const int32_t* len, const int32_t* ranked, int n, int stride, int pos_begin,
                                               int pos_end, int strategy, int force_n_reuse, int32_t* new_start,
                                               int32_t* q_start, int32_t* n_reuse, int32_t* order, int32_t* dev_flag,
-                                              unsigned char* smem, int* s_int) {
+                                              unsigned char* smem, int* s_int, int nthr) {
     int32_t* s_ord = reinterpret_cast<int32_t*>(smem);   // placement order (slots)
     int32_t* s_len = s_ord + stride;                      // length per placement rank
     int32_t* s_cum = s_len + stride;                      // distance from the query to the start
     int &bad = s_int[0], &lmax = s_int[1], &span_max = s_int[2];
-    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int tid = threadIdx.x;
     __syncthreads();
     if (tid == 0) { bad = 0; lmax = 0; span_max = 0; }
     __syncthreads();
@@ -161,13 +164,13 @@ __device__ inline bool assign_positions_block(const int32_t* len, const int32_t*
     return true;
 }
 
-// All threads must call.  doc_tok_offset/len/order/new_start point at this query's rows, out at
-// this query's segment-table row.  q_lo/q_hi: this query's rows in q.
+// doc_tok_offset/len/order/new_start point at this query's rows, out at this query's segment-table
+// row.  q_lo/q_hi: this query's rows in q.
 __device__ inline void gather_segments_block(const int64_t* doc_tok_offset, const int32_t* len, const int32_t* order, int n,
                                              const int32_t* new_start, int q_start, int q_lo, int q_hi, int stride,
                                              int prefix_len, int doc_stored_start, int q_stored_start, cf_segment* out,
-                                             int32_t* n_seg, int seg_stride, int32_t* dev_flag) {
-    const int tid = threadIdx.x, nthr = blockDim.x;
+                                             int32_t* n_seg, int seg_stride, int32_t* dev_flag, int nthr) {
+    const int tid = threadIdx.x;
     const int has_prefix = prefix_len > 0 ? 1 : 0;
     if (n < 0 || n > stride || n + has_prefix + 1 > seg_stride) {
         if (tid == 0) { raise_flag(dev_flag, CF_FLAG_BAD_INDEX); *n_seg = 0; }
@@ -200,6 +203,133 @@ __device__ inline void gather_segments_block(const int64_t* doc_tok_offset, cons
         }
         out[has_prefix + i] = sgm;
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same three stages for at most 64 candidates, executed by one wavefront with every list in
+// registers (lane i = list position i): ranks by comparing against broadcast lanes, lists turned
+// into one another through small LDS scatters, sums and maxima by wavefront scans.  No barriers, no
+// atomics.  Results are those of the block functions; on any condition they would flag (bad
+// index, non-finite score, bad length, document too long, overflow, table too small) nothing is
+// written and false is returned, so that the caller runs the block functions, which raise the flag.
+// All pointers are this query's rows and may live in LDS; keep_idx also serves as scratch (entries
+// below the candidate count); *q_start / *n_reuse are written like the block function does.
+struct SelectWaveArgs {
+    const float* score; const int32_t* len; const int32_t* cand; const int64_t* tok;
+    int32_t* keep_idx; int32_t* new_start; int32_t* order;
+    int n, keep, stride, normalise_by_len, strategy, force_n_reuse, pos_begin, pos_end;
+    int prefix_len, doc_stored_start, q_stored_start, q_lo, q_hi, seg_stride;
+};
+
+__device__ __forceinline__ int wave_max_i32(int v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o));
+    return v;
+}
+
+__device__ inline bool select_wave64(const SelectWaveArgs& s, int* n_keep_out, int* q_start, int* n_reuse, cf_segment* out,
+                                     int32_t* n_seg_out) {
+    const int lane = threadIdx.x & 63;
+    const int n = s.n;
+    if (n < 0 || n > 64 || n > s.stride) return false;
+    // ---- ranking (Alg. 2: argsort of the accumulated scores, then the cut)
+    const bool have = lane < n;
+    const int c = have ? s.cand[lane] : 0;
+    const bool c_ok = c >= 0 && c < s.stride;
+    const float sc = have && c_ok ? s.score[c] : 0.f;
+    const int ln_rank = have && c_ok && s.normalise_by_len ? s.len[c] : 1;
+    const bool bad = have && (!c_ok || !isfinite(sc) || ln_rank <= 0 || ln_rank >= (1 << 24));
+    if (__any(bad)) return false;
+    int rank = 0;
+    for (int j = 0; j < n; ++j) {
+        const float sj = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sc), j));
+        const int lj = __builtin_amdgcn_readlane(ln_rank, j), cj = __builtin_amdgcn_readlane(c, j);
+        rank += (j != lane) && ranks_before(sj, lj, cj, j, sc, ln_rank, c, lane);
+    }
+    const int k = min(s.keep, n);
+    const int has_prefix = s.prefix_len > 0 ? 1 : 0;
+    if (k + has_prefix + 1 > s.seg_stride) return false;
+    // ranked list: lane r gets the candidate of rank r
+    if (have && rank < k) s.keep_idx[rank] = c;
+    __builtin_amdgcn_wave_barrier();
+    const bool in = lane < k;
+    const int rc = in ? s.keep_idx[lane] : 0x7fffffff;
+    __builtin_amdgcn_wave_barrier();
+    // ---- placement order (Sec. 2.5): as ranked ("sort") or by ascending slot ("align"; listing order of "keep")
+    int place = lane;
+    if (s.strategy != CF_ALLOC_SORT) {
+        place = 0;
+        for (int j = 0; j < k; ++j) {
+            const int cj = __builtin_amdgcn_readlane(rc, j);
+            place += (cj < rc) || (cj == rc && j < lane);
+        }
+    }
+    if (in) s.keep_idx[place] = rc;                       // scratch use; the ranked list is written back below
+    __builtin_amdgcn_wave_barrier();
+    const int oc = in ? s.keep_idx[lane] : 0;             // slot at placement rank `lane`
+    __builtin_amdgcn_wave_barrier();
+    const int pl = in ? s.len[oc] : 0;
+    if (__any(in && pl <= 0)) return false;
+    int qs = *q_start, groups = *n_reuse;
+    int my_start = in ? s.new_start[oc] : 0;
+    bool write_pos = false;
+    if (s.strategy != CF_ALLOC_KEEP && k > 0) {
+        // ---- allocation (Eq. 6): capacity by the longest survivor, balanced contiguous groups, every group
+        // ends at the query
+        const int lmax = wave_max_i32(pl);
+        const int avail = s.pos_end - s.pos_begin;
+        const int cap = avail / lmax;
+        if (cap <= 0) return false;
+        groups = s.force_n_reuse > 0 ? s.force_n_reuse : (k + cap - 1) / cap;
+        groups = min(groups, k);
+        const int per_group = (k + groups - 1) / groups;
+        int incl = pl;                                    // inclusive prefix over placement ranks
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int u = __shfl_up(incl, o);
+            if (lane >= o) incl += u;
+        }
+        const int first = (lane / per_group) * per_group;
+        const int before = __shfl(incl, max(first - 1, 0));
+        const int cum = incl - (first > 0 ? before : 0);
+        const bool last = in && ((lane == k - 1) || ((lane + 1) % per_group == 0));
+        const int span_max = wave_max_i32(last ? cum : 0);
+        if (span_max > avail) return false;
+        qs = s.pos_begin + span_max;
+        my_start = qs - cum;
+        write_pos = true;
+    } else if (s.strategy != CF_ALLOC_KEEP) {             // nothing survives
+        qs = s.pos_begin;
+        groups = 0;
+    }
+    // ---- everything checked: write the lists and the next segment table (Alg. 2, the logical concat)
+    if (in) {
+        s.keep_idx[lane] = rc;
+        s.order[lane] = oc;
+        if (write_pos) s.new_start[oc] = my_start;
+    }
+    if (lane == 0) {
+        *n_keep_out = k;
+        if (s.strategy != CF_ALLOC_KEEP) { *q_start = qs; *n_reuse = groups; }
+        if (has_prefix) {
+            cf_segment p;
+            p.tok_offset = 0; p.len = s.prefix_len; p.stored_start = 0; p.new_start = 0;
+            p.kind = CF_SEG_PREFIX; p.doc = -1; p.reserved = 0;
+            out[0] = p;
+        }
+        cf_segment q;
+        q.tok_offset = s.q_lo; q.len = s.q_hi - s.q_lo; q.stored_start = s.q_stored_start;
+        q.new_start = qs; q.kind = CF_SEG_SELF; q.doc = -1; q.reserved = 0;
+        out[has_prefix + k] = q;
+        *n_seg_out = has_prefix + k + 1;
+    }
+    if (in) {
+        cf_segment sg;
+        sg.tok_offset = s.tok[oc]; sg.len = pl; sg.stored_start = s.doc_stored_start; sg.new_start = my_start;
+        sg.kind = CF_SEG_DOC; sg.doc = oc; sg.reserved = 0;
+        out[has_prefix + lane] = sg;
+    }
+    return true;
 }
 
 }  // namespace cf

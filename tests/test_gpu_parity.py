@@ -396,6 +396,66 @@ def test_fused_layer_equals_separate_calls(name, strategy):
         assert {s.doc: s.new_start for s in b["segs"] if s.kind == cf.CF_SEG_DOC} == ref_ns
 
 
+def _fused_and_separate(cfg, st, t, keep, strategy, **kw):
+    dev = G.upload_layer(cfg, t)
+    res = []
+    for fused in (False, True):
+        pb = G.make_batch(cfg, st)
+        out = torch.empty_like(dev["q"])
+        pb.allocate_initial()
+        for name, val in kw.items():                     # changes that apply to the prune step only
+            setattr(pb, name, val)
+        if fused:
+            pb.layer(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out, keep=keep, strategy=strategy)
+        else:
+            pb.attention(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out)
+            pb.prune(keep, strategy)
+        torch.cuda.synchronize()
+        res.append(dict(flags=pb.flags(), out=out.clone(), score=pb.score.clone(), keep=pb.keep_idx.clone(), n_keep=pb.n_keep.clone(),
+                        order=pb.order.clone(), new_start=pb.next_new_start.clone(), q_start=pb.next_q_start.clone(),
+                        n_reuse=pb.n_reuse.clone(), segs=pb.next_segs.clone(), n_seg=pb.next_n_seg.clone()))
+    return res
+
+
+@pytest.mark.parametrize("strategy", [cf.CF_ALLOC_SORT, cf.CF_ALLOC_ALIGN])
+def test_fused_layer_many_candidates_and_batch(strategy):
+    """More than 64 candidates per query (the ranking runs on the whole workgroup) and a batch of queries:
+    the fused call and the separate calls leave identical tables."""
+    cfg = wl.scaled(wl.CONFIGS["tiny_f32"], name="many_docs", geometry=wl.Geometry(4, 2, 128, "bf16", 1.0e4, 8192),
+                    n_store_docs=220, docs_per_query=70, batch=3, doc_len_range=(5, 40), tq=9, prefix_len=6,
+                    doc_stored_start=6, n_planted=2)
+    st = wl.build_structure(cfg, seed=7101)
+    a, b = _fused_and_separate(cfg, st, wl.build_layer(cfg, st, seed=31), 23, strategy)
+    assert a["flags"] == 0 and b["flags"] == 0
+    assert torch.equal(a["out"], b["out"]) and torch.equal(a["n_keep"], b["n_keep"]) and a["n_keep"].tolist() == [23] * 3
+    for q in range(3):
+        assert a["keep"][q, :23].tolist() == b["keep"][q, :23].tolist()
+        assert a["order"][q, :23].tolist() == b["order"][q, :23].tolist()
+        ref = orc.prune_topk(b["score"][q].cpu().numpy(), st.doc_lens[st.query_docs[q]], list(range(70)), 23)
+        assert b["keep"][q, :23].tolist() == ref
+    for key in ("new_start", "q_start", "n_reuse", "n_seg"):
+        assert torch.equal(a[key], b[key]), key
+    n = int(a["n_seg"][0].item())
+    assert torch.equal(a["segs"][:, :n], b["segs"][:, :n])
+
+
+def test_fused_layer_flags_like_the_separate_calls():
+    """A positional range too short for the longest survivor: both paths raise the same flag and leave the
+    positions and the placement order as they were."""
+    cfg = wl.scaled(wl.CONFIGS["tiny_f32"], name="no_room", geometry=wl.Geometry(4, 4, 128, "bf16", 1.0e4, 4096),
+                    n_store_docs=14, docs_per_query=6, batch=2, doc_len_range=(40, 60), tq=8, prefix_len=4,
+                    doc_stored_start=4, n_planted=1)
+    st = wl.build_structure(cfg, seed=7102)
+    t = wl.build_layer(cfg, st, seed=32)
+    a, b = _fused_and_separate(cfg, st, t, 3, cf.CF_ALLOC_SORT)
+    assert a["flags"] == 0 and b["flags"] == 0 and torch.equal(a["segs"], b["segs"])
+    # shrink the range handed to the allocator below one document
+    a, b = _fused_and_separate(cfg, st, t, 3, cf.CF_ALLOC_SORT, pos_end=4 + 30)
+    assert a["flags"] == b["flags"] == cf.CF_FLAG_DOC_TOO_LONG
+    for key in ("keep", "n_keep", "new_start", "q_start", "order"):
+        assert torch.equal(a[key], b[key]), key
+
+
 def test_layer_stack_with_pruning_matches_oracle():
     """A reduced layer stack in the LLaMA-2-7B geometry (the full one is 32 layers x 30 documents):
     Alg. 2, Phase 1 on the GPU through cf_prefill_layer, checked against the oracle layer by layer on
