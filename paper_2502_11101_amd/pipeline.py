@@ -93,6 +93,7 @@ class PrefillBatch:
         self.ws_bytes = cf.cf_prefill_workspace_bytes(desc, self.batch, tq, self.seg_stride, self.max_kv_tokens)
         self.workspace = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=device)   # contents are scratch
         self.n_alive = self.stride
+        self._cache = None          # device addresses and the prune-step struct of the current tables (layer())
 
     # -- Alg. 2 init: every document is a candidate, placement order = retriever order
     def allocate_initial(self, force_n_reuse: int = 0) -> None:
@@ -133,21 +134,31 @@ class PrefillBatch:
     # -- Alg. 2, one whole layer in one call: attention, S += s^l and, with `keep` given, the prune event
     def layer(self, q, k_self, v_self, k_store, v_store, out, keep: Optional[int] = None,
               strategy: int = cf.CF_ALLOC_SORT, normalise_by_len: bool = True, force_n_reuse: int = 0) -> None:
+        # the tables' addresses only change in advance(): marshal them once, not per call
+        c = self._cache
+        if c is None:
+            c = self._cache = dict(
+                steps={}, q_off=self.q_off.data_ptr(), q_start=self.q_start.data_ptr(), segs=self.segs.data_ptr(),
+                n_seg=self.n_seg.data_ptr(), mass=self.mass.data_ptr(), score=self.score.data_ptr(),
+                workspace=self.workspace.data_ptr(), dev_flag=self.dev_flag.data_ptr())
         step = None
         if keep is not None:
             if strategy == cf.CF_ALLOC_KEEP:
                 self.next_new_start.copy_(self.new_start)
                 self.next_q_start.copy_(self.q_start)
-            step = cf.make_prune_step(keep, strategy, force_n_reuse, normalise_by_len, self.stride, self.pos_begin,
-                                      self.pos_end, self.prefix_len, self.doc_stored_start, self.doc_tok_offset,
-                                      self.doc_len, self.cand, self.n_cand, self.keep_idx, self.n_keep,
-                                      self.next_new_start, self.next_q_start, self.n_reuse, self.order,
-                                      self.next_segs, self.next_n_seg)
+            key = (keep, strategy, force_n_reuse, normalise_by_len, self.pos_begin, self.pos_end)
+            step = c["steps"].get(key)
+            if step is None:
+                step = c["steps"][key] = cf.make_prune_step(
+                    keep, strategy, force_n_reuse, normalise_by_len, self.stride, self.pos_begin, self.pos_end,
+                    self.prefix_len, self.doc_stored_start, self.doc_tok_offset, self.doc_len, self.cand, self.n_cand,
+                    self.keep_idx, self.n_keep, self.next_new_start, self.next_q_start, self.n_reuse, self.order,
+                    self.next_segs, self.next_n_seg)
             self._pending_keep = keep
-        cf.cf_prefill_layer(self.desc, q, self.q_off, self.q_stored_start, self.q_start, k_store, v_store,
-                            self.n_store_tokens, k_self, v_self, self.segs, self.n_seg, self.seg_stride, self.batch,
-                            self.tq, self.max_kv_tokens, out, self.mass, self.score, self.stride, self.workspace,
-                            self.ws_bytes, step, self.dev_flag)
+        cf.cf_prefill_layer(self.desc, q.data_ptr(), c["q_off"], self.q_stored_start, c["q_start"], k_store.data_ptr(),
+                            v_store.data_ptr(), self.n_store_tokens, k_self.data_ptr(), v_self.data_ptr(), c["segs"],
+                            c["n_seg"], self.seg_stride, self.batch, self.tq, self.max_kv_tokens, out.data_ptr(),
+                            c["mass"], c["score"], self.stride, c["workspace"], self.ws_bytes, step, c["dev_flag"])
 
     # -- the survivors, in placement order, become the candidates of the following layers
     def advance(self) -> None:
@@ -158,6 +169,7 @@ class PrefillBatch:
         self.new_start, self.next_new_start = self.next_new_start, self.new_start
         self.q_start, self.next_q_start = self.next_q_start, self.q_start
         self.n_alive = min(self._pending_keep, self.n_alive)
+        self._cache = None
 
     def flags(self) -> int:
         return int(self.dev_flag.item())
