@@ -2,7 +2,7 @@
 //
 // Work decomposition.  The query rows that share a kv head (all rows of the G = Hq/Hkv heads of
 // the group, stacked: row m = g*tq + t) are cut into 16-row blocks.  A workgroup of 4 wavefronts
-// owns up to 4*NRB such blocks of one (query, kv head) — wavefront w the blocks [w*NRB, (w+1)*NRB)
+// owns up to 4*NRB such blocks (NRB = 1 or 2) of one (query, kv head) — wavefront w the blocks [w*NRB, (w+1)*NRB)
 // — and a contiguous run of the attended tokens.  Tokens are counted in tiles (32 tokens when the
 // stacked rows fit one workgroup pass of 64 — MHA, short queries: HBM-bound —, else 64) that never
 // straddle a segment; the tile list of a (query, kv head) is divided evenly over `nsplit`
@@ -47,7 +47,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 struct Plan {
     int row_blocks;     // 16-row blocks of the stacked rows of one kv head
-    int nrb;            // 16-row blocks per wavefront (1..4)
+    int nrb;            // 16-row blocks per wavefront (1 or 2)
     int rows_wg;        // 64 * nrb
     int n_rg;           // row groups per (query, kv head)
     int blocks_rg;      // 16-row blocks per row group
@@ -62,7 +62,9 @@ Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_str
     const int group = n_q_heads / n_kv_heads;
     const int row_blocks = (group * max_tq + 15) / 16;
     p.row_blocks = row_blocks;
-    p.n_rg = (row_blocks + 15) / 16;
+    // At most 8 row blocks (128 stacked rows) per workgroup: with two row blocks per wavefront the
+    // kernel fits 256 registers, so two workgroups share a CU and fill each other's waits.
+    p.n_rg = (row_blocks + 7) / 8;
     p.blocks_rg = (row_blocks + p.n_rg - 1) / p.n_rg;
     p.nrb = (p.blocks_rg + kWaves - 1) / kWaves;
     p.rows_wg = 64 * p.nrb;
@@ -226,7 +228,7 @@ __device__ __forceinline__ float2 rope_cos_sin_fast(int delta, double theta_rev)
 //   * S^T = K Q^T from LDS key fragments and register-resident Q fragments, online softmax with a
 //     stale maximum, O^T += V^T P^T with V^T fragments from transposing LDS reads.
 template <int DT, int NRB, int TILE, int GROUPS>
-__global__ __launch_bounds__(kThreads * GROUPS) void attn_tile_kernel(AttnArgs a, RopeFreq freq, Plan p) {
+__global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArgs a, RopeFreq freq, Plan p) {
     static_assert(GROUPS == 1 || (GROUPS == 2 && NRB == 1 && TILE == 32), "two groups: one row block per wavefront, 32-token tiles");
     constexpr int kKTile = TILE * kSK * 2;           // bytes, padded rows
     constexpr int kVTile = TILE * kD * 2;
@@ -878,9 +880,7 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
 #define CF_LAUNCH_DT(DT)                                   \
     if (phases & 1) switch (p.nrb) {                       \
         case 1: CF_LAUNCH(DT, 1); break;                   \
-        case 2: CF_LAUNCH(DT, 2); break;                   \
-        case 3: CF_LAUNCH(DT, 3); break;                   \
-        default: CF_LAUNCH(DT, 4); break;                  \
+        default: CF_LAUNCH(DT, 2); break;                  \
     }                                                      \
     CF_HIP(hipGetLastError());                             \
     if (phases & 2) hipLaunchKernelGGL((attn_combine_kernel<DT>), grid2, block, 0, s, a, p);
