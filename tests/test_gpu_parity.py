@@ -509,3 +509,86 @@ def test_layer_stack_with_pruning_matches_oracle():
             assert {s.doc: s.new_start for s in G.device_segments(pb, 0) if s.kind == cf.CF_SEG_DOC} == ref_ns
             alive = kept
     assert set(st.planted[0].tolist()) <= set(alive)
+
+
+# ----------------------------------------------------------------------------- full sizes, sampled
+def test_llama2_7b_stack_full_size():
+    """Configuration 4 at full size (32 layers, 30 documents x 160 tokens, pruning to 60 % after layers
+    8/16/24/32), head-major store as bench.py runs it.  Every layer: flags, mass total, accumulated
+    scores finite; every prune: the cut exact for the device's scores, the allocation bit-exact.  The
+    oracle attends on sampled layers (before and after each prune) on the tables the device holds."""
+    cfg = wl.CONFIGS["llama2_7b_stack"]
+    g = cfg.geometry
+    st = wl.build_structure(cfg)
+    lens = [int(x) for x in st.doc_lens]
+    keeps, k = {}, cfg.docs_per_query
+    for layer in cfg.prune_layers:
+        k = orc.keep_fraction(k, cfg.keep_frac)
+        keeps[layer] = k
+    assert list(keeps.values()) == [18, 11, 7, 5]
+    pb = G.make_batch(cfg, st, layout="head")
+    pb.allocate_initial()
+    assert int(pb.n_reuse[0].item()) == 2                      # 30 x 160 tokens do not fit 4096 positions once
+    alive = list(range(cfg.docs_per_query))
+    sampled = {0, 7, 8, 16, 24, 31}
+    for layer in range(cfg.n_layers):
+        t = wl.build_layer(cfg, st, layer)
+        dev = G.upload_layer(cfg, t, "head")
+        out = torch.empty_like(dev["q"])
+        if layer in sampled:
+            segs, ref_out, ref_mass = G.oracle_on_device_segments(cfg, t, pb, 0)
+        pb.layer(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out, keep=keeps.get(layer),
+                 strategy=cf.CF_ALLOC_SORT)
+        torch.cuda.synchronize()
+        assert pb.flags() == 0
+        n_seg = int(pb.n_seg[0].item())
+        mass = pb.mass.cpu().numpy()[0, :n_seg]
+        assert n_seg == len(alive) + 2 and mass.sum() == pytest.approx(g.n_q_heads * cfg.tq, rel=1e-5)
+        if layer in sampled:
+            _say(f"stack layer {layer}: {len(alive)} documents")
+            assert G.row_error(out.float().cpu().numpy(), ref_out) <= G.OUT_TOL[g.dtype]
+            assert G.rel_error(mass, ref_mass) <= G.MASS_TOL[g.dtype]
+        if layer in keeps:
+            keep = keeps[layer]
+            dev_score = pb.score.cpu().numpy()[0]
+            kept = pb.keep_idx[0, :keep].tolist()
+            assert kept == orc.prune_topk(dev_score, lens, alive, keep)
+            ref_ns, ref_q, ref_nr = orc.assign_positions(lens, kept, cfg.prefix_len, g.max_positions - cfg.tq)
+            pb.advance()
+            assert int(pb.q_start[0].item()) == ref_q and int(pb.n_reuse[0].item()) == ref_nr
+            assert {s.doc: s.new_start for s in G.device_segments(pb, 0) if s.kind == cf.CF_SEG_DOC} == ref_ns
+            alive = kept
+    assert set(st.planted[0].tolist()) <= set(alive)
+
+
+def test_qwen2_1p5b_batch_full_size_sampled():
+    """Configuration 5 at full size (store of 10 000 documents, 64 queries x 20 documents, fp16 GQA 12/2):
+    every query's mass total and the planted documents' survival, and three sampled queries against the
+    oracle element by element."""
+    cfg = wl.CONFIGS["qwen2_1p5b_batch"]
+    g = cfg.geometry
+    st = wl.build_structure(cfg)
+    t = wl.build_layer(cfg, st)
+    pb = G.make_batch(cfg, st, layout="head")
+    dev = G.upload_layer(cfg, t, "head")
+    out = torch.empty_like(dev["q"])
+    pb.allocate_initial()
+    pb.layer(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out, keep=cfg.keep,
+             strategy=cf.CF_ALLOC_SORT)
+    torch.cuda.synchronize()
+    assert pb.flags() == 0
+    mass = pb.mass.cpu().numpy()
+    score = pb.score.cpu().numpy()
+    keep_idx = pb.keep_idx.cpu().numpy()
+    out_np = out.float().cpu().numpy()
+    for b in range(cfg.batch):
+        assert mass[b, :cfg.docs_per_query + 1].sum() == pytest.approx(g.n_q_heads * cfg.tq, rel=1e-5)
+        qlens = st.doc_lens[st.query_docs[b]]
+        assert keep_idx[b, :cfg.keep].tolist() == orc.prune_topk(score[b], qlens, list(range(cfg.docs_per_query)), cfg.keep)
+        assert set(st.planted[b].tolist()) <= set(keep_idx[b, :cfg.keep].tolist())
+    for b in (0, 31, 63):
+        _say(f"batch query {b}")
+        ref_segs, ref_q, _ = H.initial_segments(cfg, st, b)
+        ref_out, ref_mass = H.oracle_query(cfg, st, t, b, ref_segs, ref_q)
+        assert G.row_error(out_np[b * cfg.tq:(b + 1) * cfg.tq], ref_out) <= G.OUT_TOL[g.dtype]
+        assert G.rel_error(mass[b, :len(ref_segs)], ref_mass) <= G.MASS_TOL[g.dtype]
