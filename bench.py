@@ -31,8 +31,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel on this workload, from the FETCH_SIZE and WRITE_SIZE counter runs
-# summarised in profiles/attn_small_kernel_llama2_7b_layer.md (scaled by a 1 GiB copy kernel: x2.000 and x1.000)
-TRAFFIC_BYTES_PER_LAUNCH = 31_220_900 + 6_815_744
+# summarised in profiles/attn_tile_kernel_llama2_7b_layer.md (scaled by a 1 GiB copy kernel: x2.000 and x1.000)
+TRAFFIC_BYTES_PER_LAUNCH = 30_897_300 + 6_660_096
 WORKLOAD = "llama2_7b_layer"
 
 
@@ -202,7 +202,7 @@ def main() -> int:
                    "step": "cf_prefill_layer: attention + mass + prune_topk + assign_positions + gather_segments"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
-                     "kernel": "attn_tile_kernel<bf16,1,32> (first kernel of cf_prefill_layer / cf_prefill_attention)",
+                     "kernel": "attn_tile_kernel<bf16,1,32,2> (first kernel of cf_prefill_layer / cf_prefill_attention)",
                      "ms_per_launch": kernel_ms, "algorithmic_bytes_per_launch": kv_tokens * bytes_per_token,
                      "ms_per_call_all_kernels": attn_ms},
     }

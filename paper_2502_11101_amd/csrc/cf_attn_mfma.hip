@@ -561,7 +561,8 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
     }
 
     // ---- partial results of this split: O^T in MFMA layout (one float4 per lane, row block and
-    // channel block) and (reference, sum) per row
+    // channel block) and (reference, sum) per row; a wavefront whose rows are all padding leaves nothing
+    if (!has_rows) return;
     f32x4* opart = reinterpret_cast<f32x4*>(ws + p.off_opart) +
                    (((int64_t)unit * p.nsplit + split) * p.rows_wg / 16 + wave * NRB) * 8 * kWave + lane;
     float2* ml = reinterpret_cast<float2*>(ws + p.off_ml) + ((int64_t)unit * p.nsplit + split) * p.rows_wg;
@@ -607,9 +608,11 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     // Everything this workgroup reads is requested up front — row statistics, partial outputs of the
     // first splits, the first slot statistics — so the three round trips to memory overlap.
     for (int idx = tid; idx < p.nsplit * 64; idx += kThreads) mlw[idx] = ml[(idx >> 6) * p.rows_wg + (idx & 63)];
+    // a wavefront whose 16 rows are all padding (the attention kernel wrote nothing for them) reads nothing
+    const bool blk_has_rows = pass * 64 + wave * 16 < min(p.blocks_rg * 16, group * min(q1 - q0, a.max_tq) - rg * p.blocks_rg * 16);
     f32x4 pre[kPre];
 #pragma unroll
-    for (int s = 0; s < kPre; ++s) pre[s] = s < p.nsplit ? src[s * split_stride] : f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < kPre; ++s) pre[s] = s < p.nsplit && blk_has_rows ? src[s * split_stride] : f32x4{0.f, 0.f, 0.f, 0.f};
     float2 sv[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -636,7 +639,8 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
 #pragma unroll
     for (int s = 0; s < kPre; ++s)
         if (s < p.nsplit) o += pre[s] * mlw[s * 64 + wave * 16 + li].x;
-    for (int s = kPre; s < p.nsplit; ++s) o += src[s * split_stride] * mlw[s * 64 + wave * 16 + li].x;
+    if (blk_has_rows)
+        for (int s = kPre; s < p.nsplit; ++s) o += src[s * split_stride] * mlw[s * 64 + wave * 16 + li].x;
     const int lrow = pass * 64 + wave * 16 + li;
     if (lrow < rows_here) {
         const int m2 = row_base + lrow;
