@@ -592,3 +592,49 @@ def test_qwen2_1p5b_batch_full_size_sampled():
         ref_out, ref_mass = H.oracle_query(cfg, st, t, b, ref_segs, ref_q)
         assert G.row_error(out_np[b * cfg.tq:(b + 1) * cfg.tq], ref_out) <= G.OUT_TOL[g.dtype]
         assert G.rel_error(mass[b, :len(ref_segs)], ref_mass) <= G.MASS_TOL[g.dtype]
+
+
+# ----------------------------------------------------------------------------- N_reuse ablation modes
+@pytest.mark.parametrize("max_positions", [4096, 2048])
+def test_n_reuse_ablation_modes(max_positions):
+    """The allocator settings of the N_reuse ablation (Sec. 3.3.2): N_reuse = k (every cache its own window),
+    1 (no reuse), k/5, a fixed 5, and the adaptive value of Eq. 6, for k = 20 caches of 160 tokens.  Positions
+    bit-exact against the oracle, attention on those positions within tolerance; a setting whose groups do not
+    fit the positional range (the overflow the paper warns about) raises the flag and allocates nothing."""
+    base = wl.CONFIGS["llama2_7b_layer"]
+    g = wl.Geometry(8, 8, 128, "bf16", 1.0e4, max_positions)
+    cfg = wl.scaled(base, name=f"ablation_{max_positions}", geometry=g, n_store_docs=20, docs_per_query=20, n_planted=2)
+    st = wl.build_structure(cfg, seed=7300)
+    t = wl.build_layer(cfg, st, seed=73)
+    dev = G.upload_layer(cfg, t)
+    k = cfg.docs_per_query
+    lens = [int(x) for x in st.doc_lens[st.query_docs[0]]]
+    pos_begin, pos_end = cfg.prefix_len, max_positions - cfg.tq
+    seen = {}
+    for name, force in [("k", k), ("one", 1), ("k/5", k // 5), ("five", 5), ("adaptive", 0)]:
+        pb = G.make_batch(cfg, st)
+        pb.allocate_initial(force_n_reuse=force)
+        torch.cuda.synchronize()
+        try:
+            ref_ns, ref_q, ref_nr = orc.assign_positions(lens, list(range(k)), pos_begin, pos_end, orc.STRATEGY_SORT, force)
+        except ValueError:
+            # the allocator writes nothing: positions and q_start keep their initial zeros
+            assert pb.flags() == cf.CF_FLAG_POS_OVERFLOW
+            assert int(pb.q_start[0].item()) == 0 and not pb.new_start.any()
+            seen[name] = "overflow"
+            continue
+        assert pb.flags() == 0
+        assert int(pb.q_start[0].item()) == ref_q and int(pb.n_reuse[0].item()) == ref_nr
+        assert pb.new_start[0].tolist() == [ref_ns[s] for s in range(k)]
+        out = torch.empty_like(dev["q"])
+        pb.attention(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out)
+        torch.cuda.synchronize()
+        segs, ref_out, ref_mass = G.oracle_on_device_segments(cfg, t, pb, 0)
+        assert G.row_error(out.float().cpu().numpy(), ref_out) <= G.OUT_TOL["bf16"]
+        assert G.rel_error(pb.mass.cpu().numpy()[0, :len(segs)], ref_mass) <= G.MASS_TOL["bf16"]
+        seen[name] = ref_nr
+    _say(f"N_reuse modes at {max_positions} positions: {seen}")
+    if max_positions == 4096:
+        assert seen == {"k": 20, "one": 1, "k/5": 4, "five": 5, "adaptive": 1}
+    else:
+        assert seen == {"k": 20, "one": "overflow", "k/5": 4, "five": 5, "adaptive": 2}
