@@ -14,6 +14,9 @@ What each function follows:
 
 * ``rope_theta``, ``rotate``            RoPE rotation matrix, Eq. 2 (Background).
 * ``reposition_keys``                   Cache Re-Positioning, Eq. 5 (Sec. 2.3).
+* ``assemble_final_cache``              Alg. 2, Phase 2 (Final Re-Positioning): the gathered,
+                                        re-positioned cache of one layer; ``decode_attention``
+                                        is Eq. 1 over it (Phase 3's attention).
 * ``prefill_attention``                 Eq. 1 over prefix + parallel document caches +
                                         the query's own causal block (Alg. 2, the
                                         ``layer_l`` step), and the document-wise
@@ -32,6 +35,10 @@ Pins (tests/test_oracle_pins.py):
                              scaled_dot_product_attention in the reducible
                              cases; invariance under a common position shift;
                              brute-force triple loop on the tiny configuration.
+  assemble_final_cache       plain attention of an absolutely positioned query over the
+                             assembled cache equals prefill_attention on the original
+                             store (relative-position invariance); zero shift copies;
+                             positions listed match the allocation.
   prune_topk                 brute force by full sort; planted documents survive.
   keep_schedule              the appendix's worked example (28, 4, 40, 5 -> 5).
   assign_positions           exhaustive slot marking; the "k = 20, N_reuse = k/5"
@@ -128,6 +135,50 @@ def reposition_keys(k_store, segments: Sequence[Segment], rope_base: float,
     for seg in segments:
         sl = slice(seg.tok_offset, seg.tok_offset + seg.len)
         out[sl] = rotate(out[sl], seg.new_start - seg.stored_start, rope_base, pairing)
+    return out
+
+
+def assemble_final_cache(k_store, v_store, k_self, v_self, segments: Sequence[Segment],
+                         tq: int, rope_base: float, pairing: str = "half"):
+    """Alg. 2, Phase 2 (Final Re-Positioning) for one layer and one query:
+    C_final = concat(repos(C, ids), C_Q).  The listed segments, in table order, are
+    gathered into one contiguous cache; every key is moved from its stored position
+    to its final one by Eq. 5 (the query's own block like any other segment, from
+    the position it was computed at to the final q_start); values are copied.
+    Returns (k_final [N, Hkv, d], v_final [N, Hkv, d], pos [N]): pos is the position
+    each gathered token now sits at.  Only the first ``tq`` tokens of the own block
+    exist."""
+    ks, vs, ps = [], [], []
+    for seg in segments:
+        own = seg.kind == KIND_SELF
+        n = min(seg.len, tq) if own else seg.len
+        src_k = k_self if own else k_store
+        src_v = v_self if own else v_store
+        k = np.asarray(src_k[seg.tok_offset:seg.tok_offset + n], dtype=np.float64)
+        ks.append(rotate(k, seg.new_start - seg.stored_start, rope_base, pairing))
+        vs.append(np.asarray(src_v[seg.tok_offset:seg.tok_offset + n], dtype=np.float64))
+        ps.append(seg.new_start + np.arange(n))
+    if not ks:
+        raise ValueError("no segments")
+    return np.concatenate(ks), np.concatenate(vs), np.concatenate(ps)
+
+
+def decode_attention(q_abs, k_final, v_final, n_kv_heads: int, scale: Optional[float] = None):
+    """Eq. 1 for decode-time queries over an assembled cache (Alg. 2, Phase 3): q_abs
+    [T, Hq, d] already carries RoPE for its absolute position, the keys of k_final
+    theirs; every query sees the whole cache.  Plain softmax(q k^T / sqrt(d)) v."""
+    q = np.asarray(q_abs, dtype=np.float64)
+    k = np.asarray(k_final, dtype=np.float64)
+    v = np.asarray(v_final, dtype=np.float64)
+    t, hq, d = q.shape
+    g = hq // n_kv_heads
+    sc = (1.0 / math.sqrt(d)) if scale is None else scale
+    out = np.zeros_like(q)
+    for h in range(hq):
+        s = sc * (q[:, h, :] @ k[:, h // g, :].T)
+        p = np.exp(s - s.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        out[:, h, :] = p @ v[:, h // g, :]
     return out
 
 

@@ -479,3 +479,62 @@ def test_driver_invariants():
         assert rec["mass"].sum() == pytest.approx(g.n_q_heads * cfg.tq, rel=1e-9)
     assert [len(r["ids"]) for r in trace] == [6, 6, 4, 4, 2, 2]
     assert len(ids) == 2
+
+
+# ------------------------------------------------------------------ Alg. 2 Phase 2: the assembled cache
+def _phase2_case(seed=5):
+    rng = np.random.default_rng(seed)
+    hq, hkv, d, base, tq = 4, 2, 64, 1.0e4, 3
+    n_store = 90
+    k_store = rng.standard_normal((n_store, hkv, d))
+    v_store = rng.standard_normal((n_store, hkv, d))
+    k_self = rng.standard_normal((tq, hkv, d))
+    v_self = rng.standard_normal((tq, hkv, d))
+    # keys as stored: RoPE at the stored positions applied to "raw" keys, so that direct RoPE at the
+    # final position is available as an independent reference
+    segs = [orc.Segment(0, 6, 0, 0, orc.KIND_PREFIX, -1), orc.Segment(40, 17, 6, 31, orc.KIND_DOC, 1),
+            orc.Segment(10, 25, 6, 6, orc.KIND_DOC, 0), orc.Segment(0, tq, 0, 48, orc.KIND_SELF, -1)]
+    return hq, hkv, d, base, tq, k_store, v_store, k_self, v_self, segs
+
+
+def test_assembled_cache_layout_positions_and_zero_shift():
+    hq, hkv, d, base, tq, k_store, v_store, k_self, v_self, segs = _phase2_case()
+    k_f, v_f, pos = orc.assemble_final_cache(k_store, v_store, k_self, v_self, segs, tq, base)
+    assert k_f.shape == v_f.shape == (6 + 17 + 25 + tq, hkv, d)
+    assert pos.tolist() == list(range(0, 6)) + list(range(31, 48)) + list(range(6, 31)) + list(range(48, 48 + tq))
+    np.testing.assert_array_equal(k_f[:6], k_store[:6])                       # zero shift: an exact copy
+    np.testing.assert_array_equal(k_f[23:48], k_store[10:35])                 # stored at 6, stays at 6
+    np.testing.assert_array_equal(v_f[6:23], v_store[40:57])                  # values are copied, never rotated
+    np.testing.assert_array_equal(v_f[48:], v_self[:tq])
+    # a moved key is RoPE applied directly at the final position to the un-rotated key (Eq. 5, both forms)
+    raw = orc.rotate(k_store[40:57], -(6 + np.arange(17))[:, None], base)
+    direct = orc.rotate(raw, (31 + np.arange(17))[:, None], base)
+    np.testing.assert_allclose(k_f[6:23], direct, atol=1e-12)
+    np.testing.assert_allclose(np.linalg.norm(k_f, axis=-1), np.linalg.norm(
+        np.concatenate([k_store[:6], k_store[40:57], k_store[10:35], k_self[:tq]]), axis=-1), rtol=1e-12)
+
+
+def test_decode_over_assembled_cache_equals_prefill_on_the_store():
+    """Plain attention of an absolutely positioned query over C_final gives what the prefill path gives on
+    the original store with the same segment table: scores depend on relative positions only (Eq. 2)."""
+    hq, hkv, d, base, tq, k_store, v_store, k_self, v_self, segs = _phase2_case(6)
+    rng = np.random.default_rng(60)
+    k_f, v_f, pos = orc.assemble_final_cache(k_store, v_store, k_self, v_self, segs, tq, base)
+    q_raw = rng.standard_normal((1, hq, d))                 # a decode-step query before RoPE
+    p_new = 48 + tq                                         # it sits right after the query block
+    q_abs = orc.rotate(q_raw, p_new, base)
+    got = orc.decode_attention(q_abs, k_f, v_f, hkv)
+    # the same through the prefill definition: the new token as a one-row query stored at position 0 and
+    # placed at p_new; the earlier query block is now an ordinary, fully visible cached segment
+    segs_dec = [s if s.kind != orc.KIND_SELF else orc.Segment(n_store_off, s.len, s.stored_start, s.new_start, orc.KIND_DOC, -1)
+                for s, n_store_off in ((s, 90) for s in segs)]
+    store_k = np.concatenate([k_store, k_self])
+    store_v = np.concatenate([v_store, v_self])
+    ref, _ = orc.prefill_attention(q_raw, 0, p_new, store_k, store_v, None, None, segs_dec, hkv, base)
+    np.testing.assert_allclose(got, ref, atol=1e-12)
+    # and against torch's attention on the assembled cache
+    qt = torch.from_numpy(q_abs).permute(1, 0, 2)[None]
+    kt = torch.from_numpy(np.repeat(k_f, hq // hkv, axis=1)).permute(1, 0, 2)[None]
+    vt = torch.from_numpy(np.repeat(v_f, hq // hkv, axis=1)).permute(1, 0, 2)[None]
+    sdpa = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt)[0].permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(got, sdpa, atol=1e-12)
