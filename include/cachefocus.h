@@ -240,6 +240,38 @@ CF_API cf_status cf_gather_segments(const int64_t* doc_tok_offset, const int32_t
                              int32_t* dev_flag, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Alg. 2, Phase 2 (Final Re-Positioning) for one layer: C_final = concat(repos(C, ids), C_Q).
+ * Every query's listed segments are gathered, in table order, into one contiguous run of the
+ * decode cache k_final / v_final; each key is moved from its stored position to its final one
+ * (Eq. 5: rotation by new_start - stored_start; the query's own block like any other segment),
+ * values are copied.  Streaming: K and V are read once and written once.
+ *   desc           host; its store strides describe k_store / v_store
+ *   k_store,v_store device, read; k_self,v_self device [sum tq][n_kv_heads][head_dim] (may be NULL
+ *                  if no table lists an own block); q_off device int32 [batch+1]
+ *   segs, n_seg, seg_stride  device tables as for cf_prefill_attention (segments of kind SELF take
+ *                  min(len, tq) tokens, tq = min(q_off[b+1]-q_off[b], max_tq))
+ *   max_seg_len    host: upper bound of any segment's length (sizes the launch)
+ *   final_off      device int64 [batch]: token index in k_final / v_final where query b's run starts
+ *   final_capacity host: tokens k_final / v_final can hold; a run that would pass it is not written
+ *                  and raises CF_FLAG_BAD_INDEX
+ *   final_token_stride, final_head_stride  host: element strides of k_final / v_final (multiples
+ *                  of 8, at least head_dim): channel c of kv head h of token t at
+ *                  t*token_stride + h*head_stride + c
+ *   k_final,v_final device, written; must not overlap the inputs
+ *   final_len      device int32 [batch], written: tokens in query b's run
+ *   final_pos      device int32 [final_capacity] or NULL: position of every gathered token
+ * Bad table entries are skipped (zero tokens) and raise CF_FLAG_BAD_SEGMENT.
+ */
+CF_API cf_status cf_assemble_cache(const cf_layer_desc* desc, const void* k_store, const void* v_store,
+                            int64_t n_store_tokens, const void* k_self, const void* v_self,
+                            const int32_t* q_off, const cf_segment* segs, const int32_t* n_seg,
+                            int32_t seg_stride, int32_t batch, int32_t max_tq, int32_t max_seg_len,
+                            const int64_t* final_off, int64_t final_capacity,
+                            int64_t final_token_stride, int64_t final_head_stride,
+                            void* k_final, void* v_final, int32_t* final_len, int32_t* final_pos,
+                            int32_t* dev_flag, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * One whole layer of Alg. 2, Phase 1, in one call: the attention of cf_prefill_attention (with
  * S += s^l into score_accum, which must be given) followed — when `prune` is not NULL — by the
  * prune event of that layer: cf_prune_topk on the accumulated scores, cf_assign_positions for the

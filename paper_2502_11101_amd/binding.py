@@ -28,7 +28,7 @@ DTYPE_CODE = {"f32": CF_F32, "bf16": CF_BF16, "f16": CF_F16}
 
 EXPORTS = ("cf_reposition_keys", "cf_prefill_workspace_bytes", "cf_prefill_attention", "cf_prune_topk",
            "cf_assign_positions", "cf_gather_segments", "cf_last_error", "cf_version", "cf_profile_phases",
-           "cf_prefill_layer")
+           "cf_prefill_layer", "cf_assemble_cache")
 
 
 class cf_layer_desc(C.Structure):
@@ -93,6 +93,9 @@ def load() -> C.CDLL:
     lib.cf_prune_topk.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.cf_assign_positions.restype = i32
     lib.cf_assign_positions.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.cf_assemble_cache.restype = i32
+    lib.cf_assemble_cache.argtypes = [dp, vp, vp, i64, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, i64, i64, i64, vp, vp, vp,
+                                      vp, vp, vp]
     lib.cf_gather_segments.restype = i32
     lib.cf_gather_segments.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, i32, vp, vp]
     _lib = lib
@@ -202,6 +205,16 @@ def cf_prefill_layer(desc, q, q_off, q_stored_start: int, q_new_start, k_store, 
         n_store_tokens, _ptr(k_self), _ptr(v_self), _ptr(segs), _ptr(n_seg), seg_stride, batch, max_tq,
         max_kv_tokens, _ptr(out), _ptr(mass), _ptr(score_accum), score_stride, _ptr(workspace), workspace_bytes,
         C.byref(prune) if prune is not None else None, _ptr(dev_flag), _stream(stream)))
+
+
+def cf_assemble_cache(desc, k_store, v_store, n_store_tokens: int, k_self, v_self, q_off, segs, n_seg, seg_stride: int,
+                      batch: int, max_tq: int, max_seg_len: int, final_off, final_capacity: int, final_token_stride: int,
+                      final_head_stride: int, k_final, v_final, final_len, final_pos=None, dev_flag=None,
+                      stream=None) -> None:
+    _check(load().cf_assemble_cache(
+        C.byref(desc), _ptr(k_store), _ptr(v_store), n_store_tokens, _ptr(k_self), _ptr(v_self), _ptr(q_off), _ptr(segs),
+        _ptr(n_seg), seg_stride, batch, max_tq, max_seg_len, _ptr(final_off), final_capacity, final_token_stride,
+        final_head_stride, _ptr(k_final), _ptr(v_final), _ptr(final_len), _ptr(final_pos), _ptr(dev_flag), _stream(stream)))
 
 
 def cf_prune_topk(score, len_, cand, n_cand, keep: int, batch: int, stride: int, keep_idx, n_keep,

@@ -280,4 +280,44 @@ cf_status cf_gather_segments(const int64_t* doc_tok_offset, const int32_t* len, 
                          static_cast<hipStream_t>(stream));
 }
 
+cf_status cf_assemble_cache(const cf_layer_desc* desc, const void* k_store, const void* v_store, int64_t n_store_tokens,
+                            const void* k_self, const void* v_self, const int32_t* q_off, const cf_segment* segs,
+                            const int32_t* n_seg, int32_t seg_stride, int32_t batch, int32_t max_tq, int32_t max_seg_len,
+                            const int64_t* final_off, int64_t final_capacity, int64_t final_token_stride,
+                            int64_t final_head_stride, void* k_final, void* v_final, int32_t* final_len,
+                            int32_t* final_pos, int32_t* dev_flag, void* stream) {
+    cf_status st = check_desc(desc);
+    if (st != CF_OK) return st;
+    CF_REQUIRE(batch >= 0, CF_ERR_INVALID_ARG, "batch is negative");
+    CF_REQUIRE(seg_stride >= 1 && max_tq >= 1 && max_seg_len >= 1, CF_ERR_INVALID_ARG,
+               "seg_stride, max_tq and max_seg_len must be >= 1");
+    CF_REQUIRE(n_store_tokens >= 0 && final_capacity >= 0, CF_ERR_INVALID_ARG, "negative token count");
+    CF_REQUIRE(final_token_stride >= desc->head_dim && final_head_stride >= desc->head_dim &&
+                   final_token_stride % 8 == 0 && final_head_stride % 8 == 0,
+               CF_ERR_INVALID_ARG, "final strides must be multiples of 8 and at least head_dim");
+    if (batch == 0) return CF_OK;
+    CF_REQUIRE((int64_t)batch * seg_stride <= 0x7fffffff, CF_ERR_UNSUPPORTED, "batch * seg_stride too large");
+    CF_REQUIRE(q_off && segs && n_seg && final_off && k_final && v_final && final_len, CF_ERR_INVALID_ARG,
+               "q_off, segs, n_seg, final_off, k_final, v_final and final_len must not be NULL");
+    CF_REQUIRE((k_self == nullptr) == (v_self == nullptr), CF_ERR_INVALID_ARG, "k_self and v_self must be given together");
+    CF_REQUIRE(n_store_tokens == 0 || (k_store && v_store), CF_ERR_INVALID_ARG,
+               "k_store/v_store are NULL but n_store_tokens > 0");
+    CF_REQUIRE(aligned16(k_store) && aligned16(v_store) && aligned16(k_self) && aligned16(v_self) && aligned16(k_final) &&
+                   aligned16(v_final),
+               CF_ERR_INVALID_ARG, "tensor base pointers must be 16-byte aligned");
+    CF_REQUIRE(k_final != k_store && k_final != k_self && v_final != v_store && v_final != v_self && k_final != v_final,
+               CF_ERR_INVALID_ARG, "k_final / v_final must not alias the inputs or each other");
+    AssembleArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.k_store = k_store; a.v_store = v_store; a.k_self = k_self; a.v_self = v_self; a.k_final = k_final; a.v_final = v_final;
+    a.q_off = q_off; a.segs = segs; a.n_seg = n_seg; a.final_off = final_off; a.final_len = final_len; a.final_pos = final_pos;
+    a.dev_flag = dev_flag; a.n_store_tokens = n_store_tokens; a.final_capacity = final_capacity;
+    a.store_ts = store_token_stride(desc); a.store_hs = store_head_stride(desc);
+    a.final_ts = final_token_stride; a.final_hs = final_head_stride;
+    a.seg_stride = seg_stride; a.batch = batch; a.max_tq = max_tq; a.n_kv_heads = desc->n_kv_heads; a.head_dim = desc->head_dim;
+    RopeFreq f;
+    fill_rope_freq(desc, &f);
+    return launch_assemble(desc, f, a, max_seg_len, static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

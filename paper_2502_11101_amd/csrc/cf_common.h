@@ -108,6 +108,20 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // ---------------------------------------------------------------------------------- launchers
+struct AssembleArgs {
+    const void *k_store, *v_store, *k_self, *v_self;
+    void *k_final, *v_final;
+    const int32_t* q_off;
+    const cf_segment* segs;
+    const int32_t* n_seg;
+    const int64_t* final_off;
+    int32_t *final_len, *final_pos, *dev_flag;
+    int64_t n_store_tokens, final_capacity, store_ts, store_hs, final_ts, final_hs;
+    int32_t seg_stride, batch, max_tq, n_kv_heads, head_dim;
+};
+cf_status launch_assemble(const cf_layer_desc* d, const RopeFreq& f, const AssembleArgs& a, int32_t max_seg_len,
+                          hipStream_t s);
+
 cf_status launch_reposition(const cf_layer_desc* d, const RopeFreq& f, const void* k_in, void* k_out,
                             const cf_segment* segs, int32_t n_seg, int64_t n_store_tokens,
                             int32_t max_seg_len, int32_t* dev_flag, hipStream_t s);

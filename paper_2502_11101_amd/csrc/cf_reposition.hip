@@ -146,7 +146,149 @@ cf_status launch_dt(const cf_layer_desc* d, const RopeFreq& f, const void* k_in,
     return CF_OK;
 }
 
+// Final Re-Positioning (Alg. 2, Phase 2): gather + rotate.  grid = (batch * seg_stride, sweeps); block
+// (b, s) owns segment s of query b.  It first adds up the visible lengths of the query's segments (its own
+// output offset is the sum over the segments before it), then streams its tokens: per (token, kv head,
+// 8-pair item) two 16-byte K chunks are rotated and two V chunks copied, from the store's (or the own
+// block's) layout to the decode cache's.
+template <int DT, int PAIRING>
+__global__ __launch_bounds__(kThreads) void assemble_kernel(AssembleArgs a, RopeFreq freq) {
+    __shared__ float2 cs[kMaxHalf];
+    __shared__ int s_before, s_total, s_bad;
+    const int b = blockIdx.x / a.seg_stride, s = blockIdx.x - b * a.seg_stride;
+    const int tid = threadIdx.x;
+    int n = a.n_seg[b];
+    if (n < 0 || n > a.seg_stride) {
+        if (tid == 0 && s == 0 && blockIdx.y == 0) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
+        n = n < 0 ? 0 : a.seg_stride;
+    }
+    if (s >= n && s != 0) return;
+    const int q0 = a.q_off[b];
+    const int tq = min(a.q_off[b + 1] - q0, a.max_tq);
+    const int64_t q_total = a.q_off[a.batch];
+    if (tid == 0) { s_before = 0; s_total = 0; s_bad = 0; }
+    __syncthreads();
+    // visible tokens of an entry: 0 for a rejected one, min(len, tq) for the own block
+    auto visible = [&](const cf_segment& g, bool* bad) {
+        const bool self = g.kind == CF_SEG_SELF;
+        const int64_t limit = self ? q_total : a.n_store_tokens;
+        *bad = g.kind < 0 || g.kind > CF_SEG_SELF || g.len < 0 || g.tok_offset < 0 || g.tok_offset + g.len > limit ||
+               (self && (a.k_self == nullptr || a.v_self == nullptr));
+        return *bad ? 0 : (self ? min(g.len, tq) : g.len);
+    };
+    for (int t = tid; t < n; t += kThreads) {
+        bool bad;
+        const int vis = visible(a.segs[(int64_t)b * a.seg_stride + t], &bad);
+        if (bad) atomicOr(&s_bad, 1);
+        atomicAdd(&s_total, vis);
+        if (t < s) atomicAdd(&s_before, vis);
+    }
+    __syncthreads();
+    const int64_t run0 = a.final_off[b];
+    const bool fits = run0 >= 0 && run0 + s_total <= a.final_capacity;
+    if (s == 0 && blockIdx.y == 0 && tid == 0) {
+        if (s_bad) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
+        if (!fits) raise_flag(a.dev_flag, CF_FLAG_BAD_INDEX);
+        a.final_len[b] = fits ? s_total : 0;
+    }
+    if (s >= n || !fits) return;
+    const cf_segment seg = a.segs[(int64_t)b * a.seg_stride + s];
+    bool bad;
+    const int vis = visible(seg, &bad);
+    if (vis == 0) return;
+    const bool self = seg.kind == CF_SEG_SELF;
+    const int half = a.head_dim >> 1;
+    const int delta = seg.new_start - seg.stored_start;
+    for (int m = tid; m < half; m += kThreads) cs[m] = rope_cos_sin(delta, freq.rev[m]);
+    __syncthreads();
+
+    const void* k_in = self ? a.k_self : a.k_store;
+    const void* v_in = self ? a.v_self : a.v_store;
+    const int64_t in_ts = self ? (int64_t)a.n_kv_heads * a.head_dim : a.store_ts;
+    const int64_t in_hs = self ? a.head_dim : a.store_hs;
+    const int64_t out0 = run0 + s_before;
+    const int items_per_head = half / 8;                 // head_dim % 16 == 0 checked on the host
+    const int items_per_tok = a.n_kv_heads * items_per_head;
+    for (int tok0 = blockIdx.y * kTokPerBlock; tok0 < vis; tok0 += gridDim.y * kTokPerBlock) {
+        const int ntok = min(kTokPerBlock, vis - tok0);
+        const int n_items = ntok * items_per_tok;
+        for (int it = tid; it < n_items; it += kThreads) {
+            const int tok = it / items_per_tok;
+            const int r = it - tok * items_per_tok;
+            const int head = r / items_per_head;
+            const int j = r - head * items_per_head;
+            const int64_t src = (seg.tok_offset + tok0 + tok) * in_ts + (int64_t)head * in_hs;
+            const int64_t dst = (out0 + tok0 + tok) * a.final_ts + (int64_t)head * a.final_hs;
+            const int o0 = PAIRING == CF_ROPE_HALF ? 8 * j : 16 * j;
+            const int o1 = PAIRING == CF_ROPE_HALF ? half + 8 * j : 16 * j + 8;
+            float x[8], y[8], va[8], vb[8];
+            Vec8<DT>::load(k_in, src + o0, x);
+            Vec8<DT>::load(k_in, src + o1, y);
+            Vec8<DT>::load(v_in, src + o0, va);
+            Vec8<DT>::load(v_in, src + o1, vb);
+            if (delta != 0) {
+                if (PAIRING == CF_ROPE_HALF) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float2 w = cs[8 * j + e];
+                        const float nx = x[e] * w.x - y[e] * w.y;
+                        const float ny = x[e] * w.y + y[e] * w.x;
+                        x[e] = nx;
+                        y[e] = ny;
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float2 w0 = cs[8 * j + e];
+                        const float x0 = x[2 * e] * w0.x - x[2 * e + 1] * w0.y;
+                        const float y0 = x[2 * e] * w0.y + x[2 * e + 1] * w0.x;
+                        x[2 * e] = x0;
+                        x[2 * e + 1] = y0;
+                        const float2 w1 = cs[8 * j + 4 + e];
+                        const float x1 = y[2 * e] * w1.x - y[2 * e + 1] * w1.y;
+                        const float y1 = y[2 * e] * w1.y + y[2 * e + 1] * w1.x;
+                        y[2 * e] = x1;
+                        y[2 * e + 1] = y1;
+                    }
+                }
+            }
+            Vec8<DT>::store(a.k_final, dst + o0, x);
+            Vec8<DT>::store(a.k_final, dst + o1, y);
+            Vec8<DT>::store(a.v_final, dst + o0, va);
+            Vec8<DT>::store(a.v_final, dst + o1, vb);
+            if (a.final_pos && r == 0) a.final_pos[out0 + tok0 + tok] = seg.new_start + tok0 + tok;
+        }
+    }
+}
+
+template <int DT>
+cf_status launch_assemble_dt(const cf_layer_desc* d, const RopeFreq& f, const AssembleArgs& a, int32_t max_seg_len,
+                             hipStream_t s) {
+    int sweeps = (max_seg_len + kTokPerBlock - 1) / kTokPerBlock;
+    const int64_t blocks = (int64_t)a.batch * a.seg_stride;
+    int64_t cap = (256 * 8 + blocks - 1) / blocks;       // enough blocks to cover the chip a few times over
+    if (cap < 1) cap = 1;
+    if (sweeps > cap) sweeps = (int)cap;
+    if (sweeps < 1) sweeps = 1;
+    dim3 grid((unsigned)blocks, sweeps);
+    if (d->rope_pairing == CF_ROPE_HALF)
+        hipLaunchKernelGGL((assemble_kernel<DT, CF_ROPE_HALF>), grid, dim3(kThreads), 0, s, a, f);
+    else
+        hipLaunchKernelGGL((assemble_kernel<DT, CF_ROPE_INTERLEAVED>), grid, dim3(kThreads), 0, s, a, f);
+    CF_HIP(hipGetLastError());
+    return CF_OK;
+}
+
 }  // namespace
+
+cf_status launch_assemble(const cf_layer_desc* d, const RopeFreq& f, const AssembleArgs& a, int32_t max_seg_len,
+                          hipStream_t s) {
+    switch (d->dtype) {
+        case CF_F32: return launch_assemble_dt<CF_F32>(d, f, a, max_seg_len, s);
+        case CF_BF16: return launch_assemble_dt<CF_BF16>(d, f, a, max_seg_len, s);
+        default: return launch_assemble_dt<CF_F16>(d, f, a, max_seg_len, s);
+    }
+}
 
 cf_status launch_reposition(const cf_layer_desc* d, const RopeFreq& f, const void* k_in, void* k_out,
                             const cf_segment* segs, int32_t n_seg, int64_t n_store_tokens,

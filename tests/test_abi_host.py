@@ -130,3 +130,29 @@ def test_prune_and_assign_argument_checks():
 def test_last_error_is_set():
     _status(cf.cf_prune_topk, FAKE, None, FAKE, FAKE, 9, 1, 4, FAKE + 64, FAKE, stream=0)
     assert "keep" in cf.cf_last_error()
+
+
+def test_assemble_argument_checks():
+    d = _desc()
+
+    def call(**kw):
+        a = dict(desc=d, k_store=FAKE, v_store=FAKE + 0x100, n_store_tokens=100, k_self=FAKE + 0x200, v_self=FAKE + 0x300,
+                 q_off=FAKE, segs=FAKE, n_seg=FAKE, seg_stride=4, batch=1, max_tq=8, max_seg_len=64, final_off=FAKE,
+                 final_capacity=500, final_token_stride=256, final_head_stride=128, k_final=FAKE + 0x400,
+                 v_final=FAKE + 0x500, final_len=FAKE, stream=0)
+        a.update(kw)
+        return _status(cf.cf_assemble_cache, **a)
+
+    assert call(k_final=None)[0] == cf.CF_ERR_INVALID_ARG
+    assert call(final_len=None)[0] == cf.CF_ERR_INVALID_ARG
+    assert call(v_self=None)[0] == cf.CF_ERR_INVALID_ARG                    # k_self without v_self
+    assert call(final_token_stride=100)[0] == cf.CF_ERR_INVALID_ARG        # below head_dim
+    assert call(final_head_stride=132)[0] == cf.CF_ERR_INVALID_ARG         # rows not 16-byte aligned
+    assert call(k_final=FAKE)[0] == cf.CF_ERR_INVALID_ARG                  # aliases k_store
+    assert call(v_final=FAKE + 0x400)[0] == cf.CF_ERR_INVALID_ARG          # aliases k_final
+    assert call(k_final=FAKE + 0x404)[0] == cf.CF_ERR_INVALID_ARG          # misaligned
+    assert call(max_seg_len=0)[0] == cf.CF_ERR_INVALID_ARG
+    assert call(final_capacity=-1)[0] == cf.CF_ERR_INVALID_ARG
+    # an empty batch is a no-op and needs no GPU
+    cf.cf_assemble_cache(d, None, None, 0, None, None, None, None, None, 4, 0, 8, 64, None, 0, 256, 128, None, None, None,
+                         stream=0)

@@ -638,3 +638,137 @@ def test_n_reuse_ablation_modes(max_positions):
         assert seen == {"k": 20, "one": 1, "k/5": 4, "five": 5, "adaptive": 1}
     else:
         assert seen == {"k": 20, "one": "overflow", "k/5": 4, "five": 5, "adaptive": 2}
+
+
+# ----------------------------------------------------------------------------- Alg. 2 Phase 2: cf_assemble_cache
+def _assemble(cfg, st, t, pb, layout_in, layout_out, pairing=cf.CF_ROPE_HALF, capacity_pad=3):
+    """Run cf_assemble_cache on the tables `pb` holds; returns device outputs and the geometry used."""
+    g = cfg.geometry
+    dev = G.upload_layer(cfg, t, layout_in)
+    lens = st.doc_lens[st.query_docs]
+    per_query = int(cfg.prefix_len + lens.sum(axis=1).max() + cfg.tq) + capacity_pad
+    capacity = per_query * cfg.batch
+    kind, pad = G.LAYOUTS[layout_out]
+    ts, hs = pl.store_strides(capacity, g.n_kv_heads, g.head_dim, kind, pad)
+    shape = (capacity, g.n_kv_heads, g.head_dim) if kind == "token" else (g.n_kv_heads, capacity + pad, g.head_dim)
+    k_final = torch.full(shape, 7.0, dtype=pl.TORCH_DTYPE[g.dtype], device="cuda")
+    v_final = torch.full(shape, 7.0, dtype=pl.TORCH_DTYPE[g.dtype], device="cuda")
+    final_off = torch.arange(cfg.batch, dtype=torch.int64, device="cuda") * per_query
+    final_len = torch.full((cfg.batch,), -1, **I32)
+    final_pos = torch.full((capacity,), -1, **I32)
+    cf.cf_assemble_cache(pb.desc, dev["k_store"], dev["v_store"], st.n_store_tokens, dev["k_self"], dev["v_self"], pb.q_off,
+                         pb.segs, pb.n_seg, pb.seg_stride, cfg.batch, cfg.tq, int(max(lens.max(), cfg.prefix_len, cfg.tq)),
+                         final_off, capacity, ts, hs, k_final, v_final, final_len, final_pos, pb.dev_flag)
+    torch.cuda.synchronize()
+    as_tokens = (lambda x: x) if kind == "token" else (lambda x: x[:, :capacity].permute(1, 0, 2))
+    return dict(k=as_tokens(k_final).float().cpu().numpy(), v=as_tokens(v_final).float().cpu().numpy(),
+                len=final_len.cpu().numpy(), pos=final_pos.cpu().numpy(), per_query=per_query, dev=dev,
+                k_dev=k_final, v_dev=v_final, strides=(ts, hs), capacity=capacity)
+
+
+@pytest.mark.parametrize("dtype,pairing,layout_in,layout_out", [
+    ("bf16", cf.CF_ROPE_HALF, "head", "head"), ("bf16", cf.CF_ROPE_HALF, "token", "head_padded"),
+    ("f16", cf.CF_ROPE_INTERLEAVED, "head_padded", "token"), ("f32", cf.CF_ROPE_HALF, "token", "token")])
+def test_assemble_cache_matches_oracle(dtype, pairing, layout_in, layout_out):
+    """Final Re-Positioning after a prune: gathered keys within one rounding of the oracle's, values and
+    unmoved keys bit-exact copies, positions and lengths exact, nothing written outside the runs."""
+    cfg = wl.scaled(wl.CONFIGS["tiny_f32"], name=f"phase2_{dtype}", geometry=wl.Geometry(6, 3, 128, dtype, 1.0e4, 4096),
+                    n_store_docs=24, docs_per_query=7, batch=3, doc_len_range=(3, 90), tq=5, prefix_len=9,
+                    doc_stored_start=9, n_planted=1)
+    _say(f"assemble {dtype} pairing={pairing} {layout_in}->{layout_out}")
+    st = wl.build_structure(cfg, seed=7400)
+    t = wl.build_layer(cfg, st, seed=74)
+    pb = G.make_batch(cfg, st, pairing, layout_in)
+    pb.allocate_initial()
+    pb.score.copy_(torch.from_numpy(np.random.default_rng(3).random((cfg.batch, cfg.docs_per_query), dtype=np.float32)))
+    pb.prune(4, cf.CF_ALLOC_SORT)                            # survivors re-packed: most documents move
+    pb.advance()
+    r = _assemble(cfg, st, t, pb, layout_in, layout_out, pairing)
+    assert pb.flags() == 0
+    pname = "half" if pairing == cf.CF_ROPE_HALF else "interleaved"
+    tol = {"f32": 2e-6, "bf16": 2.0 ** -8, "f16": 2.0 ** -10}[dtype]
+    written = np.zeros(r["capacity"], dtype=bool)
+    for b in range(cfg.batch):
+        segs = G.device_segments(pb, b)
+        k_ref, v_ref, pos_ref = orc.assemble_final_cache(t["k_store"], t["v_store"], t["k_self"][b * cfg.tq:], t["v_self"][b * cfg.tq:],
+                                                         [s._replace(tok_offset=0) if s.kind == cf.CF_SEG_SELF else s for s in segs],
+                                                         cfg.tq, cfg.geometry.rope_base, pname)
+        n = len(pos_ref)
+        lo = b * r["per_query"]
+        assert r["len"][b] == n and r["pos"][lo:lo + n].tolist() == pos_ref.tolist()
+        assert np.max(np.abs(r["k"][lo:lo + n] - k_ref)) <= tol * max(1.0, np.abs(k_ref).max())
+        assert np.array_equal(r["v"][lo:lo + n], v_ref)
+        # segments that do not move are exact copies
+        at = 0
+        for s in segs:
+            m = min(s.len, cfg.tq) if s.kind == cf.CF_SEG_SELF else s.len
+            if s.new_start == s.stored_start:
+                assert np.array_equal(r["k"][lo + at:lo + at + m], k_ref[at:at + m])
+            at += m
+        written[lo:lo + n] = True
+    assert np.all(r["k"][~written] == 7.0) and np.all(r["v"][~written] == 7.0) and np.all(r["pos"][~written] == -1)
+
+
+def test_decode_step_over_assembled_cache():
+    """Alg. 2 Phase 3's attention: one new token per query attends over the assembled cache through
+    cf_prefill_attention (one zero-shift segment, strides of the decode cache) and matches the oracle."""
+    cfg = wl.scaled(wl.CONFIGS["tiny_f32"], name="decode", geometry=wl.Geometry(8, 8, 128, "bf16", 1.0e4, 4096),
+                    n_store_docs=12, docs_per_query=5, batch=2, doc_len_range=(100, 200), tq=48, prefix_len=32,
+                    doc_stored_start=32, n_planted=1)
+    g = cfg.geometry
+    st = wl.build_structure(cfg, seed=7401)
+    t = wl.build_layer(cfg, st, seed=75)
+    pb = G.make_batch(cfg, st, layout="head")
+    pb.allocate_initial()
+    r = _assemble(cfg, st, t, pb, "head", "head")
+    assert pb.flags() == 0
+    rng = np.random.default_rng(76)
+    q_raw = wl.round_to_dtype(rng.standard_normal((cfg.batch, g.n_q_heads, g.head_dim), dtype=np.float32), g.dtype)
+    ts, hs = r["strides"]
+    desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions,
+                        store_token_stride=ts, store_head_stride=hs)
+    # the queries arrive with RoPE for their absolute positions (right after each query block), rounded to bf16
+    p_new = [int(pb.q_start[b].item()) + cfg.tq for b in range(cfg.batch)]
+    q_abs = wl.round_to_dtype(np.stack([orc.rotate(q_raw[b].astype(np.float64), p_new[b], g.rope_base)
+                                        for b in range(cfg.batch)]).astype(np.float32), g.dtype)
+    segs = cf.segments_array([(b * r["per_query"], int(r["len"][b]), 0, 0, cf.CF_SEG_PREFIX, -1) for b in range(cfg.batch)])
+    seg_dev = cf.segments_to_device(segs)
+    n_seg = torch.ones(cfg.batch, **I32)
+    q_off = torch.arange(cfg.batch + 1, **I32)
+    zeros = torch.zeros(cfg.batch, **I32)
+    q_dev = pl.to_device(q_abs, g.dtype)
+    out = torch.empty_like(q_dev)
+    mass = torch.zeros((cfg.batch, 1), dtype=torch.float32, device="cuda")
+    max_kv = int(r["len"].max())
+    ws_bytes = cf.cf_prefill_workspace_bytes(desc, cfg.batch, 1, 1, max_kv)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    flag = torch.zeros(1, **I32)
+    cf.cf_prefill_attention(desc, q_dev, q_off, 0, zeros, r["k_dev"], r["v_dev"], r["capacity"], None, None, seg_dev, n_seg, 1,
+                            cfg.batch, 1, max_kv, out, mass, None, 1, ws, ws_bytes, flag)
+    torch.cuda.synchronize()
+    assert flag.item() == 0
+    got = out.float().cpu().numpy()
+    for b in range(cfg.batch):
+        dsegs = G.device_segments(pb, b)
+        k_ref, v_ref, _ = orc.assemble_final_cache(t["k_store"], t["v_store"], t["k_self"][b * cfg.tq:], t["v_self"][b * cfg.tq:],
+                                                   [s._replace(tok_offset=0) if s.kind == cf.CF_SEG_SELF else s for s in dsegs],
+                                                   cfg.tq, g.rope_base)
+        ref = orc.decode_attention(q_abs[b:b + 1].astype(np.float64), k_ref, v_ref, g.n_kv_heads)
+        assert G.row_error(got[b:b + 1], ref) <= G.OUT_TOL[g.dtype]
+        assert mass[b, 0].item() == pytest.approx(g.n_q_heads, rel=1e-5)
+
+
+def test_assemble_cache_flags():
+    cfg = wl.scaled(wl.CONFIGS["tiny_f32"], name="phase2_flags", geometry=wl.Geometry(4, 4, 64, "f32", 1.0e4, 4096))
+    st = wl.build_structure(cfg)
+    t = wl.build_layer(cfg, st)
+    pb = G.make_batch(cfg, st)
+    pb.allocate_initial()
+    r = _assemble(cfg, st, t, pb, "token", "token", capacity_pad=-1)          # one token short
+    assert pb.flags() == cf.CF_FLAG_BAD_INDEX and r["len"][0] == 0 and np.all(r["k"] == 7.0)
+    pb.dev_flag.zero_()
+    segs = cf.segments_from_device(pb.segs[0], 6)
+    segs[2]["len"] = -4
+    pb.segs[0].copy_(cf.segments_to_device(segs).reshape(6, 32))
+    r = _assemble(cfg, st, t, pb, "token", "token")
+    assert pb.flags() == cf.CF_FLAG_BAD_SEGMENT and r["len"][0] == 4 + 3 * 32 + 8
