@@ -83,6 +83,76 @@ def cpu_baseline(cfg, st, budget_s: float = 12.0) -> dict:
             "sample": f"{passes} layer pass(es) of {WORKLOAD} (batch 1), input generation excluded"}
 
 
+def bench_assemble(args) -> int:
+    """Final Re-Positioning (Alg. 2, Phase 2): one step gathers and re-positions one layer's prefix, surviving
+    documents and query block (LLaMA-2-7B stack geometry, 160-token documents) into a head-major decode cache.
+    Algorithmic bytes per gathered token: K and V read once and written once = 4 * Hkv * d * sizeof."""
+    import torch
+    from paper_2502_11101_amd import binding as cf
+    from paper_2502_11101_amd import pipeline as pl
+    from paper_2502_11101_amd import workloads as wl
+
+    base = wl.CONFIGS["llama2_7b_stack"]
+    cfg = wl.scaled(base, n_store_docs=args.assemble_docs, docs_per_query=args.assemble_docs,
+                    n_planted=min(3, args.assemble_docs))
+    g = cfg.geometry
+    st = wl.build_structure(cfg)
+    ts, hs = pl.store_strides(st.n_store_tokens, g.n_kv_heads, g.head_dim, args.store_layout)
+    desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions,
+                        store_token_stride=ts, store_head_stride=hs)
+    pb = pl.PrefillBatch(desc, st.doc_off[:-1][st.query_docs], st.doc_lens[st.query_docs], cfg.tq, cfg.prefix_len,
+                         cfg.doc_stored_start, st.n_store_tokens)
+    pb.allocate_initial()
+    tokens = wl.kv_tokens_per_call(cfg, st)
+    n_buf = max(2, min(args.layers, int(1.2e9 // (tokens * 2 * g.n_kv_heads * g.head_dim * 2 * 2))))
+    layers = []
+    for layer in range(n_buf):
+        t = wl.build_layer(cfg, st, layer)
+        layers.append({k: (pl.store_to_device(v, g.dtype, args.store_layout) if k in ("k_store", "v_store")
+                           else pl.to_device(v, g.dtype)) for k, v in t.items() if k != "q"})
+    fts, fhs = pl.store_strides(tokens, g.n_kv_heads, g.head_dim, "head")
+    finals = [(torch.empty((g.n_kv_heads, tokens, g.head_dim), dtype=pl.TORCH_DTYPE[g.dtype], device="cuda"),
+               torch.empty((g.n_kv_heads, tokens, g.head_dim), dtype=pl.TORCH_DTYPE[g.dtype], device="cuda"))
+              for _ in range(n_buf)]
+    final_off = torch.zeros(1, dtype=torch.int64, device="cuda")
+    final_len = torch.zeros(1, dtype=torch.int32, device="cuda")
+    max_seg = int(max(st.doc_lens.max(), cfg.prefix_len, cfg.tq))
+
+    def step(i: int) -> None:
+        L, (kf, vf) = layers[i % n_buf], finals[i % n_buf]
+        cf.cf_assemble_cache(desc, L["k_store"], L["v_store"], st.n_store_tokens, L["k_self"], L["v_self"], pb.q_off, pb.segs,
+                             pb.n_seg, pb.seg_stride, 1, cfg.tq, max_seg, final_off, tokens, fts, fhs, kf, vf, final_len,
+                             None, pb.dev_flag)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert pb.flags() == 0 and int(final_len.item()) == tokens
+    ms_per_step = 1e3 * elapsed / args.steps
+    kernel_ms = e0.elapsed_time(e1) / args.steps
+    bytes_per_token = 4 * g.n_kv_heads * g.head_dim * 2
+    achieved = tokens * bytes_per_token / (kernel_ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "KV tokens/s per layer, final re-positioning (cache assembly)", "value": tokens / (ms_per_step * 1e-3),
+        "unit": "KV tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": g.dtype, "data": "synthetic",
+        "config": {"workload": "llama2_7b_stack final survivors, one layer", "documents": args.assemble_docs,
+                   "kv_tokens_per_step": tokens, "kv_heads": g.n_kv_heads, "head_dim": g.head_dim,
+                   "layer_buffers": n_buf, "store_layout": args.store_layout, "step": "cf_assemble_cache"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "assemble_kernel<bf16, half>",
+                     "ms_per_launch": kernel_ms, "algorithmic_bytes_per_launch": tokens * bytes_per_token}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -93,6 +163,10 @@ def main() -> int:
     ap.add_argument("--store-layout", choices=["head", "token"], default="head",
                     help="layout of the cache store: head-major [kv head][token][d] (default, the layout the "
                          "store is meant to be kept in) or token-major [token][kv head][d]")
+    ap.add_argument("--path", choices=["prefill", "assemble"], default="prefill",
+                    help="prefill: the per-layer hot path (the headline metric).  assemble: Alg. 2 Phase 2, "
+                         "cf_assemble_cache of one layer of the final survivor set into a decode cache")
+    ap.add_argument("--assemble-docs", type=int, default=5, help="surviving documents per query for --path assemble")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only 10 elementwise copies of 1 GiB (read 1 GiB + write 1 GiB each): the known-size "
                          "kernel that scales the HBM byte counters of a profiler run")
@@ -120,6 +194,8 @@ def main() -> int:
                                                "write_bytes": dst.numel() * 4}}))
         return 0
     cf.load()
+    if args.path == "assemble":
+        return bench_assemble(args)
 
     cfg = wl.CONFIGS[WORKLOAD]
     g = cfg.geometry

@@ -1,6 +1,8 @@
 // Cache Re-Positioning, materialised (Sec. 2.3, Eq. 5): every key of every listed segment is
 // rotated from the position it was cached at to its new position.  Pure streaming kernel:
 // 16-byte loads and stores, one read and one write of K, bound by HBM bandwidth.
+#include <cstdlib>
+
 #include "cf_common.h"
 
 namespace cf {
@@ -152,7 +154,7 @@ cf_status launch_dt(const cf_layer_desc* d, const RopeFreq& f, const void* k_in,
 // 8-pair item) two 16-byte K chunks are rotated and two V chunks copied, from the store's (or the own
 // block's) layout to the decode cache's.
 template <int DT, int PAIRING>
-__global__ __launch_bounds__(kThreads) void assemble_kernel(AssembleArgs a, RopeFreq freq) {
+__global__ __launch_bounds__(kThreads) void assemble_kernel(AssembleArgs a, RopeFreq freq, int tok_per_block) {
     __shared__ float2 cs[kMaxHalf];
     __shared__ int s_before, s_total, s_bad;
     const int b = blockIdx.x / a.seg_stride, s = blockIdx.x - b * a.seg_stride;
@@ -209,8 +211,8 @@ __global__ __launch_bounds__(kThreads) void assemble_kernel(AssembleArgs a, Rope
     const int64_t out0 = run0 + s_before;
     const int items_per_head = half / 8;                 // head_dim % 16 == 0 checked on the host
     const int items_per_tok = a.n_kv_heads * items_per_head;
-    for (int tok0 = blockIdx.y * kTokPerBlock; tok0 < vis; tok0 += gridDim.y * kTokPerBlock) {
-        const int ntok = min(kTokPerBlock, vis - tok0);
+    for (int tok0 = blockIdx.y * tok_per_block; tok0 < vis; tok0 += gridDim.y * tok_per_block) {
+        const int ntok = min(tok_per_block, vis - tok0);
         const int n_items = ntok * items_per_tok;
         for (int it = tid; it < n_items; it += kThreads) {
             const int tok = it / items_per_tok;
@@ -264,17 +266,20 @@ __global__ __launch_bounds__(kThreads) void assemble_kernel(AssembleArgs a, Rope
 template <int DT>
 cf_status launch_assemble_dt(const cf_layer_desc* d, const RopeFreq& f, const AssembleArgs& a, int32_t max_seg_len,
                              hipStream_t s) {
-    int sweeps = (max_seg_len + kTokPerBlock - 1) / kTokPerBlock;
+    // tokens per block and sweep: few enough that even a short table fills the chip several times over
     const int64_t blocks = (int64_t)a.batch * a.seg_stride;
-    int64_t cap = (256 * 8 + blocks - 1) / blocks;       // enough blocks to cover the chip a few times over
-    if (cap < 1) cap = 1;
-    if (sweeps > cap) sweeps = (int)cap;
-    if (sweeps < 1) sweeps = 1;
-    dim3 grid((unsigned)blocks, sweeps);
+    int64_t tpb = blocks * max_seg_len / (256 * 8);
+    tpb = tpb < 2 ? 2 : (tpb > kTokPerBlock ? kTokPerBlock : tpb);
+#ifdef CF_DEV
+    if (const char* e = std::getenv("CF_TPB")) tpb = std::atoi(e);
+#endif
+    int64_t sweeps = (max_seg_len + tpb - 1) / tpb;
+    if (sweeps > 65535) sweeps = 65535;
+    dim3 grid((unsigned)blocks, (unsigned)sweeps);
     if (d->rope_pairing == CF_ROPE_HALF)
-        hipLaunchKernelGGL((assemble_kernel<DT, CF_ROPE_HALF>), grid, dim3(kThreads), 0, s, a, f);
+        hipLaunchKernelGGL((assemble_kernel<DT, CF_ROPE_HALF>), grid, dim3(kThreads), 0, s, a, f, (int)tpb);
     else
-        hipLaunchKernelGGL((assemble_kernel<DT, CF_ROPE_INTERLEAVED>), grid, dim3(kThreads), 0, s, a, f);
+        hipLaunchKernelGGL((assemble_kernel<DT, CF_ROPE_INTERLEAVED>), grid, dim3(kThreads), 0, s, a, f, (int)tpb);
     CF_HIP(hipGetLastError());
     return CF_OK;
 }
