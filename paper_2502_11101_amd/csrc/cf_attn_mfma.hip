@@ -21,7 +21,6 @@
 // the (max, sum) pairs to per-segment attention mass (the document-wise score of Alg. 2) in a
 // fixed order and adds it to the accumulated scores.  Results cross between the kernels at the
 // kernel boundaries: no fences, no atomics on the data path, bit-identical reruns.
-#include <cstdlib>
 #include <type_traits>
 
 #include "cf_common.h"
@@ -81,9 +80,6 @@ Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_str
     const int64_t cap = est_tiles / (2 * p.groups) > 1 ? est_tiles / (2 * p.groups) : 1;
     if (ns > cap) ns = cap;
     if (ns > kMaxSplit) ns = kMaxSplit;
-#ifdef CF_DEV
-    if (const char* e = std::getenv("CF_NSPLIT")) ns = std::atoi(e);
-#endif
     if (ns < 1) ns = 1;
     if (ns > kMaxSplit) ns = kMaxSplit;
     p.nsplit = (int)ns;

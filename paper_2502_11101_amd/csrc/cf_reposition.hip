@@ -1,8 +1,6 @@
 // Cache Re-Positioning, materialised (Sec. 2.3, Eq. 5): every key of every listed segment is
 // rotated from the position it was cached at to its new position.  Pure streaming kernel:
 // 16-byte loads and stores, one read and one write of K, bound by HBM bandwidth.
-#include <cstdlib>
-
 #include "cf_common.h"
 
 namespace cf {
@@ -270,9 +268,6 @@ cf_status launch_assemble_dt(const cf_layer_desc* d, const RopeFreq& f, const As
     const int64_t blocks = (int64_t)a.batch * a.seg_stride;
     int64_t tpb = blocks * max_seg_len / (256 * 8);
     tpb = tpb < 2 ? 2 : (tpb > kTokPerBlock ? kTokPerBlock : tpb);
-#ifdef CF_DEV
-    if (const char* e = std::getenv("CF_TPB")) tpb = std::atoi(e);
-#endif
     int64_t sweeps = (max_seg_len + tpb - 1) / tpb;
     if (sweeps > 65535) sweeps = 65535;
     dim3 grid((unsigned)blocks, (unsigned)sweeps);

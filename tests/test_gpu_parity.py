@@ -772,3 +772,47 @@ def test_assemble_cache_flags():
     pb.segs[0].copy_(cf.segments_to_device(segs).reshape(6, 32))
     r = _assemble(cfg, st, t, pb, "token", "token")
     assert pb.flags() == cf.CF_FLAG_BAD_SEGMENT and r["len"][0] == 4 + 3 * 32 + 8
+
+
+# ----------------------------------------------------------------------------- offline cache builder shape
+def test_document_encoding_attention_shape():
+    """The attention of query-independent parallel document caching (Sec. 2.2): every document attends to the
+    shared prefix and causally to itself, never to another document.  Expressed through the same call — each
+    document is a "query" with its own length whose table lists the prefix and its own block — and checked
+    against the oracle; ragged query lengths in one batch."""
+    rng = np.random.default_rng(81)
+    g = wl.Geometry(8, 2, 128, "bf16", 1.0e6, 32768)
+    prefix = 24
+    doc_lens = [100, 200, 137, 64, 1, 163]
+    q_off = np.concatenate([[0], np.cumsum(doc_lens)]).astype(np.int32)
+    total = int(q_off[-1])
+    rnd = lambda *shape: wl.round_to_dtype(rng.standard_normal(shape, dtype=np.float32), g.dtype)
+    q, k_self, v_self = rnd(total, g.n_q_heads, g.head_dim), rnd(total, g.n_kv_heads, g.head_dim), rnd(total, g.n_kv_heads, g.head_dim)
+    k_store, v_store = rnd(prefix, g.n_kv_heads, g.head_dim), rnd(prefix, g.n_kv_heads, g.head_dim)
+    desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions)
+    batch, seg_stride, max_tq = len(doc_lens), 2, max(doc_lens)
+    # every document is encoded right after the prefix: positions [prefix, prefix + len)
+    tables = [[orc.Segment(0, prefix, 0, 0, orc.KIND_PREFIX, -1), orc.Segment(int(q_off[b]), doc_lens[b], prefix, prefix, orc.KIND_SELF, -1)]
+              for b in range(batch)]
+    segs = cf.segments_to_device(cf.segments_array([s for tb in tables for s in tb]))
+    n_seg = torch.full((batch,), 2, **I32)
+    q_new = torch.full((batch,), prefix, **I32)
+    dev = {name: pl.to_device(x, g.dtype) for name, x in dict(q=q, k_self=k_self, v_self=v_self, k_store=k_store, v_store=v_store).items()}
+    out = torch.empty_like(dev["q"])
+    mass = torch.zeros((batch, seg_stride), dtype=torch.float32, device="cuda")
+    max_kv = prefix + max_tq
+    ws_bytes = cf.cf_prefill_workspace_bytes(desc, batch, max_tq, seg_stride, max_kv)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    flag = torch.zeros(1, **I32)
+    cf.cf_prefill_attention(desc, dev["q"], torch.from_numpy(q_off).cuda(), prefix, q_new, dev["k_store"], dev["v_store"], prefix,
+                            dev["k_self"], dev["v_self"], segs, n_seg, seg_stride, batch, max_tq, max_kv, out, mass, None, 1,
+                            ws, ws_bytes, flag)
+    torch.cuda.synchronize()
+    assert flag.item() == 0
+    got, m = out.float().cpu().numpy(), mass.cpu().numpy()
+    for b in range(batch):
+        lo, hi = int(q_off[b]), int(q_off[b + 1])
+        ref_out, ref_mass = orc.prefill_attention(q[lo:hi].astype(np.float64), prefix, prefix, k_store, v_store, k_self, v_self,
+                                                  tables[b], g.n_kv_heads, g.rope_base)
+        assert G.row_error(got[lo:hi], ref_out) <= G.OUT_TOL[g.dtype]
+        assert G.rel_error(m[b], ref_mass) <= (2e-3 if doc_lens[b] < 8 else G.MASS_TOL[g.dtype])
