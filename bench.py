@@ -124,6 +124,35 @@ def bench_assemble(args) -> int:
                              pb.n_seg, pb.seg_stride, 1, cfg.tq, max_seg, final_off, tokens, fts, fhs, kf, vf, final_len,
                              None, pb.dev_flag)
 
+    if args.path == "decode":
+        # every layer's cache is assembled once; a step is then the attention of one new token (already carrying RoPE
+        # for its position, right after the query block) over one layer's cache and over itself
+        for i in range(n_buf):
+            step(i)
+        torch.cuda.synchronize()
+        assert pb.flags() == 0 and int(final_len.item()) == tokens
+        ddesc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions,
+                             store_token_stride=fts, store_head_stride=fhs)
+        p_new = int(pb.q_start.item()) + cfg.tq
+        table = cf.segments_to_device(cf.segments_array([(0, tokens, 0, 0, cf.CF_SEG_PREFIX, -1),
+                                                         (0, 1, p_new, p_new, cf.CF_SEG_SELF, -1)]))
+        n_seg = torch.full((1,), 2, dtype=torch.int32, device="cuda")
+        q_off = torch.tensor([0, 1], dtype=torch.int32, device="cuda")
+        q_new = torch.full((1,), p_new, dtype=torch.int32, device="cuda")
+        gen = torch.Generator(device="cuda").manual_seed(5)
+        new_tok = [tuple(torch.randn(shape, generator=gen, device="cuda").to(pl.TORCH_DTYPE[g.dtype])
+                         for shape in ((1, g.n_q_heads, g.head_dim), (1, g.n_kv_heads, g.head_dim), (1, g.n_kv_heads, g.head_dim)))
+                   for _ in range(n_buf)]
+        dout = torch.empty_like(new_tok[0][0])
+        dmass = torch.zeros((1, 2), dtype=torch.float32, device="cuda")
+        ws_bytes = cf.cf_prefill_workspace_bytes(ddesc, 1, 1, 2, tokens + 1)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+
+        def step(i: int) -> None:                                                  # noqa: F811
+            (kf, vf), (q1, k1, v1) = finals[i % n_buf], new_tok[i % n_buf]
+            cf.cf_prefill_attention(ddesc, q1, q_off, p_new, q_new, kf, vf, tokens, k1, v1, table, n_seg, 2, 1, 1, tokens + 1,
+                                    dout, dmass, None, 1, ws, ws_bytes, pb.dev_flag)
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -136,6 +165,24 @@ def bench_assemble(args) -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     assert pb.flags() == 0 and int(final_len.item()) == tokens
+    if args.path == "decode":
+        assert abs(float(dmass.sum().item()) - g.n_q_heads) < 1e-3 * g.n_q_heads
+        ms_per_step = 1e3 * elapsed / args.steps
+        call_ms = e0.elapsed_time(e1) / args.steps
+        bytes_per_token = 2 * g.n_kv_heads * g.head_dim * 2
+        achieved = (tokens + 1) * bytes_per_token / (call_ms * 1e-3) / 1e9
+        print(json.dumps({
+            "metric": "KV tokens/s per layer, decode-step attention over the assembled cache",
+            "value": (tokens + 1) / (ms_per_step * 1e-3), "unit": "KV tokens/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": g.dtype, "data": "synthetic",
+            "config": {"workload": "llama2_7b_stack final survivors, one layer, one new token", "documents": args.assemble_docs,
+                       "kv_tokens_per_step": tokens + 1, "kv_heads": g.n_kv_heads, "head_dim": g.head_dim, "layer_buffers": n_buf,
+                       "step": "cf_prefill_attention (Tq = 1)"},
+            "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                         "traffic": None, "kernel": "whole call: attn_tile_kernel + attn_combine_kernel + attn_mass_kernel",
+                         "ms_per_launch": call_ms, "algorithmic_bytes_per_launch": (tokens + 1) * bytes_per_token}}))
+        return 0
     ms_per_step = 1e3 * elapsed / args.steps
     kernel_ms = e0.elapsed_time(e1) / args.steps
     bytes_per_token = 4 * g.n_kv_heads * g.head_dim * 2
@@ -163,9 +210,10 @@ def main() -> int:
     ap.add_argument("--store-layout", choices=["head", "token"], default="head",
                     help="layout of the cache store: head-major [kv head][token][d] (default, the layout the "
                          "store is meant to be kept in) or token-major [token][kv head][d]")
-    ap.add_argument("--path", choices=["prefill", "assemble"], default="prefill",
+    ap.add_argument("--path", choices=["prefill", "assemble", "decode"], default="prefill",
                     help="prefill: the per-layer hot path (the headline metric).  assemble: Alg. 2 Phase 2, "
-                         "cf_assemble_cache of one layer of the final survivor set into a decode cache")
+                         "cf_assemble_cache of one layer of the final survivor set into a decode cache.  decode: one "
+                         "decode step's attention (one new token) over an assembled cache, Alg. 2 Phase 3")
     ap.add_argument("--assemble-docs", type=int, default=5, help="surviving documents per query for --path assemble")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only 10 elementwise copies of 1 GiB (read 1 GiB + write 1 GiB each): the known-size "
@@ -194,7 +242,7 @@ def main() -> int:
                                                "write_bytes": dst.numel() * 4}}))
         return 0
     cf.load()
-    if args.path == "assemble":
+    if args.path in ("assemble", "decode"):
         return bench_assemble(args)
 
     cfg = wl.CONFIGS[WORKLOAD]
