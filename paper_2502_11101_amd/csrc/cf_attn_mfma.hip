@@ -46,8 +46,9 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 struct Plan {
     int row_blocks;     // 16-row blocks of the stacked rows of one kv head
-    int nrb;            // 16-row blocks per wavefront (1 or 2)
-    int rows_wg;        // 64 * nrb
+    int producers;      // 0: attn_tile_kernel (few rows); else attn_pc_kernel with that many loading wavefronts
+    int nrb;            // 64-row passes of a workgroup's rows (what the combine kernel handles at a time)
+    int rows_wg;        // rows a workgroup has room for: 64 * nrb
     int n_rg;           // row groups per (query, kv head)
     int blocks_rg;      // 16-row blocks per row group
     int units_per_b, units, nsplit, slots, x_count;
@@ -56,25 +57,36 @@ struct Plan {
     size_t off_ml, off_opart, off_massml, off_masspart, total;
 };
 
+constexpr int kPcWaves = 8;         // wavefronts of an attn_pc_kernel workgroup
+constexpr int kPcProducers = 2;     // of which load and stage
+
 Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_stride, int64_t max_kv_tokens) {
     Plan p;
     const int group = n_q_heads / n_kv_heads;
     const int row_blocks = (group * max_tq + 15) / 16;
     p.row_blocks = row_blocks;
-    // At most 8 row blocks (128 stacked rows) per workgroup: with two row blocks per wavefront the
-    // kernel fits 256 registers, so two workgroups share a CU and fill each other's waits.
-    p.n_rg = (row_blocks + 7) / 8;
+    if (row_blocks <= 4) {
+        // Few stacked rows (MHA-like, HBM-bound): one row block per wavefront, small tiles, so that ragged
+        // segment ends waste little and a split still holds several tiles; two groups of four wavefronts per
+        // workgroup run two tiles at a time on one CU and hide each other's LDS and barrier waits.
+        p.producers = 0;
+        p.n_rg = 1;
+        p.nrb = 1;
+        p.tile = 32;
+        p.groups = 2;
+    } else {
+        // Many rows (GQA, long queries): 64-token tiles, two row blocks per math wavefront.
+        const int blocks_wg = 2 * (kPcWaves - kPcProducers);
+        p.producers = kPcProducers;
+        p.n_rg = (row_blocks + blocks_wg - 1) / blocks_wg;
+        p.nrb = blocks_wg / 4;
+        p.tile = 64;
+        p.groups = 1;
+    }
     p.blocks_rg = (row_blocks + p.n_rg - 1) / p.n_rg;
-    p.nrb = (p.blocks_rg + kWaves - 1) / kWaves;
     p.rows_wg = 64 * p.nrb;
     p.units_per_b = n_kv_heads * p.n_rg;
     p.units = batch * p.units_per_b;
-    // Few stacked rows (MHA-like, HBM-bound): small tiles, so that ragged segment ends waste little and
-    // a split still holds several tiles.  Many rows (GQA, MFMA-bound): 64-token tiles.
-    p.tile = row_blocks <= 4 ? 32 : 64;
-    // The small-row kernel is light on registers: two groups of four wavefronts per workgroup run two
-    // tiles at a time on one CU and hide each other's LDS and barrier waits.
-    p.groups = row_blocks <= 4 ? 2 : 1;
     const int64_t est_tiles = max_kv_tokens / p.tile + seg_stride;
     int64_t ns = (256 + p.units - 1) / p.units;         // one workgroup per CU and launch wave
     const int64_t cap = est_tiles / (2 * p.groups) > 1 ? est_tiles / (2 * p.groups) : 1;
@@ -212,17 +224,266 @@ __device__ __forceinline__ float2 rope_cos_sin_fast(int delta, double theta_rev)
     return make_float2(__builtin_amdgcn_cosf(fr), __builtin_amdgcn_sinf(fr));
 }
 
+// One tile of the walk over a split's tiles; ntok == 0 marks "no tile left".
+struct Tile { int seg, tok0, ntok, delta, self; };
+
+// Walks the tiles [next_tile, t_end) of the segment table in order.  All state is wavefront-uniform;
+// the segment of the tile handed out last is cached, since most tiles continue their predecessor's.
+template <int TILE>
+struct TileWalk {
+    int next_tile, t_end;
+    int c_seg = -1, c_first = 0, c_end = 0, c_vis = 0, c_delta = 0, c_self = 0;
+    int64_t c_tok = 0;          // first token of the cached segment in its tensor
+
+    __device__ __forceinline__ TileWalk(int begin, int end) : next_tile(begin), t_end(end) {}
+
+    // The next tile, or a tile with ntok == 0 when none is left.
+    __device__ __forceinline__ Tile next(const SegTable& tbl, int lane) {
+        Tile d;
+        if (next_tile < t_end) {
+            if (next_tile >= c_end) {
+                // the first segment whose tiles reach past this one: every lane tests one entry per round
+                int s = 0;
+                for (int s0 = c_seg < 0 ? 0 : (c_seg & ~(kWave - 1));; s0 += kWave) {
+                    const int idx = s0 + lane;
+                    const unsigned long long hit = __ballot(idx < tbl.n && tbl.tile0[idx + 1] > next_tile);
+                    if (hit) { s = s0 + __builtin_ctzll(hit); break; }
+                }
+                c_seg = s;
+                c_first = tbl.tile0[s];
+                c_end = tbl.tile0[s + 1];
+                c_vis = tbl.vis[s];
+                c_delta = tbl.delta[s];
+                c_self = tbl.self[s];
+                c_tok = tbl.tok[s];
+            }
+            d.seg = c_seg;
+            d.tok0 = (next_tile - c_first) * TILE;
+            d.ntok = min(TILE, c_vis - d.tok0);
+            d.delta = c_delta;
+            d.self = c_self;
+            ++next_tile;
+        } else {
+            d.seg = 0; d.tok0 = 0; d.ntok = 0; d.delta = 0; d.self = 0;
+        }
+        return d;
+    }
+};
+
+// Where a tile's keys and values start for kv head `hkv`, and the distance between its tokens.
+// Without a tile: the first bytes of the workspace, so that a fetch always has something to read.
+struct TileSource { const char *k, *v; uint32_t row_bytes; int last; };
+
+__device__ __forceinline__ TileSource tile_source(const AttnArgs& a, const Tile& d, int64_t seg_tok, int hkv) {
+    TileSource t;
+    t.k = t.v = static_cast<const char*>(a.workspace);
+    t.row_bytes = 0;
+    t.last = -1;
+    if (d.ntok > 0) {
+        // the own block is always token-major; the store has its own strides
+        const int64_t tok_stride = d.self ? (int64_t)a.n_kv_heads * kD : a.store_ts;
+        const int64_t base = ((seg_tok + d.tok0) * tok_stride + (int64_t)hkv * (d.self ? kD : a.store_hs)) * 2;
+        t.k = static_cast<const char*>(d.self ? a.k_self : a.k_store) + base;
+        t.v = static_cast<const char*>(d.self ? a.v_self : a.v_store) + base;
+        t.row_bytes = (uint32_t)tok_stride * 2;
+        t.last = d.ntok - 1;
+    }
+    return t;
+}
+
+// Rotates the pair of 16-byte key chunks (channels c..c+7 and c+64..c+71) by the angles whose
+// (cos, sin) pairs start at `cs` (Eq. 5), in fp32, and rounds once to the storage type.
+template <int DT>
+__device__ __forceinline__ void rotate_chunk_pair(uint4& ra, uint4& rb4, const float2* cs8) {
+    uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb4.x, rb4.y, rb4.z, rb4.w};
+    const float4* cs = reinterpret_cast<const float4*>(cs8);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float4 w = cs[i];          // (cos, sin) of slices 2i, 2i + 1 of the chunk
+        const float a0 = Mma<DT>::lo(wa[i]), a1 = Mma<DT>::hi(wa[i]);
+        const float b0 = Mma<DT>::lo(wb[i]), b1 = Mma<DT>::hi(wb[i]);
+        wa[i] = Mma<DT>::pack(a0 * w.x - b0 * w.y, a1 * w.z - b1 * w.w);
+        wb[i] = Mma<DT>::pack(a0 * w.y + b0 * w.x, a1 * w.w + b1 * w.z);
+    }
+    ra = make_uint4(wa[0], wa[1], wa[2], wa[3]);
+    rb4 = make_uint4(wb[0], wb[1], wb[2], wb[3]);
+}
+
+// Running state of a wavefront's NRB 16-row blocks: lane (li, lg) holds, for query row li of each
+// block, the output channels 16*db + 4*lg + r, the reference maximum, and the sums of exp2 over the
+// tokens this lane has seen (whole call and current segment).
+template <int NRB>
+struct RowState {
+    f32x4 acc[NRB][8];
+    float m_run[NRB], l_run[NRB], seg_l[NRB];
+    __device__ __forceinline__ void clear() {
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+#pragma unroll
+            for (int db = 0; db < 8; ++db) acc[rb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+            m_run[rb] = -INFINITY; l_run[rb] = 0.f; seg_l[rb] = 0.f;
+        }
+    }
+};
+
+// The math of one staged tile for one wavefront: S^T = K Q^T from LDS key fragments and the register-resident
+// Q fragments, online softmax against a stale maximum, O^T += V^T P^T with V^T fragments from
+// transposing LDS reads.  K tile: [token][kSK] elements; V tile: row-major [token][256 bytes], chunk c of
+// row t at chunk c ^ 2*(t & 7).  `trow`: query position of the lane's row inside the own block
+// (causal mask), `tr_base`/`tr_x`: the lane's transposing-read offsets.
+template <int DT, int NRB, int TILE>
+__device__ __forceinline__ void tile_math(const Tile& cd, const uint16_t* k_lds, const unsigned char* v_lds,
+                                          const uint4 (&qf)[NRB][4], const int (&trow)[NRB], RowState<NRB>& st,
+                                          float scale_log2e, int li, int lg, uint32_t tr_base, uint32_t tr_x) {
+    const bool causal = cd.self != 0;
+#pragma unroll
+    for (int h2 = 0; h2 < TILE / 32; ++h2) {
+        const int nt = cd.ntok - 32 * h2;      // valid tokens of this half
+        if (nt <= 0) break;
+        // ---- S^T = K Q^T : lane (li, lg) gets, for query row li, tokens 32*h2 + 16*tb + 4*lg + r
+        f32x4 sc[NRB][2];
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) { sc[rb][0] = f32x4{0.f, 0.f, 0.f, 0.f}; sc[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+        uint4 kf[2][4];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                kf[tb][kk] = *reinterpret_cast<const uint4*>(k_lds + (32 * h2 + 16 * tb + li) * kSK + 32 * kk + 8 * lg);
+        __builtin_amdgcn_sched_barrier(0);       // all eight reads are out before the first MFMA waits
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int rb = 0; rb < NRB; ++rb) sc[rb][tb] = Mma<DT>::run(kf[tb][kk], qf[rb][kk], sc[rb][tb]);
+        // V^T fragments, requested before the softmax arithmetic that hides their latency
+        short4v vlo[8], vhi[8];
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+            const unsigned char* src = v_lds + h2 * 32 * 256 + tr_base + ((uint32_t)(32 * db) ^ tr_x);
+            vlo[db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(src));
+            vhi[db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(src + 16 * 256));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- online softmax (exp2 domain), fp32, against a stale row maximum (see kRescaleSlack)
+        const bool need_mask = causal || nt < 32;
+        uint4 pfrag[NRB];
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            float xv[8];
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) xv[4 * tb + e] = sc[rb][tb][e];
+            if (need_mask) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int tk = 16 * (e >> 2) + 4 * lg + (e & 3);
+                    const bool ok = tk < nt && (!causal || cd.tok0 + 32 * h2 + tk <= trow[rb]);
+                    xv[e] = ok ? xv[e] : -INFINITY;
+                }
+            }
+            float mloc = fmaxf(fmaxf(fmaxf(xv[0], xv[1]), fmaxf(xv[2], xv[3])), fmaxf(fmaxf(xv[4], xv[5]), fmaxf(xv[6], xv[7])));
+            mloc *= scale_log2e;                         // scale > 0: max commutes with it
+            if (__any(mloc > st.m_run[rb] + kRescaleSlack)) {
+                mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+                mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+                const float m_old = st.m_run[rb];
+                const float m_new = fmaxf(m_old, mloc);
+                const float alpha = __builtin_amdgcn_exp2f(m_old - (m_new == -INFINITY ? 0.f : m_new));
+                st.l_run[rb] *= alpha;
+                st.seg_l[rb] *= alpha;
+                st.m_run[rb] = m_new;
+                if (__any(alpha != 1.f && m_old != -INFINITY)) {     // nothing accumulated yet: nothing to rescale
+#pragma unroll
+                    for (int db = 0; db < 8; ++db) st.acc[rb][db] *= alpha;
+                }
+            }
+            const float m_safe = st.m_run[rb] == -INFINITY ? 0.f : st.m_run[rb];
+            float lsum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                xv[e] = __builtin_amdgcn_exp2f(fmaf(xv[e], scale_log2e, -m_safe));
+                lsum += xv[e];
+            }
+            st.l_run[rb] += lsum;
+            st.seg_l[rb] += lsum;
+            pfrag[rb] = make_uint4(Mma<DT>::pack(xv[0], xv[1]), Mma<DT>::pack(xv[2], xv[3]),
+                                   Mma<DT>::pack(xv[4], xv[5]), Mma<DT>::pack(xv[6], xv[7]));
+        }
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+            const uint2 l2 = __builtin_bit_cast(uint2, vlo[db]), h2v = __builtin_bit_cast(uint2, vhi[db]);
+            const uint4 va = make_uint4(l2.x, l2.y, h2v.x, h2v.y);
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb) st.acc[rb][db] = Mma<DT>::run(va, pfrag[rb], st.acc[rb][db]);
+        }
+    }
+}
+
+// Q fragments of a wavefront's row blocks [first_blk, first_blk + NRB) of the stacked rows of kv head
+// `hkv`: row m = g*tq + t is q[q0 + t][hkv*group + g].  Rows at or past `row_limit` are padding (zero
+// fragments, nothing to mask, results unused).
+template <int NRB>
+__device__ __forceinline__ void load_q_fragments(const AttnArgs& a, int q0, int tq, int hkv, int group, int first_blk,
+                                                 int row_base, int row_limit, int li, int lg, uint4 (&qf)[NRB][4],
+                                                 int (&trow)[NRB]) {
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        const int m = row_base + (first_blk + rb) * 16 + li;
+        const bool valid = m < row_limit;
+        const int gi = valid ? m / tq : 0;
+        const int t = valid ? m - gi * tq : 0;
+        trow[rb] = valid ? t : 0x7fffffff;
+        const uint16_t* qp = static_cast<const uint16_t*>(a.q) + (((int64_t)q0 + t) * a.n_q_heads + hkv * group + gi) * kD + 8 * lg;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+            qf[rb][kk] = valid ? *reinterpret_cast<const uint4*>(qp + 32 * kk) : make_uint4(0, 0, 0, 0);
+    }
+}
+
+// (running reference, segment sum) per row of the wavefront's row blocks for slot `slot`
+template <int NRB>
+__device__ __forceinline__ void emit_segment(const RowState<NRB>& st, float2* massml, int slot, int rows_wg, int first_blk,
+                                             int li, int lg) {
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        float tot = st.seg_l[rb] + __shfl_xor(st.seg_l[rb], 16);
+        tot += __shfl_xor(tot, 32);
+        if (lg == 0) massml[(int64_t)slot * rows_wg + (first_blk + rb) * 16 + li] = make_float2(st.m_run[rb], tot);
+    }
+}
+
+// Partial results of a split: O^T in MFMA layout (one float4 per lane, row block and channel block)
+// and (reference, row sum) per row.
+template <int NRB>
+__device__ __forceinline__ void store_partials(const AttnArgs& a, const Plan& p, int unit, int split, int first_blk,
+                                               const RowState<NRB>& st, const float (&l_row)[NRB], int lane) {
+    char* ws = static_cast<char*>(a.workspace);
+    f32x4* opart = reinterpret_cast<f32x4*>(ws + p.off_opart) +
+                   (((int64_t)unit * p.nsplit + split) * p.rows_wg / 16 + first_blk) * 8 * kWave + lane;
+    float2* ml = reinterpret_cast<float2*>(ws + p.off_ml) + ((int64_t)unit * p.nsplit + split) * p.rows_wg;
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+#pragma unroll
+        for (int db = 0; db < 8; ++db) opart[(rb * 8 + db) * kWave] = st.acc[rb][db];
+        if ((lane >> 4) == 0) ml[(first_blk + rb) * 16 + (lane & 15)] = make_float2(st.m_run[rb], l_row[rb]);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
-// The attention kernel: the four wavefronts of a workgroup stream the same TILE-token tiles and own
-// different query rows (wavefront w the 16-row blocks [w*NRB, (w+1)*NRB)), so there is nothing to
-// merge inside a workgroup.  Per tile:
+// The attention kernel for few stacked rows: the four wavefronts of a group stream the same TILE-token
+// tiles and own different query rows (wavefront w the 16-row blocks [w*NRB, (w+1)*NRB)), so there is
+// nothing to merge inside a group.  Per tile:
 //   * every thread's K/V loads for the tile two ahead are in flight in registers (a fixed number of
 //     loads per step, so the wait for one tile never covers a later one);
 //   * staging: a thread rotates the pairs (c, c + 64) of its 16-byte key chunks (Eq. 5) and writes
 //     them [token][channel] to one of two LDS tile buffers; V chunks are copied as loaded, row-major
 //     with a 32-byte XOR swizzle; one workgroup barrier per tile;
-//   * S^T = K Q^T from LDS key fragments and register-resident Q fragments, online softmax with a
-//     stale maximum, O^T += V^T P^T with V^T fragments from transposing LDS reads.
+//   * the tile's math (tile_math).
+// With GROUPS == 2 two such groups share a workgroup, stream disjoint runs of tiles and merge at the end.
 template <int DT, int NRB, int TILE, int GROUPS>
 __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArgs a, RopeFreq freq, Plan p) {
     static_assert(GROUPS == 1 || (GROUPS == 2 && NRB == 1 && TILE == 32), "two groups: one row block per wavefront, 32-token tiles");
@@ -259,135 +520,65 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
     const int b = __builtin_amdgcn_readfirstlane(x / (p.nsplit * a.n_kv_heads));
     const int unit = (b * a.n_kv_heads + hkv) * p.n_rg + rg;
 
-    const int hq = a.n_q_heads;
-    const int group = hq / a.n_kv_heads;
+    const int group = a.n_q_heads / a.n_kv_heads;
     const QueryHead qh = load_query_head(a, b);
     const double my_freq = freq.rev[tid & (kHalf - 1)];
-    const int q0 = qh.q0;
     const int tq = min(qh.tq_raw, a.max_tq);
-    const int n_rows = group * tq;
 
-    // ---- Q fragments first (loads return in order): row m = g*tq + t of the stack is q[q0 + t][hkv*group + g]
+    // ---- Q fragments first (loads return in order)
     uint4 qf[NRB][4];
     int trow[NRB];
     const int row_base = rg * p.blocks_rg * 16;
-    const int row_limit = min(n_rows, row_base + p.blocks_rg * 16);
+    const int row_limit = min(group * tq, row_base + p.blocks_rg * 16);
     const bool has_rows = row_base + wave * NRB * 16 < row_limit;        // wavefront-uniform
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        const int m = row_base + (wave * NRB + rb) * 16 + li;
-        const bool valid = m < row_limit;
-        const int gi = valid ? m / tq : 0;
-        const int t = valid ? m - gi * tq : 0;
-        trow[rb] = valid ? t : 0x7fffffff;            // padding rows: nothing to mask, results unused
-        const uint16_t* qp = static_cast<const uint16_t*>(a.q) + (((int64_t)q0 + t) * hq + hkv * group + gi) * kD + 8 * lg;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-            qf[rb][kk] = valid ? *reinterpret_cast<const uint4*>(qp + 32 * kk) : make_uint4(0, 0, 0, 0);
-    }
+    load_q_fragments<NRB>(a, qh.q0, tq, hkv, group, wave * NRB, row_base, row_limit, li, lg, qf, trow);
 
     build_table(a, qh, &tbl, TILE);
     const unsigned total = (unsigned)tbl.tile0[tbl.n];
     // a group streams a contiguous run of the workgroup's tiles of its own (sub-split `ss`)
     const unsigned nsub = (unsigned)(p.nsplit * GROUPS);
     const int ss = split * GROUPS + grp;
-    const int t_begin = split_begin(total, nsub, ss);
-    const int t_end = split_begin(total, nsub, ss + 1);
     int most_tiles = 0;                              // workgroup-uniform: the longest run among the groups
 #pragma unroll
     for (int g = 0; g < GROUPS; ++g)
         most_tiles = max(most_tiles, split_begin(total, nsub, split * GROUPS + g + 1) - split_begin(total, nsub, split * GROUPS + g));
 
-    const int64_t kv_row = (int64_t)a.n_kv_heads * kD;
     // staging items: K (row kr + 32*it, chunks kj and kj + 8), V (row vr + 16*it, chunk vc)
     const int kr = tid >> 3, kj = tid & 7;
     const int vr = tid >> 4, vc = tid & 15;
     struct StageRegs { uint4 ka[kKItems], kb[kKItems], v[kVItems]; };
-    struct Tile { int seg, tok0, ntok, delta, self; };
     StageRegs regs0, regs1;
 
-    int next_tile = t_begin;
-    // the segment of the tile fetched last, cached in scalars: most tiles continue their predecessor's segment
-    int c_seg = -1, c_first = 0, c_end = 0, c_vis = 0, c_delta = 0, c_self = 0;
-    int64_t c_tok = 0;
-    // Every call issues the same loads whether or not a tile is left (without one they re-read the first
-    // bytes of the workspace), so the number of loads in flight at any point of the loop is fixed.
-    auto fetch = [&](Tile& d, StageRegs& r) {        // ntok == 0 marks "no tile"
-        const char *kb = static_cast<const char*>(a.workspace), *vb = kb;
-        int last = -1;
-        uint32_t row_bytes = 0;                      // between consecutive tokens of this head
-        if (next_tile < t_end) {
-            if (next_tile >= c_end) {
-                // the first segment whose tiles reach past this one: every lane tests one entry per round
-                int s = 0;
-                for (int s0 = c_seg < 0 ? 0 : (c_seg & ~(kWave - 1));; s0 += kWave) {
-                    const int idx = s0 + lane;
-                    const unsigned long long hit = __ballot(idx < tbl.n && tbl.tile0[idx + 1] > next_tile);
-                    if (hit) { s = s0 + __builtin_ctzll(hit); break; }
-                }
-                c_seg = s;
-                c_first = tbl.tile0[s];
-                c_end = tbl.tile0[s + 1];
-                c_vis = tbl.vis[s];
-                c_delta = tbl.delta[s];
-                c_self = tbl.self[s];
-                c_tok = tbl.tok[s];
-            }
-            d.seg = c_seg;
-            d.tok0 = (next_tile - c_first) * TILE;
-            d.ntok = min(TILE, c_vis - d.tok0);
-            d.delta = c_delta;
-            d.self = c_self;
-            ++next_tile;
-            // the own block is always token-major; the store has its own strides
-            const int64_t tok_stride = d.self ? kv_row : a.store_ts;
-            const int64_t base = ((c_tok + d.tok0) * tok_stride + (int64_t)hkv * (d.self ? kD : a.store_hs)) * 2;
-            kb = static_cast<const char*>(d.self ? a.k_self : a.k_store) + base;
-            vb = static_cast<const char*>(d.self ? a.v_self : a.v_store) + base;
-            row_bytes = (uint32_t)tok_stride * 2;
-            last = d.ntok - 1;
-        } else {
-            d.seg = 0; d.tok0 = 0; d.ntok = 0; d.delta = 0; d.self = 0;
-        }
-        // rows past the end of a ragged tile re-read its last row (in bounds; their scores are masked)
+    TileWalk<TILE> walk(split_begin(total, nsub, ss), split_begin(total, nsub, ss + 1));
+    // Every call issues the same loads whether or not a tile is left, so the number of loads in flight
+    // at any point of the loop is fixed.  Rows past the end of a ragged tile re-read its last row (in
+    // bounds; their scores are masked).
+    auto fetch = [&](Tile& d, StageRegs& r) {
+        d = walk.next(tbl, lane);
+        const TileSource src = tile_source(a, d, walk.c_tok, hkv);
 #pragma unroll
         for (int it = 0; it < kKItems; ++it) {
-            const uint32_t off = last < 0 ? 0u : (uint32_t)min(kr + 32 * it, last) * row_bytes + 16 * kj;
-            r.ka[it] = *reinterpret_cast<const uint4*>(kb + off);
-            r.kb[it] = *reinterpret_cast<const uint4*>(kb + off + (last < 0 ? 0 : 128));
+            const uint32_t off = src.last < 0 ? 0u : (uint32_t)min(kr + 32 * it, src.last) * src.row_bytes + 16 * kj;
+            r.ka[it] = *reinterpret_cast<const uint4*>(src.k + off);
+            r.kb[it] = *reinterpret_cast<const uint4*>(src.k + off + (src.last < 0 ? 0 : 128));
         }
 #pragma unroll
         for (int it = 0; it < kVItems; ++it) {
-            const uint32_t off = last < 0 ? 0u : (uint32_t)min(vr + 16 * it, last) * row_bytes + 16 * vc;
-            r.v[it] = *reinterpret_cast<const uint4*>(vb + off);
+            const uint32_t off = src.last < 0 ? 0u : (uint32_t)min(vr + 16 * it, src.last) * src.row_bytes + 16 * vc;
+            r.v[it] = *reinterpret_cast<const uint4*>(src.v + off);
         }
     };
     Tile d0, d1;
     fetch(d0, regs0);
     fetch(d1, regs1);
 
-    f32x4 acc[NRB][8];
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-        for (int db = 0; db < 8; ++db) acc[rb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run[NRB], l_run[NRB], seg_l[NRB];
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) { m_run[rb] = -INFINITY; l_run[rb] = 0.f; seg_l[rb] = 0.f; }
-
+    RowState<NRB> st;
+    st.clear();
     char* ws = static_cast<char*>(a.workspace);
     float2* massml = reinterpret_cast<float2*>(ws + p.off_massml) + (int64_t)unit * p.slots * p.rows_wg;
-    auto emit = [&](int s) {                        // (running reference, segment sum) per row for segment s
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) {
-            float tot = seg_l[rb] + __shfl_xor(seg_l[rb], 16);
-            tot += __shfl_xor(tot, 32);
-            if (lg == 0) massml[(int64_t)(s + ss) * p.rows_wg + (wave * NRB + rb) * 16 + li] = make_float2(m_run[rb], tot);
-        }
-    };
 
-    // V staging offsets (row-major [token][256 bytes]; chunk c of row t at chunk c ^ 2*(t & 7)) and the
-    // transposing reads: lane 16*lg + s addresses row 4*lg + s/4 (+16), 8 bytes at channel 16*db + 4*(s&3)
+    // V staging offsets and the transposing reads: lane 16*lg + s addresses row 4*lg + s/4 (+16), 8 bytes at
+    // channel 16*db + 4*(s&3)
     const uint32_t vw_off = (uint32_t)vr * 256 + 16 * (vc ^ (2 * (vr & 7)));    // rows vr + 16*it keep (t & 7)
     const int tr_row = 4 * lg + (li >> 2);
     const uint32_t tr_base = (uint32_t)tr_row * 256 + 8 * (li & 3);
@@ -409,20 +600,7 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
 #pragma unroll
             for (int it = 0; it < kKItems; ++it) {
                 uint4 ra = r.ka[it], rb4 = r.kb[it];
-                if (cd.delta != 0) {
-                    uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb4.x, rb4.y, rb4.z, rb4.w};
-                    const float4* cs = reinterpret_cast<const float4*>(cs_lds[grp][cs_slot] + 8 * kj);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float4 w = cs[i];          // (cos, sin) of slices 8*kj + 2i, + 2i + 1
-                        const float a0 = Mma<DT>::lo(wa[i]), a1 = Mma<DT>::hi(wa[i]);
-                        const float b0 = Mma<DT>::lo(wb[i]), b1 = Mma<DT>::hi(wb[i]);
-                        wa[i] = Mma<DT>::pack(a0 * w.x - b0 * w.y, a1 * w.z - b1 * w.w);
-                        wb[i] = Mma<DT>::pack(a0 * w.y + b0 * w.x, a1 * w.w + b1 * w.z);
-                    }
-                    ra = make_uint4(wa[0], wa[1], wa[2], wa[3]);
-                    rb4 = make_uint4(wb[0], wb[1], wb[2], wb[3]);
-                }
+                if (cd.delta != 0) rotate_chunk_pair<DT>(ra, rb4, cs_lds[grp][cs_slot] + 8 * kj);
                 uint16_t* dst = k_lds + (kr + 32 * it) * kSK + 8 * kj;
                 *reinterpret_cast<uint4*>(dst) = ra;
                 *reinterpret_cast<uint4*>(dst + kHalf) = rb4;
@@ -438,86 +616,12 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
         __syncthreads();            // tile `cur` is staged; every wavefront is done with the other buffer
         if (!live || !has_rows) return;
         if (cd.seg != cur_seg) {
-            if (cur_seg >= 0) emit(cur_seg);
+            if (cur_seg >= 0) emit_segment<NRB>(st, massml, cur_seg + ss, p.rows_wg, wave * NRB, li, lg);
             cur_seg = cd.seg;
 #pragma unroll
-            for (int rb = 0; rb < NRB; ++rb) seg_l[rb] = 0.f;
+            for (int rb = 0; rb < NRB; ++rb) st.seg_l[rb] = 0.f;
         }
-        const bool causal = cd.self != 0;
-#pragma unroll
-        for (int h2 = 0; h2 < TILE / 32; ++h2) {
-            const int nt = cd.ntok - 32 * h2;      // valid tokens of this half
-            if (nt <= 0) break;
-            // ---- S^T = K Q^T : lane (li, lg) gets, for query row li, tokens 32*h2 + 16*tb + 4*lg + r
-            f32x4 sc[NRB][2];
-#pragma unroll
-            for (int rb = 0; rb < NRB; ++rb) { sc[rb][0] = f32x4{0.f, 0.f, 0.f, 0.f}; sc[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    const uint4 ka = *reinterpret_cast<const uint4*>(k_lds + (32 * h2 + 16 * tb + li) * kSK + 32 * kk + 8 * lg);
-#pragma unroll
-                    for (int rb = 0; rb < NRB; ++rb) sc[rb][tb] = Mma<DT>::run(ka, qf[rb][kk], sc[rb][tb]);
-                }
-            // ---- online softmax (exp2 domain), fp32, against a stale row maximum (see kRescaleSlack)
-            const bool need_mask = causal || nt < 32;
-            uint4 pfrag[NRB];
-#pragma unroll
-            for (int rb = 0; rb < NRB; ++rb) {
-                float xv[8];
-#pragma unroll
-                for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) xv[4 * tb + e] = sc[rb][tb][e];
-                if (need_mask) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int tk = 16 * (e >> 2) + 4 * lg + (e & 3);
-                        const bool ok = tk < nt && (!causal || cd.tok0 + 32 * h2 + tk <= trow[rb]);
-                        xv[e] = ok ? xv[e] : -INFINITY;
-                    }
-                }
-                float mloc = fmaxf(fmaxf(fmaxf(xv[0], xv[1]), fmaxf(xv[2], xv[3])), fmaxf(fmaxf(xv[4], xv[5]), fmaxf(xv[6], xv[7])));
-                mloc *= a.scale_log2e;                       // scale > 0: max commutes with it
-                if (__any(mloc > m_run[rb] + kRescaleSlack)) {
-                    mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-                    mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-                    const float m_old = m_run[rb];
-                    const float m_new = fmaxf(m_old, mloc);
-                    const float alpha = __builtin_amdgcn_exp2f(m_old - (m_new == -INFINITY ? 0.f : m_new));
-                    l_run[rb] *= alpha;
-                    seg_l[rb] *= alpha;
-                    m_run[rb] = m_new;
-                    if (__any(alpha != 1.f && m_old != -INFINITY)) {     // nothing accumulated yet: nothing to rescale
-#pragma unroll
-                        for (int db = 0; db < 8; ++db) acc[rb][db] *= alpha;
-                    }
-                }
-                const float m_safe = m_run[rb] == -INFINITY ? 0.f : m_run[rb];
-                float lsum = 0.f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    xv[e] = __builtin_amdgcn_exp2f(fmaf(xv[e], a.scale_log2e, -m_safe));
-                    lsum += xv[e];
-                }
-                l_run[rb] += lsum;
-                seg_l[rb] += lsum;
-                pfrag[rb] = make_uint4(Mma<DT>::pack(xv[0], xv[1]), Mma<DT>::pack(xv[2], xv[3]),
-                                       Mma<DT>::pack(xv[4], xv[5]), Mma<DT>::pack(xv[6], xv[7]));
-            }
-            // ---- O^T += V^T P^T; V^T fragments by transposing reads of the row-major tile
-#pragma unroll
-            for (int db = 0; db < 8; ++db) {
-                const unsigned char* src = v_lds + h2 * 32 * 256 + tr_base + ((uint32_t)(32 * db) ^ tr_x);
-                const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(src));
-                const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(src + 16 * 256));
-                const uint2 l2 = __builtin_bit_cast(uint2, lo), h2v = __builtin_bit_cast(uint2, hi);
-                const uint4 va = make_uint4(l2.x, l2.y, h2v.x, h2v.y);
-#pragma unroll
-                for (int rb = 0; rb < NRB; ++rb) acc[rb][db] = Mma<DT>::run(va, pfrag[rb], acc[rb][db]);
-            }
-        }
+        tile_math<DT, NRB, TILE>(cd, k_lds, v_lds, qf, trow, st, a.scale_log2e, li, lg, tr_base, tr_x);
     };
     // Steps come in pairs and the trip count is the workgroup's: every path round the loop issues the
     // same loads and meets the same barriers.  A group with fewer tiles runs steps without one.
@@ -525,12 +629,12 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
         step(d0, regs0, d1, 0);
         step(d1, regs1, d0, 1);
     }
-    if (cur_seg >= 0) emit(cur_seg);
+    if (cur_seg >= 0) emit_segment<NRB>(st, massml, cur_seg + ss, p.rows_wg, wave * NRB, li, lg);
 
     float l_row[NRB];                                // row sums (each lane holds those of its own tokens so far)
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
-        l_row[rb] = l_run[rb] + __shfl_xor(l_run[rb], 16);
+        l_row[rb] = st.l_run[rb] + __shfl_xor(st.l_run[rb], 16);
         l_row[rb] += __shfl_xor(l_row[rb], 32);
     }
     if (GROUPS == 2) {
@@ -541,33 +645,175 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
         __syncthreads();
         if (grp == 1) {
 #pragma unroll
-            for (int db = 0; db < 8; ++db) red[(wave * 8 + db) * kWave + lane] = acc[0][db];
-            if (lg == 0) red_ml[wave * 16 + li] = make_float2(m_run[0], l_row[0]);
+            for (int db = 0; db < 8; ++db) red[(wave * 8 + db) * kWave + lane] = st.acc[0][db];
+            if (lg == 0) red_ml[wave * 16 + li] = make_float2(st.m_run[0], l_row[0]);
         }
         __syncthreads();
         if (grp == 1) return;
         const float2 o = red_ml[wave * 16 + li];
-        const float m = fmaxf(m_run[0], o.x);
+        const float m = fmaxf(st.m_run[0], o.x);
         const float ms = m == -INFINITY ? 0.f : m;
-        const float f0 = __builtin_amdgcn_exp2f(m_run[0] - ms), f1 = __builtin_amdgcn_exp2f(o.x - ms);
+        const float f0 = __builtin_amdgcn_exp2f(st.m_run[0] - ms), f1 = __builtin_amdgcn_exp2f(o.x - ms);
 #pragma unroll
-        for (int db = 0; db < 8; ++db) acc[0][db] = acc[0][db] * f0 + red[(wave * 8 + db) * kWave + lane] * f1;
+        for (int db = 0; db < 8; ++db) st.acc[0][db] = st.acc[0][db] * f0 + red[(wave * 8 + db) * kWave + lane] * f1;
         l_row[0] = l_row[0] * f0 + o.y * f1;
-        m_run[0] = m;
+        st.m_run[0] = m;
+    }
+    // a wavefront whose rows are all padding leaves nothing
+    if (!has_rows) return;
+    store_partials<NRB>(a, p, unit, split, wave * NRB, st, l_row, lane);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The attention kernel for many stacked rows (GQA groups, long queries), where staging a tile costs
+// as much issue time as its math: eight wavefronts, of which the first kProducers only load, rotate
+// (Eq. 5) and stage tiles, and the others only do the math, two 16-row blocks each — so the rotation
+// and the LDS writes of tile j + 1 run beside the MFMAs and the softmax of tile j instead of before
+// them, and one staged tile serves 32*(8 - kProducers) rows.  One workgroup barrier per tile:
+//   producers:  B0; for j: { stage tile j into buffer j & 1; B }
+//   the others: B0; for j: { B; math of tile j }
+// so tile j is staged before the barrier that its math follows, and its buffer is written again (tile
+// j + 2) only after the next barrier, which the math of tile j precedes.  Both walk the same tile list.
+constexpr int kPcTile = 64;
+
+template <int DT, int kProducers>
+__global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a, RopeFreq freq, Plan p) {
+    constexpr int TILE = kPcTile, NRB = 2;
+    constexpr int kPT = kProducers * kWave;          // producer threads
+    constexpr int kKTile = TILE * kSK * 2, kVTile = TILE * kD * 2;
+    constexpr int kKItems = TILE * 8 / kPT;          // (row, chunk pair) items per producer thread
+    constexpr int kVItems = TILE * 16 / kPT;         // (row, chunk) items per producer thread
+    __shared__ SegTable tbl;
+    __shared__ __attribute__((aligned(16))) unsigned char k_buf[2][kKTile];
+    __shared__ __attribute__((aligned(16))) unsigned char v_buf[2][kVTile];
+    __shared__ __attribute__((aligned(16))) float2 cs_lds[2][kHalf];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int li = lane & 15, lg = lane >> 4;
+
+    const int bid = blockIdx.x;
+    const int rg = bid / p.x_count;
+    const int x = bid - rg * p.x_count;
+    const int split = x % p.nsplit;
+    const int hkv = (x / p.nsplit) % a.n_kv_heads;
+    const int b = __builtin_amdgcn_readfirstlane(x / (p.nsplit * a.n_kv_heads));
+    const int unit = (b * a.n_kv_heads + hkv) * p.n_rg + rg;
+    const int group = a.n_q_heads / a.n_kv_heads;
+    const QueryHead qh = load_query_head(a, b);
+    const int tq = min(qh.tq_raw, a.max_tq);
+    const int row_base = rg * p.blocks_rg * 16;
+    const int row_limit = min(group * tq, row_base + p.blocks_rg * 16);
+    const int cw = wave - kProducers;                // index among the wavefronts that do the math
+    const bool has_rows = cw >= 0 && row_base + cw * NRB * 16 < row_limit;       // wavefront-uniform
+    uint4 qf[NRB][4];
+    int trow[NRB];
+    if (cw >= 0) load_q_fragments<NRB>(a, qh.q0, tq, hkv, group, cw * NRB, row_base, row_limit, li, lg, qf, trow);
+    build_table(a, qh, &tbl, TILE);
+    const unsigned total = (unsigned)tbl.tile0[tbl.n];
+    const int t_begin = split_begin(total, (unsigned)p.nsplit, split), t_end = split_begin(total, (unsigned)p.nsplit, split + 1);
+    const int n_tiles = t_end - t_begin;
+
+    if (wave < kProducers) {
+        // ------------------------------------------------------------------ producers
+        const double my_freq = freq.rev[tid & (kHalf - 1)];
+        // staging items: K (row kr + (kPT/8)*it, chunks kj and kj + 8), V (row vr + (kPT/16)*it, chunk vc)
+        const int kr = tid >> 3, kj = tid & 7;
+        const int vr = tid >> 4, vc = tid & 15;
+        struct StageRegs { uint4 ka[kKItems], kb[kKItems], v[kVItems]; };
+        StageRegs regs0, regs1;
+        TileWalk<TILE> walk(t_begin, t_end);
+        auto fetch = [&](Tile& d, StageRegs& r) {    // a fixed number of loads, as in attn_tile_kernel
+            d = walk.next(tbl, lane);
+            const TileSource src = tile_source(a, d, walk.c_tok, hkv);
+#pragma unroll
+            for (int it = 0; it < kKItems; ++it) {
+                const uint32_t off = src.last < 0 ? 0u : (uint32_t)min(kr + (kPT / 8) * it, src.last) * src.row_bytes + 16 * kj;
+                r.ka[it] = *reinterpret_cast<const uint4*>(src.k + off);
+                r.kb[it] = *reinterpret_cast<const uint4*>(src.k + off + (src.last < 0 ? 0 : 128));
+            }
+#pragma unroll
+            for (int it = 0; it < kVItems; ++it) {
+                const uint32_t off = src.last < 0 ? 0u : (uint32_t)min(vr + (kPT / 16) * it, src.last) * src.row_bytes + 16 * vc;
+                r.v[it] = *reinterpret_cast<const uint4*>(src.v + off);
+            }
+        };
+        Tile d0, d1;
+        fetch(d0, regs0);
+        fetch(d1, regs1);
+        int cs_slot = 0;
+        if (d0.ntok > 0 && d0.delta != 0 && tid < kHalf) cs_lds[0][tid] = rope_cos_sin_fast(d0.delta, my_freq);
+        __syncthreads();                             // B0
+        auto stage = [&](Tile& cur, StageRegs& r, const Tile& nxt, int buf) {
+            const Tile cd = cur;
+            uint16_t* k_lds = reinterpret_cast<uint16_t*>(k_buf[buf]);
+            unsigned char* v_lds = v_buf[buf];
+            if (cd.ntok > 0) {
+#pragma unroll
+                for (int it = 0; it < kKItems; ++it) {
+                    uint4 ra = r.ka[it], rb4 = r.kb[it];
+                    if (cd.delta != 0) rotate_chunk_pair<DT>(ra, rb4, cs_lds[cs_slot] + 8 * kj);
+                    uint16_t* dst = k_lds + (kr + (kPT / 8) * it) * kSK + 8 * kj;
+                    *reinterpret_cast<uint4*>(dst) = ra;
+                    *reinterpret_cast<uint4*>(dst + kHalf) = rb4;
+                }
+#pragma unroll
+                for (int it = 0; it < kVItems; ++it) {
+                    const int t = vr + (kPT / 16) * it;
+                    *reinterpret_cast<uint4*>(v_lds + t * 256 + 16 * (vc ^ (2 * (t & 7)))) = r.v[it];
+                }
+            }
+            fetch(cur, r);
+            if (nxt.ntok > 0 && nxt.seg != cd.seg && nxt.delta != 0) {
+                cs_slot ^= 1;
+                if (tid < kHalf) cs_lds[cs_slot][tid] = rope_cos_sin_fast(nxt.delta, my_freq);
+            }
+            __syncthreads();
+        };
+        for (int it = 0; it < n_tiles; it += 2) {
+            stage(d0, regs0, d1, 0);
+            stage(d1, regs1, d0, 1);
+        }
+        return;
     }
 
-    // ---- partial results of this split: O^T in MFMA layout (one float4 per lane, row block and
-    // channel block) and (reference, sum) per row; a wavefront whose rows are all padding leaves nothing
+    // ---------------------------------------------------------------------- the others: math
+    TileWalk<TILE> walk(t_begin, t_end);
+    RowState<NRB> st;
+    st.clear();
+    float2* massml = reinterpret_cast<float2*>(static_cast<char*>(a.workspace) + p.off_massml) + (int64_t)unit * p.slots * p.rows_wg;
+    const int tr_row = 4 * lg + (li >> 2);
+    const uint32_t tr_base = (uint32_t)tr_row * 256 + 8 * (li & 3);
+    const uint32_t tr_x = (uint32_t)(tr_row & 7) * 32;
+    int cur_seg = -1;
+    __syncthreads();                                 // B0
+    auto math = [&](int buf) {
+        __syncthreads();                             // the tile is staged
+        const Tile cd = walk.next(tbl, lane);
+        if (cd.ntok <= 0 || !has_rows) return;
+        if (cd.seg != cur_seg) {
+            if (cur_seg >= 0) emit_segment<NRB>(st, massml, cur_seg + split, p.rows_wg, cw * NRB, li, lg);
+            cur_seg = cd.seg;
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb) st.seg_l[rb] = 0.f;
+        }
+        tile_math<DT, NRB, TILE>(cd, reinterpret_cast<const uint16_t*>(k_buf[buf]), v_buf[buf], qf, trow, st, a.scale_log2e,
+                                 li, lg, tr_base, tr_x);
+    };
+    for (int it = 0; it < n_tiles; it += 2) {
+        math(0);
+        math(1);
+    }
     if (!has_rows) return;
-    f32x4* opart = reinterpret_cast<f32x4*>(ws + p.off_opart) +
-                   (((int64_t)unit * p.nsplit + split) * p.rows_wg / 16 + wave * NRB) * 8 * kWave + lane;
-    float2* ml = reinterpret_cast<float2*>(ws + p.off_ml) + ((int64_t)unit * p.nsplit + split) * p.rows_wg;
+    if (cur_seg >= 0) emit_segment<NRB>(st, massml, cur_seg + split, p.rows_wg, cw * NRB, li, lg);
+    float l_row[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
-#pragma unroll
-        for (int db = 0; db < 8; ++db) opart[(rb * 8 + db) * kWave] = acc[rb][db];
-        if (lg == 0) ml[(wave * NRB + rb) * 16 + li] = make_float2(m_run[rb], l_row[rb]);
+        l_row[rb] = st.l_run[rb] + __shfl_xor(st.l_run[rb], 16);
+        l_row[rb] += __shfl_xor(l_row[rb], 32);
     }
+    store_partials<NRB>(a, p, unit, split, cw * NRB, st, l_row, lane);
 }
 
 // Second kernel: one workgroup per (unit, 64-row pass, eighth of the output channels) merges the
@@ -871,22 +1117,17 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
     const Plan p = make_plan(a.n_q_heads, a.n_kv_heads, a.batch, a.max_tq, a.seg_stride, a.max_kv_tokens);
     const dim3 grid((unsigned)(p.x_count * p.n_rg)), block(kThreads);
     const dim3 grid2((unsigned)(p.units * p.nrb * 8)), grid3((unsigned)a.batch);
-#define CF_LAUNCH(DT, N)                                                                             \
-    do {                                                                                             \
-        if (p.groups == 2) hipLaunchKernelGGL((attn_tile_kernel<DT, 1, 32, 2>), grid, dim3(2 * kThreads), 0, s, a, f, p); \
-        else if (p.tile == 32) hipLaunchKernelGGL((attn_tile_kernel<DT, N, 32, 1>), grid, block, 0, s, a, f, p); \
-        else hipLaunchKernelGGL((attn_tile_kernel<DT, N, 64, 1>), grid, block, 0, s, a, f, p);       \
-    } while (0)
-#define CF_LAUNCH_DT(DT)                                   \
-    if (phases & 1) switch (p.nrb) {                       \
-        case 1: CF_LAUNCH(DT, 1); break;                   \
-        default: CF_LAUNCH(DT, 2); break;                  \
-    }                                                      \
-    CF_HIP(hipGetLastError());                             \
+#define CF_LAUNCH_DT(DT)                                                                                                       \
+    if (!(phases & 1)) {                                                                                                       \
+    } else if (p.producers == 0) {                                                                                             \
+        hipLaunchKernelGGL((attn_tile_kernel<DT, 1, 32, 2>), grid, dim3(2 * kThreads), 0, s, a, f, p);                         \
+    } else {                                                                                                                   \
+        hipLaunchKernelGGL((attn_pc_kernel<DT, kPcProducers>), grid, dim3(kPcWaves * kWave), 0, s, a, f, p);                   \
+    }                                                                                                                          \
+    CF_HIP(hipGetLastError());                                                                                                 \
     if (phases & 2) hipLaunchKernelGGL((attn_combine_kernel<DT>), grid2, block, 0, s, a, p);
     if (a.dtype == CF_BF16) { CF_LAUNCH_DT(CF_BF16) } else { CF_LAUNCH_DT(CF_F16) }
 #undef CF_LAUNCH_DT
-#undef CF_LAUNCH
     CF_HIP(hipGetLastError());
     if (prune) {
         PruneArgs pr;
