@@ -33,7 +33,7 @@ constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr int kD = 128;
 constexpr int kHalf = 64;
-constexpr int kSK = 136;        // LDS row stride of the staged K tile, elements (272 B)
+constexpr int kKRow = 272;      // bytes per token of a staged K tile
 constexpr int kMaxSegs = 256;
 constexpr int kMaxSplit = 32;
 
@@ -88,12 +88,13 @@ Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_str
     p.units_per_b = n_kv_heads * p.n_rg;
     p.units = batch * p.units_per_b;
     const int64_t est_tiles = max_kv_tokens / p.tile + seg_stride;
-    int64_t ns = (256 + p.units - 1) / p.units;         // one workgroup per CU and launch wave
+    // One workgroup per CU and launch wave.  A CU holds one attn_pc_kernel workgroup at a time, so there the
+    // count stays within the 256 CUs; two of the small kernel's fit, and a few more than 256 do no harm.
+    int64_t ns = p.producers ? 256 / p.units : (256 + p.units - 1) / p.units;
     const int64_t cap = est_tiles / (2 * p.groups) > 1 ? est_tiles / (2 * p.groups) : 1;
     if (ns > cap) ns = cap;
     if (ns > kMaxSplit) ns = kMaxSplit;
     if (ns < 1) ns = 1;
-    if (ns > kMaxSplit) ns = kMaxSplit;
     p.nsplit = (int)ns;
     p.slots = seg_stride + p.nsplit * p.groups;
     p.x_count = batch * n_kv_heads * p.nsplit;
@@ -212,7 +213,10 @@ template <> struct Mma<CF_F16> {
     }
 };
 
-constexpr float kRescaleSlack = 8.f;                   // log2 of the largest probability kept relative to the running reference
+// The softmax reference of a row is a stale maximum: it only moves when the eight probabilities a lane
+// has just formed against it add up to more than this (so none of them is larger), which is rare after a
+// row's first tiles; the common path has no maximum and no cross-lane exchange.
+constexpr float kProbLimit = 256.f;
 
 typedef short short4v __attribute__((ext_vector_type(4)));
 
@@ -309,6 +313,18 @@ __device__ __forceinline__ void rotate_chunk_pair(uint4& ra, uint4& rb4, const f
     rb4 = make_uint4(wb[0], wb[1], wb[2], wb[3]);
 }
 
+// Staged K tile: [token][kKRow bytes], 128 channels and 16 bytes of padding per token, so that the
+// fragment reads of the 16 lanes that share a channel group fall into different banks.  (Measured on this part: a
+// 16-byte LDS read runs at half the byte rate of an 8-byte one, but splitting the fragment into two 8-byte reads,
+// in either a two-plane or an in-row layout, made the kernels slower, not faster.)
+__device__ __forceinline__ void k_tile_write(unsigned char* k_lds, int t, int j, uint4 v) {
+    *reinterpret_cast<uint4*>(k_lds + t * kKRow + 16 * j) = v;
+}
+// the MFMA operand of a lane for token t, channels 8*slot .. 8*slot + 7
+__device__ __forceinline__ uint4 k_tile_fragment(const unsigned char* k_lds, int t, int slot) {
+    return *reinterpret_cast<const uint4*>(k_lds + t * kKRow + 16 * slot);
+}
+
 // Running state of a wavefront's NRB 16-row blocks: lane (li, lg) holds, for query row li of each
 // block, the output channels 16*db + 4*lg + r, the reference maximum, and the sums of exp2 over the
 // tokens this lane has seen (whole call and current segment).
@@ -328,11 +344,11 @@ struct RowState {
 
 // The math of one staged tile for one wavefront: S^T = K Q^T from LDS key fragments and the register-resident
 // Q fragments, online softmax against a stale maximum, O^T += V^T P^T with V^T fragments from
-// transposing LDS reads.  K tile: [token][kSK] elements; V tile: row-major [token][256 bytes], chunk c of
+// transposing LDS reads.  K tile: see k_tile_write; V tile: row-major [token][256 bytes], chunk c of
 // row t at chunk c ^ 2*(t & 7).  `trow`: query position of the lane's row inside the own block
 // (causal mask), `tr_base`/`tr_x`: the lane's transposing-read offsets.
 template <int DT, int NRB, int TILE>
-__device__ __forceinline__ void tile_math(const Tile& cd, const uint16_t* k_lds, const unsigned char* v_lds,
+__device__ __forceinline__ void tile_math(const Tile& cd, const unsigned char* k_lds, const unsigned char* v_lds,
                                           const uint4 (&qf)[NRB][4], const int (&trow)[NRB], RowState<NRB>& st,
                                           float scale_log2e, int li, int lg, uint32_t tr_base, uint32_t tr_x) {
     const bool causal = cd.self != 0;
@@ -349,7 +365,7 @@ __device__ __forceinline__ void tile_math(const Tile& cd, const uint16_t* k_lds,
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
-                kf[tb][kk] = *reinterpret_cast<const uint4*>(k_lds + (32 * h2 + 16 * tb + li) * kSK + 32 * kk + 8 * lg);
+                kf[tb][kk] = k_tile_fragment(k_lds, 32 * h2 + 16 * tb + li, 4 * kk + lg);
         __builtin_amdgcn_sched_barrier(0);       // all eight reads are out before the first MFMA waits
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
@@ -366,7 +382,7 @@ __device__ __forceinline__ void tile_math(const Tile& cd, const uint16_t* k_lds,
             vhi[db] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)(src + 16 * 256));
         }
         __builtin_amdgcn_sched_barrier(0);
-        // ---- online softmax (exp2 domain), fp32, against a stale row maximum (see kRescaleSlack)
+        // ---- online softmax (exp2 domain), fp32, against a stale row maximum (see kProbLimit)
         const bool need_mask = causal || nt < 32;
         uint4 pfrag[NRB];
 #pragma unroll
@@ -384,9 +400,24 @@ __device__ __forceinline__ void tile_math(const Tile& cd, const uint16_t* k_lds,
                     xv[e] = ok ? xv[e] : -INFINITY;
                 }
             }
-            float mloc = fmaxf(fmaxf(fmaxf(xv[0], xv[1]), fmaxf(xv[2], xv[3])), fmaxf(fmaxf(xv[4], xv[5]), fmaxf(xv[6], xv[7])));
-            mloc *= scale_log2e;                         // scale > 0: max commutes with it
-            if (__any(mloc > st.m_run[rb] + kRescaleSlack)) {
+            // Probabilities against the reference as it stands; their sum tells whether one of them left the
+            // range the reference allows (or no reference exists yet) — only then is the maximum worked out,
+            // the reference moved, everything accumulated so far rescaled, and the probabilities redone.
+            float pv[8];
+            float lsum = 0.f;
+            auto probabilities = [&](float m_ref) {
+                const float m_safe = m_ref == -INFINITY ? 0.f : m_ref;
+                lsum = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    pv[e] = __builtin_amdgcn_exp2f(fmaf(xv[e], scale_log2e, -m_safe));
+                    lsum += pv[e];
+                }
+            };
+            probabilities(st.m_run[rb]);
+            if (__any(!(lsum <= kProbLimit) || st.m_run[rb] == -INFINITY)) {
+                float mloc = fmaxf(fmaxf(fmaxf(xv[0], xv[1]), fmaxf(xv[2], xv[3])), fmaxf(fmaxf(xv[4], xv[5]), fmaxf(xv[6], xv[7])));
+                mloc *= scale_log2e;                     // scale > 0: max commutes with it
                 mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
                 mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
                 const float m_old = st.m_run[rb];
@@ -399,14 +430,10 @@ __device__ __forceinline__ void tile_math(const Tile& cd, const uint16_t* k_lds,
 #pragma unroll
                     for (int db = 0; db < 8; ++db) st.acc[rb][db] *= alpha;
                 }
+                probabilities(m_new);
             }
-            const float m_safe = st.m_run[rb] == -INFINITY ? 0.f : st.m_run[rb];
-            float lsum = 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                xv[e] = __builtin_amdgcn_exp2f(fmaf(xv[e], scale_log2e, -m_safe));
-                lsum += xv[e];
-            }
+            for (int e = 0; e < 8; ++e) xv[e] = pv[e];
             st.l_run[rb] += lsum;
             st.seg_l[rb] += lsum;
             pfrag[rb] = make_uint4(Mma<DT>::pack(xv[0], xv[1]), Mma<DT>::pack(xv[2], xv[3]),
@@ -487,7 +514,7 @@ __device__ __forceinline__ void store_partials(const AttnArgs& a, const Plan& p,
 template <int DT, int NRB, int TILE, int GROUPS>
 __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArgs a, RopeFreq freq, Plan p) {
     static_assert(GROUPS == 1 || (GROUPS == 2 && NRB == 1 && TILE == 32), "two groups: one row block per wavefront, 32-token tiles");
-    constexpr int kKTile = TILE * kSK * 2;           // bytes, padded rows
+    constexpr int kKTile = TILE * kKRow;             // bytes
     constexpr int kVTile = TILE * kD * 2;
     constexpr int kKItems = TILE / 32;               // (row, chunk pair) items per thread
     constexpr int kVItems = TILE / 16;               // (row, chunk) items per thread
@@ -594,16 +621,15 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
     auto step = [&](Tile& cur, StageRegs& r, const Tile& nxt, int buf) {
         const Tile cd = cur;
         const bool live = cd.ntok > 0;
-        uint16_t* k_lds = reinterpret_cast<uint16_t*>(k_buf[grp][buf]);
+        unsigned char* k_lds = k_buf[grp][buf];
         unsigned char* v_lds = v_buf[grp][buf];
         if (live) {
 #pragma unroll
             for (int it = 0; it < kKItems; ++it) {
                 uint4 ra = r.ka[it], rb4 = r.kb[it];
                 if (cd.delta != 0) rotate_chunk_pair<DT>(ra, rb4, cs_lds[grp][cs_slot] + 8 * kj);
-                uint16_t* dst = k_lds + (kr + 32 * it) * kSK + 8 * kj;
-                *reinterpret_cast<uint4*>(dst) = ra;
-                *reinterpret_cast<uint4*>(dst + kHalf) = rb4;
+                k_tile_write(k_lds, kr + 32 * it, kj, ra);
+                k_tile_write(k_lds, kr + 32 * it, kj + 8, rb4);
             }
 #pragma unroll
             for (int it = 0; it < kVItems; ++it) *reinterpret_cast<uint4*>(v_lds + it * 16 * 256 + vw_off) = r.v[it];
@@ -680,7 +706,7 @@ template <int DT, int kProducers>
 __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a, RopeFreq freq, Plan p) {
     constexpr int TILE = kPcTile, NRB = 2;
     constexpr int kPT = kProducers * kWave;          // producer threads
-    constexpr int kKTile = TILE * kSK * 2, kVTile = TILE * kD * 2;
+    constexpr int kKTile = TILE * kKRow, kVTile = TILE * kD * 2;
     constexpr int kKItems = TILE * 8 / kPT;          // (row, chunk pair) items per producer thread
     constexpr int kVItems = TILE * 16 / kPT;         // (row, chunk) items per producer thread
     __shared__ SegTable tbl;
@@ -747,16 +773,15 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
         __syncthreads();                             // B0
         auto stage = [&](Tile& cur, StageRegs& r, const Tile& nxt, int buf) {
             const Tile cd = cur;
-            uint16_t* k_lds = reinterpret_cast<uint16_t*>(k_buf[buf]);
+            unsigned char* k_lds = k_buf[buf];
             unsigned char* v_lds = v_buf[buf];
             if (cd.ntok > 0) {
 #pragma unroll
                 for (int it = 0; it < kKItems; ++it) {
                     uint4 ra = r.ka[it], rb4 = r.kb[it];
                     if (cd.delta != 0) rotate_chunk_pair<DT>(ra, rb4, cs_lds[cs_slot] + 8 * kj);
-                    uint16_t* dst = k_lds + (kr + (kPT / 8) * it) * kSK + 8 * kj;
-                    *reinterpret_cast<uint4*>(dst) = ra;
-                    *reinterpret_cast<uint4*>(dst + kHalf) = rb4;
+                    k_tile_write(k_lds, kr + (kPT / 8) * it, kj, ra);
+                    k_tile_write(k_lds, kr + (kPT / 8) * it, kj + 8, rb4);
                 }
 #pragma unroll
                 for (int it = 0; it < kVItems; ++it) {
@@ -798,8 +823,7 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
 #pragma unroll
             for (int rb = 0; rb < NRB; ++rb) st.seg_l[rb] = 0.f;
         }
-        tile_math<DT, NRB, TILE>(cd, reinterpret_cast<const uint16_t*>(k_buf[buf]), v_buf[buf], qf, trow, st, a.scale_log2e,
-                                 li, lg, tr_base, tr_x);
+        tile_math<DT, NRB, TILE>(cd, k_buf[buf], v_buf[buf], qf, trow, st, a.scale_log2e, li, lg, tr_base, tr_x);
     };
     for (int it = 0; it < n_tiles; it += 2) {
         math(0);
