@@ -30,6 +30,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2500.0      # dense bf16 / fp16
 # HBM bytes per launch of the dominant kernel on this workload, from the FETCH_SIZE and WRITE_SIZE counter runs
 # summarised in profiles/attn_tile_kernel_llama2_7b_layer.md (scaled by a 1 GiB copy kernel: x2.000 and x1.000)
 TRAFFIC_BYTES_PER_LAUNCH = 30_897_300 + 6_660_096
@@ -207,6 +208,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--layers", type=int, default=24, help="distinct layer buffers cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", choices=[WORKLOAD, "qwen2_7b_layer", "qwen2_1p5b_batch"], default=WORKLOAD,
+                    help="the headline workload (default), or one of the GQA configurations, whose attention kernel is "
+                         "priced against the MFMA peak instead of HBM bandwidth")
     ap.add_argument("--store-layout", choices=["head", "token"], default="head",
                     help="layout of the cache store: head-major [kv head][token][d] (default, the layout the "
                          "store is meant to be kept in) or token-major [token][kv head][d]")
@@ -245,8 +249,10 @@ def main() -> int:
     if args.path in ("assemble", "decode"):
         return bench_assemble(args)
 
-    cfg = wl.CONFIGS[WORKLOAD]
+    cfg = wl.CONFIGS[args.workload]
     g = cfg.geometry
+    if args.workload == "qwen2_1p5b_batch":
+        args.layers = min(args.layers, 2)             # 1.5 GB of store per layer copy
     st = wl.build_structure(cfg)
     ts, hs = pl.store_strides(st.n_store_tokens, g.n_kv_heads, g.head_dim, args.store_layout)
     desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions,
@@ -305,6 +311,20 @@ def main() -> int:
     kernel_ms = timed_attention(1)
     attn_ms = timed_attention(7)
     achieved = kv_tokens * bytes_per_token / (kernel_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                "kernel": "attn_tile_kernel<bf16,1,32,2> (first kernel of cf_prefill_layer / cf_prefill_attention)",
+                "ms_per_launch": kernel_ms, "algorithmic_bytes_per_launch": kv_tokens * bytes_per_token,
+                "ms_per_call_all_kernels": attn_ms}
+    if args.workload != WORKLOAD:
+        # GQA shapes: a dense contraction, 4 * Tq * d * Hq flops per attended token (S = Q K^T and O = P V)
+        flops = kv_tokens * 4.0 * cfg.tq * g.head_dim * g.n_q_heads
+        tflops = flops / (kernel_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": tflops / MFMA_PEAK_TFLOPS, "traffic": None,
+                    "kernel": f"attn_pc_kernel<{g.dtype},2> (first kernel of cf_prefill_layer / cf_prefill_attention)",
+                    "ms_per_launch": kernel_ms, "algorithmic_flops_per_launch": flops,
+                    "algorithmic_bytes_per_launch": kv_tokens * bytes_per_token, "ms_per_call_all_kernels": attn_ms}
 
     result = {
         "metric": "KV tokens/s per layer, re-positioned cached-KV prefill",
@@ -319,16 +339,12 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": g.dtype,
         "data": "synthetic",
-        "config": {"workload": WORKLOAD, "batch": cfg.batch, "kv_tokens_per_step": kv_tokens,
+        "config": {"workload": args.workload, "batch": cfg.batch, "kv_tokens_per_step": kv_tokens,
                    "q_heads": g.n_q_heads, "kv_heads": g.n_kv_heads, "head_dim": g.head_dim, "tq": cfg.tq,
                    "docs": cfg.docs_per_query, "keep": cfg.keep, "layer_buffers": len(layers),
                    "store_layout": args.store_layout,
                    "step": "cf_prefill_layer: attention + mass + prune_topk + assign_positions + gather_segments"},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
-                     "kernel": "attn_tile_kernel<bf16,1,32,2> (first kernel of cf_prefill_layer / cf_prefill_attention)",
-                     "ms_per_launch": kernel_ms, "algorithmic_bytes_per_launch": kv_tokens * bytes_per_token,
-                     "ms_per_call_all_kernels": attn_ms},
+        "roofline": roofline,
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, st)

@@ -325,6 +325,8 @@ def test_qwen2_1p5b_batch_reduced():
     (8, 2, 5, 1, (33, 33), 7),         # one document, ragged everything
     (6, 2, 17, 9, (1, 40), 3),         # stacked rows straddle the 64-row tile
     (2, 2, 70, 4, (90, 130), 16),      # more rows than one tile in MHA
+    (14, 2, 13, 6, (1, 150), 5),       # GQA, six row blocks: the producer/consumer kernel with idle math wavefronts
+    (12, 2, 40, 5, (20, 90), 0),       # GQA, fifteen row blocks: two row groups of unequal size, no prefix
 ])
 def test_mfma_path_edge_shapes(dtype, layout, hq, hkv, tq, docs, len_range, prefix):
     cfg = wl.scaled(wl.CONFIGS["tiny_f32"], name=f"edge_{dtype}_{hq}_{hkv}_{tq}",
