@@ -1,13 +1,16 @@
 // 16-bit MFMA prefill attention for gfx950 (head_dim 128, half-split RoPE pairing).
 //
 // Work decomposition.  The query rows that share a kv head (all rows of the G = Hq/Hkv heads of
-// the group, stacked: row m = g*tq + t) are cut into 16-row blocks.  A workgroup of 4 wavefronts
-// owns up to 4*NRB such blocks (NRB = 1 or 2) of one (query, kv head) — wavefront w the blocks [w*NRB, (w+1)*NRB)
-// — and a contiguous run of the attended tokens.  Tokens are counted in tiles (32 tokens when the
-// stacked rows fit one workgroup pass of 64 — MHA, short queries: HBM-bound —, else 64) that never
-// straddle a segment; the tile list of a (query, kv head) is divided evenly over `nsplit`
-// workgroups.  Per tile:
-//   * all 256 threads fetch the tile two ahead with coalesced 16-byte loads into registers,
+// the group, stacked: row m = g*tq + t) are cut into 16-row blocks; a workgroup owns a run of such blocks of one
+// (query, kv head) and a contiguous run of the attended tokens.  Tokens are counted in tiles that never
+// straddle a segment; the tile list of a (query, kv head) is divided evenly over `nsplit` workgroups.
+//   * At most 4 row blocks (MHA, short queries: HBM- and latency-bound): attn_tile_kernel, 32-token tiles,
+//     one row block per wavefront, every wavefront loads, stages and computes; two groups of four wavefronts
+//     per workgroup stream disjoint runs of tiles.
+//   * More (GQA groups, long queries: MFMA-bound): attn_pc_kernel, 64-token tiles, two wavefronts load, rotate
+//     and stage while six do the math of the previous tile, two row blocks each (up to 192 rows per workgroup).
+// Per tile, in both:
+//   * the tile two ahead is in flight in registers (coalesced 16-byte loads),
 //   * the key tile is rotated in registers by its segment's relative position shift (Eq. 5;
 //     cos/sin per 2-D slice from an fp64-reduced angle), rounded once to the storage type and
 //     staged into LDS — rotated keys never return to memory; V is staged as loaded,
