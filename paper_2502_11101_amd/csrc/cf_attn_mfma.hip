@@ -62,6 +62,7 @@ struct Plan {
 
 constexpr int kPcWaves = 8;         // wavefronts of an attn_pc_kernel workgroup
 constexpr int kPcProducers = 2;     // of which load and stage
+constexpr int kPcNrb = 2;           // 16-row blocks per math wavefront
 
 Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_stride, int64_t max_kv_tokens) {
     Plan p;
@@ -79,7 +80,7 @@ Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int seg_str
         p.groups = 2;
     } else {
         // Many rows (GQA, long queries): 64-token tiles, two row blocks per math wavefront.
-        const int blocks_wg = 2 * (kPcWaves - kPcProducers);
+        const int blocks_wg = kPcNrb * (kPcWaves - kPcProducers);
         p.producers = kPcProducers;
         p.n_rg = (row_blocks + blocks_wg - 1) / blocks_wg;
         p.nrb = blocks_wg / 4;
@@ -298,12 +299,23 @@ __device__ __forceinline__ TileSource tile_source(const AttnArgs& a, const Tile&
     return t;
 }
 
-// Rotates the pair of 16-byte key chunks (channels c..c+7 and c+64..c+71) by the angles whose
-// (cos, sin) pairs start at `cs` (Eq. 5), in fp32, and rounds once to the storage type.
+// The (cos, sin) pairs of a thread's eight 2-D slices (chunk kj: slices 8*kj .. 8*kj + 7), two pairs per
+// float4, read from the segment's LDS table once per tile.
+struct ChunkAngles { float4 cs[4]; };
+__device__ __forceinline__ ChunkAngles load_chunk_angles(const float2* cs8) {
+    ChunkAngles c;
+    const float4* p = reinterpret_cast<const float4*>(cs8);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) c.cs[i] = p[i];
+    return c;
+}
+
+// Rotates the pair of 16-byte key chunks (channels c..c+7 and c+64..c+71) by the chunk's angles (Eq. 5),
+// in fp32, and rounds once to the storage type.
 template <int DT>
-__device__ __forceinline__ void rotate_chunk_pair(uint4& ra, uint4& rb4, const float2* cs8) {
+__device__ __forceinline__ void rotate_chunk_pair(uint4& ra, uint4& rb4, const ChunkAngles& ang) {
     uint32_t wa[4] = {ra.x, ra.y, ra.z, ra.w}, wb[4] = {rb4.x, rb4.y, rb4.z, rb4.w};
-    const float4* cs = reinterpret_cast<const float4*>(cs8);
+    const float4 (&cs)[4] = ang.cs;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const float4 w = cs[i];          // (cos, sin) of slices 2i, 2i + 1 of the chunk
@@ -355,12 +367,8 @@ __device__ __forceinline__ void tile_math(const Tile& cd, const unsigned char* k
                                           const uint4 (&qf)[NRB][4], const int (&trow)[NRB], RowState<NRB>& st,
                                           float scale_log2e, int li, int lg, uint32_t tr_base, uint32_t tr_x) {
     const bool causal = cd.self != 0;
-#pragma unroll
-    for (int h2 = 0; h2 < TILE / 32; ++h2) {
-        const int nt = cd.ntok - 32 * h2;      // valid tokens of this half
-        if (nt <= 0) break;
-        // ---- S^T = K Q^T : lane (li, lg) gets, for query row li, tokens 32*h2 + 16*tb + 4*lg + r
-        f32x4 sc[NRB][2];
+    // ---- S^T = K Q^T of 32-token half h2: lane (li, lg) gets, for query row li, tokens 32*h2 + 16*tb + 4*lg + r
+    auto scores = [&](int h2, f32x4 (&sc)[NRB][2]) {
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) { sc[rb][0] = f32x4{0.f, 0.f, 0.f, 0.f}; sc[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
         uint4 kf[2][4];
@@ -376,6 +384,10 @@ __device__ __forceinline__ void tile_math(const Tile& cd, const unsigned char* k
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
                 for (int rb = 0; rb < NRB; ++rb) sc[rb][tb] = Mma<DT>::run(kf[tb][kk], qf[rb][kk], sc[rb][tb]);
+    };
+    // ---- softmax of half h2 and O^T += V^T P^T
+    auto weigh = [&](int h2, f32x4 (&sc)[NRB][2]) {
+        const int nt = cd.ntok - 32 * h2;      // valid tokens of this half
         // V^T fragments, requested before the softmax arithmetic that hides their latency
         short4v vlo[8], vhi[8];
 #pragma unroll
@@ -450,6 +462,19 @@ __device__ __forceinline__ void tile_math(const Tile& cd, const unsigned char* k
 #pragma unroll
             for (int rb = 0; rb < NRB; ++rb) st.acc[rb][db] = Mma<DT>::run(va, pfrag[rb], st.acc[rb][db]);
         }
+    };
+    // The scores of the second half are requested before the first half is weighed: their MFMAs run
+    // beside the first half's softmax arithmetic.  A ragged tile of at most 32 tokens has no second half.
+    f32x4 sc0[NRB][2];
+    scores(0, sc0);
+    if (TILE == 64) {
+        f32x4 sc1[NRB][2];
+        const bool two = cd.ntok > 32;
+        if (two) scores(1, sc1);
+        weigh(0, sc0);
+        if (two) weigh(1, sc1);
+    } else {
+        weigh(0, sc0);
     }
 }
 
@@ -627,10 +652,12 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
         unsigned char* k_lds = k_buf[grp][buf];
         unsigned char* v_lds = v_buf[grp][buf];
         if (live) {
+            ChunkAngles ang;
+            if (cd.delta != 0) ang = load_chunk_angles(cs_lds[grp][cs_slot] + 8 * kj);
 #pragma unroll
             for (int it = 0; it < kKItems; ++it) {
                 uint4 ra = r.ka[it], rb4 = r.kb[it];
-                if (cd.delta != 0) rotate_chunk_pair<DT>(ra, rb4, cs_lds[grp][cs_slot] + 8 * kj);
+                if (cd.delta != 0) rotate_chunk_pair<DT>(ra, rb4, ang);
                 k_tile_write(k_lds, kr + 32 * it, kj, ra);
                 k_tile_write(k_lds, kr + 32 * it, kj + 8, rb4);
             }
@@ -702,12 +729,13 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
 //   producers:  B0; for j: { stage tile j into buffer j & 1; B }
 //   the others: B0; for j: { B; math of tile j }
 // so tile j is staged before the barrier that its math follows, and its buffer is written again (tile
-// j + 2) only after the next barrier, which the math of tile j precedes.  Both walk the same tile list.
+// j + 2) only after the next barrier, which the math of tile j precedes.  Only the producers walk the segment
+// table; the others take each tile's description from a small ring in LDS.
 constexpr int kPcTile = 64;
 
 template <int DT, int kProducers>
 __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a, RopeFreq freq, Plan p) {
-    constexpr int TILE = kPcTile, NRB = 2;
+    constexpr int TILE = kPcTile, NRB = kPcNrb;
     constexpr int kPT = kProducers * kWave;          // producer threads
     constexpr int kKTile = TILE * kKRow, kVTile = TILE * kD * 2;
     constexpr int kKItems = TILE * 8 / kPT;          // (row, chunk pair) items per producer thread
@@ -716,6 +744,9 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
     __shared__ __attribute__((aligned(16))) unsigned char k_buf[2][kKTile];
     __shared__ __attribute__((aligned(16))) unsigned char v_buf[2][kVTile];
     __shared__ __attribute__((aligned(16))) float2 cs_lds[2][kHalf];
+    // (segment, first token, tokens, own block) of tile j in entry j & 3, written by the producers when they
+    // fetch the tile, two steps before its math: the math wavefronts do not walk the table themselves
+    __shared__ int4 tile_ring[4];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -753,8 +784,11 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
         struct StageRegs { uint4 ka[kKItems], kb[kKItems], v[kVItems]; };
         StageRegs regs0, regs1;
         TileWalk<TILE> walk(t_begin, t_end);
+        int n_fetched = 0;
         auto fetch = [&](Tile& d, StageRegs& r) {    // a fixed number of loads, as in attn_tile_kernel
             d = walk.next(tbl, lane);
+            if (tid == 0) tile_ring[n_fetched & 3] = make_int4(d.seg, d.tok0, d.ntok, d.self);
+            ++n_fetched;
             const TileSource src = tile_source(a, d, walk.c_tok, hkv);
 #pragma unroll
             for (int it = 0; it < kKItems; ++it) {
@@ -779,10 +813,12 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
             unsigned char* k_lds = k_buf[buf];
             unsigned char* v_lds = v_buf[buf];
             if (cd.ntok > 0) {
+                ChunkAngles ang;
+                if (cd.delta != 0) ang = load_chunk_angles(cs_lds[cs_slot] + 8 * kj);
 #pragma unroll
                 for (int it = 0; it < kKItems; ++it) {
                     uint4 ra = r.ka[it], rb4 = r.kb[it];
-                    if (cd.delta != 0) rotate_chunk_pair<DT>(ra, rb4, cs_lds[cs_slot] + 8 * kj);
+                    if (cd.delta != 0) rotate_chunk_pair<DT>(ra, rb4, ang);
                     k_tile_write(k_lds, kr + (kPT / 8) * it, kj, ra);
                     k_tile_write(k_lds, kr + (kPT / 8) * it, kj + 8, rb4);
                 }
@@ -807,7 +843,6 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
     }
 
     // ---------------------------------------------------------------------- the others: math
-    TileWalk<TILE> walk(t_begin, t_end);
     RowState<NRB> st;
     st.clear();
     float2* massml = reinterpret_cast<float2*>(static_cast<char*>(a.workspace) + p.off_massml) + (int64_t)unit * p.slots * p.rows_wg;
@@ -816,10 +851,31 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
     const uint32_t tr_x = (uint32_t)(tr_row & 7) * 32;
     int cur_seg = -1;
     __syncthreads();                                 // B0
+    // the tile to do next, in scalars; its successor's ring entry is read while the tile's math runs
+    auto ring_tile = [&](int j) {
+        const int4 e = tile_ring[j & 3];
+        Tile t;
+        t.seg = __builtin_amdgcn_readfirstlane(e.x);
+        t.tok0 = __builtin_amdgcn_readfirstlane(e.y);
+        t.ntok = __builtin_amdgcn_readfirstlane(e.z);
+        t.self = __builtin_amdgcn_readfirstlane(e.w);
+        t.delta = 0;                                 // the staged keys are rotated already
+        return t;
+    };
+    Tile upcoming = ring_tile(0);
+    int n_done = 0;
     auto math = [&](int buf) {
         __syncthreads();                             // the tile is staged
-        const Tile cd = walk.next(tbl, lane);
-        if (cd.ntok <= 0 || !has_rows) return;
+        const Tile cd = upcoming;
+        const int4 next_entry = tile_ring[(n_done + 1) & 3];     // written before the barrier just passed
+        ++n_done;
+        auto take_next = [&]() {
+            upcoming.seg = __builtin_amdgcn_readfirstlane(next_entry.x);
+            upcoming.tok0 = __builtin_amdgcn_readfirstlane(next_entry.y);
+            upcoming.ntok = __builtin_amdgcn_readfirstlane(next_entry.z);
+            upcoming.self = __builtin_amdgcn_readfirstlane(next_entry.w);
+        };
+        if (cd.ntok <= 0 || !has_rows) { take_next(); return; }
         if (cd.seg != cur_seg) {
             if (cur_seg >= 0) emit_segment<NRB>(st, massml, cur_seg + split, p.rows_wg, cw * NRB, li, lg);
             cur_seg = cd.seg;
@@ -827,6 +883,7 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
             for (int rb = 0; rb < NRB; ++rb) st.seg_l[rb] = 0.f;
         }
         tile_math<DT, NRB, TILE>(cd, k_buf[buf], v_buf[buf], qf, trow, st, a.scale_log2e, li, lg, tr_base, tr_x);
+        take_next();
     };
     for (int it = 0; it < n_tiles; it += 2) {
         math(0);
