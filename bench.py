@@ -313,7 +313,7 @@ def main() -> int:
     achieved = kv_tokens * bytes_per_token / (kernel_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
-                "kernel": "attn_tile_kernel<bf16,1,32,2> (first kernel of cf_prefill_layer / cf_prefill_attention)",
+                "kernel": "attn_tile_kernel<bf16,1,32,2,true> (first kernel of cf_prefill_layer / cf_prefill_attention)",
                 "ms_per_launch": kernel_ms, "algorithmic_bytes_per_launch": kv_tokens * bytes_per_token,
                 "ms_per_call_all_kernels": attn_ms}
     if args.workload != WORKLOAD:

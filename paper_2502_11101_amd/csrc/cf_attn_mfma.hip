@@ -132,9 +132,11 @@ struct QueryHead {
     cf_segment seg;
 };
 
-__device__ __forceinline__ QueryHead load_query_head(const AttnArgs& a, int b) {   // b: wave-uniform
+// `entry`: which table entry this thread takes (its index in the workgroup for the LDS table, its lane
+// for the register table).
+__device__ __forceinline__ QueryHead load_query_head(const AttnArgs& a, int b, int entry) {   // b: wave-uniform
     QueryHead h;
-    if ((int)threadIdx.x < a.seg_stride) h.seg = a.segs[(int64_t)b * a.seg_stride + threadIdx.x];   // seg_stride <= kMaxSegs == kThreads
+    if (entry < a.seg_stride) h.seg = a.segs[(int64_t)b * a.seg_stride + entry];   // seg_stride <= kMaxSegs == kThreads
     const int q0 = a.q_off[b], q1 = a.q_off[b + 1], qt = a.q_off[a.batch], n = a.n_seg[b], qn = a.q_new_start[b];
     asm volatile("" ::"s"(q0), "s"(q1), "s"(qt), "s"(n), "s"(qn));    // all five scalar loads are out before any is used
     h.q0 = q0;
@@ -235,6 +237,96 @@ __device__ __forceinline__ float2 rope_cos_sin_fast(int delta, double theta_rev)
 // One tile of the walk over a split's tiles; ntok == 0 marks "no tile left".
 struct Tile { int seg, tok0, ntok, delta, self; };
 
+// In-register inclusive scan over the 64 lanes of a wavefront (DPP row shifts, then the two row broadcasts).
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+// The same table for at most 64 segments, held in registers: lane s of every wavefront describes segment s.
+// Built by each wavefront for itself — no LDS, no barrier — and searched with a ballot and lane reads.
+struct RegSegTable {
+    int64_t tok;                // this lane's segment, as in SegTable
+    int32_t vis, delta, self;
+    int32_t t0, t1;             // its tiles [t0, t1)
+    int32_t n, total;           // wavefront-uniform: segments, tiles
+};
+
+// `h.seg` is entry `lane`; seg_stride <= 64.
+__device__ __forceinline__ RegSegTable build_reg_table(const AttnArgs& a, const QueryHead& h, int lane, int tile_tokens) {
+    RegSegTable t;
+    const cf_segment& seg = h.seg;
+    int n = h.n_seg;
+    if (n < 0 || n > a.seg_stride) {
+        if (lane == 0) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
+        n = n < 0 ? 0 : a.seg_stride;
+    }
+    const int tq = min(h.tq_raw, a.max_tq);
+    int vis = 0;
+    t.tok = 0; t.delta = 0; t.self = 0;
+    if (lane < n) {
+        const bool self = seg.kind == CF_SEG_SELF;
+        const int64_t limit = self ? h.q_total : a.n_store_tokens;
+        const bool bad = seg.kind < 0 || seg.kind > CF_SEG_SELF || seg.len < 0 || seg.tok_offset < 0 ||
+                         seg.tok_offset + seg.len > limit || (self && a.k_self == nullptr);
+        if (bad) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
+        vis = bad ? 0 : (self ? min(seg.len, tq) : seg.len);
+        t.tok = seg.tok_offset;
+        t.delta = seg.new_start - seg.stored_start - h.qdelta;
+        t.self = self ? 1 : 0;
+    }
+    t.vis = vis;
+    const int tiles = (vis + tile_tokens - 1) / tile_tokens;
+    t.t1 = wave_inclusive_scan(tiles);
+    t.t0 = t.t1 - tiles;
+    t.n = n;
+    t.total = __builtin_amdgcn_readlane(t.t1, kWave - 1);
+    return t;
+}
+
+// The segment that owns tile x (x < total) and its fields, in scalars.  `prev`: the segment found last (-1: none).
+struct FoundSegment { int seg, first, end, vis, delta, self; int64_t tok; };
+
+__device__ __forceinline__ FoundSegment find_segment(const SegTable& tbl, int x, int lane, int prev) {
+    // the first segment whose tiles reach past x: every lane tests one entry per round
+    int s = 0;
+    for (int s0 = prev < 0 ? 0 : (prev & ~(kWave - 1));; s0 += kWave) {
+        const int idx = s0 + lane;
+        const unsigned long long hit = __ballot(idx < tbl.n && tbl.tile0[idx + 1] > x);
+        if (hit) { s = s0 + __builtin_ctzll(hit); break; }
+    }
+    FoundSegment f;
+    f.seg = s;
+    f.first = tbl.tile0[s];
+    f.end = tbl.tile0[s + 1];
+    f.vis = tbl.vis[s];
+    f.delta = tbl.delta[s];
+    f.self = tbl.self[s];
+    f.tok = tbl.tok[s];
+    return f;
+}
+
+__device__ __forceinline__ FoundSegment find_segment(const RegSegTable& t, int x, int lane, int) {
+    const unsigned long long hit = __ballot(lane < t.n && t.t1 > x);
+    const int s = hit ? __builtin_ctzll(hit) : 0;       // x < total: some lane always answers
+    FoundSegment f;
+    f.seg = s;
+    f.first = __builtin_amdgcn_readlane(t.t0, s);
+    f.end = __builtin_amdgcn_readlane(t.t1, s);
+    f.vis = __builtin_amdgcn_readlane(t.vis, s);
+    f.delta = __builtin_amdgcn_readlane(t.delta, s);
+    f.self = __builtin_amdgcn_readlane(t.self, s);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)t.tok, s);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)t.tok >> 32), s);
+    f.tok = (int64_t)(((uint64_t)hi << 32) | lo);
+    return f;
+}
+
 // Walks the tiles [next_tile, t_end) of the segment table in order.  All state is wavefront-uniform;
 // the segment of the tile handed out last is cached, since most tiles continue their predecessor's.
 template <int TILE>
@@ -246,28 +338,23 @@ struct TileWalk {
     __device__ __forceinline__ TileWalk(int begin, int end) : next_tile(begin), t_end(end) {}
 
     // The next tile, or a tile with ntok == 0 when none is left.
-    __device__ __forceinline__ Tile next(const SegTable& tbl, int lane) {
+    template <class Table>
+    __device__ __forceinline__ Tile next(const Table& tbl, int lane) {
         Tile d;
         if (next_tile < t_end) {
             if (next_tile >= c_end) {
-                // the first segment whose tiles reach past this one: every lane tests one entry per round
-                int s = 0;
-                for (int s0 = c_seg < 0 ? 0 : (c_seg & ~(kWave - 1));; s0 += kWave) {
-                    const int idx = s0 + lane;
-                    const unsigned long long hit = __ballot(idx < tbl.n && tbl.tile0[idx + 1] > next_tile);
-                    if (hit) { s = s0 + __builtin_ctzll(hit); break; }
-                }
-                c_seg = s;
-                c_first = tbl.tile0[s];
-                c_end = tbl.tile0[s + 1];
-                c_vis = tbl.vis[s];
-                c_delta = tbl.delta[s];
-                c_self = tbl.self[s];
-                c_tok = tbl.tok[s];
+                const FoundSegment f = find_segment(tbl, next_tile, lane, c_seg);
+                c_seg = f.seg;
+                c_first = f.first;
+                c_end = f.end;
+                c_vis = f.vis;
+                c_delta = f.delta;
+                c_self = f.self;
+                c_tok = f.tok;
             }
             d.seg = c_seg;
             d.tok0 = (next_tile - c_first) * TILE;
-            d.ntok = min(TILE, c_vis - d.tok0);
+            d.ntok = max(0, min(TILE, c_vis - d.tok0));
             d.delta = c_delta;
             d.self = c_self;
             ++next_tile;
@@ -539,9 +626,9 @@ __device__ __forceinline__ void store_partials(const AttnArgs& a, const Plan& p,
 //     with a 32-byte XOR swizzle; one workgroup barrier per tile;
 //   * the tile's math (tile_math).
 // With GROUPS == 2 two such groups share a workgroup, stream disjoint runs of tiles and merge at the end.
-template <int DT, int NRB, int TILE, int GROUPS>
+template <int DT, int NRB, int TILE, int GROUPS, bool REG_TABLE>
 __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArgs a, RopeFreq freq, Plan p) {
-    static_assert(GROUPS == 1 || (GROUPS == 2 && NRB == 1 && TILE == 32), "two groups: one row block per wavefront, 32-token tiles");
+    static_assert(GROUPS == 1 || (GROUPS == 2 && NRB == 1), "two groups: one row block per wavefront");
     constexpr int kKTile = TILE * kKRow;             // bytes
     constexpr int kVTile = TILE * kD * 2;
     constexpr int kKItems = TILE / 32;               // (row, chunk pair) items per thread
@@ -576,7 +663,7 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
     const int unit = (b * a.n_kv_heads + hkv) * p.n_rg + rg;
 
     const int group = a.n_q_heads / a.n_kv_heads;
-    const QueryHead qh = load_query_head(a, b);
+    const QueryHead qh = load_query_head(a, b, REG_TABLE ? lane : (int)threadIdx.x);
     const double my_freq = freq.rev[tid & (kHalf - 1)];
     const int tq = min(qh.tq_raw, a.max_tq);
 
@@ -588,8 +675,16 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
     const bool has_rows = row_base + wave * NRB * 16 < row_limit;        // wavefront-uniform
     load_q_fragments<NRB>(a, qh.q0, tq, hkv, group, wave * NRB, row_base, row_limit, li, lg, qf, trow);
 
-    build_table(a, qh, &tbl, TILE);
-    const unsigned total = (unsigned)tbl.tile0[tbl.n];
+    // at most 64 table entries: every wavefront keeps the table in registers; more: one table in LDS
+    RegSegTable rtbl;
+    unsigned total;
+    if constexpr (REG_TABLE) {
+        rtbl = build_reg_table(a, qh, lane, TILE);
+        total = (unsigned)rtbl.total;
+    } else {
+        build_table(a, qh, &tbl, TILE);
+        total = (unsigned)tbl.tile0[tbl.n];
+    }
     // a group streams a contiguous run of the workgroup's tiles of its own (sub-split `ss`)
     const unsigned nsub = (unsigned)(p.nsplit * GROUPS);
     const int ss = split * GROUPS + grp;
@@ -609,7 +704,8 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
     // at any point of the loop is fixed.  Rows past the end of a ragged tile re-read its last row (in
     // bounds; their scores are masked).
     auto fetch = [&](Tile& d, StageRegs& r) {
-        d = walk.next(tbl, lane);
+        if constexpr (REG_TABLE) d = walk.next(rtbl, lane);
+        else d = walk.next(tbl, lane);
         const TileSource src = tile_source(a, d, walk.c_tok, hkv);
 #pragma unroll
         for (int it = 0; it < kKItems; ++it) {
@@ -733,7 +829,7 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
 // table; the others take each tile's description from a small ring in LDS.
 constexpr int kPcTile = 64;
 
-template <int DT, int kProducers>
+template <int DT, int kProducers, bool REG_TABLE>
 __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a, RopeFreq freq, Plan p) {
     constexpr int TILE = kPcTile, NRB = kPcNrb;
     constexpr int kPT = kProducers * kWave;          // producer threads
@@ -761,7 +857,7 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
     const int b = __builtin_amdgcn_readfirstlane(x / (p.nsplit * a.n_kv_heads));
     const int unit = (b * a.n_kv_heads + hkv) * p.n_rg + rg;
     const int group = a.n_q_heads / a.n_kv_heads;
-    const QueryHead qh = load_query_head(a, b);
+    const QueryHead qh = load_query_head(a, b, REG_TABLE ? lane : (int)threadIdx.x);
     const int tq = min(qh.tq_raw, a.max_tq);
     const int row_base = rg * p.blocks_rg * 16;
     const int row_limit = min(group * tq, row_base + p.blocks_rg * 16);
@@ -770,8 +866,15 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
     uint4 qf[NRB][4];
     int trow[NRB];
     if (cw >= 0) load_q_fragments<NRB>(a, qh.q0, tq, hkv, group, cw * NRB, row_base, row_limit, li, lg, qf, trow);
-    build_table(a, qh, &tbl, TILE);
-    const unsigned total = (unsigned)tbl.tile0[tbl.n];
+    RegSegTable rtbl;
+    unsigned total;
+    if constexpr (REG_TABLE) {
+        rtbl = build_reg_table(a, qh, lane, TILE);
+        total = (unsigned)rtbl.total;
+    } else {
+        build_table(a, qh, &tbl, TILE);
+        total = (unsigned)tbl.tile0[tbl.n];
+    }
     const int t_begin = split_begin(total, (unsigned)p.nsplit, split), t_end = split_begin(total, (unsigned)p.nsplit, split + 1);
     const int n_tiles = t_end - t_begin;
 
@@ -786,7 +889,8 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
         TileWalk<TILE> walk(t_begin, t_end);
         int n_fetched = 0;
         auto fetch = [&](Tile& d, StageRegs& r) {    // a fixed number of loads, as in attn_tile_kernel
-            d = walk.next(tbl, lane);
+            if constexpr (REG_TABLE) d = walk.next(rtbl, lane);
+            else d = walk.next(tbl, lane);
             if (tid == 0) tile_ring[n_fetched & 3] = make_int4(d.seg, d.tok0, d.ntok, d.self);
             ++n_fetched;
             const TileSource src = tile_source(a, d, walk.c_tok, hkv);
@@ -1057,7 +1161,7 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p)
     __shared__ float stage[kMassStage];
     const char* ws = static_cast<const char*>(a.workspace);
     const int b = __builtin_amdgcn_readfirstlane(blockIdx.x);
-    const QueryHead qh = load_query_head(a, b);
+    const QueryHead qh = load_query_head(a, b, (int)threadIdx.x);
     build_table(a, qh, &tbl, p.tile);
     const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * p.units_per_b * p.nrb * p.slots;
     segment_masses_block(p, tbl, mp_b, stage, &ms, [&](int s, float m) {
@@ -1119,7 +1223,7 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
     const int64_t off = (int64_t)b * stride;
     const int nparts = p.units_per_b * p.nrb;
     const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * nparts * p.slots;
-    const QueryHead qh = load_query_head(a, b);
+    const QueryHead qh = load_query_head(a, b, (int)threadIdx.x);
     const int n_cand = pr.n_cand[b];
     if (tid == 0) { s_int[4] = pr.q_start[b]; s_int[5] = pr.n_reuse[b]; }
     for (int i = tid; i < stride; i += kEpiThreads) {
@@ -1201,12 +1305,15 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
     const Plan p = make_plan(a.n_q_heads, a.n_kv_heads, a.batch, a.max_tq, a.seg_stride, a.max_kv_tokens);
     const dim3 grid((unsigned)(p.x_count * p.n_rg)), block(kThreads);
     const dim3 grid2((unsigned)(p.units * p.nrb * 8)), grid3((unsigned)a.batch);
+    const bool reg_table = a.seg_stride <= kWave;    // the attention kernels keep a table this small in registers
 #define CF_LAUNCH_DT(DT)                                                                                                       \
     if (!(phases & 1)) {                                                                                                       \
     } else if (p.producers == 0) {                                                                                             \
-        hipLaunchKernelGGL((attn_tile_kernel<DT, 1, 32, 2>), grid, dim3(2 * kThreads), 0, s, a, f, p);                         \
+        if (reg_table) hipLaunchKernelGGL((attn_tile_kernel<DT, 1, 32, 2, true>), grid, dim3(2 * kThreads), 0, s, a, f, p);    \
+        else hipLaunchKernelGGL((attn_tile_kernel<DT, 1, 32, 2, false>), grid, dim3(2 * kThreads), 0, s, a, f, p);             \
     } else {                                                                                                                   \
-        hipLaunchKernelGGL((attn_pc_kernel<DT, kPcProducers>), grid, dim3(kPcWaves * kWave), 0, s, a, f, p);                   \
+        if (reg_table) hipLaunchKernelGGL((attn_pc_kernel<DT, kPcProducers, true>), grid, dim3(kPcWaves * kWave), 0, s, a, f, p); \
+        else hipLaunchKernelGGL((attn_pc_kernel<DT, kPcProducers, false>), grid, dim3(kPcWaves * kWave), 0, s, a, f, p);       \
     }                                                                                                                          \
     CF_HIP(hipGetLastError());                                                                                                 \
     if (phases & 2) hipLaunchKernelGGL((attn_combine_kernel<DT>), grid2, block, 0, s, a, p);
