@@ -191,9 +191,9 @@ __device__ __forceinline__ void build_table(const AttnArgs& a, const QueryHead& 
 }
 
 // split i of a list of `total` tiles owns [total*i/nsplit, total*(i+1)/nsplit)
-__device__ __forceinline__ int split_begin(unsigned total, unsigned nsplit, unsigned i) { return (int)(total * i / nsplit); }
+__device__ __forceinline__ int split_begin(unsigned total, unsigned nsplit, unsigned i) { return (int)div_exact(total * i, nsplit); }
 // the split that owns tile x
-__device__ __forceinline__ int split_of(unsigned total, unsigned nsplit, unsigned x) { return (int)(((x + 1) * nsplit - 1) / total); }
+__device__ __forceinline__ int split_of(unsigned total, unsigned nsplit, unsigned x) { return (int)div_exact((x + 1) * nsplit - 1, total); }
 
 template <int DT> struct Mma;
 template <> struct Mma<CF_BF16> {
@@ -236,17 +236,6 @@ __device__ __forceinline__ float2 rope_cos_sin_fast(int delta, double theta_rev)
 
 // One tile of the walk over a split's tiles; ntok == 0 marks "no tile left".
 struct Tile { int seg, tok0, ntok, delta, self; };
-
-// In-register inclusive scan over the 64 lanes of a wavefront (DPP row shifts, then the two row broadcasts).
-__device__ __forceinline__ int wave_inclusive_scan(int v) {
-    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
-    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
-    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
-    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
-    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
-    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
-    return v;
-}
 
 // The same table for at most 64 segments, held in registers: lane s of every wavefront describes segment s.
 // Built by each wavefront for itself — no LDS, no barrier — and searched with a ballot and lane reads.
@@ -1100,8 +1089,25 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
 // slot's partials are added over the (unit, pass) parts, then a segment adds the slots of the
 // splits that hold its tiles.  A split between a segment's first and last may own no tile at
 // all (fewer tiles than splits): its slot was not written by this call and is skipped.
-// `parts`: [nparts][slots] floats, in LDS (stage == nullptr) or in memory (stage: kMassStage floats of LDS).
-// `on_mass(s, m)` is called once per segment.  Both forms add in the same order.
+// `parts`: [nparts][slots] floats, in LDS (stage == nullptr; overwritten) or in memory (stage: kMassStage floats
+// of LDS).  `on_mass(s, m)` is called once per segment.  Both forms add in the same order: the parts of a
+// column in groups of eight, each group from zero, then the group sums from zero.
+// Sum of n <= 8 values `pitch` floats apart, added in order from zero.  A full group's loads all go out
+// before the first add (a loop with a run-time bound would wait for each in turn).
+__device__ __forceinline__ float group_sum(const float* x, int pitch, int n) {
+    float gs = 0.f;
+    if (n == 8) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = x[i * pitch];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) gs += v[i];
+    } else {
+        for (int i = 0; i < n; ++i) gs += x[i * pitch];
+    }
+    return gs;
+}
+
 struct MassScratch {
     float colsum[kMaxSegs + 2 * kMaxSplit];
     int32_t sub_begin[2 * kMaxSplit + 1];
@@ -1109,20 +1115,28 @@ struct MassScratch {
 constexpr int kMassStage = 4096;            // floats of partials staged per round by the stand-alone mass kernel
 
 template <class F>
-__device__ __forceinline__ void segment_masses_block(const Plan& p, const SegTable& tbl, const float* parts, float* stage,
+__device__ __forceinline__ void segment_masses_block(const Plan& p, const SegTable& tbl, float* parts, float* stage,
                                                      MassScratch* ms, F on_mass) {
     const int tid = threadIdx.x, nthr = blockDim.x;
     const unsigned total = (unsigned)tbl.tile0[tbl.n];
     const unsigned nsub = (unsigned)(p.nsplit * p.groups);
     const int nparts = p.units_per_b * p.nrb;
-    if (stage == nullptr) {                          // partials already in LDS
+    constexpr int kGroup = 8;
+    if (stage == nullptr) {                          // partials already in LDS: one thread per (group, column), in place
+        const int ngroups = (nparts + kGroup - 1) / kGroup;
+        for (int idx = tid; idx < ngroups * p.slots; idx += nthr) {
+            const int g = idx / p.slots, k = idx - g * p.slots;
+            const float gs = group_sum(parts + g * kGroup * p.slots + k, p.slots, min(kGroup, nparts - g * kGroup));
+            parts[g * kGroup * p.slots + k] = gs;
+        }
+        __syncthreads();
         for (int k = tid; k < p.slots; k += nthr) {
             float c = 0.f;
-            for (int part = 0; part < nparts; ++part) c += parts[(int64_t)part * p.slots + k];
+            for (int g = 0; g < ngroups; ++g) c += parts[g * kGroup * p.slots + k];
             ms->colsum[k] = c;
         }
     } else {                                         // partials in memory: whole rows through LDS, many loads in flight
-        const int rows = max(1, kMassStage / p.slots);   // slots <= kMassStage
+        const int rows = kMassStage / p.slots / kGroup * kGroup;   // slots <= kMassStage / kGroup: whole groups per round
         float c[2] = {0.f, 0.f};                     // this thread's columns tid, tid + nthr (slots <= 2 * nthr)
         for (int r0 = 0; r0 < nparts; r0 += rows) {
             const int nr = min(rows, nparts - r0);
@@ -1133,7 +1147,7 @@ __device__ __forceinline__ void segment_masses_block(const Plan& p, const SegTab
             for (int j = 0; j < 2; ++j) {
                 const int k = tid + j * nthr;
                 if (k < p.slots)
-                    for (int r = 0; r < nr; ++r) c[j] += stage[r * p.slots + k];
+                    for (int g0 = 0; g0 < nr; g0 += kGroup) c[j] += group_sum(stage + g0 * p.slots + k, p.slots, min(kGroup, nr - g0));
             }
         }
 #pragma unroll
@@ -1154,6 +1168,33 @@ __device__ __forceinline__ void segment_masses_block(const Plan& p, const SegTab
     }
 }
 
+// The same for one wavefront on its own, for a query with at most 64 slots and a register table: lane k adds
+// up column k, lane s then collects segment s's slots — the same sums in the same order, no barrier.
+template <class F>
+__device__ __forceinline__ void segment_masses_wave(const Plan& p, const RegSegTable& t, const float* parts, int lane, F on_mass) {
+    const unsigned total = (unsigned)t.total;
+    const unsigned nsub = (unsigned)(p.nsplit * p.groups);
+    const int nparts = p.units_per_b * p.nrb;
+    constexpr int kGroup = 8;
+    float c = 0.f;                                   // column `lane`
+    if (lane < p.slots)
+        for (int g0 = 0; g0 < nparts; g0 += kGroup) c += group_sum(parts + g0 * p.slots + lane, p.slots, min(kGroup, nparts - g0));
+    // sub-splits that own at least one tile (a split between a segment's first and last may own none)
+    const bool owns = lane < (int)nsub && split_begin(total, nsub, lane) < split_begin(total, nsub, lane + 1);
+    const unsigned long long owns_mask = __ballot(owns);
+    const bool has_tiles = lane < t.n && t.t1 > t.t0;
+    int s0 = 0, s1 = -1;
+    if (has_tiles) { s0 = split_of(total, nsub, t.t0); s1 = split_of(total, nsub, t.t1 - 1); }
+    const int span = wave_max_i32(s1 - s0);
+    float m = 0.f;
+    for (int d = 0; d <= span; ++d) {
+        const int sp = s0 + d;
+        const float cv = __shfl(c, (lane + sp) & (kWave - 1));       // slot = segment + sub-split
+        if (has_tiles && sp <= s1 && ((owns_mask >> sp) & 1)) m += cv;
+    }
+    if (lane < t.n) on_mass(lane, m);
+}
+
 // Third kernel: per-segment attention mass, one workgroup per query; then S += mass.
 __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p) {
     __shared__ SegTable tbl;
@@ -1164,7 +1205,7 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p)
     const QueryHead qh = load_query_head(a, b, (int)threadIdx.x);
     build_table(a, qh, &tbl, p.tile);
     const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * p.units_per_b * p.nrb * p.slots;
-    segment_masses_block(p, tbl, mp_b, stage, &ms, [&](int s, float m) {
+    segment_masses_block(p, tbl, const_cast<float*>(mp_b), stage, &ms, [&](int s, float m) {
         a.mass[(int64_t)b * a.seg_stride + s] = m;
         const int doc = tbl.doc[s];
         if (a.score_accum && doc >= 0 && doc < a.score_stride) atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], m);
@@ -1223,10 +1264,28 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
     const int64_t off = (int64_t)b * stride;
     const int nparts = p.units_per_b * p.nrb;
     const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * nparts * p.slots;
+    // The first batch of row loads and slot partials goes out before anything waits for the query's scalars.
+    const bool row0 = tid < stride;
+    int64_t r_tok = 0;
+    int32_t r_len = 0, r_cand = 0, r_start = 0, r_order = 0;
+    float r_score = 0.f, r_part = 0.f;
+    if (row0) {
+        r_tok = pr.doc_tok_offset[off + tid];
+        r_len = pr.doc_len[off + tid];
+        r_cand = pr.cand[off + tid];
+        r_score = a.score_accum[off + tid];
+        r_start = pr.new_start[off + tid];
+        r_order = pr.order[off + tid];
+    }
+    if (tid < nparts * p.slots) r_part = mp_b[tid];
     const QueryHead qh = load_query_head(a, b, (int)threadIdx.x);
     const int n_cand = pr.n_cand[b];
     if (tid == 0) { s_int[4] = pr.q_start[b]; s_int[5] = pr.n_reuse[b]; }
-    for (int i = tid; i < stride; i += kEpiThreads) {
+    if (row0) {
+        l_tok[tid] = r_tok; l_len[tid] = r_len; l_cand[tid] = r_cand; l_score[tid] = r_score; l_start[tid] = r_start;
+        l_order[tid] = r_order;
+    }
+    for (int i = tid + kEpiThreads; i < stride; i += kEpiThreads) {
         l_tok[i] = pr.doc_tok_offset[off + i];
         l_len[i] = pr.doc_len[off + i];
         l_cand[i] = pr.cand[off + i];
@@ -1234,17 +1293,31 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
         l_start[i] = pr.new_start[off + i];
         l_order[i] = pr.order[off + i];
     }
-    for (int i = tid; i < nparts * p.slots; i += kEpiThreads) l_part[i] = mp_b[i];
-    build_table(a, qh, &tbl, p.tile);                // its barriers also publish the rows above
-    segment_masses_block(p, tbl, l_part, nullptr, &ms, [&](int s, float m) {
-        a.mass[(int64_t)b * a.seg_stride + s] = m;
-        const int doc = tbl.doc[s];
-        if (doc >= 0 && doc < stride) atomicAdd(&l_score[doc], m);
-    });
-    __syncthreads();
+    if (tid < nparts * p.slots) l_part[tid] = r_part;
+    for (int i = tid + kEpiThreads; i < nparts * p.slots; i += kEpiThreads) l_part[i] = mp_b[i];
     // With few candidates one wavefront finishes alone: the others leave, and the barriers of the stages
     // below (which only wait for wavefronts that are still running) cost nothing.
     const int nthr = n_cand <= 2 * kWave ? kWave : kEpiThreads;
+    if (nthr == kWave && p.slots <= kWave && a.seg_stride <= kWave) {
+        // small query: the first wavefront also does the masses, from a table in its registers
+        __syncthreads();                             // publishes the rows above
+        if (tid >= kWave) return;
+        const RegSegTable rtbl = build_reg_table(a, qh, tid, p.tile);
+        segment_masses_wave(p, rtbl, l_part, tid, [&](int s, float m) {
+            a.mass[(int64_t)b * a.seg_stride + s] = m;
+            const int doc = qh.seg.doc;              // this lane's entry
+            if (doc >= 0 && doc < stride) atomicAdd(&l_score[doc], m);
+        });
+        __syncthreads();
+    } else {
+        build_table(a, qh, &tbl, p.tile);            // its barriers also publish the rows above
+        segment_masses_block(p, tbl, l_part, nullptr, &ms, [&](int s, float m) {
+            a.mass[(int64_t)b * a.seg_stride + s] = m;
+            const int doc = tbl.doc[s];
+            if (doc >= 0 && doc < stride) atomicAdd(&l_score[doc], m);
+        });
+        __syncthreads();
+    }
     if (tid >= nthr) return;
     for (int i = tid; i < stride; i += nthr) a.score_accum[off + i] = l_score[i];
     int k = min(pr.keep, n_cand);

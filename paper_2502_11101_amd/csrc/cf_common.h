@@ -9,6 +9,18 @@
 namespace cf {
 
 constexpr int kWave = 64;
+
+// a / b for unsigned a and b >= 1, exactly: below 2^21 through the float reciprocal and two corrections
+// (the estimate is off by less than one), else the long way.  A fraction of the instructions of the compiler's
+// general 32-bit division, which the short latency-bound kernels here would otherwise run several times.
+__device__ __forceinline__ unsigned div_exact(unsigned a, unsigned b) {
+    if (a >= (1u << 21) || b >= (1u << 21)) return a / b;
+    int q = (int)((float)a * __builtin_amdgcn_rcpf((float)b));
+    int r = (int)a - q * (int)b;
+    if (r < 0) { --q; r += (int)b; }
+    if (r >= (int)b) ++q;
+    return (unsigned)q;
+}
 constexpr int kMaxHeadDim = 256;
 constexpr int kMaxHalf = kMaxHeadDim / 2;
 

@@ -221,10 +221,26 @@ struct SelectWaveArgs {
     int prefix_len, doc_stored_start, q_stored_start, q_lo, q_hi, seg_stride;
 };
 
-__device__ __forceinline__ int wave_max_i32(int v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o));
+// In-register reductions over the 64 lanes of a wavefront with DPP (row shifts, then the two row broadcasts,
+// lane 63 ends up with the result): an inclusive prefix sum, and a maximum handed to every lane.
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
     return v;
+}
+
+__device__ __forceinline__ int wave_max_i32(int v) {
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x111, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x112, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x114, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x118, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x142, 0xa, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x143, 0xc, 0xf, false));
+    return __builtin_amdgcn_readlane(v, 63);
 }
 
 __device__ inline bool select_wave64(const SelectWaveArgs& s, int* n_keep_out, int* q_start, int* n_reuse, cf_segment* out,
@@ -241,10 +257,24 @@ __device__ inline bool select_wave64(const SelectWaveArgs& s, int* n_keep_out, i
     const bool bad = have && (!c_ok || !isfinite(sc) || ln_rank <= 0 || ln_rank >= (1 << 24));
     if (__any(bad)) return false;
     int rank = 0;
-    for (int j = 0; j < n; ++j) {
-        const float sj = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sc), j));
-        const int lj = __builtin_amdgcn_readlane(ln_rank, j), cj = __builtin_amdgcn_readlane(c, j);
-        rank += (j != lane) && ranks_before(sj, lj, cj, j, sc, ln_rank, c, lane);
+    if (s.stride <= (1 << 26) && __all(!have || ln_rank == __builtin_amdgcn_readlane(ln_rank, 0))) {
+        // equal lengths (the paper's regime, or no normalisation): the products of ranks_before compare as the
+        // scores themselves do
+        // as one unsigned key per lane: score (order-preserving bits, -0 as +0), then lower slot, then earlier position
+        uint32_t u = __float_as_uint(sc + 0.f);
+        u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;
+        const uint32_t low = ((uint32_t)(s.stride - 1 - c) << 6) | (uint32_t)(63 - lane);     // stride <= 2^26
+        const uint64_t key = ((uint64_t)u << 32) | low;
+        for (int j = 0; j < n; ++j) {
+            const uint32_t hj = (uint32_t)__builtin_amdgcn_readlane((int)u, j), lj = (uint32_t)__builtin_amdgcn_readlane((int)low, j);
+            rank += (((uint64_t)hj << 32) | lj) > key;
+        }
+    } else {
+        for (int j = 0; j < n; ++j) {
+            const float sj = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sc), j));
+            const int lj = __builtin_amdgcn_readlane(ln_rank, j), cj = __builtin_amdgcn_readlane(c, j);
+            rank += (j != lane) && ranks_before(sj, lj, cj, j, sc, ln_rank, c, lane);
+        }
     }
     const int k = min(s.keep, n);
     const int has_prefix = s.prefix_len > 0 ? 1 : 0;
@@ -278,21 +308,16 @@ __device__ inline bool select_wave64(const SelectWaveArgs& s, int* n_keep_out, i
         // ends at the query
         const int lmax = wave_max_i32(pl);
         const int avail = s.pos_end - s.pos_begin;
-        const int cap = avail / lmax;
+        const int cap = (int)div_exact((unsigned)max(avail, 0), (unsigned)lmax);      // lmax >= 1: every kept length is positive
         if (cap <= 0) return false;
-        groups = s.force_n_reuse > 0 ? s.force_n_reuse : (k + cap - 1) / cap;
+        groups = s.force_n_reuse > 0 ? s.force_n_reuse : (cap >= k ? 1 : (int)div_exact((unsigned)(k + cap - 1), (unsigned)cap));
         groups = min(groups, k);
-        const int per_group = (k + groups - 1) / groups;
-        int incl = pl;                                    // inclusive prefix over placement ranks
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int u = __shfl_up(incl, o);
-            if (lane >= o) incl += u;
-        }
-        const int first = (lane / per_group) * per_group;
+        const int per_group = (int)div_exact((unsigned)(k + groups - 1), (unsigned)groups);
+        const int incl = wave_inclusive_scan(pl);         // inclusive prefix over placement ranks
+        const int first = (int)div_exact((unsigned)lane, (unsigned)per_group) * per_group;
         const int before = __shfl(incl, max(first - 1, 0));
         const int cum = incl - (first > 0 ? before : 0);
-        const bool last = in && ((lane == k - 1) || ((lane + 1) % per_group == 0));
+        const bool last = in && ((lane == k - 1) || (lane + 1 == first + per_group));
         const int span_max = wave_max_i32(last ? cum : 0);
         if (span_max > avail) return false;
         qs = s.pos_begin + span_max;
