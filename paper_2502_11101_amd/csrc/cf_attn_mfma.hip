@@ -1027,11 +1027,11 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     // Everything this workgroup reads is requested up front — row statistics, partial outputs of the
     // first splits, the first slot statistics — so the three round trips to memory overlap.
     for (int idx = tid; idx < p.nsplit * 64; idx += kThreads) mlw[idx] = ml[(idx >> 6) * p.rows_wg + (idx & 63)];
-    // a wavefront whose 16 rows are all padding (the attention kernel wrote nothing for them) reads nothing
-    const bool blk_has_rows = pass * 64 + wave * 16 < min(p.blocks_rg * 16, group * min(q1 - q0, a.max_tq) - rg * p.blocks_rg * 16);
+    // (a wavefront whose 16 rows are all padding reads what an earlier call left there: in bounds, never stored;
+    // not waiting for the query's length here saves a round trip)
     f32x4 pre[kPre];
 #pragma unroll
-    for (int s = 0; s < kPre; ++s) pre[s] = s < p.nsplit && blk_has_rows ? src[s * split_stride] : f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < kPre; ++s) pre[s] = s < p.nsplit ? src[s * split_stride] : f32x4{0.f, 0.f, 0.f, 0.f};
     float2 sv[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -1042,6 +1042,7 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     const int n_rows = group * tq;
     const int row_base = rg * p.blocks_rg * 16;
     const int rows_here = min(p.blocks_rg * 16, n_rows - row_base);
+    const bool blk_has_rows = pass * 64 + wave * 16 < rows_here;
     __syncthreads();
     if (tid < 64) {
         float m = -INFINITY;
@@ -1076,7 +1077,7 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
         float* masspart = reinterpret_cast<float*>(ws + p.off_masspart) + ((int64_t)unit * p.nrb + pass) * p.slots;
         const float2 st = rstat[lane];
         auto reduce = [&](int k, float2 v) {
-            const float c = wave_sum(st.y > 0.f ? v.y * exp2f(v.x - st.x) * st.y : 0.f);
+            const float c = wave_sum_dpp(st.y > 0.f ? v.y * exp2f(v.x - st.x) * st.y : 0.f);
             if (lane == 0 && k < p.slots) masspart[k] = c;
         };
 #pragma unroll
