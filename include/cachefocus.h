@@ -329,6 +329,18 @@ CF_API const char* cf_last_error(void);
  * Default 7 (all).  With a partial mask the call's outputs are not meaningful. */
 CF_API void cf_profile_phases(int32_t mask);
 
+/* Profiling aid (not part of the method): while enabled (nonzero), every launch of the attention kernel proper
+ * by cf_prefill_attention / cf_prefill_layer on this thread's 16-bit path carries a start and a stop event that
+ * take the time at which that dispatch begins and ends on the GPU; the events of the last 1024 launches are kept.  Enabling creates the events (host memory
+ * only) and forgets earlier launches; disabling destroys them.  Host call, not to be issued during stream capture.
+ * Returns CF_OK or CF_ERR_DEVICE. */
+CF_API cf_status cf_profile_kernel_events(int32_t enable);
+
+/* Waits for the bracketed launches to finish and reports their number (at most 1024) and the mean of their
+ * event-to-event durations in milliseconds (0 when there are none).  Both pointers are host memory, non-NULL.
+ * CF_ERR_INVALID_ARG when timing is not enabled or a pointer is NULL, CF_ERR_DEVICE on a runtime error. */
+CF_API cf_status cf_profile_kernel_ms(double* mean_ms, int32_t* launches);
+
 /* Library version as major*10000 + minor*100 + patch. */
 CF_API int32_t cf_version(void);
 

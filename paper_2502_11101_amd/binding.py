@@ -27,7 +27,7 @@ CF_FLAG_BAD_SEGMENT, CF_FLAG_NONFINITE_SCORE, CF_FLAG_DOC_TOO_LONG, CF_FLAG_POS_
 DTYPE_CODE = {"f32": CF_F32, "bf16": CF_BF16, "f16": CF_F16}
 
 EXPORTS = ("cf_reposition_keys", "cf_prefill_workspace_bytes", "cf_prefill_attention", "cf_prune_topk",
-           "cf_assign_positions", "cf_gather_segments", "cf_last_error", "cf_version", "cf_profile_phases",
+           "cf_assign_positions", "cf_gather_segments", "cf_last_error", "cf_version", "cf_profile_phases", "cf_profile_kernel_events", "cf_profile_kernel_ms",
            "cf_prefill_layer", "cf_assemble_cache")
 
 
@@ -79,6 +79,10 @@ def load() -> C.CDLL:
     lib.cf_version.argtypes = []
     lib.cf_profile_phases.restype = None
     lib.cf_profile_phases.argtypes = [i32]
+    lib.cf_profile_kernel_events.restype = i32
+    lib.cf_profile_kernel_events.argtypes = [i32]
+    lib.cf_profile_kernel_ms.restype = i32
+    lib.cf_profile_kernel_ms.argtypes = [C.POINTER(C.c_double), C.POINTER(i32)]
     lib.cf_reposition_keys.restype = i32
     lib.cf_reposition_keys.argtypes = [dp, vp, vp, vp, i32, i64, i32, vp, vp]
     lib.cf_prefill_workspace_bytes.restype = sz
@@ -160,6 +164,17 @@ def cf_version() -> int:
 
 def cf_profile_phases(mask: int) -> None:
     load().cf_profile_phases(mask)
+
+
+def cf_profile_kernel_events(enable: bool) -> None:
+    _check(load().cf_profile_kernel_events(1 if enable else 0))
+
+
+def cf_profile_kernel_ms():
+    """(mean milliseconds, launches) of the attention kernel's bracketed launches."""
+    mean, n = C.c_double(0.0), C.c_int32(0)
+    _check(load().cf_profile_kernel_ms(C.byref(mean), C.byref(n)))
+    return mean.value, n.value
 
 
 def cf_last_error() -> str:

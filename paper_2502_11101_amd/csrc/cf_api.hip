@@ -17,6 +17,24 @@ thread_local int g_phases = 7;
 
 int profile_phases() { return g_phases; }
 
+namespace {
+constexpr int kTimerPairs = 1024;
+struct KernelTimer {
+    bool on = false;
+    long long launches = 0;
+    hipEvent_t begin[kTimerPairs], end[kTimerPairs];
+};
+thread_local KernelTimer g_timer;
+}  // namespace
+
+void profile_kernel_pair(hipEvent_t* start, hipEvent_t* stop) {
+    *start = *stop = nullptr;
+    if (!g_timer.on) return;
+    *start = g_timer.begin[g_timer.launches % kTimerPairs];
+    *stop = g_timer.end[g_timer.launches % kTimerPairs];
+    ++g_timer.launches;
+}
+
 void set_error(const char* fmt, ...) {
     va_list ap;
     va_start(ap, fmt);
@@ -85,6 +103,43 @@ const char* cf_last_error(void) { return g_err; }
 int32_t cf_version(void) { return 100; }
 
 void cf_profile_phases(int32_t mask) { g_phases = mask & 7; }
+
+cf_status cf_profile_kernel_events(int32_t enable) {
+    if (g_timer.on) {
+        for (int i = 0; i < kTimerPairs; ++i) { (void)hipEventDestroy(g_timer.begin[i]); (void)hipEventDestroy(g_timer.end[i]); }
+        g_timer.on = false;
+    }
+    g_timer.launches = 0;
+    if (!enable) return CF_OK;
+    for (int i = 0; i < kTimerPairs; ++i) {
+        hipError_t e = hipEventCreate(&g_timer.begin[i]);
+        if (e == hipSuccess) e = hipEventCreate(&g_timer.end[i]);
+        if (e != hipSuccess) {
+            // destroy what exists (a failed begin[i] leaves end[i] uncreated)
+            for (int j = 0; j < i; ++j) { (void)hipEventDestroy(g_timer.begin[j]); (void)hipEventDestroy(g_timer.end[j]); }
+            set_error("hipEventCreate: %s", hipGetErrorString(e));
+            return CF_ERR_DEVICE;
+        }
+    }
+    g_timer.on = true;
+    return CF_OK;
+}
+
+cf_status cf_profile_kernel_ms(double* mean_ms, int32_t* launches) {
+    CF_REQUIRE(mean_ms && launches, CF_ERR_INVALID_ARG, "mean_ms and launches must not be NULL");
+    CF_REQUIRE(g_timer.on, CF_ERR_INVALID_ARG, "kernel timing is not enabled");
+    const int n = (int)(g_timer.launches < kTimerPairs ? g_timer.launches : kTimerPairs);
+    double total = 0.0;
+    for (int i = 0; i < n; ++i) {
+        CF_HIP(hipEventSynchronize(g_timer.end[i]));
+        float ms = 0.f;
+        CF_HIP(hipEventElapsedTime(&ms, g_timer.begin[i], g_timer.end[i]));
+        total += ms;
+    }
+    *mean_ms = n ? total / n : 0.0;
+    *launches = n;
+    return CF_OK;
+}
 
 cf_status cf_reposition_keys(const cf_layer_desc* desc, const void* k_in, void* k_out, const cf_segment* segs,
                              int32_t n_seg, int64_t n_store_tokens, int32_t max_seg_len, int32_t* dev_flag,

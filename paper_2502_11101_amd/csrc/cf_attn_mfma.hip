@@ -26,6 +26,8 @@
 // kernel boundaries: no fences, no atomics on the data path, bit-identical reruns.
 #include <type_traits>
 
+#include <hip/hip_ext.h>
+
 #include "cf_common.h"
 #include "cf_select_dev.h"
 
@@ -1380,19 +1382,24 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
     const dim3 grid((unsigned)(p.x_count * p.n_rg)), block(kThreads);
     const dim3 grid2((unsigned)(p.units * p.nrb * 8)), grid3((unsigned)a.batch);
     const bool reg_table = a.seg_stride <= kWave;    // the attention kernels keep a table this small in registers
+    // the attention kernel's launch carries the profiling aid's start/stop events (null when it is off)
+    hipEvent_t ev_start = nullptr, ev_stop = nullptr;
+    if (phases & 1) profile_kernel_pair(&ev_start, &ev_stop);
+#define CF_LAUNCH_TIMED(KERNEL, BLOCK) hipExtLaunchKernelGGL(KERNEL, grid, BLOCK, 0, s, ev_start, ev_stop, 0, a, f, p)
 #define CF_LAUNCH_DT(DT)                                                                                                       \
     if (!(phases & 1)) {                                                                                                       \
     } else if (p.producers == 0) {                                                                                             \
-        if (reg_table) hipLaunchKernelGGL((attn_tile_kernel<DT, 1, 32, 2, true>), grid, dim3(2 * kThreads), 0, s, a, f, p);    \
-        else hipLaunchKernelGGL((attn_tile_kernel<DT, 1, 32, 2, false>), grid, dim3(2 * kThreads), 0, s, a, f, p);             \
+        if (reg_table) CF_LAUNCH_TIMED((attn_tile_kernel<DT, 1, 32, 2, true>), dim3(2 * kThreads));                            \
+        else CF_LAUNCH_TIMED((attn_tile_kernel<DT, 1, 32, 2, false>), dim3(2 * kThreads));                                     \
     } else {                                                                                                                   \
-        if (reg_table) hipLaunchKernelGGL((attn_pc_kernel<DT, kPcProducers, true>), grid, dim3(kPcWaves * kWave), 0, s, a, f, p); \
-        else hipLaunchKernelGGL((attn_pc_kernel<DT, kPcProducers, false>), grid, dim3(kPcWaves * kWave), 0, s, a, f, p);       \
+        if (reg_table) CF_LAUNCH_TIMED((attn_pc_kernel<DT, kPcProducers, true>), dim3(kPcWaves * kWave));                      \
+        else CF_LAUNCH_TIMED((attn_pc_kernel<DT, kPcProducers, false>), dim3(kPcWaves * kWave));                               \
     }                                                                                                                          \
     CF_HIP(hipGetLastError());                                                                                                 \
     if (phases & 2) hipLaunchKernelGGL((attn_combine_kernel<DT>), grid2, block, 0, s, a, p);
     if (a.dtype == CF_BF16) { CF_LAUNCH_DT(CF_BF16) } else { CF_LAUNCH_DT(CF_F16) }
 #undef CF_LAUNCH_DT
+#undef CF_LAUNCH_TIMED
     CF_HIP(hipGetLastError());
     if (prune) {
         PruneArgs pr;

@@ -353,6 +353,34 @@ def test_mfma_path_is_deterministic():
     assert torch.equal(masses[0], masses[1]) and torch.equal(masses[0], masses[2])
 
 
+def test_kernel_timing_aid_counts_launches_and_leaves_results_alone():
+    """cf_profile_kernel_events / cf_profile_kernel_ms: one bracketed launch per call of the 16-bit path, a positive
+    mean duration, an error when timing is off, and outputs identical to an untimed call."""
+    cfg = wl.CONFIGS["llama2_7b_layer"]
+    st = wl.build_structure(cfg)
+    dev = G.upload_layer(cfg, wl.build_layer(cfg, st))
+    pb = G.make_batch(cfg, st)
+    pb.allocate_initial()
+    ref = torch.empty_like(dev["q"])
+    pb.attention(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], ref, accumulate=False)
+    torch.cuda.synchronize()
+    with pytest.raises(cf.CacheFocusError):
+        cf.cf_profile_kernel_ms()
+    cf.cf_profile_kernel_events(True)
+    try:
+        assert cf.cf_profile_kernel_ms() == (0.0, 0)
+        out = torch.empty_like(dev["q"])
+        for _ in range(3):
+            pb.attention(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out, accumulate=False)
+        mean_ms, n = cf.cf_profile_kernel_ms()
+        assert n == 3 and 0.0 < mean_ms < 5.0
+        assert torch.equal(out, ref)
+    finally:
+        cf.cf_profile_kernel_events(False)
+    with pytest.raises(cf.CacheFocusError):
+        cf.cf_profile_kernel_ms()
+
+
 # ----------------------------------------------------------------------------- fused layer call
 @pytest.mark.parametrize("name", ["tiny_f32", "llama2_7b_layer", "qwen2_7b_layer"])
 @pytest.mark.parametrize("strategy", [cf.CF_ALLOC_SORT, cf.CF_ALLOC_ALIGN, cf.CF_ALLOC_KEEP])
