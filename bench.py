@@ -152,7 +152,7 @@ def bench_assemble(args) -> int:
         def step(i: int) -> None:                                                  # noqa: F811
             (kf, vf), (q1, k1, v1) = finals[i % n_buf], new_tok[i % n_buf]
             cf.cf_prefill_attention(ddesc, q1, q_off, p_new, q_new, kf, vf, tokens, k1, v1, table, n_seg, 2, 1, 1, tokens + 1,
-                                    dout, dmass, None, 1, ws, ws_bytes, pb.dev_flag)
+                                    dout, None, None, 1, ws, ws_bytes, pb.dev_flag)           # outputs only: no mass
 
     for i in range(args.warmup):
         step(i)
@@ -167,7 +167,7 @@ def bench_assemble(args) -> int:
     elapsed = time.perf_counter() - t0
     assert pb.flags() == 0 and int(final_len.item()) == tokens
     if args.path == "decode":
-        assert abs(float(dmass.sum().item()) - g.n_q_heads) < 1e-3 * g.n_q_heads
+        assert bool(torch.isfinite(dout.float()).all())
         ms_per_step = 1e3 * elapsed / args.steps
         call_ms = e0.elapsed_time(e1) / args.steps
         bytes_per_token = 2 * g.n_kv_heads * g.head_dim * 2
@@ -181,7 +181,7 @@ def bench_assemble(args) -> int:
                        "kv_tokens_per_step": tokens + 1, "kv_heads": g.n_kv_heads, "head_dim": g.head_dim, "layer_buffers": n_buf,
                        "step": "cf_prefill_attention (Tq = 1)"},
             "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                         "traffic": None, "kernel": "whole call: attn_tile_kernel + attn_combine_kernel + attn_mass_kernel",
+                         "traffic": None, "kernel": "whole call: attn_tile_kernel + attn_combine_kernel (no mass asked for)",
                          "ms_per_launch": call_ms, "algorithmic_bytes_per_launch": (tokens + 1) * bytes_per_token}}))
         return 0
     ms_per_step = 1e3 * elapsed / args.steps

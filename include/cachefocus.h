@@ -158,7 +158,8 @@ CF_API size_t cf_prefill_workspace_bytes(const cf_layer_desc* desc, int32_t batc
  *   n_seg        device int32 [batch], each <= seg_stride
  *   max_kv_tokens host: upper bound on the tokens one query attends (sizing only)
  *   out          device [q_off[batch], n_q_heads, head_dim], desc->dtype
- *   mass         device float [batch*seg_stride]
+ *   mass         device float [batch*seg_stride]; may be NULL when score_accum is NULL too (outputs only, as
+ *                in a decode step, Alg. 2 Phase 3: no mass is reduced)
  *   score_accum  device float [batch*score_stride] or NULL
  *   workspace    device, >= cf_prefill_workspace_bytes(desc, batch, max_tq, seg_stride, max_kv_tokens),
  *                256-byte aligned; contents are scratch

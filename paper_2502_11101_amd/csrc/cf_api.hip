@@ -214,8 +214,10 @@ static cf_status prefill_impl(const cf_layer_desc* desc, const void* q, const in
         if (st != CF_OK) return st;
     }
     if (batch == 0) return CF_OK;
-    CF_REQUIRE(q && q_off && q_new_start && segs && n_seg && out && mass, CF_ERR_INVALID_ARG,
-               "q, q_off, q_new_start, segs, n_seg, out and mass must not be NULL");
+    CF_REQUIRE(q && q_off && q_new_start && segs && n_seg && out, CF_ERR_INVALID_ARG,
+               "q, q_off, q_new_start, segs, n_seg and out must not be NULL");
+    CF_REQUIRE(mass != nullptr || (score_accum == nullptr && prune == nullptr), CF_ERR_INVALID_ARG,
+               "mass may be NULL only when neither scores nor a prune step are asked for");
     CF_REQUIRE((k_self == nullptr) == (v_self == nullptr), CF_ERR_INVALID_ARG,
                "k_self and v_self must be given together");
     CF_REQUIRE(n_store_tokens == 0 || (k_store && v_store), CF_ERR_INVALID_ARG,

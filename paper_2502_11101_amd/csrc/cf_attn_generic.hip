@@ -224,6 +224,7 @@ cf_status launch_attention_generic(const AttnArgs& a, const RopeFreq& f, hipStre
     else { if (halfp) CF_LAUNCH_ROWS(CF_F16, CF_ROPE_HALF); else CF_LAUNCH_ROWS(CF_F16, CF_ROPE_INTERLEAVED); }
 #undef CF_LAUNCH_ROWS
     CF_HIP(hipGetLastError());
+    if (a.mass == nullptr) return CF_OK;             // outputs only
     hipLaunchKernelGGL(mass_reduce_kernel, dim3(a.seg_stride, a.batch), dim3(kThreads), 0, s, a, rowstat, rowseg);
     CF_HIP(hipGetLastError());
     return CF_OK;

@@ -1075,7 +1075,7 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     }
     // slot partials: slot k = segment + split; slots no split wrote this call hold stale pairs and
     // give meaningless numbers that the mass kernel never reads
-    {
+    if (a.mass != nullptr) {
         float* masspart = reinterpret_cast<float*>(ws + p.off_masspart) + ((int64_t)unit * p.nrb + pass) * p.slots;
         const float2 st = rstat[lane];
         auto reduce = [&](int k, float2 v) {
@@ -1419,7 +1419,7 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
             CF_HIP(hipGetLastError());
             return launch_prune_step(a, prune, s);
         }
-    } else if (phases & 4) {
+    } else if ((phases & 4) && a.mass != nullptr) {
         hipLaunchKernelGGL(attn_mass_kernel, grid3, block, 0, s, a, p);
     }
     CF_HIP(hipGetLastError());

@@ -92,12 +92,17 @@ def test_prefill_argument_checks():
     assert call(max_tq=0)[0] == cf.CF_ERR_INVALID_ARG
     assert call(seg_stride=0)[0] == cf.CF_ERR_INVALID_ARG
     assert call(score_accum=FAKE, score_stride=0)[0] == cf.CF_ERR_INVALID_ARG
+    assert call(mass=None, score_accum=FAKE, score_stride=4)[0] == cf.CF_ERR_INVALID_ARG     # scores need the masses
+    assert call(mass=None, workspace=None)[0] == cf.CF_ERR_WORKSPACE                          # outputs only: accepted so far
     assert call(q_stored_start=4096)[0] == cf.CF_ERR_RANGE
     assert call(workspace=None)[0] == cf.CF_ERR_WORKSPACE
     assert call(workspace_bytes=16)[0] == cf.CF_ERR_WORKSPACE
     assert call(workspace=0x10010)[0] == cf.CF_ERR_WORKSPACE
     st, msg = call(workspace_bytes=16)
     assert "workspace" in msg
+    # the kernel timing aid: nothing to report while it is off, switching it off twice is fine (no GPU needed)
+    assert _status(cf.cf_profile_kernel_ms)[0] == cf.CF_ERR_INVALID_ARG
+    cf.cf_profile_kernel_events(False)
     # an empty batch is a no-op and needs no GPU
     cf.cf_prefill_attention(d, None, None, 0, None, None, None, 0, None, None, None, None, 4, 0, 8, 0, None, None,
                             None, 0, None, 0, stream=0)
@@ -153,6 +158,9 @@ def test_assemble_argument_checks():
     assert call(k_final=FAKE + 0x404)[0] == cf.CF_ERR_INVALID_ARG          # misaligned
     assert call(max_seg_len=0)[0] == cf.CF_ERR_INVALID_ARG
     assert call(final_capacity=-1)[0] == cf.CF_ERR_INVALID_ARG
+    # the kernel timing aid: nothing to report while it is off, switching it off twice is fine (no GPU needed)
+    assert _status(cf.cf_profile_kernel_ms)[0] == cf.CF_ERR_INVALID_ARG
+    cf.cf_profile_kernel_events(False)
     # an empty batch is a no-op and needs no GPU
     cf.cf_assemble_cache(d, None, None, 0, None, None, None, None, None, 4, 0, 8, 64, None, 0, 256, 128, None, None, None,
                          stream=0)

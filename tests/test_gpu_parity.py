@@ -786,6 +786,12 @@ def test_decode_step_over_assembled_cache():
         ref = orc.decode_attention(q_abs[b:b + 1].astype(np.float64), k_ref, v_ref, g.n_kv_heads)
         assert G.row_error(got[b:b + 1], ref) <= G.OUT_TOL[g.dtype]
         assert mass[b, 0].item() == pytest.approx(g.n_q_heads, rel=1e-5)
+    # outputs only (no mass buffer, as a decode loop would call it): the same outputs, bit for bit
+    out2 = torch.empty_like(out)
+    cf.cf_prefill_attention(desc, q_dev, q_off, 0, zeros, r["k_dev"], r["v_dev"], r["capacity"], None, None, seg_dev, n_seg, 1,
+                            cfg.batch, 1, max_kv, out2, None, None, 1, ws, ws_bytes, flag)
+    torch.cuda.synchronize()
+    assert flag.item() == 0 and torch.equal(out2, out)
 
 
 def test_assemble_cache_flags():
