@@ -1062,7 +1062,14 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     for (int s = 0; s < kPre; ++s)
         if (s < p.nsplit) o += pre[s] * mlw[s * 64 + wave * 16 + li].x;
     if (blk_has_rows)
-        for (int s = kPre; s < p.nsplit; ++s) o += src[s * split_stride] * mlw[s * 64 + wave * 16 + li].x;
+        for (int s0 = kPre; s0 < p.nsplit; s0 += kPre) {         // further splits, eight loads at a time
+            f32x4 more[kPre];
+#pragma unroll
+            for (int i = 0; i < kPre; ++i) more[i] = s0 + i < p.nsplit ? src[(s0 + i) * split_stride] : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < kPre; ++i)
+                if (s0 + i < p.nsplit) o += more[i] * mlw[(s0 + i) * 64 + wave * 16 + li].x;
+        }
     const int lrow = pass * 64 + wave * 16 + li;
     if (lrow < rows_here) {
         const int m2 = row_base + lrow;
@@ -1171,17 +1178,20 @@ __device__ __forceinline__ void segment_masses_block(const Plan& p, const SegTab
     }
 }
 
-// The same for one wavefront on its own, for a query with at most 64 slots and a register table: lane k adds
-// up column k, lane s then collects segment s's slots — the same sums in the same order, no barrier.
+// The same for one wavefront on its own, for a query with at most 128 slots and a register table: lane k adds
+// up columns k and k + 64, lane s then collects segment s's slots — the same sums in the same order, no barrier.
 template <class F>
 __device__ __forceinline__ void segment_masses_wave(const Plan& p, const RegSegTable& t, const float* parts, int lane, F on_mass) {
     const unsigned total = (unsigned)t.total;
     const unsigned nsub = (unsigned)(p.nsplit * p.groups);
     const int nparts = p.units_per_b * p.nrb;
     constexpr int kGroup = 8;
-    float c = 0.f;                                   // column `lane`
-    if (lane < p.slots)
-        for (int g0 = 0; g0 < nparts; g0 += kGroup) c += group_sum(parts + g0 * p.slots + lane, p.slots, min(kGroup, nparts - g0));
+    float c[2] = {0.f, 0.f};                         // columns lane, lane + 64
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+        if (lane + 64 * j < p.slots)
+            for (int g0 = 0; g0 < nparts; g0 += kGroup)
+                c[j] += group_sum(parts + g0 * p.slots + lane + 64 * j, p.slots, min(kGroup, nparts - g0));
     // sub-splits that own at least one tile (a split between a segment's first and last may own none)
     const bool owns = lane < (int)nsub && split_begin(total, nsub, lane) < split_begin(total, nsub, lane + 1);
     const unsigned long long owns_mask = __ballot(owns);
@@ -1192,8 +1202,9 @@ __device__ __forceinline__ void segment_masses_wave(const Plan& p, const RegSegT
     float m = 0.f;
     for (int d = 0; d <= span; ++d) {
         const int sp = s0 + d;
-        const float cv = __shfl(c, (lane + sp) & (kWave - 1));       // slot = segment + sub-split
-        if (has_tiles && sp <= s1 && ((owns_mask >> sp) & 1)) m += cv;
+        const int slot = lane + sp;                                  // slot = segment + sub-split, < 128
+        const float c_lo = __shfl(c[0], slot & (kWave - 1)), c_hi = __shfl(c[1], slot & (kWave - 1));
+        if (has_tiles && sp <= s1 && ((owns_mask >> sp) & 1)) m += slot < kWave ? c_lo : c_hi;
     }
     if (lane < t.n) on_mass(lane, m);
 }
@@ -1301,7 +1312,7 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
     // With few candidates one wavefront finishes alone: the others leave, and the barriers of the stages
     // below (which only wait for wavefronts that are still running) cost nothing.
     const int nthr = n_cand <= 2 * kWave ? kWave : kEpiThreads;
-    if (nthr == kWave && p.slots <= kWave && a.seg_stride <= kWave) {
+    if (nthr == kWave && p.slots <= 2 * kWave && a.seg_stride <= kWave) {
         // small query: the first wavefront also does the masses, from a table in its registers
         __syncthreads();                             // publishes the rows above
         if (tid >= kWave) return;

@@ -270,10 +270,21 @@ __device__ inline bool select_wave64(const SelectWaveArgs& s, int* n_keep_out, i
             rank += (((uint64_t)hj << 32) | lj) > key;
         }
     } else {
+        // Unequal lengths: the quotient score/len in fp64 orders exactly as the cross products of ranks_before do —
+        // two different cross products (a 24-bit significand times an integer below 2^24 each) make quotients
+        // that differ by more than 2^-48 of their size, far above the quotient's rounding, and equal ones give
+        // the same quotient — so every lane divides once and the loop compares, without branches.
+        const double q = (double)sc / (double)ln_rank;
+        const int q_lo = (int)(uint32_t)__builtin_bit_cast(uint64_t, q), q_hi = (int)(uint32_t)(__builtin_bit_cast(uint64_t, q) >> 32);
+        const uint32_t low = ((uint32_t)(s.stride - 1 - c) << 6) | (uint32_t)(63 - lane);   // lower slot, then earlier position
+        const bool wide = s.stride > (1 << 26);                                               // `low` would not hold the slot
         for (int j = 0; j < n; ++j) {
-            const float sj = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sc), j));
-            const int lj = __builtin_amdgcn_readlane(ln_rank, j), cj = __builtin_amdgcn_readlane(c, j);
-            rank += (j != lane) && ranks_before(sj, lj, cj, j, sc, ln_rank, c, lane);
+            const uint64_t bits = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(q_hi, j) << 32) |
+                                  (uint32_t)__builtin_amdgcn_readlane(q_lo, j);
+            const double qj = __builtin_bit_cast(double, bits);
+            const int cj = __builtin_amdgcn_readlane(c, j);
+            const bool tie_first = wide ? (cj != c ? cj < c : j < lane) : (uint32_t)__builtin_amdgcn_readlane((int)low, j) > low;
+            rank += (int)((qj > q) | ((qj == q) & tie_first));
         }
     }
     const int k = min(s.keep, n);
