@@ -265,9 +265,13 @@ __device__ inline bool select_wave64(const SelectWaveArgs& s, int* n_keep_out, i
         u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;
         const uint32_t low = ((uint32_t)(s.stride - 1 - c) << 6) | (uint32_t)(63 - lane);     // stride <= 2^26
         const uint64_t key = ((uint64_t)u << 32) | low;
-        for (int j = 0; j < n; ++j) {
-            const uint32_t hj = (uint32_t)__builtin_amdgcn_readlane((int)u, j), lj = (uint32_t)__builtin_amdgcn_readlane((int)low, j);
-            rank += (((uint64_t)hj << 32) | lj) > key;
+        for (int j0 = 0; j0 < n; j0 += 4) {          // four at a time: their lane reads and compares overlap
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int j = j0 + i;                // lanes past n are read and not counted
+                const uint32_t hj = (uint32_t)__builtin_amdgcn_readlane((int)u, j & 63), lj = (uint32_t)__builtin_amdgcn_readlane((int)low, j & 63);
+                rank += (int)((j < n) & ((((uint64_t)hj << 32) | lj) > key));
+            }
         }
     } else {
         // Unequal lengths: the quotient score/len in fp64 orders exactly as the cross products of ranks_before do —
@@ -277,14 +281,27 @@ __device__ inline bool select_wave64(const SelectWaveArgs& s, int* n_keep_out, i
         const double q = (double)sc / (double)ln_rank;
         const int q_lo = (int)(uint32_t)__builtin_bit_cast(uint64_t, q), q_hi = (int)(uint32_t)(__builtin_bit_cast(uint64_t, q) >> 32);
         const uint32_t low = ((uint32_t)(s.stride - 1 - c) << 6) | (uint32_t)(63 - lane);   // lower slot, then earlier position
-        const bool wide = s.stride > (1 << 26);                                               // `low` would not hold the slot
-        for (int j = 0; j < n; ++j) {
+        auto lane_quotient = [&](int j) {
             const uint64_t bits = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(q_hi, j) << 32) |
                                   (uint32_t)__builtin_amdgcn_readlane(q_lo, j);
-            const double qj = __builtin_bit_cast(double, bits);
-            const int cj = __builtin_amdgcn_readlane(c, j);
-            const bool tie_first = wide ? (cj != c ? cj < c : j < lane) : (uint32_t)__builtin_amdgcn_readlane((int)low, j) > low;
-            rank += (int)((qj > q) | ((qj == q) & tie_first));
+            return __builtin_bit_cast(double, bits);
+        };
+        if (s.stride <= (1 << 26)) {
+            for (int j0 = 0; j0 < n; j0 += 4) {      // four at a time: their lane reads and compares overlap
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int j = j0 + i;            // < 64 + 3; lanes past n are read and not counted
+                    const double qj = lane_quotient(j & 63);
+                    const bool tie_first = (uint32_t)__builtin_amdgcn_readlane((int)low, j & 63) > low;
+                    rank += (int)((j < n) & ((qj > q) | ((qj == q) & tie_first)));
+                }
+            }
+        } else {                                     // `low` would not hold the slot
+            for (int j = 0; j < n; ++j) {
+                const double qj = lane_quotient(j);
+                const int cj = __builtin_amdgcn_readlane(c, j);
+                rank += (int)((qj > q) | ((qj == q) & (cj != c ? cj < c : j < lane)));
+            }
         }
     }
     const int k = min(s.keep, n);
