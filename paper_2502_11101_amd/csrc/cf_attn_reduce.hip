@@ -1,0 +1,412 @@
+// What follows the attention kernel of a call on the 16-bit path: the merge of the splits' partial outputs
+// (with the slot partial masses as a by-product), the per-segment mass reduction, and the fused layer epilogue
+// (masses, S += mass, ranking, allocation, next segment table).
+#include "cf_attn_plan.h"
+
+namespace cf {
+using namespace attn;
+namespace {
+
+// Second kernel: one workgroup per (unit, 64-row pass, eighth of the output channels) merges the
+// splits' partial outputs and writes its output rows; the eight workgroups of a (unit, pass) also share
+// the reduction, over the pass's 64 rows, of every (segment, split) slot's (max, sum) pairs to
+// sum * exp2(max - row max) / row sum, which the mass kernel then only has to add up.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan p) {
+    __shared__ float2 mlw[kMaxSplit * 64];       // (m, l) per split and row, then the split's weight in .x
+    __shared__ float2 rstat[64];                 // (max, 1/sum) per row of this pass
+    constexpr int kPre = 8;                      // splits whose partial outputs are fetched before the statistics are ready
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const int li = lane & 15, lg = lane >> 4;
+    char* ws = static_cast<char*>(a.workspace);
+    const int hq = a.n_q_heads, group = hq / a.n_kv_heads;
+    const int dbq = blockIdx.x & 7;
+    const int pass = (blockIdx.x >> 3) % p.nrb;
+    const int unit = blockIdx.x / (8 * p.nrb);
+    const int rg = unit % p.n_rg;
+    const int hkv = (unit / p.n_rg) % a.n_kv_heads;
+    const int b = unit / p.units_per_b;
+    const int q0 = a.q_off[b], q1 = a.q_off[b + 1];
+    const float2* ml = reinterpret_cast<const float2*>(ws + p.off_ml) + (int64_t)unit * p.nsplit * p.rows_wg + pass * 64;
+    const f32x4* opart = reinterpret_cast<const f32x4*>(ws + p.off_opart) + (int64_t)unit * p.nsplit * p.rows_wg * (kD / 4);
+    const int blk = pass * kWaves + wave;                      // row block inside the workgroup tile
+    const f32x4* src = opart + ((int64_t)blk * 8 + dbq) * kWave + lane;
+    const int64_t split_stride = (int64_t)p.rows_wg / 16 * 8 * kWave;
+    const float2* massml = reinterpret_cast<const float2*>(ws + p.off_massml) + (int64_t)unit * p.slots * p.rows_wg + pass * 64 + lane;
+    const int k_first = dbq * kWaves + wave, k_step = 8 * kWaves;
+
+    // Everything this workgroup reads is requested up front — row statistics, partial outputs of the
+    // first splits, the first slot statistics — so the three round trips to memory overlap.
+    for (int idx = tid; idx < p.nsplit * 64; idx += kThreads) mlw[idx] = ml[(idx >> 6) * p.rows_wg + (idx & 63)];
+    // (a wavefront whose 16 rows are all padding reads what an earlier call left there: in bounds, never stored;
+    // not waiting for the query's length here saves a round trip)
+    f32x4 pre[kPre];
+#pragma unroll
+    for (int s = 0; s < kPre; ++s) pre[s] = s < p.nsplit ? src[s * split_stride] : f32x4{0.f, 0.f, 0.f, 0.f};
+    float2 sv[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int k = k_first + j * k_step;
+        sv[j] = k < p.slots ? massml[(int64_t)k * p.rows_wg] : make_float2(0.f, 0.f);
+    }
+    const int tq = min(q1 - q0, a.max_tq);
+    const int n_rows = group * tq;
+    const int row_base = rg * p.blocks_rg * 16;
+    const int rows_here = min(p.blocks_rg * 16, n_rows - row_base);
+    const bool blk_has_rows = pass * 64 + wave * 16 < rows_here;
+    __syncthreads();
+    if (tid < 64) {
+        float m = -INFINITY;
+        for (int s = 0; s < p.nsplit; ++s) m = fmaxf(m, mlw[s * 64 + tid].x);
+        const float ms = m == -INFINITY ? 0.f : m;
+        float z = 0.f;
+        for (int s = 0; s < p.nsplit; ++s) z += mlw[s * 64 + tid].y * exp2f(mlw[s * 64 + tid].x - ms);
+        const float iz = z > 0.f ? 1.f / z : 0.f;
+        for (int s = 0; s < p.nsplit; ++s) mlw[s * 64 + tid].x = exp2f(mlw[s * 64 + tid].x - ms) * iz;
+        rstat[tid] = make_float2(ms, pass * 64 + tid < rows_here ? iz : 0.f);    // padding rows carry no mass
+    }
+    __syncthreads();
+    f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < kPre; ++s)
+        if (s < p.nsplit) o += pre[s] * mlw[s * 64 + wave * 16 + li].x;
+    if (blk_has_rows)
+        for (int s0 = kPre; s0 < p.nsplit; s0 += kPre) {         // further splits, eight loads at a time
+            f32x4 more[kPre];
+#pragma unroll
+            for (int i = 0; i < kPre; ++i) more[i] = s0 + i < p.nsplit ? src[(s0 + i) * split_stride] : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < kPre; ++i)
+                if (s0 + i < p.nsplit) o += more[i] * mlw[(s0 + i) * 64 + wave * 16 + li].x;
+        }
+    const int lrow = pass * 64 + wave * 16 + li;
+    if (lrow < rows_here) {
+        const int m2 = row_base + lrow;
+        const int gi = m2 / tq, t = m2 - gi * tq;
+        uint16_t* op = static_cast<uint16_t*>(a.out) + (((int64_t)q0 + t) * hq + hkv * group + gi) * kD + 16 * dbq + 4 * lg;
+        uint2 pk;
+        pk.x = Mma<DT>::pack(o[0], o[1]);
+        pk.y = Mma<DT>::pack(o[2], o[3]);
+        *reinterpret_cast<uint2*>(op) = pk;
+    }
+    // slot partials: slot k = segment + split; slots no split wrote this call hold stale pairs and
+    // give meaningless numbers that the mass kernel never reads
+    if (a.mass != nullptr) {
+        float* masspart = reinterpret_cast<float*>(ws + p.off_masspart) + ((int64_t)unit * p.nrb + pass) * p.slots;
+        const float2 st = rstat[lane];
+        auto reduce = [&](int k, float2 v) {
+            const float c = wave_sum_dpp(st.y > 0.f ? v.y * exp2f(v.x - st.x) * st.y : 0.f);
+            if (lane == 0 && k < p.slots) masspart[k] = c;
+        };
+#pragma unroll
+        for (int j = 0; j < 2; ++j) reduce(k_first + j * k_step, sv[j]);
+        for (int k = k_first + 2 * k_step; k < p.slots; k += k_step) reduce(k, massml[(int64_t)k * p.rows_wg]);
+    }
+}
+
+// Per-segment attention mass of one query, by the whole workgroup, in a fixed order: first every
+// slot's partials are added over the (unit, pass) parts, then a segment adds the slots of the
+// splits that hold its tiles.  A split between a segment's first and last may own no tile at
+// all (fewer tiles than splits): its slot was not written by this call and is skipped.
+// `parts`: [nparts][slots] floats, in LDS (stage == nullptr; overwritten) or in memory (stage: kMassStage floats
+// of LDS).  `on_mass(s, m)` is called once per segment.  Both forms add in the same order: the parts of a
+// column in groups of eight, each group from zero, then the group sums from zero.
+// Sum of n <= 8 values `pitch` floats apart, added in order from zero.  A full group's loads all go out
+// before the first add (a loop with a run-time bound would wait for each in turn).
+__device__ __forceinline__ float group_sum(const float* x, int pitch, int n) {
+    float gs = 0.f;
+    if (n == 8) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = x[i * pitch];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) gs += v[i];
+    } else {
+        for (int i = 0; i < n; ++i) gs += x[i * pitch];
+    }
+    return gs;
+}
+
+struct MassScratch {
+    float colsum[kMaxSegs + 2 * kMaxSplit];
+    int32_t sub_begin[2 * kMaxSplit + 1];
+};
+constexpr int kMassStage = 4096;            // floats of partials staged per round by the stand-alone mass kernel
+
+template <class F>
+__device__ __forceinline__ void segment_masses_block(const Plan& p, const SegTable& tbl, float* parts, float* stage,
+                                                     MassScratch* ms, F on_mass) {
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const unsigned total = (unsigned)tbl.tile0[tbl.n];
+    const unsigned nsub = (unsigned)(p.nsplit * p.groups);
+    const int nparts = p.units_per_b * p.nrb;
+    constexpr int kGroup = 8;
+    if (stage == nullptr) {                          // partials already in LDS: one thread per (group, column), in place
+        const int ngroups = (nparts + kGroup - 1) / kGroup;
+        for (int idx = tid; idx < ngroups * p.slots; idx += nthr) {
+            const int g = idx / p.slots, k = idx - g * p.slots;
+            const float gs = group_sum(parts + g * kGroup * p.slots + k, p.slots, min(kGroup, nparts - g * kGroup));
+            parts[g * kGroup * p.slots + k] = gs;
+        }
+        __syncthreads();
+        for (int k = tid; k < p.slots; k += nthr) {
+            float c = 0.f;
+            for (int g = 0; g < ngroups; ++g) c += parts[g * kGroup * p.slots + k];
+            ms->colsum[k] = c;
+        }
+    } else {                                         // partials in memory: whole rows through LDS, many loads in flight
+        const int rows = kMassStage / p.slots / kGroup * kGroup;   // slots <= kMassStage / kGroup: whole groups per round
+        float c[2] = {0.f, 0.f};                     // this thread's columns tid, tid + nthr (slots <= 2 * nthr)
+        for (int r0 = 0; r0 < nparts; r0 += rows) {
+            const int nr = min(rows, nparts - r0);
+            __syncthreads();
+            for (int i = tid; i < nr * p.slots; i += nthr) stage[i] = parts[(int64_t)r0 * p.slots + i];
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int k = tid + j * nthr;
+                if (k < p.slots)
+                    for (int g0 = 0; g0 < nr; g0 += kGroup) c[j] += group_sum(stage + g0 * p.slots + k, p.slots, min(kGroup, nr - g0));
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (tid + j * nthr < p.slots) ms->colsum[tid + j * nthr] = c[j];
+    }
+    for (int sp = tid; sp <= (int)nsub; sp += nthr) ms->sub_begin[sp] = split_begin(total, nsub, sp);
+    __syncthreads();
+    for (int s = tid; s < tbl.n; s += nthr) {
+        const int ts = tbl.tile0[s], te = tbl.tile0[s + 1];
+        float m = 0.f;
+        if (te > ts) {
+            const int s0 = split_of(total, nsub, ts), s1 = split_of(total, nsub, te - 1);
+            for (int sp = s0; sp <= s1; ++sp)
+                if (ms->sub_begin[sp] < ms->sub_begin[sp + 1]) m += ms->colsum[s + sp];
+        }
+        on_mass(s, m);
+    }
+}
+
+// The same for one wavefront on its own, for a query with at most 128 slots and a register table: lane k adds
+// up columns k and k + 64, lane s then collects segment s's slots — the same sums in the same order, no barrier.
+template <class F>
+__device__ __forceinline__ void segment_masses_wave(const Plan& p, const RegSegTable& t, const float* parts, int lane, F on_mass) {
+    const unsigned total = (unsigned)t.total;
+    const unsigned nsub = (unsigned)(p.nsplit * p.groups);
+    const int nparts = p.units_per_b * p.nrb;
+    constexpr int kGroup = 8;
+    float c[2] = {0.f, 0.f};                         // columns lane, lane + 64
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+        if (lane + 64 * j < p.slots)
+            for (int g0 = 0; g0 < nparts; g0 += kGroup)
+                c[j] += group_sum(parts + g0 * p.slots + lane + 64 * j, p.slots, min(kGroup, nparts - g0));
+    // sub-splits that own at least one tile (a split between a segment's first and last may own none)
+    const bool owns = lane < (int)nsub && split_begin(total, nsub, lane) < split_begin(total, nsub, lane + 1);
+    const unsigned long long owns_mask = __ballot(owns);
+    const bool has_tiles = lane < t.n && t.t1 > t.t0;
+    int s0 = 0, s1 = -1;
+    if (has_tiles) { s0 = split_of(total, nsub, t.t0); s1 = split_of(total, nsub, t.t1 - 1); }
+    const int span = wave_max_i32(s1 - s0);
+    float m = 0.f;
+    for (int d = 0; d <= span; ++d) {
+        const int sp = s0 + d;
+        const int slot = lane + sp;                                  // slot = segment + sub-split, < 128
+        const float c_lo = __shfl(c[0], slot & (kWave - 1)), c_hi = __shfl(c[1], slot & (kWave - 1));
+        if (has_tiles && sp <= s1 && ((owns_mask >> sp) & 1)) m += slot < kWave ? c_lo : c_hi;
+    }
+    if (lane < t.n) on_mass(lane, m);
+}
+
+// Third kernel: per-segment attention mass, one workgroup per query; then S += mass.
+__global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p) {
+    __shared__ SegTable tbl;
+    __shared__ MassScratch ms;
+    __shared__ float stage[kMassStage];
+    const char* ws = static_cast<const char*>(a.workspace);
+    const int b = __builtin_amdgcn_readfirstlane(blockIdx.x);
+    const QueryHead qh = load_query_head(a, b, (int)threadIdx.x);
+    build_table(a, qh, &tbl, p.tile);
+    const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * p.units_per_b * p.nrb * p.slots;
+    segment_masses_block(p, tbl, const_cast<float*>(mp_b), stage, &ms, [&](int s, float m) {
+        a.mass[(int64_t)b * a.seg_stride + s] = m;
+        const int doc = tbl.doc[s];
+        if (a.score_accum && doc >= 0 && doc < a.score_stride) atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], m);
+    });
+}
+
+// Fused layer epilogue (third kernel of cf_prefill_layer): one workgroup per query computes the
+// attention mass of every segment (fixed summation order), adds it to the accumulated scores, and — when a prune step is attached —
+// ranks the candidates, allocates the survivors' positions and writes the next layer's segment
+// table, i.e. Alg. 2's "S += s; ids_sort = argsort(S); ids = prun(ids_sort)" followed by the
+// allocation of Sec. 2.5, without leaving the GPU.
+constexpr int kEpiThreads = 1024;
+
+struct PruneArgs {
+    int32_t enabled, keep, strategy, force_n_reuse, normalise_by_len, stride, pos_begin, pos_end, prefix_len,
+        doc_stored_start;
+    const int64_t* doc_tok_offset;
+    const int32_t* doc_len;
+    const int32_t* cand;
+    const int32_t* n_cand;
+    int32_t* keep_idx;
+    int32_t* n_keep;
+    int32_t* new_start;
+    int32_t* q_start;
+    int32_t* n_reuse;
+    int32_t* order;
+    cf_segment* next_segs;
+    int32_t* next_n_seg;
+};
+
+// Every per-document row of the query (scores, lengths, candidates, offsets, positions) and the slot
+// partial masses are fetched into LDS in one batch at the start: the ranking, the allocation and the
+// table rebuild then run out of LDS with workgroup barriers between them instead of a round trip
+// through memory per stage, and the results are written back at the end.
+// Dynamic LDS: 44*stride + 4*parts*slots bytes; larger problems take the stand-alone kernels.
+__global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a, Plan p, PruneArgs pr) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn_smem[];
+    __shared__ SegTable tbl;
+    __shared__ MassScratch ms;
+    __shared__ int s_int[6];
+
+    const int tid = threadIdx.x;
+    const int stride = pr.stride;
+    int64_t* l_tok = reinterpret_cast<int64_t*>(dyn_smem);
+    unsigned char* scratch = dyn_smem + (size_t)8 * stride;            // 3*stride words for ranking / allocation
+    float* l_score = reinterpret_cast<float*>(scratch + (size_t)12 * stride);
+    int32_t* l_len = reinterpret_cast<int32_t*>(l_score + stride);
+    int32_t* l_cand = l_len + stride;
+    int32_t* l_keep = l_cand + stride;
+    int32_t* l_start = l_keep + stride;
+    int32_t* l_order = l_start + stride;
+    float* l_part = reinterpret_cast<float*>(l_order + stride);
+
+    const char* ws = static_cast<const char*>(a.workspace);
+    const int b = __builtin_amdgcn_readfirstlane(blockIdx.x);
+    const int64_t off = (int64_t)b * stride;
+    const int nparts = p.units_per_b * p.nrb;
+    const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * nparts * p.slots;
+    // The first batch of row loads and slot partials goes out before anything waits for the query's scalars.
+    const bool row0 = tid < stride;
+    int64_t r_tok = 0;
+    int32_t r_len = 0, r_cand = 0, r_start = 0, r_order = 0;
+    float r_score = 0.f, r_part = 0.f;
+    if (row0) {
+        r_tok = pr.doc_tok_offset[off + tid];
+        r_len = pr.doc_len[off + tid];
+        r_cand = pr.cand[off + tid];
+        r_score = a.score_accum[off + tid];
+        r_start = pr.new_start[off + tid];
+        r_order = pr.order[off + tid];
+    }
+    if (tid < nparts * p.slots) r_part = mp_b[tid];
+    const QueryHead qh = load_query_head(a, b, (int)threadIdx.x);
+    const int n_cand = pr.n_cand[b];
+    if (tid == 0) { s_int[4] = pr.q_start[b]; s_int[5] = pr.n_reuse[b]; }
+    if (row0) {
+        l_tok[tid] = r_tok; l_len[tid] = r_len; l_cand[tid] = r_cand; l_score[tid] = r_score; l_start[tid] = r_start;
+        l_order[tid] = r_order;
+    }
+    for (int i = tid + kEpiThreads; i < stride; i += kEpiThreads) {
+        l_tok[i] = pr.doc_tok_offset[off + i];
+        l_len[i] = pr.doc_len[off + i];
+        l_cand[i] = pr.cand[off + i];
+        l_score[i] = a.score_accum[off + i];
+        l_start[i] = pr.new_start[off + i];
+        l_order[i] = pr.order[off + i];
+    }
+    if (tid < nparts * p.slots) l_part[tid] = r_part;
+    for (int i = tid + kEpiThreads; i < nparts * p.slots; i += kEpiThreads) l_part[i] = mp_b[i];
+    // With few candidates one wavefront finishes alone: the others leave, and the barriers of the stages
+    // below (which only wait for wavefronts that are still running) cost nothing.
+    const int nthr = n_cand <= 2 * kWave ? kWave : kEpiThreads;
+    if (nthr == kWave && p.slots <= 2 * kWave && a.seg_stride <= kWave) {
+        // small query: the first wavefront also does the masses, from a table in its registers
+        __syncthreads();                             // publishes the rows above
+        if (tid >= kWave) return;
+        const RegSegTable rtbl = build_reg_table(a, qh, tid, p.tile);
+        segment_masses_wave(p, rtbl, l_part, tid, [&](int s, float m) {
+            a.mass[(int64_t)b * a.seg_stride + s] = m;
+            const int doc = qh.seg.doc;              // this lane's entry
+            if (doc >= 0 && doc < stride) atomicAdd(&l_score[doc], m);
+        });
+        __syncthreads();
+    } else {
+        build_table(a, qh, &tbl, p.tile);            // its barriers also publish the rows above
+        segment_masses_block(p, tbl, l_part, nullptr, &ms, [&](int s, float m) {
+            a.mass[(int64_t)b * a.seg_stride + s] = m;
+            const int doc = tbl.doc[s];
+            if (doc >= 0 && doc < stride) atomicAdd(&l_score[doc], m);
+        });
+        __syncthreads();
+    }
+    if (tid >= nthr) return;
+    for (int i = tid; i < stride; i += nthr) a.score_accum[off + i] = l_score[i];
+    int k = min(pr.keep, n_cand);
+    bool done = false;
+    if (n_cand <= kWave) {                               // the usual case: everything in one wavefront's registers
+        SelectWaveArgs sw;
+        sw.score = l_score; sw.len = l_len; sw.cand = l_cand; sw.tok = l_tok; sw.keep_idx = l_keep; sw.new_start = l_start;
+        sw.order = l_order; sw.n = n_cand; sw.keep = pr.keep; sw.stride = stride; sw.normalise_by_len = pr.normalise_by_len;
+        sw.strategy = pr.strategy; sw.force_n_reuse = pr.force_n_reuse; sw.pos_begin = pr.pos_begin; sw.pos_end = pr.pos_end;
+        sw.prefix_len = pr.prefix_len; sw.doc_stored_start = pr.doc_stored_start; sw.q_stored_start = a.q_stored_start;
+        sw.q_lo = qh.q0; sw.q_hi = qh.q0 + qh.tq_raw; sw.seg_stride = a.seg_stride;
+        done = select_wave64(sw, pr.n_keep + b, &s_int[4], &s_int[5], pr.next_segs + (int64_t)b * a.seg_stride,
+                             pr.next_n_seg + b);
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (!done) {
+        k = prune_topk_block(l_score, pr.normalise_by_len ? l_len : nullptr, l_cand, n_cand, pr.keep, stride, l_keep,
+                             a.dev_flag, scratch, &s_int[3], nthr);
+        if (tid == 0) pr.n_keep[b] = k;
+        __syncthreads();
+        assign_positions_block(l_len, l_keep, k, stride, pr.pos_begin, pr.pos_end, pr.strategy, pr.force_n_reuse, l_start,
+                               &s_int[4], &s_int[5], l_order, a.dev_flag, scratch, s_int, nthr);
+        __syncthreads();
+        gather_segments_block(l_tok, l_len, l_order, k, l_start, s_int[4], qh.q0, qh.q0 + qh.tq_raw, stride, pr.prefix_len,
+                              pr.doc_stored_start, a.q_stored_start, pr.next_segs + (int64_t)b * a.seg_stride,
+                              pr.next_n_seg + b, a.seg_stride, a.dev_flag, nthr);
+    }
+    for (int i = tid; i < stride; i += nthr) {
+        if (i < k) pr.keep_idx[off + i] = l_keep[i];
+        pr.new_start[off + i] = l_start[i];
+        pr.order[off + i] = l_order[i];
+    }
+    if (tid == 0) { pr.q_start[b] = s_int[4]; pr.n_reuse[b] = s_int[5]; }
+}
+
+}  // namespace
+
+void launch_combine(const AttnArgs& a, const Plan& p, hipStream_t s) {
+    const dim3 grid((unsigned)(p.units * p.nrb * 8)), block(kThreads);
+    if (a.dtype == CF_BF16) hipLaunchKernelGGL((attn_combine_kernel<CF_BF16>), grid, block, 0, s, a, p);
+    else hipLaunchKernelGGL((attn_combine_kernel<CF_F16>), grid, block, 0, s, a, p);
+}
+
+void launch_mass(const AttnArgs& a, const Plan& p, hipStream_t s) {
+    hipLaunchKernelGGL(attn_mass_kernel, dim3((unsigned)a.batch), dim3(kThreads), 0, s, a, p);
+}
+
+static size_t epilogue_lds_bytes(const Plan& p, const cf_prune_step* prune) {
+    return (size_t)44 * prune->stride + (size_t)4 * p.units_per_b * p.nrb * p.slots;
+}
+
+bool epilogue_fits(const Plan& p, const cf_prune_step* prune) { return epilogue_lds_bytes(p, prune) <= 60 * 1024; }
+
+void launch_epilogue(const AttnArgs& a, const Plan& p, const cf_prune_step* prune, hipStream_t s) {
+    PruneArgs pr;
+    pr.enabled = 1; pr.keep = prune->keep; pr.strategy = prune->strategy; pr.force_n_reuse = prune->force_n_reuse;
+    pr.normalise_by_len = prune->normalise_by_len; pr.stride = prune->stride; pr.pos_begin = prune->pos_begin;
+    pr.pos_end = prune->pos_end; pr.prefix_len = prune->prefix_len; pr.doc_stored_start = prune->doc_stored_start;
+    pr.doc_tok_offset = prune->doc_tok_offset; pr.doc_len = prune->doc_len; pr.cand = prune->cand;
+    pr.n_cand = prune->n_cand; pr.keep_idx = prune->keep_idx; pr.n_keep = prune->n_keep;
+    pr.new_start = prune->new_start; pr.q_start = prune->q_start; pr.n_reuse = prune->n_reuse;
+    pr.order = prune->order; pr.next_segs = prune->next_segs; pr.next_n_seg = prune->next_n_seg;
+    hipLaunchKernelGGL(layer_epilogue_kernel, dim3(a.batch), dim3(kEpiThreads), epilogue_lds_bytes(p, prune), s, a, p, pr);
+}
+
+}  // namespace cf
