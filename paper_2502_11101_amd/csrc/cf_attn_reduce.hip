@@ -22,13 +22,15 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     const int wave = tid / kWave;
     const int li = lane & 15, lg = lane >> 4;
     char* ws = static_cast<char*>(a.workspace);
-    const int hq = a.n_q_heads, group = hq / a.n_kv_heads;
+    const int hq = a.n_q_heads, group = (int)div_exact((unsigned)hq, (unsigned)a.n_kv_heads);
     const int dbq = blockIdx.x & 7;
-    const int pass = (blockIdx.x >> 3) % p.nrb;
-    const int unit = blockIdx.x / (8 * p.nrb);
-    const int rg = unit % p.n_rg;
-    const int hkv = (unit / p.n_rg) % a.n_kv_heads;
-    const int b = unit / p.units_per_b;
+    const int up = (int)(blockIdx.x >> 3);                                            // (unit, pass)
+    const int unit = (int)div_exact((unsigned)up, (unsigned)p.nrb);
+    const int pass = up - unit * p.nrb;
+    const int uh = (int)div_exact((unsigned)unit, (unsigned)p.n_rg);                  // (query, kv head)
+    const int rg = unit - uh * p.n_rg;
+    const int b = (int)div_exact((unsigned)uh, (unsigned)a.n_kv_heads);
+    const int hkv = uh - b * a.n_kv_heads;
     const int q0 = a.q_off[b], q1 = a.q_off[b + 1];
     const float2* ml = reinterpret_cast<const float2*>(ws + p.off_ml) + (int64_t)unit * p.nsplit * p.rows_wg + pass * 64;
     const f32x4* opart = reinterpret_cast<const f32x4*>(ws + p.off_opart) + (int64_t)unit * p.nsplit * p.rows_wg * (kD / 4);
@@ -85,7 +87,7 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     const int lrow = pass * 64 + wave * 16 + li;
     if (lrow < rows_here) {
         const int m2 = row_base + lrow;
-        const int gi = m2 / tq, t = m2 - gi * tq;
+        const int gi = (int)div_exact((unsigned)m2, (unsigned)tq), t = m2 - gi * tq;
         uint16_t* op = static_cast<uint16_t*>(a.out) + (((int64_t)q0 + t) * hq + hkv * group + gi) * kD + 16 * dbq + 4 * lg;
         uint2 pk;
         pk.x = Mma<DT>::pack(o[0], o[1]);
@@ -147,7 +149,7 @@ __device__ __forceinline__ void segment_masses_block(const Plan& p, const SegTab
     if (stage == nullptr) {                          // partials already in LDS: one thread per (group, column), in place
         const int ngroups = (nparts + kGroup - 1) / kGroup;
         for (int idx = tid; idx < ngroups * p.slots; idx += nthr) {
-            const int g = idx / p.slots, k = idx - g * p.slots;
+            const int g = (int)div_exact((unsigned)idx, (unsigned)p.slots), k = idx - g * p.slots;
             const float gs = group_sum(parts + g * kGroup * p.slots + k, p.slots, min(kGroup, nparts - g * kGroup));
             parts[g * kGroup * p.slots + k] = gs;
         }

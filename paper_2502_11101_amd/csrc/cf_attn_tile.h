@@ -234,7 +234,7 @@ __device__ __forceinline__ void load_q_fragments(const AttnArgs& a, int q0, int 
     for (int rb = 0; rb < NRB; ++rb) {
         const int m = row_base + (first_blk + rb) * 16 + li;
         const bool valid = m < row_limit;
-        const int gi = valid ? m / tq : 0;
+        const int gi = valid ? (int)div_exact((unsigned)m, (unsigned)tq) : 0;
         const int t = valid ? m - gi * tq : 0;
         trow[rb] = valid ? t : 0x7fffffff;
         const uint16_t* qp = static_cast<const uint16_t*>(a.q) + (((int64_t)q0 + t) * a.n_q_heads + hkv * group + gi) * kD + 8 * lg;
