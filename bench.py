@@ -119,6 +119,47 @@ def bench_assemble(args) -> int:
     final_len = torch.zeros(1, dtype=torch.int32, device="cuda")
     max_seg = int(max(st.doc_lens.max(), cfg.prefix_len, cfg.tq))
 
+    if args.path == "reposition":
+        # the documents' keys of one layer moved to their allocated positions, out of place (Eq. 5 as its own pass)
+        doc_segs = cf.segments_to_device(cf.segments_array(
+            [(int(st.doc_off[d]), int(st.doc_lens[d]), cfg.doc_stored_start, cfg.doc_stored_start + 7 + 3 * j, cf.CF_SEG_DOC, j)
+             for j, d in enumerate(st.query_docs[0])]))
+        n_docs = len(st.query_docs[0])
+        moved = int(np.sum(st.doc_lens[st.query_docs[0]]))
+        outs = [torch.empty_like(L["k_store"]) for L in layers]
+
+        def rstep(i: int) -> None:
+            cf.cf_reposition_keys(desc, layers[i % n_buf]["k_store"], outs[i % n_buf], doc_segs, n_docs, st.n_store_tokens,
+                                  max_seg, pb.dev_flag)
+
+        for i in range(args.warmup):
+            rstep(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for i in range(args.steps):
+            rstep(args.warmup + i)
+        e1.record()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        assert pb.flags() == 0
+        ms_per_step = 1e3 * elapsed / args.steps
+        call_ms = e0.elapsed_time(e1) / args.steps
+        nbytes = moved * 2 * g.n_kv_heads * g.head_dim * 2          # read + write of every moved key
+        achieved = nbytes / (call_ms * 1e-3) / 1e9
+        print(json.dumps({
+            "metric": "key tokens/s per layer, stand-alone re-positioning", "value": moved / (ms_per_step * 1e-3),
+            "unit": "key tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": g.dtype, "data": "synthetic",
+            "config": {"workload": "llama2_7b_stack documents, one layer", "documents": n_docs, "key_tokens_per_step": moved,
+                       "kv_heads": g.n_kv_heads, "head_dim": g.head_dim, "layer_buffers": n_buf, "store_layout": args.store_layout,
+                       "step": "cf_reposition_keys, out of place"},
+            "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                         "traffic": None, "kernel": "reposition_kernel", "ms_per_launch": call_ms,
+                         "algorithmic_bytes_per_launch": nbytes}}))
+        return 0
+
     def step(i: int) -> None:
         L, (kf, vf) = layers[i % n_buf], finals[i % n_buf]
         cf.cf_assemble_cache(desc, L["k_store"], L["v_store"], st.n_store_tokens, L["k_self"], L["v_self"], pb.q_off, pb.segs,
@@ -214,10 +255,11 @@ def main() -> int:
     ap.add_argument("--store-layout", choices=["head", "token"], default="head",
                     help="layout of the cache store: head-major [kv head][token][d] (default, the layout the "
                          "store is meant to be kept in) or token-major [token][kv head][d]")
-    ap.add_argument("--path", choices=["prefill", "assemble", "decode"], default="prefill",
+    ap.add_argument("--path", choices=["prefill", "assemble", "decode", "reposition"], default="prefill",
                     help="prefill: the per-layer hot path (the headline metric).  assemble: Alg. 2 Phase 2, "
                          "cf_assemble_cache of one layer of the final survivor set into a decode cache.  decode: one "
-                         "decode step's attention (one new token) over an assembled cache, Alg. 2 Phase 3")
+                         "decode step's attention (one new token) over an assembled cache, Alg. 2 Phase 3.  reposition: "
+                         "the stand-alone Eq. 5 call, cf_reposition_keys, out of place over the documents of one layer")
     ap.add_argument("--assemble-docs", type=int, default=5, help="surviving documents per query for --path assemble")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only 10 elementwise copies of 1 GiB (read 1 GiB + write 1 GiB each): the known-size "
@@ -246,7 +288,7 @@ def main() -> int:
                                                "write_bytes": dst.numel() * 4}}))
         return 0
     cf.load()
-    if args.path in ("assemble", "decode"):
+    if args.path in ("assemble", "decode", "reposition"):
         return bench_assemble(args)
 
     cfg = wl.CONFIGS[args.workload]

@@ -61,7 +61,7 @@ template <int DT, int PAIRING>
 __global__ __launch_bounds__(kThreads) void reposition_kernel(
     const void* k_in, void* k_out, const cf_segment* __restrict__ segs,
     int64_t n_store_tokens, int n_kv_heads, int head_dim, int64_t tok_stride, int64_t head_stride, RopeFreq freq,
-    int32_t* dev_flag) {
+    int32_t* dev_flag, int tok_per_block) {
     __shared__ float2 cs[kMaxHalf];
     const cf_segment seg = segs[blockIdx.x];
     const int half = head_dim >> 1;
@@ -75,13 +75,13 @@ __global__ __launch_bounds__(kThreads) void reposition_kernel(
 
     const int items_per_head = half / 8;                 // head_dim % 16 == 0 checked on the host
     const int items_per_tok = n_kv_heads * items_per_head;
-    for (int tok0 = blockIdx.y * kTokPerBlock; tok0 < seg.len; tok0 += gridDim.y * kTokPerBlock) {
-        const int ntok = min(kTokPerBlock, seg.len - tok0);
+    for (int tok0 = blockIdx.y * tok_per_block; tok0 < seg.len; tok0 += gridDim.y * tok_per_block) {
+        const int ntok = min(tok_per_block, seg.len - tok0);
         const int n_items = ntok * items_per_tok;
         for (int it = threadIdx.x; it < n_items; it += kThreads) {
-            const int tok = it / items_per_tok;
+            const int tok = (int)div_exact((unsigned)it, (unsigned)items_per_tok);
             const int r = it - tok * items_per_tok;
-            const int head = r / items_per_head;
+            const int head = (int)div_exact((unsigned)r, (unsigned)items_per_head);
             const int j = r - head * items_per_head;
             const int64_t base = (seg.tok_offset + tok0 + tok) * tok_stride + (int64_t)head * head_stride;
             float a[8], b[8];
@@ -125,7 +125,10 @@ template <int DT>
 cf_status launch_dt(const cf_layer_desc* d, const RopeFreq& f, const void* k_in, void* k_out,
                     const cf_segment* segs, int32_t n_seg, int64_t n_store_tokens, int32_t max_seg_len,
                     int32_t* dev_flag, hipStream_t s) {
-    int sweeps = (max_seg_len + kTokPerBlock - 1) / kTokPerBlock;
+    // tokens per block and sweep: few enough that even a short table fills the chip several times over
+    int64_t tpb = (int64_t)n_seg * max_seg_len / (256 * 8);
+    tpb = tpb < 2 ? 2 : (tpb > kTokPerBlock ? kTokPerBlock : tpb);
+    int sweeps = (int)((max_seg_len + tpb - 1) / tpb);
     // enough blocks to cover the chip a few times over, no more
     const int64_t want = 256 * 8;
     int64_t cap = (want + n_seg - 1) / n_seg;
@@ -137,11 +140,11 @@ cf_status launch_dt(const cf_layer_desc* d, const RopeFreq& f, const void* k_in,
     if (d->rope_pairing == CF_ROPE_HALF)
         hipLaunchKernelGGL((reposition_kernel<DT, CF_ROPE_HALF>), grid, dim3(kThreads), 0, s, k_in, k_out,
                            segs, n_store_tokens, d->n_kv_heads, d->head_dim, store_token_stride(d), store_head_stride(d), f,
-                           dev_flag);
+                           dev_flag, (int)tpb);
     else
         hipLaunchKernelGGL((reposition_kernel<DT, CF_ROPE_INTERLEAVED>), grid, dim3(kThreads), 0, s, k_in,
                            k_out, segs, n_store_tokens, d->n_kv_heads, d->head_dim, store_token_stride(d),
-                           store_head_stride(d), f, dev_flag);
+                           store_head_stride(d), f, dev_flag, (int)tpb);
     CF_HIP(hipGetLastError());
     return CF_OK;
 }
@@ -213,9 +216,9 @@ __global__ __launch_bounds__(kThreads) void assemble_kernel(AssembleArgs a, Rope
         const int ntok = min(tok_per_block, vis - tok0);
         const int n_items = ntok * items_per_tok;
         for (int it = tid; it < n_items; it += kThreads) {
-            const int tok = it / items_per_tok;
+            const int tok = (int)div_exact((unsigned)it, (unsigned)items_per_tok);
             const int r = it - tok * items_per_tok;
-            const int head = r / items_per_head;
+            const int head = (int)div_exact((unsigned)r, (unsigned)items_per_head);
             const int j = r - head * items_per_head;
             const int64_t src = (seg.tok_offset + tok0 + tok) * in_ts + (int64_t)head * in_hs;
             const int64_t dst = (out0 + tok0 + tok) * a.final_ts + (int64_t)head * a.final_hs;
