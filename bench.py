@@ -242,6 +242,95 @@ def bench_assemble(args) -> int:
     return 0
 
 
+def bench_stack(args) -> int:
+    """Alg. 2 Phase 1 over a whole layer stack (LLaMA-2-7B geometry, 32 layers, 30 documents x 160 tokens, a prune
+    event after layers 8/16/24/32 that keeps 60 % of the candidates, positions re-allocated each time): one step is
+    the initial allocation plus 32 cf_prefill_layer calls, every layer with K/V buffers of its own.  The roofline
+    entry adds up the algorithmic K+V bytes of all attention launches of a step over the sum of their durations."""
+    import math
+
+    import torch
+    from paper_2502_11101_amd import binding as cf
+    from paper_2502_11101_amd import pipeline as pl
+    from paper_2502_11101_amd import workloads as wl
+
+    cfg = wl.CONFIGS["llama2_7b_stack"]
+    g = cfg.geometry
+    st = wl.build_structure(cfg)
+    ts, hs = pl.store_strides(st.n_store_tokens, g.n_kv_heads, g.head_dim, args.store_layout)
+    desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions,
+                        store_token_stride=ts, store_head_stride=hs)
+    pb = pl.PrefillBatch(desc, st.doc_off[:-1][st.query_docs], st.doc_lens[st.query_docs], cfg.tq, cfg.prefix_len,
+                         cfg.doc_stored_start, st.n_store_tokens)
+    layers = []
+    for layer in range(cfg.n_layers):
+        t = wl.build_layer(cfg, st, layer)
+        layers.append({k: (pl.store_to_device(v, g.dtype, args.store_layout) if k in ("k_store", "v_store")
+                           else pl.to_device(v, g.dtype)) for k, v in t.items()})
+    out = torch.empty_like(layers[0]["q"])
+    keeps, alive, k = {}, [], cfg.docs_per_query
+    for layer in range(cfg.n_layers):
+        alive.append(k)
+        if layer in cfg.prune_layers:
+            k = max(1, math.ceil(cfg.keep_frac * k))
+            keeps[layer] = k
+    doc_len = int(st.doc_lens[0])
+    kv_tokens = sum(cfg.prefix_len + n * doc_len + cfg.tq for n in alive)
+    bytes_per_token = 2 * g.n_kv_heads * g.head_dim * 2
+    cand0 = torch.arange(pb.stride, dtype=torch.int32, device="cuda").repeat(pb.batch, 1)
+
+    def step(_: int) -> None:
+        pb.cand.copy_(cand0)
+        pb.n_cand.fill_(pb.stride)
+        pb.score.zero_()
+        pb.n_alive = pb.stride
+        pb.allocate_initial()
+        for layer, L in enumerate(layers):
+            pb.layer(L["q"], L["k_self"], L["v_self"], L["k_store"], L["v_store"], out, keep=keeps.get(layer),
+                     strategy=cf.CF_ALLOC_SORT)
+            if layer in keeps:
+                pb.advance()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    assert pb.flags() == 0 and int(pb.n_cand[0].item()) == k
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert pb.flags() == 0 and int(pb.n_cand[0].item()) == k
+    ms_per_step = 1e3 * elapsed / args.steps
+    cf.cf_profile_kernel_events(True)
+    n_timed = min(args.steps, 1000 // cfg.n_layers)
+    for i in range(n_timed):
+        step(i)
+    torch.cuda.synchronize()
+    kernel_ms, n_bracketed = cf.cf_profile_kernel_ms()
+    cf.cf_profile_kernel_events(False)
+    assert n_bracketed == n_timed * cfg.n_layers
+    attn_ms = kernel_ms * cfg.n_layers                      # all attention launches of one step
+    achieved = kv_tokens * bytes_per_token / (attn_ms * 1e-3) / 1e9
+    step_gbs = kv_tokens * bytes_per_token / (ms_per_step * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "KV tokens/s per layer, re-positioned cached-KV prefill over a pruned layer stack",
+        "value": kv_tokens / (ms_per_step * 1e-3), "unit": "KV tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": g.dtype, "data": "synthetic",
+        "config": {"workload": "llama2_7b_stack", "layers": cfg.n_layers, "documents_per_layer": alive,
+                   "kv_tokens_per_step": kv_tokens, "q_heads": g.n_q_heads, "kv_heads": g.n_kv_heads, "head_dim": g.head_dim,
+                   "tq": cfg.tq, "store_layout": args.store_layout, "whole_step_gbs": step_gbs,
+                   "whole_step_frac_of_hbm_peak": step_gbs / HBM_PEAK_GBS,
+                   "step": "initial allocation + 32 x cf_prefill_layer (prune events after layers 8, 16, 24, 32)"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "attn_tile_kernel<bf16,1,32,2,true>, the 32 launches of a step taken together",
+                     "ms_per_launch": kernel_ms, "launches_timed": n_bracketed,
+                     "algorithmic_bytes_per_launch": kv_tokens * bytes_per_token / cfg.n_layers}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -255,11 +344,12 @@ def main() -> int:
     ap.add_argument("--store-layout", choices=["head", "token"], default="head",
                     help="layout of the cache store: head-major [kv head][token][d] (default, the layout the "
                          "store is meant to be kept in) or token-major [token][kv head][d]")
-    ap.add_argument("--path", choices=["prefill", "assemble", "decode", "reposition"], default="prefill",
+    ap.add_argument("--path", choices=["prefill", "assemble", "decode", "reposition", "stack"], default="prefill",
                     help="prefill: the per-layer hot path (the headline metric).  assemble: Alg. 2 Phase 2, "
                          "cf_assemble_cache of one layer of the final survivor set into a decode cache.  decode: one "
                          "decode step's attention (one new token) over an assembled cache, Alg. 2 Phase 3.  reposition: "
-                         "the stand-alone Eq. 5 call, cf_reposition_keys, out of place over the documents of one layer")
+                         "the stand-alone Eq. 5 call, cf_reposition_keys, out of place over the documents of one layer.  stack: "
+                         "Alg. 2 Phase 1 over 32 layers with four prune events (one step = the whole stack)")
     ap.add_argument("--assemble-docs", type=int, default=5, help="surviving documents per query for --path assemble")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only 10 elementwise copies of 1 GiB (read 1 GiB + write 1 GiB each): the known-size "
@@ -290,6 +380,8 @@ def main() -> int:
     cf.load()
     if args.path in ("assemble", "decode", "reposition"):
         return bench_assemble(args)
+    if args.path == "stack":
+        return bench_stack(args)
 
     cfg = wl.CONFIGS[args.workload]
     g = cfg.geometry
