@@ -269,15 +269,15 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int li = lane & 15, lg = lane >> 4;
 
+    // (plain scalar divisions here: this kernel has no registers to spare for the vector form)
     const int bid = blockIdx.x;
-    const int rg = (int)div_exact((unsigned)bid, (unsigned)p.x_count);
+    const int rg = bid / p.x_count;
     const int x = bid - rg * p.x_count;
-    const int xs = (int)div_exact((unsigned)x, (unsigned)p.nsplit);                   // (query, kv head)
-    const int split = x - xs * p.nsplit;
-    const int b = __builtin_amdgcn_readfirstlane((int)div_exact((unsigned)xs, (unsigned)a.n_kv_heads));
-    const int hkv = xs - b * a.n_kv_heads;
+    const int split = x % p.nsplit;
+    const int hkv = (x / p.nsplit) % a.n_kv_heads;
+    const int b = __builtin_amdgcn_readfirstlane(x / (p.nsplit * a.n_kv_heads));
     const int unit = (b * a.n_kv_heads + hkv) * p.n_rg + rg;
-    const int group = (int)div_exact((unsigned)a.n_q_heads, (unsigned)a.n_kv_heads);
+    const int group = a.n_q_heads / a.n_kv_heads;
     const QueryHead qh = load_query_head(a, b, REG_TABLE ? lane : (int)threadIdx.x);
     const int tq = min(qh.tq_raw, a.max_tq);
     const int row_base = rg * p.blocks_rg * 16;

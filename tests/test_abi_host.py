@@ -164,3 +164,23 @@ def test_assemble_argument_checks():
     # an empty batch is a no-op and needs no GPU
     cf.cf_assemble_cache(d, None, None, 0, None, None, None, None, None, 4, 0, 8, 64, None, 0, 256, 128, None, None, None,
                          stream=0)
+
+
+def test_hot_path_kernels_keep_everything_in_registers():
+    """The build records what the compiler reports per kernel; the kernels of the hot path must not spill
+    to scratch memory (the build itself refuses that, this keeps the record and the refusal in place)."""
+    import json
+
+    from paper_2502_11101_amd import build as cfbuild
+
+    assert os.path.exists(cfbuild.RESOURCES), "run python -m paper_2502_11101_amd.build"
+    usage = json.load(open(cfbuild.RESOURCES))
+    for name in cfbuild.NO_SCRATCH:
+        hits = {k: u for k, u in usage.items() if name in k}
+        assert hits, name
+        for k, u in hits.items():
+            assert u["scratch_bytes"] == 0, (k, u)
+    # both attention kernels are sized for one workgroup per CU: two wavefronts per SIMD
+    for k, u in usage.items():
+        if "attn_tile_kernel" in k or "attn_pc_kernel" in k:
+            assert u["waves_per_simd"] == 2 and u["vgprs"] + u["agprs"] <= 256, (k, u)
