@@ -331,6 +331,81 @@ def bench_stack(args) -> int:
     return 0
 
 
+def bench_encode(args) -> int:
+    """Query-independent parallel document caching (Sec. 2.2) for one layer: a step encodes the documents of the
+    LLaMA-2-7B stack geometry (each attends to the 32-token prefix in the store and causally to itself) and writes
+    their keys, moved to the cached positions, and values into the store: cf_prefill_attention + cf_assemble_cache.
+    The attention is a dense contraction: 4 * d * Hq flops per (query row, visible key) pair."""
+    import torch
+    from paper_2502_11101_amd import binding as cf
+    from paper_2502_11101_amd import pipeline as pl
+    from paper_2502_11101_amd import workloads as wl
+
+    base = wl.CONFIGS["llama2_7b_stack"]
+    cfg = wl.scaled(base, n_store_docs=args.assemble_docs, docs_per_query=args.assemble_docs,
+                    n_planted=min(3, args.assemble_docs))
+    g = cfg.geometry
+    st = wl.build_structure(cfg)
+    ts, hs = pl.store_strides(st.n_store_tokens, g.n_kv_heads, g.head_dim, args.store_layout)
+    desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions,
+                        store_token_stride=ts, store_head_stride=hs)
+    lens = st.doc_lens.astype(np.int64)
+    sb = pl.StoreBuilder(desc, st.doc_off[:-1], lens, np.full(len(lens), cfg.doc_stored_start), cfg.prefix_len,
+                         st.n_store_tokens)
+    doc_tokens = int(lens.sum())
+    n_buf = max(2, min(args.layers, 8))
+    dt = pl.TORCH_DTYPE[g.dtype]
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    shape = (st.n_store_tokens, g.n_kv_heads, g.head_dim) if args.store_layout == "token" else \
+        (g.n_kv_heads, st.n_store_tokens, g.head_dim)
+    bufs = []
+    for _ in range(n_buf):
+        fresh = [torch.randn((doc_tokens, h, g.head_dim), generator=gen, device="cuda").to(dt)
+                 for h in (g.n_q_heads, g.n_kv_heads, g.n_kv_heads)]
+        stores = [torch.randn(shape, generator=gen, device="cuda").to(dt) for _ in range(2)]     # the prefix rows matter
+        bufs.append((fresh, stores))
+    out = torch.empty_like(bufs[0][0][0])
+
+    def step(i: int) -> None:
+        (q, k, v), (ks, vs) = bufs[i % n_buf]
+        sb.attend(q, k, v, ks, vs, out)
+        sb.write(k, v, ks, vs, ts, hs)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert sb.flags() == 0 and bool(torch.isfinite(out.float()).all())
+    ms_per_step = 1e3 * elapsed / args.steps
+    cf.cf_profile_kernel_events(True)
+    for i in range(min(args.steps, 1000)):
+        step(i)
+    torch.cuda.synchronize()
+    kernel_ms, n_bracketed = cf.cf_profile_kernel_ms()
+    cf.cf_profile_kernel_events(False)
+    pairs = float(sum(int(n) * cfg.prefix_len + int(n) * (int(n) + 1) // 2 for n in lens))     # (row, visible key)
+    flops = 4.0 * g.head_dim * g.n_q_heads * pairs
+    tflops = flops / (kernel_ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "document tokens/s per layer, offline document encoding into the cache store",
+        "value": doc_tokens / (ms_per_step * 1e-3), "unit": "document tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": g.dtype, "data": "synthetic",
+        "config": {"workload": "llama2_7b_stack documents, one layer", "documents": len(lens), "document_tokens_per_step": doc_tokens,
+                   "prefix": cfg.prefix_len, "q_heads": g.n_q_heads, "kv_heads": g.n_kv_heads, "head_dim": g.head_dim,
+                   "layer_buffers": n_buf, "store_layout": args.store_layout,
+                   "step": "cf_prefill_attention (each document over the prefix and causally over itself) + cf_assemble_cache into the store"},
+        "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / MFMA_PEAK_TFLOPS, "traffic": None,
+                     "kernel": f"attn_pc_kernel<{g.dtype},2> (first kernel of cf_prefill_attention)",
+                     "ms_per_launch": kernel_ms, "launches_timed": n_bracketed, "algorithmic_flops_per_launch": flops}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -344,12 +419,13 @@ def main() -> int:
     ap.add_argument("--store-layout", choices=["head", "token"], default="head",
                     help="layout of the cache store: head-major [kv head][token][d] (default, the layout the "
                          "store is meant to be kept in) or token-major [token][kv head][d]")
-    ap.add_argument("--path", choices=["prefill", "assemble", "decode", "reposition", "stack"], default="prefill",
+    ap.add_argument("--path", choices=["prefill", "assemble", "decode", "reposition", "stack", "encode"], default="prefill",
                     help="prefill: the per-layer hot path (the headline metric).  assemble: Alg. 2 Phase 2, "
                          "cf_assemble_cache of one layer of the final survivor set into a decode cache.  decode: one "
                          "decode step's attention (one new token) over an assembled cache, Alg. 2 Phase 3.  reposition: "
                          "the stand-alone Eq. 5 call, cf_reposition_keys, out of place over the documents of one layer.  stack: "
-                         "Alg. 2 Phase 1 over 32 layers with four prune events (one step = the whole stack)")
+                         "Alg. 2 Phase 1 over 32 layers with four prune events (one step = the whole stack).  encode: offline "
+                         "document encoding of one layer into the cache store (Sec. 2.2), --assemble-docs documents")
     ap.add_argument("--assemble-docs", type=int, default=5, help="surviving documents per query for --path assemble")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only 10 elementwise copies of 1 GiB (read 1 GiB + write 1 GiB each): the known-size "
@@ -382,6 +458,8 @@ def main() -> int:
         return bench_assemble(args)
     if args.path == "stack":
         return bench_stack(args)
+    if args.path == "encode":
+        return bench_encode(args)
 
     cfg = wl.CONFIGS[args.workload]
     g = cfg.geometry

@@ -233,7 +233,7 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
     }
     // a wavefront whose rows are all padding leaves nothing
     if (!has_rows) return;
-    store_partials<NRB>(a, p, unit, split, wave * NRB, st, l_row, lane);
+    store_partials<DT, NRB>(a, p, unit, split, wave * NRB, st, l_row, lane, qh.q0, tq, hkv, group, row_base, row_limit);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -422,7 +422,7 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
         l_row[rb] = st.l_run[rb] + __shfl_xor(st.l_run[rb], 16);
         l_row[rb] += __shfl_xor(l_row[rb], 32);
     }
-    store_partials<NRB>(a, p, unit, split, cw * NRB, st, l_row, lane);
+    store_partials<DT, NRB>(a, p, unit, split, cw * NRB, st, l_row, lane, qh.q0, tq, hkv, group, row_base, row_limit);
 }
 
 }  // namespace
@@ -467,7 +467,7 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
     if (a.dtype == CF_BF16) { CF_LAUNCH_DT(CF_BF16) } else { CF_LAUNCH_DT(CF_F16) }
 #undef CF_LAUNCH_DT
 #undef CF_LAUNCH_TIMED
-    if (phases & 2) launch_combine(a, p, s);
+    if ((phases & 2) && !(p.direct_out && a.mass == nullptr)) launch_combine(a, p, s);    // else nothing left to merge or reduce
     CF_HIP(hipGetLastError());
     if (prune) {
         if (!(phases & 4)) {

@@ -34,6 +34,7 @@ struct Plan {
     int units_per_b, units, nsplit, slots, x_count;
     int tile;           // tokens per tile: 32 or 64
     int groups;         // groups of four wavefronts per workgroup (each streams its own run of tiles): 1 or 2
+    int direct_out;     // one split: the attention kernel writes the output rows itself, nothing to merge
     size_t off_ml, off_opart, off_massml, off_masspart, total;
 };
 
@@ -77,12 +78,13 @@ inline Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int 
     if (ns > kMaxSplit) ns = kMaxSplit;
     if (ns < 1) ns = 1;
     p.nsplit = (int)ns;
+    p.direct_out = p.nsplit == 1;
     p.slots = seg_stride + p.nsplit * p.groups;
     p.x_count = batch * n_kv_heads * p.nsplit;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
     p.off_ml = take((size_t)p.units * p.nsplit * p.rows_wg * sizeof(float2));
-    p.off_opart = take((size_t)p.units * p.nsplit * p.rows_wg * kD * sizeof(float));
+    p.off_opart = take(p.direct_out ? 0 : (size_t)p.units * p.nsplit * p.rows_wg * kD * sizeof(float));
     p.off_massml = take((size_t)p.units * p.slots * p.rows_wg * sizeof(float2));
     p.off_masspart = take((size_t)p.units * p.nrb * p.slots * sizeof(float));
     p.total = off;

@@ -45,9 +45,11 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     for (int idx = tid; idx < p.nsplit * 64; idx += kThreads) mlw[idx] = ml[(idx >> 6) * p.rows_wg + (idx & 63)];
     // (a wavefront whose 16 rows are all padding reads what an earlier call left there: in bounds, never stored;
     // not waiting for the query's length here saves a round trip)
+    // (one split only: the attention kernel wrote the output rows itself, only the slot statistics are left)
+    const bool merge = !p.direct_out;
     f32x4 pre[kPre];
 #pragma unroll
-    for (int s = 0; s < kPre; ++s) pre[s] = s < p.nsplit ? src[s * split_stride] : f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < kPre; ++s) pre[s] = merge && s < p.nsplit ? src[s * split_stride] : f32x4{0.f, 0.f, 0.f, 0.f};
     float2 sv[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -75,7 +77,7 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
 #pragma unroll
     for (int s = 0; s < kPre; ++s)
         if (s < p.nsplit) o += pre[s] * mlw[s * 64 + wave * 16 + li].x;
-    if (blk_has_rows)
+    if (merge && blk_has_rows)
         for (int s0 = kPre; s0 < p.nsplit; s0 += kPre) {         // further splits, eight loads at a time
             f32x4 more[kPre];
 #pragma unroll
@@ -85,7 +87,7 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
                 if (s0 + i < p.nsplit) o += more[i] * mlw[(s0 + i) * 64 + wave * 16 + li].x;
         }
     const int lrow = pass * 64 + wave * 16 + li;
-    if (lrow < rows_here) {
+    if (merge && lrow < rows_here) {
         const int m2 = row_base + lrow;
         const int gi = (int)div_exact((unsigned)m2, (unsigned)tq), t = m2 - gi * tq;
         uint16_t* op = static_cast<uint16_t*>(a.out) + (((int64_t)q0 + t) * hq + hkv * group + gi) * kD + 16 * dbq + 4 * lg;

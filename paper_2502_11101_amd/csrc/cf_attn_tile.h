@@ -256,15 +256,39 @@ __device__ __forceinline__ void emit_segment(const RowState<NRB>& st, float2* ma
     }
 }
 
-// Partial results of a split: O^T in MFMA layout (one float4 per lane, row block and channel block)
-// and (reference, row sum) per row.
-template <int NRB>
+// Results of a split.  Several splits: partial O^T in MFMA layout (one float4 per lane, row block and
+// channel block) for the merge kernel.  One split: nothing to merge, the rows are normalised and written to
+// `out` here (row m = g*tq + t of the stacked rows is out[q0 + t][hkv*group + g]).  Either way (reference,
+// row sum) per row, which the mass reduction needs.
+template <int DT, int NRB>
 __device__ __forceinline__ void store_partials(const AttnArgs& a, const Plan& p, int unit, int split, int first_blk,
-                                               const RowState<NRB>& st, const float (&l_row)[NRB], int lane) {
+                                               const RowState<NRB>& st, const float (&l_row)[NRB], int lane, int q0, int tq,
+                                               int hkv, int group, int row_base, int row_limit) {
     char* ws = static_cast<char*>(a.workspace);
+    float2* ml = reinterpret_cast<float2*>(ws + p.off_ml) + ((int64_t)unit * p.nsplit + split) * p.rows_wg;
+    if (p.direct_out) {
+        const int li = lane & 15, lg = lane >> 4;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            const int m = row_base + (first_blk + rb) * 16 + li;
+            if (lg == 0) ml[(first_blk + rb) * 16 + li] = make_float2(st.m_run[rb], l_row[rb]);
+            if (m >= row_limit) continue;
+            const int gi = (int)div_exact((unsigned)m, (unsigned)tq), t = m - gi * tq;
+            const float inv = l_row[rb] > 0.f ? 1.f / l_row[rb] : 0.f;
+            uint16_t* op = static_cast<uint16_t*>(a.out) + (((int64_t)q0 + t) * a.n_q_heads + hkv * group + gi) * kD + 4 * lg;
+#pragma unroll
+            for (int db = 0; db < 8; ++db) {
+                const f32x4 o = st.acc[rb][db] * inv;
+                uint2 pk;
+                pk.x = Mma<DT>::pack(o[0], o[1]);
+                pk.y = Mma<DT>::pack(o[2], o[3]);
+                *reinterpret_cast<uint2*>(op + 16 * db) = pk;
+            }
+        }
+        return;
+    }
     f32x4* opart = reinterpret_cast<f32x4*>(ws + p.off_opart) +
                    (((int64_t)unit * p.nsplit + split) * p.rows_wg / 16 + first_blk) * 8 * kWave + lane;
-    float2* ml = reinterpret_cast<float2*>(ws + p.off_ml) + ((int64_t)unit * p.nsplit + split) * p.rows_wg;
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
 #pragma unroll

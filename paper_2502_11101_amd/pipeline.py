@@ -173,3 +173,62 @@ class PrefillBatch:
 
     def flags(self) -> int:
         return int(self.dev_flag.item())
+
+
+class StoreBuilder:
+    """Query-independent parallel document caching (Sec. 2.2, Alg. 2 "offline") for one layer.
+
+    Every text of a batch (the shared prefix on its own, or the documents) attends to the first
+    ``prefix_len`` tokens of the store and causally to itself at positions
+    [position, position + len); its keys, moved to those positions, and its values are then
+    written to the Context KV Cache Store at ``store_off``.  Sequencing only: the attention is
+    cf_prefill_attention with each text as a "query" whose table lists the prefix and its own block, the
+    write is cf_assemble_cache with the store as the target (Eq. 5 from the local position to the cached one).
+
+    store_off / lens / positions: host arrays [n]; the fresh q / k / v of the texts are packed back to back,
+    [sum lens][heads][head_dim], row t of a text carrying RoPE for its local position t.
+    """
+
+    def __init__(self, desc: cf.cf_layer_desc, store_off: np.ndarray, lens: np.ndarray, positions: np.ndarray,
+                 prefix_len: int, n_store_tokens: int, device="cuda"):
+        self.desc = desc
+        self.n = len(lens)
+        self.prefix_len = int(prefix_len)
+        self.n_store_tokens = int(n_store_tokens)
+        self.max_len = int(np.max(lens))
+        q_off = np.zeros(self.n + 1, dtype=np.int64)
+        q_off[1:] = np.cumsum(np.asarray(lens, dtype=np.int64))
+        self.total = int(q_off[-1])
+        i32 = dict(dtype=torch.int32, device=device)
+        self.q_off = torch.from_numpy(q_off.astype(np.int32)).to(device)
+        self.q_new = torch.from_numpy(np.asarray(positions, dtype=np.int32)).to(device)
+        own = [(int(q_off[b]), int(lens[b]), 0, int(positions[b]), cf.CF_SEG_SELF, -1) for b in range(self.n)]
+        pre = (0, self.prefix_len, 0, 0, cf.CF_SEG_PREFIX, -1)
+        self.seg_stride = 2 if self.prefix_len else 1
+        attend = [s for o in own for s in (([pre] if self.prefix_len else []) + [o])]
+        self.attend_segs = cf.segments_to_device(cf.segments_array(attend), device)
+        self.attend_n = torch.full((self.n,), self.seg_stride, **i32)
+        self.write_segs = cf.segments_to_device(cf.segments_array(own), device)
+        self.write_n = torch.ones((self.n,), **i32)
+        self.final_off = torch.from_numpy(np.asarray(store_off, dtype=np.int64)).to(device)
+        self.final_len = torch.zeros((self.n,), **i32)
+        self.dev_flag = torch.zeros((1,), **i32)
+        self.max_kv_tokens = self.prefix_len + self.max_len
+        self.ws_bytes = cf.cf_prefill_workspace_bytes(desc, self.n, self.max_len, self.seg_stride, self.max_kv_tokens)
+        self.workspace = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=device)
+
+    def attend(self, q, k, v, k_store, v_store, out) -> None:
+        """out = attention of every text over the prefix (read from the store) and causally over itself."""
+        cf.cf_prefill_attention(self.desc, q, self.q_off, 0, self.q_new, k_store if self.prefix_len else None,
+                                v_store if self.prefix_len else None, self.n_store_tokens if self.prefix_len else 0, k, v,
+                                self.attend_segs, self.attend_n, self.seg_stride, self.n, self.max_len, self.max_kv_tokens,
+                                out, None, None, 1, self.workspace, self.ws_bytes, self.dev_flag)
+
+    def write(self, k, v, k_store, v_store, store_token_stride: int, store_head_stride: int) -> None:
+        """The texts' keys, rotated to their cached positions, and values go to their place in the store."""
+        cf.cf_assemble_cache(self.desc, None, None, 0, k, v, self.q_off, self.write_segs, self.write_n, 1, self.n,
+                             self.max_len, self.max_len, self.final_off, self.n_store_tokens, store_token_stride,
+                             store_head_stride, k_store, v_store, self.final_len, None, self.dev_flag)
+
+    def flags(self) -> int:
+        return int(self.dev_flag.item())

@@ -852,3 +852,90 @@ def test_document_encoding_attention_shape():
                                                   tables[b], g.n_kv_heads, g.rope_base)
         assert G.row_error(got[lo:hi], ref_out) <= G.OUT_TOL[g.dtype]
         assert G.rel_error(m[b], ref_mass) <= (2e-3 if doc_lens[b] < 8 else G.MASS_TOL[g.dtype])
+
+
+@pytest.mark.parametrize("layout", ["head", "token"])
+def test_offline_store_builder_writes_the_cache_store(layout):
+    """Sec. 2.2 end to end for one layer: the shared prefix, then the documents, are encoded (attention over
+    the prefix and causally over themselves, each from local position 0) and their keys, moved to the positions
+    they are cached at (Eq. 5), and values are written into the store; a query then prefills over the store the device built.  The
+    store must equal the oracle's rotation of the fresh keys within one rounding (values bit for bit), the
+    encoders' outputs and the query's outputs and masses must match the oracle."""
+    rng = np.random.default_rng(83)
+    g = wl.Geometry(8, 2, 128, "bf16", 1.0e6, 32768)
+    prefix = 24
+    doc_lens = np.array([100, 200, 137, 64, 1, 163], dtype=np.int32)
+    doc_off = np.concatenate([[prefix], prefix + np.cumsum(doc_lens)]).astype(np.int64)
+    n_store = int(doc_off[-1])
+    _say(f"store builder {layout}: {len(doc_lens)} documents, {n_store} store tokens")
+    rnd = lambda *shape: wl.round_to_dtype(rng.standard_normal(shape, dtype=np.float32), g.dtype)
+    fresh = {name: (rnd(n, g.n_q_heads, g.head_dim), rnd(n, g.n_kv_heads, g.head_dim), rnd(n, g.n_kv_heads, g.head_dim))
+             for name, n in (("prefix", prefix), ("docs", int(doc_lens.sum())))}
+    ts, hs = pl.store_strides(n_store, g.n_kv_heads, g.head_dim, layout)
+    desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions,
+                        store_token_stride=ts, store_head_stride=hs)
+    shape = (n_store, g.n_kv_heads, g.head_dim) if layout == "token" else (g.n_kv_heads, n_store, g.head_dim)
+    k_store = torch.full(shape, 7.0, dtype=torch.bfloat16, device="cuda")
+    v_store = torch.full(shape, 7.0, dtype=torch.bfloat16, device="cuda")
+    as_tokens = (lambda x: x) if layout == "token" else (lambda x: x.permute(1, 0, 2))
+
+    # ---- the device builds the store: the prefix at positions [0, prefix), every document at [prefix, prefix + len)
+    builders = {"prefix": pl.StoreBuilder(desc, np.array([0]), np.array([prefix]), np.array([0]), 0, n_store),
+                "docs": pl.StoreBuilder(desc, doc_off[:-1], doc_lens, np.full(len(doc_lens), prefix), prefix, n_store)}
+    outs = {}
+    for name in ("prefix", "docs"):
+        q, k, v = (pl.to_device(x, g.dtype) for x in fresh[name])
+        outs[name] = torch.empty_like(q)
+        builders[name].attend(q, k, v, k_store, v_store, outs[name])
+        builders[name].write(k, v, k_store, v_store, ts, hs)
+        torch.cuda.synchronize()
+        assert builders[name].flags() == 0
+    assert builders["docs"].final_len.tolist() == doc_lens.tolist()
+    k_dev = as_tokens(k_store).float().cpu().numpy()
+    v_dev = as_tokens(v_store).float().cpu().numpy()
+
+    # ---- the store the oracle expects
+    # (a text's fresh keys carry RoPE for its local positions 0..len-1; the documents move by `prefix`, Eq. 5)
+    k_ref = np.concatenate([fresh["prefix"][1].astype(np.float64),
+                            orc.rotate(fresh["docs"][1].astype(np.float64), prefix, g.rope_base)])
+    assert np.max(np.abs(k_dev - k_ref)) <= 2.0 ** -8 * max(1.0, np.abs(k_ref).max())
+    assert np.array_equal(v_dev, np.concatenate([fresh["prefix"][2], fresh["docs"][2]]))
+    assert np.array_equal(k_dev[:prefix], fresh["prefix"][1])                  # the prefix does not move: exact copies
+    assert not np.array_equal(k_dev[prefix:], fresh["docs"][1])
+
+    # ---- the encoders' outputs against the oracle, on the store the device holds
+    q_p, k_p, v_p = fresh["prefix"]
+    ref, _ = orc.prefill_attention(q_p.astype(np.float64), 0, 0, k_dev, v_dev, k_p, v_p,
+                                   [orc.Segment(0, prefix, 0, 0, orc.KIND_SELF, -1)], g.n_kv_heads, g.rope_base)
+    assert G.row_error(outs["prefix"].float().cpu().numpy(), ref) <= G.OUT_TOL[g.dtype]
+    q_d, k_d, v_d = fresh["docs"]
+    got = outs["docs"].float().cpu().numpy()
+    q_off = np.concatenate([[0], np.cumsum(doc_lens)])
+    for b in range(len(doc_lens)):
+        lo, hi = int(q_off[b]), int(q_off[b + 1])
+        table = [orc.Segment(0, prefix, 0, 0, orc.KIND_PREFIX, -1), orc.Segment(lo, hi - lo, 0, prefix, orc.KIND_SELF, -1)]
+        ref, _ = orc.prefill_attention(q_d[lo:hi].astype(np.float64), 0, prefix, k_dev, v_dev, k_d, v_d, table,
+                                       g.n_kv_heads, g.rope_base)
+        assert G.row_error(got[lo:hi], ref) <= G.OUT_TOL[g.dtype]
+
+    # ---- a query prefills over the store the device built (every document a candidate, keep 3)
+    tq = 16
+    pb = pl.PrefillBatch(desc, doc_off[:-1][None, :], doc_lens[None, :], tq, prefix, prefix, n_store)
+    pb.allocate_initial()
+    q, k_self, v_self = rnd(tq, g.n_q_heads, g.head_dim), rnd(tq, g.n_kv_heads, g.head_dim), rnd(tq, g.n_kv_heads, g.head_dim)
+    dq, dk, dv = (pl.to_device(x, g.dtype) for x in (q, k_self, v_self))
+    out = torch.empty_like(dq)
+    segs = G.device_segments(pb, 0)
+    pb.layer(dq, dk, dv, k_store, v_store, out, keep=3)
+    torch.cuda.synchronize()
+    assert pb.flags() == 0
+    ref_out, ref_mass = orc.prefill_attention(q.astype(np.float64), 0, int(pb.q_start[0].item()), k_dev, v_dev, k_self, v_self,
+                                              segs, g.n_kv_heads, g.rope_base)
+    assert G.row_error(out.float().cpu().numpy(), ref_out) <= G.OUT_TOL[g.dtype]
+    mass = pb.mass.cpu().numpy()[0, :len(segs)]
+    long_ = np.array([sg.len >= 8 for sg in segs])            # a one-token document's mass hangs on one rounded key
+    assert G.rel_error(mass[long_], ref_mass[long_]) <= G.MASS_TOL[g.dtype]
+    assert G.rel_error(mass[~long_], ref_mass[~long_]) <= 2e-3
+    score = H.doc_scores(segs, ref_mass, len(doc_lens))
+    assert pb.keep_idx[0, :3].tolist() == orc.prune_topk(pb.score.cpu().numpy()[0], [int(x) for x in doc_lens], list(range(len(doc_lens))), 3)
+    assert np.isfinite(score).all()
