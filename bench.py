@@ -213,6 +213,12 @@ def bench_assemble(args) -> int:
         call_ms = e0.elapsed_time(e1) / args.steps
         bytes_per_token = 2 * g.n_kv_heads * g.head_dim * 2
         achieved = (tokens + 1) * bytes_per_token / (call_ms * 1e-3) / 1e9
+        cf.cf_profile_kernel_events(True)                       # the attention kernel's own dispatches
+        for i in range(min(args.steps, 1000)):
+            step(i)
+        torch.cuda.synchronize()
+        kernel_ms, n_bracketed = cf.cf_profile_kernel_ms()
+        cf.cf_profile_kernel_events(False)
         print(json.dumps({
             "metric": "KV tokens/s per layer, decode-step attention over the assembled cache",
             "value": (tokens + 1) / (ms_per_step * 1e-3), "unit": "KV tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -223,7 +229,9 @@ def bench_assemble(args) -> int:
                        "step": "cf_prefill_attention (Tq = 1)"},
             "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                          "traffic": None, "kernel": "whole call: attn_tile_kernel + attn_combine_kernel (no mass asked for)",
-                         "ms_per_launch": call_ms, "algorithmic_bytes_per_launch": (tokens + 1) * bytes_per_token}}))
+                         "ms_per_launch": call_ms, "algorithmic_bytes_per_launch": (tokens + 1) * bytes_per_token,
+                         "attention_kernel_ms": kernel_ms, "attention_kernel_launches_timed": n_bracketed,
+                         "attention_kernel_gbs": (tokens + 1) * bytes_per_token / (kernel_ms * 1e-3) / 1e9}}))
         return 0
     ms_per_step = 1e3 * elapsed / args.steps
     kernel_ms = e0.elapsed_time(e1) / args.steps

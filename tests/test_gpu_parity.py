@@ -336,6 +336,54 @@ def test_mfma_path_edge_shapes(dtype, layout, hq, hkv, tq, docs, len_range, pref
     _run_single_layer(cfg, seed=77, mass_tol=2e-3, layout=layout)
 
 
+@pytest.mark.parametrize("dtype,layout", [("bf16", "token"), ("f16", "head"), ("bf16", "head_padded")])
+@pytest.mark.parametrize("hq,hkv,tq,docs,len_range,prefix,batch", [
+    (4, 4, 1, 3, (1, 70), 0, 2),            # one row per kv head, no prefix
+    (32, 32, 1, 10, (160, 160), 32, 1),     # a decode step of the LLaMA-2-7B shape: several splits
+    (8, 4, 1, 5, (20, 90), 3, 2),           # GQA group of two
+    (4, 4, 2, 4, (5, 64), 2, 3),            # two query tokens: the causal own block
+    (6, 2, 1, 6, (1, 150), 5, 2),           # group of three: one padding row in the four-row instance
+    (2, 2, 4, 3, (33, 33), 7, 2),           # four query tokens
+    (4, 2, 2, 7, (1, 100), 0, 2),           # group of two times two tokens
+    (4, 4, 1, 2, (10, 40), 4, 70),          # many queries: a single split, rows written by the attention kernel
+])
+def test_few_rows_outputs_only(dtype, layout, hq, hkv, tq, docs, len_range, prefix, batch):
+    """Outputs-only calls (no mass buffer) with at most four stacked rows per kv head, the shape of decode steps:
+    checked against the oracle on re-positioned tables (documents moved from where they were cached), and
+    against the same call with masses."""
+    cfg = wl.scaled(wl.CONFIGS["tiny_f32"], name=f"fewrow_{dtype}_{hq}_{hkv}_{tq}_{batch}",
+                    geometry=wl.Geometry(hq, hkv, 128, dtype, 1.0e4, 8192), n_store_docs=batch * docs,
+                    docs_per_query=docs, batch=batch, doc_len_range=len_range, tq=tq, prefix_len=prefix,
+                    doc_stored_start=prefix + 11, n_planted=1)
+    _say(f"few rows {cfg.name} [{layout}]")
+    g = cfg.geometry
+    st = wl.build_structure(cfg, seed=7090)
+    t = wl.build_layer(cfg, st, seed=91)
+    pb = G.make_batch(cfg, st, layout=layout)
+    dev = G.upload_layer(cfg, t, layout)
+    pb.allocate_initial()
+    pb.workspace.fill_(0xFF)
+    out = torch.full_like(dev["q"], 7.0)
+    cf.cf_prefill_attention(pb.desc, dev["q"], pb.q_off, pb.q_stored_start, pb.q_start, dev["k_store"], dev["v_store"],
+                            pb.n_store_tokens, dev["k_self"], dev["v_self"], pb.segs, pb.n_seg, pb.seg_stride, pb.batch, pb.tq,
+                            pb.max_kv_tokens, out, None, None, pb.stride, pb.workspace, pb.ws_bytes, pb.dev_flag)
+    torch.cuda.synchronize()
+    assert pb.flags() == 0
+    with_mass = torch.empty_like(out)
+    pb.attention(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], with_mass, accumulate=False)
+    torch.cuda.synchronize()
+    out_np, other = out.float().cpu().numpy(), with_mass.float().cpu().numpy()
+    worst = 0.0
+    for b in range(min(cfg.batch, 6)):
+        segs, q_start, _ = H.initial_segments(cfg, st, b)
+        assert any(sg.new_start != sg.stored_start for sg in segs if sg.kind == cf.CF_SEG_DOC)
+        ref_out, _ = H.oracle_query(cfg, st, t, b, segs, q_start)
+        worst = max(worst, G.row_error(out_np[b * cfg.tq:(b + 1) * cfg.tq], ref_out))
+    _say(f"  out err {worst:.3e}")
+    assert worst <= G.OUT_TOL[g.dtype]
+    assert G.row_error(out_np, other) <= G.OUT_TOL[g.dtype]
+
+
 def test_mfma_path_is_deterministic():
     cfg = wl.CONFIGS["llama2_7b_layer"]
     st = wl.build_structure(cfg)
@@ -786,12 +834,12 @@ def test_decode_step_over_assembled_cache():
         ref = orc.decode_attention(q_abs[b:b + 1].astype(np.float64), k_ref, v_ref, g.n_kv_heads)
         assert G.row_error(got[b:b + 1], ref) <= G.OUT_TOL[g.dtype]
         assert mass[b, 0].item() == pytest.approx(g.n_q_heads, rel=1e-5)
-    # outputs only (no mass buffer, as a decode loop would call it): the same outputs, bit for bit
+    # outputs only (no mass buffer, as a decode loop calls it): the same bar
     out2 = torch.empty_like(out)
     cf.cf_prefill_attention(desc, q_dev, q_off, 0, zeros, r["k_dev"], r["v_dev"], r["capacity"], None, None, seg_dev, n_seg, 1,
                             cfg.batch, 1, max_kv, out2, None, None, 1, ws, ws_bytes, flag)
     torch.cuda.synchronize()
-    assert flag.item() == 0 and torch.equal(out2, out)
+    assert flag.item() == 0 and torch.equal(out2, out)           # the same kernels: the same outputs, bit for bit
 
 
 def test_assemble_cache_flags():
