@@ -71,18 +71,11 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
                      "s"(p.off_ml), "s"(p.off_opart), "s"(p.off_massml));
     }
 
-    // block -> (row group, query, kv head, split); workgroups that read the same K/V tiles differ
-    // by a multiple of x_count
-    const int bid = blockIdx.x;
-    const int rg = (int)div_exact((unsigned)bid, (unsigned)p.x_count);
-    const int x = bid - rg * p.x_count;
-    const int xs = (int)div_exact((unsigned)x, (unsigned)p.nsplit);                   // (query, kv head)
-    const int split = x - xs * p.nsplit;
-    const int b = __builtin_amdgcn_readfirstlane((int)div_exact((unsigned)xs, (unsigned)a.n_kv_heads));
-    const int hkv = xs - b * a.n_kv_heads;
-    const int unit = (b * a.n_kv_heads + hkv) * p.n_rg + rg;
-
-    const int group = (int)div_exact((unsigned)a.n_q_heads, (unsigned)a.n_kv_heads);
+    // grid (split, kv head, query): nothing to divide; one row group (at most four row blocks)
+    const int split = blockIdx.x, hkv = blockIdx.y, b = blockIdx.z;
+    constexpr int rg = 0;
+    const int unit = b * a.n_kv_heads + hkv;
+    const int group = p.group;
     const QueryHead qh = load_query_head(a, b, REG_TABLE ? lane : (int)threadIdx.x);
     const double my_freq = freq.rev[tid & (kHalf - 1)];
     const int tq = min(qh.tq_raw, a.max_tq);
@@ -108,10 +101,6 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
     // a group streams a contiguous run of the workgroup's tiles of its own (sub-split `ss`)
     const unsigned nsub = (unsigned)(p.nsplit * GROUPS);
     const int ss = split * GROUPS + grp;
-    int most_tiles = 0;                              // workgroup-uniform: the longest run among the groups
-#pragma unroll
-    for (int g = 0; g < GROUPS; ++g)
-        most_tiles = max(most_tiles, split_begin(total, nsub, split * GROUPS + g + 1) - split_begin(total, nsub, split * GROUPS + g));
 
     // staging items: K (row kr + 32*it, chunks kj and kj + 8), V (row vr + 16*it, chunk vc)
     const int kr = tid >> 3, kj = tid & 7;
@@ -142,6 +131,12 @@ __global__ __launch_bounds__(kThreads * GROUPS, 2) void attn_tile_kernel(AttnArg
     Tile d0, d1;
     fetch(d0, regs0);
     fetch(d1, regs1);
+    // workgroup-uniform: the longest run among the groups (not needed before the loop, so worked out once the
+    // first loads are out)
+    int most_tiles = 0;
+#pragma unroll
+    for (int g = 0; g < GROUPS; ++g)
+        most_tiles = max(most_tiles, split_begin(total, nsub, split * GROUPS + g + 1) - split_begin(total, nsub, split * GROUPS + g));
 
     RowState<NRB> st;
     st.clear();
@@ -277,7 +272,7 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
     const int hkv = (x / p.nsplit) % a.n_kv_heads;
     const int b = __builtin_amdgcn_readfirstlane(x / (p.nsplit * a.n_kv_heads));
     const int unit = (b * a.n_kv_heads + hkv) * p.n_rg + rg;
-    const int group = a.n_q_heads / a.n_kv_heads;
+    const int group = p.group;
     const QueryHead qh = load_query_head(a, b, REG_TABLE ? lane : (int)threadIdx.x);
     const int tq = min(qh.tq_raw, a.max_tq);
     const int row_base = rg * p.blocks_rg * 16;
@@ -449,19 +444,24 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
     const int phases = profile_phases();
     const Plan p = make_plan(a.n_q_heads, a.n_kv_heads, a.batch, a.max_tq, a.seg_stride, a.max_kv_tokens);
     const dim3 grid((unsigned)(p.x_count * p.n_rg));
+    const dim3 grid3((unsigned)p.nsplit, (unsigned)a.n_kv_heads, (unsigned)a.batch);     // attn_tile_kernel's
+    if (p.producers == 0 && (a.batch > 65535 || a.n_kv_heads > 65535)) {
+        set_error("batch and n_kv_heads must not exceed 65535 on this path");
+        return CF_ERR_UNSUPPORTED;
+    }
     const bool reg_table = a.seg_stride <= kWave;    // the attention kernels keep a table this small in registers
     // the attention kernel's launch carries the profiling aid's start/stop events (null when it is off)
     hipEvent_t ev_start = nullptr, ev_stop = nullptr;
     if (phases & 1) profile_kernel_pair(&ev_start, &ev_stop);
-#define CF_LAUNCH_TIMED(KERNEL, BLOCK) hipExtLaunchKernelGGL(KERNEL, grid, BLOCK, 0, s, ev_start, ev_stop, 0, a, f, p)
+#define CF_LAUNCH_TIMED(KERNEL, GRID, BLOCK) hipExtLaunchKernelGGL(KERNEL, GRID, BLOCK, 0, s, ev_start, ev_stop, 0, a, f, p)
 #define CF_LAUNCH_DT(DT)                                                                                                       \
     if (!(phases & 1)) {                                                                                                       \
     } else if (p.producers == 0) {                                                                                             \
-        if (reg_table) CF_LAUNCH_TIMED((attn_tile_kernel<DT, 1, 32, 2, true>), dim3(2 * kThreads));                            \
-        else CF_LAUNCH_TIMED((attn_tile_kernel<DT, 1, 32, 2, false>), dim3(2 * kThreads));                                     \
+        if (reg_table) CF_LAUNCH_TIMED((attn_tile_kernel<DT, 1, 32, 2, true>), grid3, dim3(2 * kThreads));                            \
+        else CF_LAUNCH_TIMED((attn_tile_kernel<DT, 1, 32, 2, false>), grid3, dim3(2 * kThreads));                                     \
     } else {                                                                                                                   \
-        if (reg_table) CF_LAUNCH_TIMED((attn_pc_kernel<DT, kPcProducers, true>), dim3(kPcWaves * kWave));                      \
-        else CF_LAUNCH_TIMED((attn_pc_kernel<DT, kPcProducers, false>), dim3(kPcWaves * kWave));                               \
+        if (reg_table) CF_LAUNCH_TIMED((attn_pc_kernel<DT, kPcProducers, true>), grid, dim3(kPcWaves * kWave));                      \
+        else CF_LAUNCH_TIMED((attn_pc_kernel<DT, kPcProducers, false>), grid, dim3(kPcWaves * kWave));                               \
     }                                                                                                                          \
     CF_HIP(hipGetLastError());
     if (a.dtype == CF_BF16) { CF_LAUNCH_DT(CF_BF16) } else { CF_LAUNCH_DT(CF_F16) }

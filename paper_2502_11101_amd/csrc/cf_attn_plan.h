@@ -25,6 +25,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 struct Plan {
+    int group;          // query heads per kv head
     int row_blocks;     // 16-row blocks of the stacked rows of one kv head
     int producers;      // 0: attn_tile_kernel (few rows); else attn_pc_kernel with that many loading wavefronts
     int nrb;            // 64-row passes of a workgroup's rows (what the combine kernel handles at a time)
@@ -46,6 +47,7 @@ inline Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int 
     Plan p;
     const int group = n_q_heads / n_kv_heads;
     const int row_blocks = (group * max_tq + 15) / 16;
+    p.group = group;
     p.row_blocks = row_blocks;
     if (row_blocks <= 4) {
         // Few stacked rows (MHA-like, HBM-bound): one row block per wavefront, small tiles, so that ragged
