@@ -445,8 +445,8 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
     const Plan p = make_plan(a.n_q_heads, a.n_kv_heads, a.batch, a.max_tq, a.seg_stride, a.max_kv_tokens);
     const dim3 grid((unsigned)(p.x_count * p.n_rg));
     const dim3 grid3((unsigned)p.nsplit, (unsigned)a.n_kv_heads, (unsigned)a.batch);     // attn_tile_kernel's
-    if (p.producers == 0 && (a.batch > 65535 || a.n_kv_heads > 65535)) {
-        set_error("batch and n_kv_heads must not exceed 65535 on this path");
+    if (a.batch > 65535 || (int64_t)a.n_kv_heads * p.n_rg > 65535) {          // grid dimensions of this path's kernels
+        set_error("batch and n_kv_heads * row groups must not exceed 65535 on this path");
         return CF_ERR_UNSUPPORTED;
     }
     const bool reg_table = a.seg_stride <= kWave;    // the attention kernels keep a table this small in registers

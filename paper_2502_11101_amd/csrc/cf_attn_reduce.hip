@@ -7,7 +7,7 @@ namespace cf {
 using namespace attn;
 namespace {
 
-// Second kernel: one workgroup per (unit, 64-row pass, eighth of the output channels) merges the
+// Second kernel: one workgroup per (unit = (query, kv head, row group), 64-row pass, eighth of the output channels) merges the
 // splits' partial outputs and writes its output rows; the eight workgroups of a (unit, pass) also share
 // the reduction, over the pass's 64 rows, of every (segment, split) slot's (max, sum) pairs to
 // sum * exp2(max - row max) / row sum, which the mass kernel then only has to add up.
@@ -22,15 +22,14 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     const int wave = tid / kWave;
     const int li = lane & 15, lg = lane >> 4;
     char* ws = static_cast<char*>(a.workspace);
-    const int hq = a.n_q_heads, group = (int)div_exact((unsigned)hq, (unsigned)a.n_kv_heads);
+    // grid (channel block + 8 * pass, kv head * row groups + row group, query)
+    const int hq = a.n_q_heads, group = p.group;
     const int dbq = blockIdx.x & 7;
-    const int up = (int)(blockIdx.x >> 3);                                            // (unit, pass)
-    const int unit = (int)div_exact((unsigned)up, (unsigned)p.nrb);
-    const int pass = up - unit * p.nrb;
-    const int uh = (int)div_exact((unsigned)unit, (unsigned)p.n_rg);                  // (query, kv head)
-    const int rg = unit - uh * p.n_rg;
-    const int b = (int)div_exact((unsigned)uh, (unsigned)a.n_kv_heads);
-    const int hkv = uh - b * a.n_kv_heads;
+    const int pass = (int)(blockIdx.x >> 3);
+    const int b = blockIdx.z;
+    const int hkv = p.n_rg == 1 ? (int)blockIdx.y : (int)div_exact(blockIdx.y, (unsigned)p.n_rg);
+    const int rg = (int)blockIdx.y - hkv * p.n_rg;
+    const int unit = b * (int)gridDim.y + (int)blockIdx.y;
     const int q0 = a.q_off[b], q1 = a.q_off[b + 1];
     const float2* ml = reinterpret_cast<const float2*>(ws + p.off_ml) + (int64_t)unit * p.nsplit * p.rows_wg + pass * 64;
     const f32x4* opart = reinterpret_cast<const f32x4*>(ws + p.off_opart) + (int64_t)unit * p.nsplit * p.rows_wg * (kD / 4);
@@ -386,7 +385,7 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
 }  // namespace
 
 void launch_combine(const AttnArgs& a, const Plan& p, hipStream_t s) {
-    const dim3 grid((unsigned)(p.units * p.nrb * 8)), block(kThreads);
+    const dim3 grid((unsigned)(8 * p.nrb), (unsigned)(a.n_kv_heads * p.n_rg), (unsigned)a.batch), block(kThreads);
     if (a.dtype == CF_BF16) hipLaunchKernelGGL((attn_combine_kernel<CF_BF16>), grid, block, 0, s, a, p);
     else hipLaunchKernelGGL((attn_combine_kernel<CF_F16>), grid, block, 0, s, a, p);
 }
