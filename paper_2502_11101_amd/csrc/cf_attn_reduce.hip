@@ -231,9 +231,31 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p)
     __shared__ float stage[kMassStage];
     const char* ws = static_cast<const char*>(a.workspace);
     const int b = __builtin_amdgcn_readfirstlane(blockIdx.x);
+    const int tid = threadIdx.x;
+    const int n_part_floats = p.units_per_b * p.nrb * p.slots;
+    const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * n_part_floats;
+    if (p.slots <= 2 * kWave && a.seg_stride <= kWave && n_part_floats <= kMassStage) {
+        // small query: the partials go to LDS in one batch (requested before the query's scalars are waited for),
+        // then one wavefront finishes alone from a table in its registers — the same sums in the same order
+        float r_part[kMassStage / kThreads];
+#pragma unroll
+        for (int i = 0; i < kMassStage / kThreads; ++i) r_part[i] = tid + i * kThreads < n_part_floats ? mp_b[tid + i * kThreads] : 0.f;
+        const QueryHead qh = load_query_head(a, b, tid & (kWave - 1));
+#pragma unroll
+        for (int i = 0; i < kMassStage / kThreads; ++i)
+            if (tid + i * kThreads < n_part_floats) stage[tid + i * kThreads] = r_part[i];
+        __syncthreads();
+        if (tid >= kWave) return;
+        const RegSegTable rtbl = build_reg_table(a, qh, tid, p.tile);
+        segment_masses_wave(p, rtbl, stage, tid, [&](int s, float m) {
+            a.mass[(int64_t)b * a.seg_stride + s] = m;
+            const int doc = qh.seg.doc;              // this lane's entry
+            if (a.score_accum && doc >= 0 && doc < a.score_stride) atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], m);
+        });
+        return;
+    }
     const QueryHead qh = load_query_head(a, b, (int)threadIdx.x);
     build_table(a, qh, &tbl, p.tile);
-    const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * p.units_per_b * p.nrb * p.slots;
     segment_masses_block(p, tbl, const_cast<float*>(mp_b), stage, &ms, [&](int s, float m) {
         a.mass[(int64_t)b * a.seg_stride + s] = m;
         const int doc = tbl.doc[s];

@@ -489,7 +489,8 @@ def _fused_and_separate(cfg, st, t, keep, strategy, **kw):
             pb.attention(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out)
             pb.prune(keep, strategy)
         torch.cuda.synchronize()
-        res.append(dict(flags=pb.flags(), out=out.clone(), score=pb.score.clone(), keep=pb.keep_idx.clone(), n_keep=pb.n_keep.clone(),
+        res.append(dict(flags=pb.flags(), out=out.clone(), score=pb.score.clone(), mass=pb.mass.clone(), keep=pb.keep_idx.clone(),
+                        n_keep=pb.n_keep.clone(),
                         order=pb.order.clone(), new_start=pb.next_new_start.clone(), q_start=pb.next_q_start.clone(),
                         n_reuse=pb.n_reuse.clone(), segs=pb.next_segs.clone(), n_seg=pb.next_n_seg.clone()))
     return res
@@ -515,6 +516,21 @@ def test_fused_layer_many_candidates_and_batch(strategy):
         assert torch.equal(a[key], b[key]), key
     n = int(a["n_seg"][0].item())
     assert torch.equal(a["segs"][:, :n], b["segs"][:, :n])
+
+
+def test_mass_reduction_forms_add_in_the_same_order():
+    """Many kv heads: the separate call's mass kernel stages the slot partials through LDS in rounds, the fused
+    epilogue's single wavefront reads them all at once; both must add in the same order — masses and accumulated
+    scores bit for bit, and so the same survivors."""
+    cfg = wl.scaled(wl.CONFIGS["tiny_f32"], name="many_heads", geometry=wl.Geometry(80, 80, 128, "bf16", 1.0e4, 8192),
+                    n_store_docs=100, docs_per_query=50, batch=2, doc_len_range=(5, 30), tq=3, prefix_len=6,
+                    doc_stored_start=6, n_planted=2)
+    st = wl.build_structure(cfg, seed=7102)
+    a, b = _fused_and_separate(cfg, st, wl.build_layer(cfg, st, seed=32), 20, cf.CF_ALLOC_SORT)
+    assert a["flags"] == 0 and b["flags"] == 0
+    assert torch.equal(a["out"], b["out"]) and torch.equal(a["mass"], b["mass"]) and torch.equal(a["score"], b["score"])
+    assert torch.equal(a["keep"][:, :20], b["keep"][:, :20]) and torch.equal(a["segs"][:, :22], b["segs"][:, :22])
+    assert float(a["mass"][0, :52].sum()) == pytest.approx(80 * 3, rel=1e-5)
 
 
 def test_fused_layer_flags_like_the_separate_calls():
