@@ -13,8 +13,8 @@ namespace {
 // sum * exp2(max - row max) / row sum, which the mass kernel then only has to add up.
 template <int DT>
 __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan p) {
-    __shared__ float2 mlw[kMaxSplit * 64];       // (m, l) per split and row, then the split's weight in .x
-    __shared__ float2 rstat[64];                 // (max, 1/sum) per row of this pass
+    __shared__ float2 mlw[kMaxSplit * 64];       // (m, l) per split and row, then exp2(m - row maximum) in .x
+    __shared__ float part_stat[kWaves][64], part_sum[kWaves][64];   // per wavefront: its splits' maximum and sum, per row
     constexpr int kPre = 8;                      // splits whose partial outputs are fetched before the statistics are ready
 
     const int tid = threadIdx.x;
@@ -61,17 +61,35 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     const int rows_here = min(p.blocks_rg * 16, n_rows - row_base);
     const bool blk_has_rows = pass * 64 + wave * 16 < rows_here;
     __syncthreads();
-    if (tid < 64) {
+    // Row statistics by the whole workgroup: wavefront w takes the splits w, w + 4, ... of every row, the four
+    // partial maxima and then the four partial sums (added in a fixed order) meet in LDS.  A split's weight stays
+    // unnormalised in LDS; the rows are divided by their sum once at the end.
+    {
         float m = -INFINITY;
-        for (int s = 0; s < p.nsplit; ++s) m = fmaxf(m, mlw[s * 64 + tid].x);
-        const float ms = m == -INFINITY ? 0.f : m;
-        float z = 0.f;
-        for (int s = 0; s < p.nsplit; ++s) z += mlw[s * 64 + tid].y * exp2f(mlw[s * 64 + tid].x - ms);
-        const float iz = z > 0.f ? 1.f / z : 0.f;
-        for (int s = 0; s < p.nsplit; ++s) mlw[s * 64 + tid].x = exp2f(mlw[s * 64 + tid].x - ms) * iz;
-        rstat[tid] = make_float2(ms, pass * 64 + tid < rows_here ? iz : 0.f);    // padding rows carry no mass
+        for (int s = wave; s < p.nsplit; s += kWaves) m = fmaxf(m, mlw[s * 64 + lane].x);
+        part_stat[wave][lane] = m;
     }
     __syncthreads();
+    auto row_max = [&](int row) {
+        const float m = fmaxf(fmaxf(part_stat[0][row], part_stat[1][row]), fmaxf(part_stat[2][row], part_stat[3][row]));
+        return m == -INFINITY ? 0.f : m;
+    };
+    {
+        const float ms = row_max(lane);
+        float z = 0.f;
+        for (int s = wave; s < p.nsplit; s += kWaves) {
+            const float2 v = mlw[s * 64 + lane];
+            const float e = exp2f(v.x - ms);
+            z += v.y * e;
+            mlw[s * 64 + lane].x = e;
+        }
+        part_sum[wave][lane] = z;
+    }
+    __syncthreads();
+    auto row_inv_sum = [&](int row) {
+        const float z = ((part_sum[0][row] + part_sum[1][row]) + part_sum[2][row]) + part_sum[3][row];
+        return z > 0.f ? 1.f / z : 0.f;
+    };
     f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < kPre; ++s)
@@ -86,6 +104,7 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
                 if (s0 + i < p.nsplit) o += more[i] * mlw[(s0 + i) * 64 + wave * 16 + li].x;
         }
     const int lrow = pass * 64 + wave * 16 + li;
+    o *= row_inv_sum(wave * 16 + li);
     if (merge && lrow < rows_here) {
         const int m2 = row_base + lrow;
         const int gi = (int)div_exact((unsigned)m2, (unsigned)tq), t = m2 - gi * tq;
@@ -99,7 +118,7 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     // give meaningless numbers that the mass kernel never reads
     if (a.mass != nullptr) {
         float* masspart = reinterpret_cast<float*>(ws + p.off_masspart) + ((int64_t)unit * p.nrb + pass) * p.slots;
-        const float2 st = rstat[lane];
+        const float2 st = make_float2(row_max(lane), pass * 64 + lane < rows_here ? row_inv_sum(lane) : 0.f);   // padding rows carry no mass
         auto reduce = [&](int k, float2 v) {
             const float c = wave_sum_dpp(st.y > 0.f ? v.y * exp2f(v.x - st.x) * st.y : 0.f);
             if (lane == 0 && k < p.slots) masspart[k] = c;
