@@ -22,10 +22,11 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     const int wave = tid / kWave;
     const int li = lane & 15, lg = lane >> 4;
     char* ws = static_cast<char*>(a.workspace);
-    // grid (channel block + 8 * pass, kv head * row groups + row group, query)
+    // grid (channel block + 8 * pass — or just the pass when there is nothing to merge —, kv head * row groups + row group, query)
     const int hq = a.n_q_heads, group = p.group;
-    const int dbq = blockIdx.x & 7;
-    const int pass = (int)(blockIdx.x >> 3);
+    const int x_shift = p.direct_out ? 0 : 3;        // nothing to merge: one workgroup per (unit, pass) reduces every slot
+    const int dbq = blockIdx.x & ((1 << x_shift) - 1);
+    const int pass = (int)(blockIdx.x >> x_shift);
     const int b = blockIdx.z;
     const int hkv = p.n_rg == 1 ? (int)blockIdx.y : (int)div_exact(blockIdx.y, (unsigned)p.n_rg);
     const int rg = (int)blockIdx.y - hkv * p.n_rg;
@@ -37,7 +38,8 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     const f32x4* src = opart + ((int64_t)blk * 8 + dbq) * kWave + lane;
     const int64_t split_stride = (int64_t)p.rows_wg / 16 * 8 * kWave;
     const float2* massml = reinterpret_cast<const float2*>(ws + p.off_massml) + (int64_t)unit * p.slots * p.rows_wg + pass * 64 + lane;
-    const int k_first = dbq * kWaves + wave, k_step = 8 * kWaves;
+    const int k_first = dbq * kWaves + wave, k_step = kWaves << x_shift;
+    constexpr int kSv = 8;                           // slot statistics fetched up front per wavefront
 
     // Everything this workgroup reads is requested up front — row statistics, partial outputs of the
     // first splits, the first slot statistics — so the three round trips to memory overlap.
@@ -49,11 +51,11 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     f32x4 pre[kPre];
 #pragma unroll
     for (int s = 0; s < kPre; ++s) pre[s] = merge && s < p.nsplit ? src[s * split_stride] : f32x4{0.f, 0.f, 0.f, 0.f};
-    float2 sv[2];
+    float2 sv[kSv];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < kSv; ++j) {
         const int k = k_first + j * k_step;
-        sv[j] = k < p.slots ? massml[(int64_t)k * p.rows_wg] : make_float2(0.f, 0.f);
+        sv[j] = a.mass != nullptr && k < p.slots ? massml[(int64_t)k * p.rows_wg] : make_float2(0.f, 0.f);
     }
     const int tq = min(q1 - q0, a.max_tq);
     const int n_rows = group * tq;
@@ -124,8 +126,9 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
             if (lane == 0 && k < p.slots) masspart[k] = c;
         };
 #pragma unroll
-        for (int j = 0; j < 2; ++j) reduce(k_first + j * k_step, sv[j]);
-        for (int k = k_first + 2 * k_step; k < p.slots; k += k_step) reduce(k, massml[(int64_t)k * p.rows_wg]);
+        for (int j = 0; j < kSv; ++j)
+            if (k_first + j * k_step < p.slots) reduce(k_first + j * k_step, sv[j]);
+        for (int k = k_first + kSv * k_step; k < p.slots; k += k_step) reduce(k, massml[(int64_t)k * p.rows_wg]);
     }
 }
 
@@ -426,7 +429,7 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
 }  // namespace
 
 void launch_combine(const AttnArgs& a, const Plan& p, hipStream_t s) {
-    const dim3 grid((unsigned)(8 * p.nrb), (unsigned)(a.n_kv_heads * p.n_rg), (unsigned)a.batch), block(kThreads);
+    const dim3 grid((unsigned)((p.direct_out ? 1 : 8) * p.nrb), (unsigned)(a.n_kv_heads * p.n_rg), (unsigned)a.batch), block(kThreads);
     if (a.dtype == CF_BF16) hipLaunchKernelGGL((attn_combine_kernel<CF_BF16>), grid, block, 0, s, a, p);
     else hipLaunchKernelGGL((attn_combine_kernel<CF_F16>), grid, block, 0, s, a, p);
 }
