@@ -273,7 +273,7 @@ __global__ __launch_bounds__(kPcWaves * kWave, 2) void attn_pc_kernel(AttnArgs a
     const int b = __builtin_amdgcn_readfirstlane(x / (p.nsplit * a.n_kv_heads));
     const int unit = (b * a.n_kv_heads + hkv) * p.n_rg + rg;
     const int group = p.group;
-    const QueryHead qh = load_query_head(a, b, REG_TABLE ? lane : (int)threadIdx.x);
+    const QueryHead qh = load_query_head<false>(a, b, REG_TABLE ? lane : (int)threadIdx.x);
     const int tq = min(qh.tq_raw, a.max_tq);
     const int row_base = rg * p.blocks_rg * 16;
     const int row_limit = min(group * tq, row_base + p.blocks_rg * 16);

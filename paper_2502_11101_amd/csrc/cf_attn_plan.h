@@ -115,9 +115,17 @@ struct QueryHead {
 
 // `entry`: which table entry this thread takes (its index in the workgroup for the LDS table, its lane
 // for the register table).
+// kAlways: threads past the stride re-read the last entry instead of skipping the load — a conditional load makes
+// the compiler wait for it inside the branch, before the scalar loads below are even issued (a whole round trip).
+// (The producer/consumer attention kernel keeps the conditional form: it has no register to spare and runs long.)
+template <bool kAlways = true>
 __device__ __forceinline__ QueryHead load_query_head(const AttnArgs& a, int b, int entry) {   // b: wave-uniform
     QueryHead h;
-    if (entry < a.seg_stride) h.seg = a.segs[(int64_t)b * a.seg_stride + entry];   // seg_stride <= kMaxSegs == kThreads
+    if constexpr (kAlways) {
+        h.seg = a.segs[(int64_t)b * a.seg_stride + min(entry, a.seg_stride - 1)];   // seg_stride >= 1; callers test entry < n
+    } else {
+        if (entry < a.seg_stride) h.seg = a.segs[(int64_t)b * a.seg_stride + entry];   // seg_stride <= kMaxSegs
+    }
     const int q0 = a.q_off[b], q1 = a.q_off[b + 1], qt = a.q_off[a.batch], n = a.n_seg[b], qn = a.q_new_start[b];
     asm volatile("" ::"s"(q0), "s"(q1), "s"(qt), "s"(n), "s"(qn));    // all five scalar loads are out before any is used
     h.q0 = q0;

@@ -41,22 +41,33 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     const int k_first = dbq * kWaves + wave, k_step = kWaves << x_shift;
     constexpr int kSv = 8;                           // slot statistics fetched up front per wavefront
 
-    // Everything this workgroup reads is requested up front — row statistics, partial outputs of the
-    // first splits, the first slot statistics — so the three round trips to memory overlap.
-    for (int idx = tid; idx < p.nsplit * 64; idx += kThreads) mlw[idx] = ml[(idx >> 6) * p.rows_wg + (idx & 63)];
-    // (a wavefront whose 16 rows are all padding reads what an earlier call left there: in bounds, never stored;
-    // not waiting for the query's length here saves a round trip)
-    // (one split only: the attention kernel wrote the output rows itself, only the slot statistics are left)
+    // Everything this workgroup reads is requested up front — row statistics, partial outputs of the first splits,
+    // the first slot statistics — so the round trips to memory overlap.  Every load is unconditional (a clamped,
+    // in-bounds address; what lies past the end is dropped afterwards): a load inside a branch makes the compiler
+    // wait for it before the branch ends, which would put the round trips one behind the other.
+    // (A wavefront whose 16 rows are all padding reads what an earlier call left there: never stored; not waiting for
+    // the query's length here saves a round trip.  With one split the attention kernel wrote the output rows itself:
+    // nothing to merge, the partial outputs' area does not exist and a harmless address is read instead.)
     const bool merge = !p.direct_out;
+    constexpr int kMl = kMaxSplit * 64 / kThreads;   // (m, l) pairs per thread
+    const int n_ml = p.nsplit * 64;
+    float2 ml_regs[kMl];
+#pragma unroll
+    for (int i = 0; i < kMl; ++i) {
+        const int idx = min(tid + i * kThreads, n_ml - 1);
+        ml_regs[i] = ml[(idx >> 6) * p.rows_wg + (idx & 63)];
+    }
+    const f32x4* src_safe = merge ? src : reinterpret_cast<const f32x4*>(ws + p.off_ml) + (lane & 31);
+    const int64_t stride_safe = merge ? split_stride : 0;
     f32x4 pre[kPre];
 #pragma unroll
-    for (int s = 0; s < kPre; ++s) pre[s] = merge && s < p.nsplit ? src[s * split_stride] : f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < kPre; ++s) pre[s] = src_safe[min(s, p.nsplit - 1) * stride_safe];
     float2 sv[kSv];
 #pragma unroll
-    for (int j = 0; j < kSv; ++j) {
-        const int k = k_first + j * k_step;
-        sv[j] = a.mass != nullptr && k < p.slots ? massml[(int64_t)k * p.rows_wg] : make_float2(0.f, 0.f);
-    }
+    for (int j = 0; j < kSv; ++j) sv[j] = massml[(int64_t)min(k_first + j * k_step, p.slots - 1) * p.rows_wg];
+#pragma unroll
+    for (int i = 0; i < kMl; ++i)
+        if (tid + i * kThreads < n_ml) mlw[tid + i * kThreads] = ml_regs[i];
     const int tq = min(q1 - q0, a.max_tq);
     const int n_rows = group * tq;
     const int row_base = rg * p.blocks_rg * 16;
@@ -100,7 +111,7 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
         for (int s0 = kPre; s0 < p.nsplit; s0 += kPre) {         // further splits, eight loads at a time
             f32x4 more[kPre];
 #pragma unroll
-            for (int i = 0; i < kPre; ++i) more[i] = s0 + i < p.nsplit ? src[(s0 + i) * split_stride] : f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int i = 0; i < kPre; ++i) more[i] = src[min(s0 + i, p.nsplit - 1) * split_stride];      // unconditional, as above
 #pragma unroll
             for (int i = 0; i < kPre; ++i)
                 if (s0 + i < p.nsplit) o += more[i] * mlw[(s0 + i) * 64 + wave * 16 + li].x;
@@ -261,7 +272,7 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p)
         // then one wavefront finishes alone from a table in its registers — the same sums in the same order
         float r_part[kMassStage / kThreads];
 #pragma unroll
-        for (int i = 0; i < kMassStage / kThreads; ++i) r_part[i] = tid + i * kThreads < n_part_floats ? mp_b[tid + i * kThreads] : 0.f;
+        for (int i = 0; i < kMassStage / kThreads; ++i) r_part[i] = mp_b[min(tid + i * kThreads, n_part_floats - 1)];   // unconditional
         const QueryHead qh = load_query_head(a, b, tid & (kWave - 1));
 #pragma unroll
         for (int i = 0; i < kMassStage / kThreads; ++i)
@@ -337,23 +348,24 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
     const int64_t off = (int64_t)b * stride;
     const int nparts = p.units_per_b * p.nrb;
     const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * nparts * p.slots;
-    // The first batch of row loads and slot partials goes out before anything waits for the query's scalars.
+    // The first batch of row loads, the slot partials and the query's scalars all go out before anything is waited
+    // for; every load is unconditional (a clamped, in-bounds index: threads past the end re-read the last element and
+    // drop it), since a load inside a branch is waited for before the branch ends.
     const bool row0 = tid < stride;
-    int64_t r_tok = 0;
-    int32_t r_len = 0, r_cand = 0, r_start = 0, r_order = 0;
-    float r_score = 0.f, r_part = 0.f;
-    if (row0) {
-        r_tok = pr.doc_tok_offset[off + tid];
-        r_len = pr.doc_len[off + tid];
-        r_cand = pr.cand[off + tid];
-        r_score = a.score_accum[off + tid];
-        r_start = pr.new_start[off + tid];
-        r_order = pr.order[off + tid];
-    }
-    if (tid < nparts * p.slots) r_part = mp_b[tid];
-    const QueryHead qh = load_query_head(a, b, (int)threadIdx.x);
+    const int row_i = min(tid, stride - 1);
+    const int64_t r_tok = pr.doc_tok_offset[off + row_i];
+    const int32_t r_len = pr.doc_len[off + row_i], r_cand = pr.cand[off + row_i];
+    const float r_score = a.score_accum[off + row_i];
+    const int32_t r_start = pr.new_start[off + row_i], r_order = pr.order[off + row_i];
+    constexpr int kPartRegs = 4;                     // slot partials per thread fetched with the first batch
+    const int n_part_floats = nparts * p.slots;
+    float r_part[kPartRegs];
+#pragma unroll
+    for (int i = 0; i < kPartRegs; ++i) r_part[i] = mp_b[min(tid + i * kEpiThreads, n_part_floats - 1)];
     const int n_cand = pr.n_cand[b];
-    if (tid == 0) { s_int[4] = pr.q_start[b]; s_int[5] = pr.n_reuse[b]; }
+    const int r_q_start = pr.q_start[b], r_n_reuse = pr.n_reuse[b];
+    const QueryHead qh = load_query_head(a, b, (int)threadIdx.x);
+    if (tid == 0) { s_int[4] = r_q_start; s_int[5] = r_n_reuse; }
     if (row0) {
         l_tok[tid] = r_tok; l_len[tid] = r_len; l_cand[tid] = r_cand; l_score[tid] = r_score; l_start[tid] = r_start;
         l_order[tid] = r_order;
@@ -366,8 +378,10 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
         l_start[i] = pr.new_start[off + i];
         l_order[i] = pr.order[off + i];
     }
-    if (tid < nparts * p.slots) l_part[tid] = r_part;
-    for (int i = tid + kEpiThreads; i < nparts * p.slots; i += kEpiThreads) l_part[i] = mp_b[i];
+#pragma unroll
+    for (int i = 0; i < kPartRegs; ++i)
+        if (tid + i * kEpiThreads < n_part_floats) l_part[tid + i * kEpiThreads] = r_part[i];
+    for (int i = tid + kPartRegs * kEpiThreads; i < n_part_floats; i += kEpiThreads) l_part[i] = mp_b[i];
     // With few candidates one wavefront finishes alone: the others leave, and the barriers of the stages
     // below (which only wait for wavefronts that are still running) cost nothing.
     const int nthr = n_cand <= 2 * kWave ? kWave : kEpiThreads;
