@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = 2500.0      # dense bf16 / fp16
 # HBM bytes per launch of the dominant kernel on this workload, from the FETCH_SIZE and WRITE_SIZE counter runs
 # summarised in profiles/attn_tile_kernel_llama2_7b_layer.md (scaled by a 1 GiB copy kernel: x2.000 and x1.000)
-TRAFFIC_BYTES_PER_LAUNCH = 30_880_430 + 6_660_096
+TRAFFIC_BYTES_PER_LAUNCH = 30_892_694 + 6_660_096
 WORKLOAD = "llama2_7b_layer"
 
 
