@@ -41,7 +41,7 @@ extern "C" {
 typedef enum cf_status {
     CF_OK = 0,
     CF_ERR_INVALID_ARG = -1,  /* null pointer, negative size, misaligned base, keep > stride ...   */
-    CF_ERR_UNSUPPORTED = -2,  /* head_dim / dtype / pairing combination no kernel exists for        */
+    CF_ERR_UNSUPPORTED = -2,  /* head_dim / dtype / pairing combination no kernel exists for, or a size past a kernel's limit */
     CF_ERR_RANGE = -3,        /* positions outside [0, max_positions), range too small              */
     CF_ERR_WORKSPACE = -4,    /* workspace missing or smaller than cf_prefill_workspace_bytes()     */
     CF_ERR_DEVICE = -5        /* a HIP runtime call failed; see cf_last_error()                     */
@@ -164,6 +164,8 @@ CF_API size_t cf_prefill_workspace_bytes(const cf_layer_desc* desc, int32_t batc
  *   workspace    device, >= cf_prefill_workspace_bytes(desc, batch, max_tq, seg_stride, max_kv_tokens),
  *                256-byte aligned; contents are scratch
  * Reductions run in a fixed order: the same inputs give bit-identical outputs.
+ * Limits of the 16-bit kernels (CF_ERR_UNSUPPORTED beyond them): batch <= 65535 and
+ * n_kv_heads * ceil(n_q_heads / n_kv_heads * max_tq / 192) <= 65535 (grid dimensions).
  */
 CF_API cf_status cf_prefill_attention(const cf_layer_desc* desc,
                                const void* q, const int32_t* q_off, int32_t q_stored_start,

@@ -100,6 +100,10 @@ def test_prefill_argument_checks():
     assert call(workspace=0x10010)[0] == cf.CF_ERR_WORKSPACE
     st, msg = call(workspace_bytes=16)
     assert "workspace" in msg
+    # more queries than a grid dimension holds: refused before any launch
+    big = cf.cf_prefill_workspace_bytes(d, 70000, 8, 4, 100)
+    st, msg = call(batch=70000, workspace_bytes=big)
+    assert st == cf.CF_ERR_UNSUPPORTED and "65535" in msg
     # the kernel timing aid: nothing to report while it is off, switching it off twice is fine (no GPU needed)
     assert _status(cf.cf_profile_kernel_ms)[0] == cf.CF_ERR_INVALID_ARG
     cf.cf_profile_kernel_events(False)
