@@ -384,6 +384,36 @@ def test_few_rows_outputs_only(dtype, layout, hq, hkv, tq, docs, len_range, pref
     assert G.row_error(out_np, other) <= G.OUT_TOL[g.dtype]
 
 
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(n):
+        hkv = int(rng.choice([1, 2, 3, 4, 8]))
+        group = int(rng.choice([1, 1, 2, 4, 7]))
+        tq = int(rng.choice([1, 2, 3, 8, 16, 17, 31, 48, 64, 70]))
+        docs = int(rng.integers(1, 13))
+        lo = int(rng.integers(1, 60))
+        hi = lo + int(rng.integers(0, 120))
+        prefix = int(rng.choice([0, 0, 1, 7, 32, 33]))
+        batch = int(rng.choice([1, 2, 3, 5]))
+        dtype = str(rng.choice(["bf16", "f16"]))
+        layout = str(rng.choice(["token", "head", "head_padded"]))
+        shapes.append((dtype, layout, hkv * group, hkv, tq, docs, (lo, hi), prefix, batch))
+    return shapes
+
+
+@pytest.mark.parametrize("dtype,layout,hq,hkv,tq,docs,len_range,prefix,batch", _random_shapes(24, 20250211))
+def test_mfma_path_seeded_random_shapes(dtype, layout, hq, hkv, tq, docs, len_range, prefix, batch):
+    """A seeded sweep over head counts, group sizes, query lengths, document counts and lengths, prefixes, batches,
+    dtypes and store layouts: outputs, masses, accumulated scores and tables against the oracle (both 16-bit
+    attention kernels, single-split and multi-split plans, ragged tiles, one-token documents)."""
+    cfg = wl.scaled(wl.CONFIGS["tiny_f32"], name=f"rand_{dtype}_{hq}_{hkv}_{tq}_{docs}_{batch}",
+                    geometry=wl.Geometry(hq, hkv, 128, dtype, 1.0e6, 32768), n_store_docs=batch * docs + 3,
+                    docs_per_query=docs, batch=batch, doc_len_range=len_range, tq=tq, prefix_len=prefix,
+                    doc_stored_start=prefix + 5, n_planted=1)
+    _run_single_layer(cfg, seed=int(hq * 131 + tq * 17 + docs), mass_tol=4e-3, layout=layout)
+
+
 def test_mfma_path_is_deterministic():
     cfg = wl.CONFIGS["llama2_7b_layer"]
     st = wl.build_structure(cfg)
@@ -516,6 +546,55 @@ def test_fused_layer_many_candidates_and_batch(strategy):
         assert torch.equal(a[key], b[key]), key
     n = int(a["n_seg"][0].item())
     assert torch.equal(a["segs"][:, :n], b["segs"][:, :n])
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_fused_layer_seeded_random_prunes(case):
+    """A seeded sweep of prune events through cf_prefill_layer: random geometry, candidate count, keep and
+    strategy; the cut must be exact for the scores the device accumulated, the allocation and the next table
+    bit-exact against the oracle's allocator."""
+    rng = np.random.default_rng(4100 + case)
+    hkv = int(rng.choice([1, 2, 4, 8]))
+    group = int(rng.choice([1, 2, 7]))
+    tq = int(rng.choice([1, 5, 16, 48]))
+    docs = int(rng.integers(2, 40))
+    keep = int(rng.integers(1, docs + 1))
+    lo = int(rng.integers(1, 50))
+    hi = lo + int(rng.integers(0, 60))
+    prefix = int(rng.choice([0, 3, 32]))
+    batch = int(rng.choice([1, 2, 4]))
+    strategy = int(rng.choice([cf.CF_ALLOC_SORT, cf.CF_ALLOC_ALIGN]))
+    dtype = str(rng.choice(["bf16", "f16"]))
+    cfg = wl.scaled(wl.CONFIGS["tiny_f32"], name=f"randprune_{case}", geometry=wl.Geometry(hkv * group, hkv, 128, dtype, 1.0e4, 8192),
+                    n_store_docs=batch * docs, docs_per_query=docs, batch=batch, doc_len_range=(lo, hi), tq=tq,
+                    prefix_len=prefix, doc_stored_start=prefix, n_planted=1)
+    _say(f"random prune {case}: {dtype} {hkv * group}/{hkv} heads, tq {tq}, {docs} documents keep {keep}, batch {batch}, strategy {strategy}")
+    g = cfg.geometry
+    st = wl.build_structure(cfg, seed=7200 + case)
+    t = wl.build_layer(cfg, st, seed=300 + case)
+    pb = G.make_batch(cfg, st, layout="head")
+    dev = G.upload_layer(cfg, t, "head")
+    out = torch.empty_like(dev["q"])
+    pb.allocate_initial()
+    pb.layer(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out, keep=keep, strategy=strategy)
+    torch.cuda.synchronize()
+    assert pb.flags() == 0
+    score = pb.score.cpu().numpy()
+    pb.advance()
+    for b in range(batch):
+        lens = [int(x) for x in st.doc_lens[st.query_docs[b]]]
+        kept = pb.cand[b, :keep].tolist() if strategy == cf.CF_ALLOC_SORT else None
+        ranked = orc.prune_topk(score[b], lens, list(range(docs)), keep)
+        assert int(pb.n_cand[b].item()) == keep
+        assert sorted(pb.cand[b, :keep].tolist()) == sorted(ranked)
+        if kept is not None:
+            assert kept == ranked
+        order = ranked if strategy == cf.CF_ALLOC_SORT else sorted(ranked)
+        ref_ns, ref_q, ref_nr = orc.assign_positions(lens, order, cfg.prefix_len, g.max_positions - cfg.tq)
+        assert int(pb.q_start[b].item()) == ref_q and int(pb.n_reuse[b].item()) == ref_nr
+        assert {sg.doc: sg.new_start for sg in G.device_segments(pb, b) if sg.kind == cf.CF_SEG_DOC} == ref_ns
+        segs = G.device_segments(pb, b)
+        assert len(segs) == keep + (1 if prefix else 0) + 1 and segs[-1].kind == cf.CF_SEG_SELF and segs[-1].new_start == ref_q
 
 
 def test_mass_reduction_forms_add_in_the_same_order():
