@@ -414,6 +414,25 @@ def test_mfma_path_seeded_random_shapes(dtype, layout, hq, hkv, tq, docs, len_ra
     _run_single_layer(cfg, seed=int(hq * 131 + tq * 17 + docs), mass_tol=4e-3, layout=layout)
 
 
+@pytest.mark.parametrize("docs,fused", [(254, False), (300, False), (300, True)])
+def test_more_segments_than_the_16_bit_kernels_hold(docs, fused):
+    """254 documents fill the 256-entry segment table of the 16-bit kernels exactly; 300 do not fit and the call
+    takes the generic kernel (and, fused, the stand-alone prune kernels) — same results either way."""
+    cfg = wl.scaled(wl.CONFIGS["tiny_f32"], name=f"segs_{docs}", geometry=wl.Geometry(4, 2, 128, "bf16", 1.0e4, 8192),
+                    n_store_docs=docs, docs_per_query=docs, batch=1, doc_len_range=(1, 9), tq=3, prefix_len=2,
+                    doc_stored_start=2, n_planted=3)
+    if not fused:
+        _run_single_layer(cfg, seed=55, mass_tol=4e-3)
+        return
+    st = wl.build_structure(cfg, seed=7055)
+    a, b = _fused_and_separate(cfg, st, wl.build_layer(cfg, st, seed=55), 40, cf.CF_ALLOC_SORT)
+    assert a["flags"] == 0 and b["flags"] == 0
+    assert torch.equal(a["out"], b["out"]) and torch.equal(a["score"], b["score"])
+    assert torch.equal(a["keep"][:, :40], b["keep"][:, :40]) and torch.equal(a["segs"][:, :42], b["segs"][:, :42])
+    ref = orc.prune_topk(b["score"][0].cpu().numpy(), st.doc_lens[st.query_docs[0]], list(range(docs)), 40)
+    assert b["keep"][0, :40].tolist() == ref
+
+
 def test_mfma_path_is_deterministic():
     cfg = wl.CONFIGS["llama2_7b_layer"]
     st = wl.build_structure(cfg)
