@@ -631,6 +631,23 @@ def test_mass_reduction_forms_add_in_the_same_order():
     assert float(a["mass"][0, :52].sum()) == pytest.approx(80 * 3, rel=1e-5)
 
 
+def test_fused_layer_too_large_for_the_epilogue_kernel():
+    """128 kv heads times 120 documents: the slot partials of a query do not fit the fused epilogue's LDS, so the
+    fused call falls back to the mass kernel and the stand-alone prune kernels; same tables as the separate calls."""
+    cfg = wl.scaled(wl.CONFIGS["tiny_f32"], name="big_epilogue", geometry=wl.Geometry(128, 128, 128, "bf16", 1.0e4, 8192),
+                    n_store_docs=120, docs_per_query=120, batch=1, doc_len_range=(2, 12), tq=2, prefix_len=3,
+                    doc_stored_start=3, n_planted=2)
+    st = wl.build_structure(cfg, seed=7103)
+    a, b = _fused_and_separate(cfg, st, wl.build_layer(cfg, st, seed=33), 30, cf.CF_ALLOC_SORT)
+    assert a["flags"] == 0 and b["flags"] == 0
+    assert torch.equal(a["out"], b["out"]) and torch.equal(a["mass"], b["mass"]) and torch.equal(a["score"], b["score"])
+    assert torch.equal(a["keep"][:, :30], b["keep"][:, :30]) and torch.equal(a["segs"][:, :32], b["segs"][:, :32])
+    ref = orc.prune_topk(b["score"][0].cpu().numpy(), st.doc_lens[st.query_docs[0]], list(range(120)), 30)
+    assert b["keep"][0, :30].tolist() == ref
+    assert float(a["mass"][0, :122].sum()) == pytest.approx(128 * 2, rel=1e-5)
+    # (44 bytes per document row + 4 bytes per (kv head, slot) partial: 5280 + 4 * 128 * 126 = 69 792 > 60 KB)
+
+
 def test_fused_layer_flags_like_the_separate_calls():
     """A positional range too short for the longest survivor: both paths raise the same flag and leave the
     positions and the placement order as they were."""
