@@ -1118,3 +1118,49 @@ def test_offline_store_builder_writes_the_cache_store(layout):
     score = H.doc_scores(segs, ref_mass, len(doc_lens))
     assert pb.keep_idx[0, :3].tolist() == orc.prune_topk(pb.score.cpu().numpy()[0], [int(x) for x in doc_lens], list(range(len(doc_lens))), 3)
     assert np.isfinite(score).all()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_ragged_batch_with_an_empty_query(dtype):
+    """Queries of 5, 0 and 7 rows in one batch (the middle one has no rows at all) over shared documents: the
+    non-empty ones match the oracle, the empty one leaves zero masses, nothing is written out of place."""
+    rng = np.random.default_rng(97)
+    g = wl.Geometry(4, 2, 128 if dtype == "bf16" else 64, dtype, 1.0e4, 4096)
+    prefix, doc_lens, tqs = 6, [40, 33, 1], [5, 0, 7]
+    doc_off = np.concatenate([[prefix], prefix + np.cumsum(doc_lens)])
+    n_store = int(doc_off[-1])
+    q_off = np.concatenate([[0], np.cumsum(tqs)]).astype(np.int32)
+    total = int(q_off[-1])
+    rnd = lambda *shape: wl.round_to_dtype(rng.standard_normal(shape, dtype=np.float32), g.dtype)
+    q, k_self, v_self = rnd(total, g.n_q_heads, g.head_dim), rnd(total, g.n_kv_heads, g.head_dim), rnd(total, g.n_kv_heads, g.head_dim)
+    k_store, v_store = rnd(n_store, g.n_kv_heads, g.head_dim), rnd(n_store, g.n_kv_heads, g.head_dim)
+    desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions)
+    batch, seg_stride, max_tq = 3, 5, max(tqs)
+    q_pos = [100, 200, 300]
+    tables = [[orc.Segment(0, prefix, 0, 0, orc.KIND_PREFIX, -1)] +
+              [orc.Segment(int(doc_off[d]), doc_lens[d], prefix, 10 + 50 * d + 3 * b, orc.KIND_DOC, d) for d in range(3)] +
+              [orc.Segment(int(q_off[b]), tqs[b], 0, q_pos[b], orc.KIND_SELF, -1)] for b in range(batch)]
+    segs = cf.segments_to_device(cf.segments_array([s for tb in tables for s in tb]))
+    n_seg = torch.full((batch,), 5, **I32)
+    dev = {name: pl.to_device(x, g.dtype) for name, x in dict(q=q, k_self=k_self, v_self=v_self, k_store=k_store, v_store=v_store).items()}
+    out = torch.full_like(dev["q"], 7.0)
+    mass = torch.full((batch, seg_stride), -1.0, dtype=torch.float32, device="cuda")
+    score = torch.zeros((batch, 3), dtype=torch.float32, device="cuda")
+    max_kv = prefix + sum(doc_lens) + max_tq
+    ws_bytes = cf.cf_prefill_workspace_bytes(desc, batch, max_tq, seg_stride, max_kv)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    flag = torch.zeros(1, **I32)
+    cf.cf_prefill_attention(desc, dev["q"], torch.from_numpy(q_off).cuda(), 0, torch.tensor(q_pos, **I32), dev["k_store"], dev["v_store"],
+                            n_store, dev["k_self"], dev["v_self"], segs, n_seg, seg_stride, batch, max_tq, max_kv, out, mass, score, 3,
+                            ws, ws_bytes, flag)
+    torch.cuda.synchronize()
+    assert flag.item() == 0
+    got, m, sc = out.float().cpu().numpy(), mass.cpu().numpy(), score.cpu().numpy()
+    for b in (0, 2):
+        lo, hi = int(q_off[b]), int(q_off[b + 1])
+        ref_out, ref_mass = orc.prefill_attention(q[lo:hi].astype(np.float64), 0, q_pos[b], k_store, v_store, k_self, v_self,
+                                                  tables[b], g.n_kv_heads, g.rope_base)
+        assert G.row_error(got[lo:hi], ref_out) <= G.OUT_TOL[g.dtype]
+        assert G.rel_error(m[b], ref_mass) <= (4e-3 if dtype == "bf16" else G.MASS_TOL[g.dtype])
+        assert G.rel_error(sc[b], ref_mass[1:4]) <= (4e-3 if dtype == "bf16" else G.MASS_TOL[g.dtype])
+    assert np.all(m[1] == 0.0) and np.all(sc[1] == 0.0)
