@@ -1164,3 +1164,44 @@ def test_ragged_batch_with_an_empty_query(dtype):
         assert G.rel_error(m[b], ref_mass) <= (4e-3 if dtype == "bf16" else G.MASS_TOL[g.dtype])
         assert G.rel_error(sc[b], ref_mass[1:4]) <= (4e-3 if dtype == "bf16" else G.MASS_TOL[g.dtype])
     assert np.all(m[1] == 0.0) and np.all(sc[1] == 0.0)
+
+
+@pytest.mark.parametrize("base,max_pos", [(1.0e4, 4096), (1.0e6, 32768)])
+def test_largest_relative_shifts(base, max_pos):
+    """Documents at the start of the positional range and the query at its very end (and the other way round): the
+    relative shift of a key reaches the whole range; cos/sin of that many positions times theta must still be
+    accurate (angle reduced in fp64)."""
+    rng = np.random.default_rng(98)
+    g = wl.Geometry(4, 4, 128, "bf16", base, max_pos)
+    doc_lens, tq = [70, 45], 6
+    doc_off = np.concatenate([[0], np.cumsum(doc_lens)])
+    n_store = int(doc_off[-1])
+    rnd = lambda *shape: wl.round_to_dtype(rng.standard_normal(shape, dtype=np.float32), g.dtype)
+    q, k_self, v_self = rnd(2 * tq, g.n_q_heads, g.head_dim), rnd(2 * tq, g.n_kv_heads, g.head_dim), rnd(2 * tq, g.n_kv_heads, g.head_dim)
+    k_store, v_store = rnd(n_store, g.n_kv_heads, g.head_dim), rnd(n_store, g.n_kv_heads, g.head_dim)
+    desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions)
+    q_pos = [max_pos - tq, 0]                        # query 0 at the end of the range, query 1 at its start
+    tables = [[orc.Segment(0, 70, max_pos - 70, 0, orc.KIND_DOC, 0), orc.Segment(70, 45, 0, 70, orc.KIND_DOC, 1),
+               orc.Segment(0, tq, 0, q_pos[0], orc.KIND_SELF, -1)],
+              [orc.Segment(0, 70, 0, max_pos - 200, orc.KIND_DOC, 0), orc.Segment(70, 45, 17, max_pos - 130, orc.KIND_DOC, 1),
+               orc.Segment(tq, tq, max_pos - tq, q_pos[1], orc.KIND_SELF, -1)]]
+    segs = cf.segments_to_device(cf.segments_array([s for tb in tables for s in tb]))
+    n_seg = torch.full((2,), 3, **I32)
+    dev = {name: pl.to_device(x, g.dtype) for name, x in dict(q=q, k_self=k_self, v_self=v_self, k_store=k_store, v_store=v_store).items()}
+    out = torch.empty_like(dev["q"])
+    mass = torch.zeros((2, 3), dtype=torch.float32, device="cuda")
+    ws_bytes = cf.cf_prefill_workspace_bytes(desc, 2, tq, 3, n_store + tq)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    flag = torch.zeros(1, **I32)
+    # q rows carry RoPE for local positions (q_stored_start 0); the own block of query 1 was stored at the range's end
+    cf.cf_prefill_attention(desc, dev["q"], torch.tensor([0, tq, 2 * tq], **I32), 0, torch.tensor(q_pos, **I32), dev["k_store"],
+                            dev["v_store"], n_store, dev["k_self"], dev["v_self"], segs, n_seg, 3, 2, tq, n_store + tq, out, mass,
+                            None, 1, ws, ws_bytes, flag)
+    torch.cuda.synchronize()
+    assert flag.item() == 0
+    got, m = out.float().cpu().numpy(), mass.cpu().numpy()
+    for b in range(2):
+        ref_out, ref_mass = orc.prefill_attention(q[b * tq:(b + 1) * tq].astype(np.float64), 0, q_pos[b], k_store, v_store, k_self,
+                                                  v_self, tables[b], g.n_kv_heads, g.rope_base)
+        assert G.row_error(got[b * tq:(b + 1) * tq], ref_out) <= G.OUT_TOL[g.dtype]
+        assert G.rel_error(m[b], ref_mass) <= 4e-3
