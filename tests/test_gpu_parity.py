@@ -1205,3 +1205,48 @@ def test_largest_relative_shifts(base, max_pos):
                                                   v_self, tables[b], g.n_kv_heads, g.rope_base)
         assert G.row_error(got[b * tq:(b + 1) * tq], ref_out) <= G.OUT_TOL[g.dtype]
         assert G.rel_error(m[b], ref_mass) <= 4e-3
+
+
+def test_layer_calls_replay_from_a_hip_graph():
+    """The library allocates nothing and clears nothing with memsets, so its calls can be captured: four layer calls
+    (a prune event in each) recorded into one HIP graph replay to exactly the eager results, several times, with
+    eager work and synchronisations between the replays."""
+    cfg = wl.CONFIGS["llama2_7b_layer"]
+    st = wl.build_structure(cfg)
+    layers = [G.upload_layer(cfg, wl.build_layer(cfg, st, layer), "head") for layer in range(4)]
+    pb = G.make_batch(cfg, st, layout="head")
+    pb.allocate_initial()
+    outs = [torch.empty_like(layers[0]["q"]) for _ in layers]
+
+    def run_all():
+        for L, o in zip(layers, outs):
+            pb.layer(L["q"], L["k_self"], L["v_self"], L["k_store"], L["v_store"], o, keep=cfg.keep)
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        pb.score.zero_()
+        run_all()
+        torch.cuda.synchronize()
+        assert pb.flags() == 0
+        eager = dict(outs=[o.clone() for o in outs], score=pb.score.clone(), keep=pb.keep_idx.clone(), segs=pb.next_segs.clone(),
+                     mass=pb.mass.clone())
+        graph = torch.cuda.CUDAGraph()
+        pb.score.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run_all()
+        scratch = torch.zeros(1 << 20, device="cuda")
+        for rep in range(3):
+            pb.score.zero_()
+            pb.mass.fill_(-1.0)
+            pb.next_segs.zero_()
+            for o in outs:
+                o.zero_()
+            scratch.add_(1.0)                        # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert pb.flags() == 0
+            assert all(torch.equal(a, b) for a, b in zip(outs, eager["outs"])), rep
+            assert torch.equal(pb.score, eager["score"]) and torch.equal(pb.keep_idx, eager["keep"]), rep
+            assert torch.equal(pb.next_segs, eager["segs"]) and torch.equal(pb.mass, eager["mass"]), rep
