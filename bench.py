@@ -424,6 +424,9 @@ def main() -> int:
     ap.add_argument("--workload", choices=[WORKLOAD, "qwen2_7b_layer", "qwen2_1p5b_batch"], default=WORKLOAD,
                     help="the headline workload (default), or one of the GQA configurations, whose attention kernel is "
                          "priced against the MFMA peak instead of HBM bandwidth")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="queries per step for --workload llama2_7b_layer (default: the configuration's own, 1); each query "
+                         "gets documents of its own, so the step streams batch times the K/V")
     ap.add_argument("--store-layout", choices=["head", "token"], default="head",
                     help="layout of the cache store: head-major [kv head][token][d] (default, the layout the "
                          "store is meant to be kept in) or token-major [token][kv head][d]")
@@ -473,6 +476,10 @@ def main() -> int:
     g = cfg.geometry
     if args.workload == "qwen2_1p5b_batch":
         args.layers = min(args.layers, 2)             # 1.5 GB of store per layer copy
+    if args.batch > 1 and args.workload == WORKLOAD:
+        cfg = wl.scaled(cfg, batch=args.batch, n_store_docs=args.batch * cfg.docs_per_query)
+        per_layer = args.batch * cfg.docs_per_query * cfg.doc_len_range[1] * 2 * g.n_kv_heads * g.head_dim * 2
+        args.layers = max(2, min(args.layers, int(3.0e9 // per_layer)))       # still well past the last-level cache
     st = wl.build_structure(cfg)
     ts, hs = pl.store_strides(st.n_store_tokens, g.n_kv_heads, g.head_dim, args.store_layout)
     desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions,
@@ -538,7 +545,7 @@ def main() -> int:
     assert pb.flags() == 0, f"device flag {pb.flags()}"
     achieved = kv_tokens * bytes_per_token / (kernel_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                "frac": achieved / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH if cfg.batch == 1 else None,
                 "kernel": "attn_tile_kernel<bf16,1,32,2,true> (first kernel of cf_prefill_layer / cf_prefill_attention)",
                 "ms_per_launch": kernel_ms, "algorithmic_bytes_per_launch": kv_tokens * bytes_per_token,
                 "launches_timed": n_bracketed, "ms_per_step_events": step_ms, "ms_per_step_without_this_kernel": rest_ms}
