@@ -188,3 +188,12 @@ def test_hot_path_kernels_keep_everything_in_registers():
     for k, u in usage.items():
         if "attn_tile_kernel" in k or "attn_pc_kernel" in k:
             assert u["waves_per_simd"] == 2 and u["vgprs"] + u["agprs"] <= 256, (k, u)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py says so and exits without touching a device."""
+    import subprocess
+    import sys
+
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
