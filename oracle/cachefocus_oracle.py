@@ -33,8 +33,10 @@ Pins (tests/test_oracle_pins.py):
   prefill_attention          softmax rows sum to 1; masses sum to Hq*Tq; closed
                              form for Q = 0; equality with torch's
                              scaled_dot_product_attention in the reducible
-                             cases; invariance under a common position shift;
-                             brute-force triple loop on the tiny configuration.
+                             cases (also with a non-default ``scale``, against the
+                             library's own scale argument); invariance under a
+                             common position shift; brute-force triple loop on the
+                             tiny configuration.
   assemble_final_cache       plain attention of an absolutely positioned query over the
                              assembled cache equals prefill_attention on the original
                              store (relative-position invariance); zero shift copies;

@@ -230,6 +230,48 @@ def test_reduces_to_library_sdpa(hq, hkv):
     assert np.max(np.abs(out - ref.permute(1, 0, 2).numpy())) < 1e-12
 
 
+@pytest.mark.parametrize("factor", [8.0, 0.05, 1.7])
+def test_scale_argument_against_library_sdpa(factor):
+    """Eq. 1's scale when it is not the default 1/sqrt(d): the ``scale`` argument of prefill_attention and of
+    decode_attention against torch's scaled_dot_product_attention(scale=...) — cached document, causal own
+    block (GQA, kv heads repeated), and the document-wise mass against probabilities formed from torch's
+    softmax of the scaled scores."""
+    rng = np.random.default_rng(81)
+    tq, n, d, hq, hkv = 5, 23, 64, 6, 2
+    scale = factor / np.sqrt(d)
+    q = rng.standard_normal((tq, hq, d))
+    k = rng.standard_normal((n, hkv, d))
+    v = rng.standard_normal((n, hkv, d))
+    ks = rng.standard_normal((tq, hkv, d))
+    vs = rng.standard_normal((tq, hkv, d))
+    rep = hq // hkv
+    heads_first = lambda x, r=1: torch.from_numpy(x).permute(1, 0, 2).repeat_interleave(r, dim=0)
+    sdpa = torch.nn.functional.scaled_dot_product_attention
+    # one cached document at its stored position
+    out, mass = orc.prefill_attention(q, 0, 0, k, v, None, None, [orc.Segment(0, n, 5, 5, orc.KIND_DOC, 0)], hkv, 1.0e4,
+                                      scale=scale)
+    ref = sdpa(heads_first(q), heads_first(k, rep), heads_first(v, rep), scale=scale).permute(1, 0, 2).numpy()
+    assert np.max(np.abs(out - ref)) < 1e-12
+    # the default differs from it (the argument is not ignored)
+    plain, _ = orc.prefill_attention(q, 0, 0, k, v, None, None, [orc.Segment(0, n, 5, 5, orc.KIND_DOC, 0)], hkv, 1.0e4)
+    assert np.max(np.abs(out - plain)) > 1e-3
+    # the own block alone, causal
+    out, _ = orc.prefill_attention(q, 0, 0, None, None, ks, vs, [orc.Segment(0, tq, 0, 0, orc.KIND_SELF, -1)], hkv, 1.0e4,
+                                   scale=scale)
+    ref = sdpa(heads_first(q), heads_first(ks, rep), heads_first(vs, rep), is_causal=True, scale=scale)
+    assert np.max(np.abs(out - ref.permute(1, 0, 2).numpy())) < 1e-12
+    # two documents: per-document mass from torch's softmax of the scaled scores
+    segs = [orc.Segment(0, 9, 2, 2, orc.KIND_DOC, 0), orc.Segment(9, n - 9, 2, 2, orc.KIND_DOC, 1)]
+    _, mass = orc.prefill_attention(q, 0, 0, k, v, None, None, segs, hkv, 1.0e4, scale=scale)
+    probs = torch.softmax(scale * torch.einsum("htd,hnd->htn", heads_first(q), heads_first(k, rep)), dim=-1).numpy()
+    assert mass[0] == pytest.approx(probs[:, :, :9].sum(), rel=1e-12)
+    assert mass[1] == pytest.approx(probs[:, :, 9:].sum(), rel=1e-12)
+    # decode-time attention over an assembled cache
+    got = orc.decode_attention(q, k, v, hkv, scale=scale)
+    ref = sdpa(heads_first(q), heads_first(k, rep), heads_first(v, rep), scale=scale).permute(1, 0, 2).numpy()
+    assert np.max(np.abs(got - ref)) < 1e-12
+
+
 def test_repositioned_attention_equals_attention_on_directly_roped_keys():
     """Keys cached at one position and moved by Eq. 5 give the same attention as
     keys that were given RoPE for the new position in the first place (torch SDPA
