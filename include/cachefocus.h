@@ -73,7 +73,8 @@ typedef enum cf_dev_flag {
     CF_FLAG_NONFINITE_SCORE = 2,/* NaN/Inf in the score array handed to cf_prune_topk              */
     CF_FLAG_DOC_TOO_LONG = 4,   /* a document longer than the positional range                     */
     CF_FLAG_POS_OVERFLOW = 8,   /* an allocation that does not fit [pos_begin, pos_end)            */
-    CF_FLAG_BAD_INDEX = 16      /* candidate / ranked index outside [0, stride)                    */
+    CF_FLAG_BAD_INDEX = 16,     /* candidate / ranked index outside [0, stride)                    */
+    CF_FLAG_POS_RANGE = 32      /* a segment or query whose stored or new positions leave [0, max_positions) */
 } cf_dev_flag;
 
 /* Geometry of one attention layer (host struct, passed by pointer, read during the call). */

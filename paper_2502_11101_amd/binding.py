@@ -23,6 +23,7 @@ CF_ROPE_HALF, CF_ROPE_INTERLEAVED = 0, 1
 CF_SEG_PREFIX, CF_SEG_DOC, CF_SEG_SELF = 0, 1, 2
 CF_ALLOC_KEEP, CF_ALLOC_ALIGN, CF_ALLOC_SORT = 0, 1, 2
 CF_FLAG_BAD_SEGMENT, CF_FLAG_NONFINITE_SCORE, CF_FLAG_DOC_TOO_LONG, CF_FLAG_POS_OVERFLOW, CF_FLAG_BAD_INDEX = 1, 2, 4, 8, 16
+CF_FLAG_POS_RANGE = 32
 
 DTYPE_CODE = {"f32": CF_F32, "bf16": CF_BF16, "f16": CF_F16}
 

@@ -247,6 +247,7 @@ static cf_status prefill_impl(const cf_layer_desc* desc, const void* q, const in
     a.scale_log2e = (float)(scale * 1.4426950408889634073599246810019);
     a.store_ts = store_token_stride(desc);
     a.store_hs = store_head_stride(desc);
+    a.max_positions = desc->max_positions;
     RopeFreq f;
     fill_rope_freq(desc, &f);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -372,6 +373,7 @@ cf_status cf_assemble_cache(const cf_layer_desc* desc, const void* k_store, cons
     a.store_ts = store_token_stride(desc); a.store_hs = store_head_stride(desc);
     a.final_ts = final_token_stride; a.final_hs = final_head_stride;
     a.seg_stride = seg_stride; a.batch = batch; a.max_tq = max_tq; a.n_kv_heads = desc->n_kv_heads; a.head_dim = desc->head_dim;
+    a.max_positions = desc->max_positions;
     RopeFreq f;
     fill_rope_freq(desc, &f);
     return launch_assemble(desc, f, a, max_seg_len, static_cast<hipStream_t>(stream));

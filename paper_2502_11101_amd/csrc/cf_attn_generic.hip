@@ -74,8 +74,13 @@ __global__ __launch_bounds__(kThreads) void attn_rows_kernel(AttnArgs a, RopeFre
         if (lane == 0) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
         nseg = nseg < 0 ? 0 : a.seg_stride;
     }
-    const int qdelta = a.q_new_start[b] - a.q_stored_start;
+    const int q_new = a.q_new_start[b];
+    const int qdelta = q_new - a.q_stored_start;
     const int64_t rs_base = (row * hq + h) * (int64_t)a.seg_stride;
+    // a query placed (or stored) outside the positional range attends nothing
+    const int tq_vis = min(tq, a.max_tq);
+    const bool q_ok = positions_ok(q_new, tq_vis, a.max_positions) && positions_ok(a.q_stored_start, tq_vis, a.max_positions);
+    if (!q_ok && lane == 0) raise_flag(a.dev_flag, CF_FLAG_POS_RANGE);
 
     float m_run = -INFINITY, l_run = 0.f;
     float o[4] = {0.f, 0.f, 0.f, 0.f};
@@ -87,8 +92,13 @@ __global__ __launch_bounds__(kThreads) void attn_rows_kernel(AttnArgs a, RopeFre
         const bool bad = seg.kind < 0 || seg.kind > CF_SEG_SELF || seg.len < 0 || seg.tok_offset < 0 ||
                          seg.tok_offset + seg.len > limit || (self && a.k_self == nullptr);
         float seg_l = 0.f;
+        const int len_vis = bad ? 0 : (self ? min(seg.len, tq_vis) : seg.len);
+        const bool off_range = !(positions_ok(seg.new_start, len_vis, a.max_positions) &&
+                                 positions_ok(seg.stored_start, len_vis, a.max_positions));
         if (bad) {
             if (lane == 0) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
+        } else if (off_range || !q_ok) {
+            if (off_range && lane == 0) raise_flag(a.dev_flag, CF_FLAG_POS_RANGE);
         } else {
             const int vis = self ? min(seg.len, t + 1) : seg.len;
             const int delta = seg.new_start - seg.stored_start - qdelta;
@@ -194,13 +204,22 @@ __global__ __launch_bounds__(kThreads) void mass_reduce_kernel(AttnArgs a, const
         if (threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
         __syncthreads();
     }
-    if (threadIdx.x == 0) {
-        const float m = (float)part[0];
-        a.mass[(int64_t)b * a.seg_stride + s] = m;
-        const int doc = a.segs[(int64_t)b * a.seg_stride + s].doc;
-        if (a.score_accum && doc >= 0 && doc < a.score_stride)
-            atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], m);
-    }
+    if (threadIdx.x == 0) a.mass[(int64_t)b * a.seg_stride + s] = (float)part[0];
+}
+
+// S += s^l (Alg. 2): one thread per (query, document slot) adds the masses of the segments that feed its
+// slot, in table order — no atomics, so the result does not depend on timing even when a document is
+// listed as several segments.
+__global__ __launch_bounds__(kThreads) void score_add_kernel(AttnArgs a) {
+    const int b = blockIdx.y;
+    const int doc = blockIdx.x * kThreads + threadIdx.x;
+    if (doc >= a.score_stride) return;
+    const int nseg = min(max(a.n_seg[b], 0), a.seg_stride);
+    float sum = 0.f;
+    bool any = false;
+    for (int s = 0; s < nseg; ++s)
+        if (a.segs[(int64_t)b * a.seg_stride + s].doc == doc) { sum += a.mass[(int64_t)b * a.seg_stride + s]; any = true; }
+    if (any) a.score_accum[(int64_t)b * a.score_stride + doc] += sum;
 }
 
 }  // namespace
@@ -226,6 +245,9 @@ cf_status launch_attention_generic(const AttnArgs& a, const RopeFreq& f, hipStre
     CF_HIP(hipGetLastError());
     if (a.mass == nullptr) return CF_OK;             // outputs only
     hipLaunchKernelGGL(mass_reduce_kernel, dim3(a.seg_stride, a.batch), dim3(kThreads), 0, s, a, rowstat, rowseg);
+    CF_HIP(hipGetLastError());
+    if (a.score_accum == nullptr) return CF_OK;
+    hipLaunchKernelGGL(score_add_kernel, dim3((a.score_stride + kThreads - 1) / kThreads, a.batch), dim3(kThreads), 0, s, a);
     CF_HIP(hipGetLastError());
     return CF_OK;
 }

@@ -108,7 +108,7 @@ struct SegTable {
 // Per-query scalars and this thread's segment-table entry, fetched in one batch: the entry is
 // read for the whole stride so that its load does not wait for the segment count.
 struct QueryHead {
-    int q0, tq_raw, n_seg, qdelta;
+    int q0, tq_raw, n_seg, qdelta, q_new;
     int64_t q_total;
     cf_segment seg;
 };
@@ -133,6 +133,7 @@ __device__ __forceinline__ QueryHead load_query_head(const AttnArgs& a, int b, i
     h.q_total = qt;
     h.n_seg = n;
     h.qdelta = qn - a.q_stored_start;
+    h.q_new = qn;
     return h;
 }
 
@@ -146,13 +147,20 @@ __device__ __forceinline__ void build_table(const AttnArgs& a, const QueryHead& 
         n = n < 0 ? 0 : a.seg_stride;
     }
     const int tq = min(h.tq_raw, a.max_tq);
+    // a query placed (or stored) outside the positional range attends nothing: every entry counts as empty
+    const bool q_ok = positions_ok(h.q_new, tq, a.max_positions) && positions_ok(a.q_stored_start, tq, a.max_positions);
+    if (!q_ok && tid == 0) raise_flag(a.dev_flag, CF_FLAG_POS_RANGE);
     if (tid < n) {
         const bool self = seg.kind == CF_SEG_SELF;
         const int64_t limit = self ? h.q_total : a.n_store_tokens;
         const bool bad = seg.kind < 0 || seg.kind > CF_SEG_SELF || seg.len < 0 || seg.tok_offset < 0 ||
                          seg.tok_offset + seg.len > limit || (self && a.k_self == nullptr);
         if (bad) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
-        const int vis = bad ? 0 : (self ? min(seg.len, tq) : seg.len);
+        const int len_vis = bad ? 0 : (self ? min(seg.len, tq) : seg.len);
+        const bool off_range = !(positions_ok(seg.new_start, len_vis, a.max_positions) &&
+                                 positions_ok(seg.stored_start, len_vis, a.max_positions));
+        if (off_range && !bad) raise_flag(a.dev_flag, CF_FLAG_POS_RANGE);
+        const int vis = off_range || !q_ok ? 0 : len_vis;
         t->tok[tid] = seg.tok_offset;
         t->vis[tid] = vis;
         t->delta[tid] = seg.new_start - seg.stored_start - h.qdelta;
@@ -230,6 +238,9 @@ __device__ __forceinline__ RegSegTable build_reg_table(const AttnArgs& a, const 
         n = n < 0 ? 0 : a.seg_stride;
     }
     const int tq = min(h.tq_raw, a.max_tq);
+    // a query placed (or stored) outside the positional range attends nothing: every entry counts as empty
+    const bool q_ok = positions_ok(h.q_new, tq, a.max_positions) && positions_ok(a.q_stored_start, tq, a.max_positions);
+    if (!q_ok && lane == 0) raise_flag(a.dev_flag, CF_FLAG_POS_RANGE);
     int vis = 0;
     t.tok = 0; t.delta = 0; t.self = 0;
     if (lane < n) {
@@ -238,7 +249,11 @@ __device__ __forceinline__ RegSegTable build_reg_table(const AttnArgs& a, const 
         const bool bad = seg.kind < 0 || seg.kind > CF_SEG_SELF || seg.len < 0 || seg.tok_offset < 0 ||
                          seg.tok_offset + seg.len > limit || (self && a.k_self == nullptr);
         if (bad) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
-        vis = bad ? 0 : (self ? min(seg.len, tq) : seg.len);
+        const int len_vis = bad ? 0 : (self ? min(seg.len, tq) : seg.len);
+        const bool off_range = !(positions_ok(seg.new_start, len_vis, a.max_positions) &&
+                                 positions_ok(seg.stored_start, len_vis, a.max_positions));
+        if (off_range && !bad) raise_flag(a.dev_flag, CF_FLAG_POS_RANGE);
+        vis = off_range || !q_ok ? 0 : len_vis;
         t.tok = seg.tok_offset;
         t.delta = seg.new_start - seg.stored_start - h.qdelta;
         t.self = self ? 1 : 0;

@@ -169,7 +169,43 @@ __device__ __forceinline__ float group_sum(const float* x, int pitch, int n) {
 struct MassScratch {
     float colsum[kMaxSegs + 2 * kMaxSplit];
     int32_t sub_begin[2 * kMaxSplit + 1];
+    float seg_mass[kMaxSegs];               // every entry's mass, for the per-document sums
 };
+
+// S += s^l (Alg. 2) without atomics, so that the sum does not depend on timing when a document slot is fed by
+// several table entries: the first entry of a slot adds up the masses of all entries of that slot in table
+// order and is the only one that touches the slot's score.
+// Block form: `doc` and `seg_mass` of the n entries in LDS; `score` has `stride` slots (LDS or memory).
+__device__ __forceinline__ void add_doc_scores_block(const int32_t* doc, const float* seg_mass, int n, float* score, int stride) {
+    for (int s = threadIdx.x; s < n; s += blockDim.x) {
+        const int d = doc[s];
+        if (d < 0 || d >= stride) continue;
+        bool first = true;
+        float sum = seg_mass[s];
+        for (int j = 0; j < n; ++j) {
+            if (doc[j] != d) continue;
+            if (j < s) first = false;
+            else if (j > s) sum += seg_mass[j];
+        }
+        if (first) score[d] += sum;
+    }
+}
+// Wavefront form: lane s < n holds entry s's slot and mass.  The loop runs once per table entry.
+__device__ __forceinline__ void add_doc_scores_wave(int doc, float m, int n, int lane, float* score, int stride) {
+    const bool valid = lane < n && doc >= 0 && doc < stride;
+    const int d = valid ? doc : -1;
+    bool first = valid;
+    float sum = m;
+    for (int j = 0; j < n; ++j) {
+        const int dj = __builtin_amdgcn_readlane(d, j);
+        const float mj = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, m), j));
+        if (dj == d) {
+            if (j < lane) first = false;
+            else if (j > lane) sum += mj;
+        }
+    }
+    if (first) score[d] += sum;
+}
 constexpr int kMassStage = 4096;            // floats of partials staged per round by the stand-alone mass kernel
 
 template <class F>
@@ -228,8 +264,8 @@ __device__ __forceinline__ void segment_masses_block(const Plan& p, const SegTab
 
 // The same for one wavefront on its own, for a query with at most 128 slots and a register table: lane k adds
 // up columns k and k + 64, lane s then collects segment s's slots — the same sums in the same order, no barrier.
-template <class F>
-__device__ __forceinline__ void segment_masses_wave(const Plan& p, const RegSegTable& t, const float* parts, int lane, F on_mass) {
+// Returns lane s's segment mass (0 for lanes past the table).
+__device__ __forceinline__ float segment_masses_wave(const Plan& p, const RegSegTable& t, const float* parts, int lane) {
     const unsigned total = (unsigned)t.total;
     const unsigned nsub = (unsigned)(p.nsplit * p.groups);
     const int nparts = p.units_per_b * p.nrb;
@@ -254,7 +290,7 @@ __device__ __forceinline__ void segment_masses_wave(const Plan& p, const RegSegT
         const float c_lo = __shfl(c[0], slot & (kWave - 1)), c_hi = __shfl(c[1], slot & (kWave - 1));
         if (has_tiles && sp <= s1 && ((owns_mask >> sp) & 1)) m += slot < kWave ? c_lo : c_hi;
     }
-    if (lane < t.n) on_mass(lane, m);
+    return lane < t.n ? m : 0.f;
 }
 
 // Third kernel: per-segment attention mass, one workgroup per query; then S += mass.
@@ -280,20 +316,21 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p)
         __syncthreads();
         if (tid >= kWave) return;
         const RegSegTable rtbl = build_reg_table(a, qh, tid, p.tile);
-        segment_masses_wave(p, rtbl, stage, tid, [&](int s, float m) {
-            a.mass[(int64_t)b * a.seg_stride + s] = m;
-            const int doc = qh.seg.doc;              // this lane's entry
-            if (a.score_accum && doc >= 0 && doc < a.score_stride) atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], m);
-        });
+        const float m = segment_masses_wave(p, rtbl, stage, tid);
+        if (tid < rtbl.n) a.mass[(int64_t)b * a.seg_stride + tid] = m;
+        if (a.score_accum)                           // qh.seg is this lane's entry
+            add_doc_scores_wave(qh.seg.doc, m, rtbl.n, tid, a.score_accum + (int64_t)b * a.score_stride, a.score_stride);
         return;
     }
     const QueryHead qh = load_query_head(a, b, (int)threadIdx.x);
     build_table(a, qh, &tbl, p.tile);
     segment_masses_block(p, tbl, const_cast<float*>(mp_b), stage, &ms, [&](int s, float m) {
         a.mass[(int64_t)b * a.seg_stride + s] = m;
-        const int doc = tbl.doc[s];
-        if (a.score_accum && doc >= 0 && doc < a.score_stride) atomicAdd(&a.score_accum[(int64_t)b * a.score_stride + doc], m);
+        ms.seg_mass[s] = m;
     });
+    if (a.score_accum == nullptr) return;
+    __syncthreads();
+    add_doc_scores_block(tbl.doc, ms.seg_mass, tbl.n, a.score_accum + (int64_t)b * a.score_stride, a.score_stride);
 }
 
 // Fused layer epilogue (third kernel of cf_prefill_layer): one workgroup per query computes the
@@ -390,19 +427,18 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
         __syncthreads();                             // publishes the rows above
         if (tid >= kWave) return;
         const RegSegTable rtbl = build_reg_table(a, qh, tid, p.tile);
-        segment_masses_wave(p, rtbl, l_part, tid, [&](int s, float m) {
-            a.mass[(int64_t)b * a.seg_stride + s] = m;
-            const int doc = qh.seg.doc;              // this lane's entry
-            if (doc >= 0 && doc < stride) atomicAdd(&l_score[doc], m);
-        });
+        const float m = segment_masses_wave(p, rtbl, l_part, tid);
+        if (tid < rtbl.n) a.mass[(int64_t)b * a.seg_stride + tid] = m;
+        add_doc_scores_wave(qh.seg.doc, m, rtbl.n, tid, l_score, stride);       // qh.seg is this lane's entry
         __syncthreads();
     } else {
         build_table(a, qh, &tbl, p.tile);            // its barriers also publish the rows above
         segment_masses_block(p, tbl, l_part, nullptr, &ms, [&](int s, float m) {
             a.mass[(int64_t)b * a.seg_stride + s] = m;
-            const int doc = tbl.doc[s];
-            if (doc >= 0 && doc < stride) atomicAdd(&l_score[doc], m);
+            ms.seg_mass[s] = m;
         });
+        __syncthreads();
+        add_doc_scores_block(tbl.doc, ms.seg_mass, tbl.n, l_score, stride);
         __syncthreads();
     }
     if (tid >= nthr) return;

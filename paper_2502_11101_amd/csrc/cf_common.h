@@ -111,6 +111,11 @@ __device__ __forceinline__ void raise_flag(int32_t* dev_flag, int bits) {
     if (dev_flag) atomicOr(dev_flag, bits);
 }
 
+// whether `len` tokens starting at position `start` all sit inside [0, max_positions)
+__device__ __forceinline__ bool positions_ok(int start, int len, int max_positions) {
+    return start >= 0 && (int64_t)start + len <= (int64_t)max_positions;
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
@@ -145,7 +150,7 @@ struct AssembleArgs {
     const int64_t* final_off;
     int32_t *final_len, *final_pos, *dev_flag;
     int64_t n_store_tokens, final_capacity, store_ts, store_hs, final_ts, final_hs;
-    int32_t seg_stride, batch, max_tq, n_kv_heads, head_dim;
+    int32_t seg_stride, batch, max_tq, n_kv_heads, head_dim, max_positions;
 };
 cf_status launch_assemble(const cf_layer_desc* d, const RopeFreq& f, const AssembleArgs& a, int32_t max_seg_len,
                           hipStream_t s);
@@ -180,6 +185,7 @@ struct AttnArgs {
     int32_t n_q_heads, n_kv_heads, head_dim, dtype, pairing;
     float scale_log2e;   // softmax scale times log2(e)
     int64_t store_ts, store_hs;   // element strides of the cache store between tokens / kv heads
+    int32_t max_positions;        // positions are valid in [0, max_positions)
 };
 
 inline int64_t store_token_stride(const cf_layer_desc* d) {

@@ -61,12 +61,16 @@ template <int DT, int PAIRING>
 __global__ __launch_bounds__(kThreads) void reposition_kernel(
     const void* k_in, void* k_out, const cf_segment* __restrict__ segs,
     int64_t n_store_tokens, int n_kv_heads, int head_dim, int64_t tok_stride, int64_t head_stride, RopeFreq freq,
-    int32_t* dev_flag, int tok_per_block) {
+    int32_t* dev_flag, int tok_per_block, int max_positions) {
     __shared__ float2 cs[kMaxHalf];
     const cf_segment seg = segs[blockIdx.x];
     const int half = head_dim >> 1;
     if (seg.len < 0 || seg.tok_offset < 0 || seg.tok_offset + seg.len > n_store_tokens) {
         if (threadIdx.x == 0 && blockIdx.y == 0) raise_flag(dev_flag, CF_FLAG_BAD_SEGMENT);
+        return;
+    }
+    if (!positions_ok(seg.stored_start, seg.len, max_positions) || !positions_ok(seg.new_start, seg.len, max_positions)) {
+        if (threadIdx.x == 0 && blockIdx.y == 0) raise_flag(dev_flag, CF_FLAG_POS_RANGE);
         return;
     }
     const int delta = seg.new_start - seg.stored_start;
@@ -140,11 +144,11 @@ cf_status launch_dt(const cf_layer_desc* d, const RopeFreq& f, const void* k_in,
     if (d->rope_pairing == CF_ROPE_HALF)
         hipLaunchKernelGGL((reposition_kernel<DT, CF_ROPE_HALF>), grid, dim3(kThreads), 0, s, k_in, k_out,
                            segs, n_store_tokens, d->n_kv_heads, d->head_dim, store_token_stride(d), store_head_stride(d), f,
-                           dev_flag, (int)tpb);
+                           dev_flag, (int)tpb, d->max_positions);
     else
         hipLaunchKernelGGL((reposition_kernel<DT, CF_ROPE_INTERLEAVED>), grid, dim3(kThreads), 0, s, k_in,
                            k_out, segs, n_store_tokens, d->n_kv_heads, d->head_dim, store_token_stride(d),
-                           store_head_stride(d), f, dev_flag, (int)tpb);
+                           store_head_stride(d), f, dev_flag, (int)tpb, d->max_positions);
     CF_HIP(hipGetLastError());
     return CF_OK;
 }
@@ -157,7 +161,7 @@ cf_status launch_dt(const cf_layer_desc* d, const RopeFreq& f, const void* k_in,
 template <int DT, int PAIRING>
 __global__ __launch_bounds__(kThreads) void assemble_kernel(AssembleArgs a, RopeFreq freq, int tok_per_block) {
     __shared__ float2 cs[kMaxHalf];
-    __shared__ int s_before, s_total, s_bad;
+    __shared__ int s_before, s_total, s_bad, s_off_range;
     const int b = blockIdx.x / a.seg_stride, s = blockIdx.x - b * a.seg_stride;
     const int tid = threadIdx.x;
     int n = a.n_seg[b];
@@ -169,20 +173,25 @@ __global__ __launch_bounds__(kThreads) void assemble_kernel(AssembleArgs a, Rope
     const int q0 = a.q_off[b];
     const int tq = min(a.q_off[b + 1] - q0, a.max_tq);
     const int64_t q_total = a.q_off[a.batch];
-    if (tid == 0) { s_before = 0; s_total = 0; s_bad = 0; }
+    if (tid == 0) { s_before = 0; s_total = 0; s_bad = 0; s_off_range = 0; }
     __syncthreads();
-    // visible tokens of an entry: 0 for a rejected one, min(len, tq) for the own block
-    auto visible = [&](const cf_segment& g, bool* bad) {
+    // visible tokens of an entry: 0 for a rejected one (bad: malformed; *bad == 2: positions outside the
+    // range), min(len, tq) for the own block
+    auto visible = [&](const cf_segment& g, int* bad) {
         const bool self = g.kind == CF_SEG_SELF;
         const int64_t limit = self ? q_total : a.n_store_tokens;
         *bad = g.kind < 0 || g.kind > CF_SEG_SELF || g.len < 0 || g.tok_offset < 0 || g.tok_offset + g.len > limit ||
                (self && (a.k_self == nullptr || a.v_self == nullptr));
-        return *bad ? 0 : (self ? min(g.len, tq) : g.len);
+        if (*bad) return 0;
+        const int vis = self ? min(g.len, tq) : g.len;
+        if (!positions_ok(g.stored_start, vis, a.max_positions) || !positions_ok(g.new_start, vis, a.max_positions)) *bad = 2;
+        return *bad ? 0 : vis;
     };
     for (int t = tid; t < n; t += kThreads) {
-        bool bad;
+        int bad;
         const int vis = visible(a.segs[(int64_t)b * a.seg_stride + t], &bad);
-        if (bad) atomicOr(&s_bad, 1);
+        if (bad == 1) atomicOr(&s_bad, 1);
+        if (bad == 2) atomicOr(&s_off_range, 1);
         atomicAdd(&s_total, vis);
         if (t < s) atomicAdd(&s_before, vis);
     }
@@ -191,12 +200,13 @@ __global__ __launch_bounds__(kThreads) void assemble_kernel(AssembleArgs a, Rope
     const bool fits = run0 >= 0 && run0 + s_total <= a.final_capacity;
     if (s == 0 && blockIdx.y == 0 && tid == 0) {
         if (s_bad) raise_flag(a.dev_flag, CF_FLAG_BAD_SEGMENT);
+        if (s_off_range) raise_flag(a.dev_flag, CF_FLAG_POS_RANGE);
         if (!fits) raise_flag(a.dev_flag, CF_FLAG_BAD_INDEX);
         a.final_len[b] = fits ? s_total : 0;
     }
     if (s >= n || !fits) return;
     const cf_segment seg = a.segs[(int64_t)b * a.seg_stride + s];
-    bool bad;
+    int bad;
     const int vis = visible(seg, &bad);
     if (vis == 0) return;
     const bool self = seg.kind == CF_SEG_SELF;

@@ -197,9 +197,11 @@ def test_assign_keep_only_lists_survivors():
 
 # ----------------------------------------------------------------------------- generic attention path
 def _run_single_layer(cfg, pairing=cf.CF_ROPE_HALF, seed=None, mass_tol=None, layout="token"):
-    """mass_tol overrides the configuration-level mass tolerance for shapes with so few rows and
-    tokens that the 16-bit rounding of the rotated keys (about 2^-9 relative per probability) is
-    not averaged away."""
+    """Masses are checked twice.  Against the rounded-key reference (the oracle on keys moved by Eq. 5 and
+    rounded once to the storage type, as the fused kernels hold them) the bound is always the tight one,
+    1e-4 for 16-bit types: what is left there is the kernels' own arithmetic.  Against the plain oracle
+    ``mass_tol`` may loosen the bound for shapes with so few rows and tokens that the one rounding of a
+    moved key (2^-9 relative per element) is not averaged away."""
     st = wl.build_structure(cfg, seed=None if seed is None else 7000 + seed)
     t = wl.build_layer(cfg, st, seed=seed)
     g = cfg.geometry
@@ -215,7 +217,7 @@ def _run_single_layer(cfg, pairing=cf.CF_ROPE_HALF, seed=None, mass_tol=None, la
     out_np = out.float().cpu().numpy()
     mass_np = pb.mass.cpu().numpy()
     score_np = pb.score.cpu().numpy()
-    worst_out = worst_mass = 0.0
+    worst_out = worst_mass = worst_near = 0.0
     mass_tol = G.MASS_TOL[g.dtype] if mass_tol is None else mass_tol
     for b in range(cfg.batch):
         # positions and segment table: bit-exact against the oracle's own allocation
@@ -228,9 +230,14 @@ def _run_single_layer(cfg, pairing=cf.CF_ROPE_HALF, seed=None, mass_tol=None, la
         ref_score = H.doc_scores(ref_segs, ref_mass, cfg.docs_per_query)
         assert G.rel_error(score_np[b], ref_score) <= mass_tol
         assert mass_np[b, :len(segs)].sum() == pytest.approx(g.n_q_heads * cfg.tq, rel=1e-5)
-    _say(f"{cfg.name} [{layout}]: out err {worst_out:.3e}  mass err {worst_mass:.3e}")
+        rows = t["q"][b * cfg.tq:(b + 1) * cfg.tq]
+        _, near_mass = H.rounded_key_reference(g.dtype, rows, 0, ref_q, t["k_store"], t["v_store"], t["k_self"], t["v_self"],
+                                               ref_segs, g.n_kv_heads, g.rope_base, pname)
+        worst_near = max(worst_near, G.rel_error(mass_np[b, :len(segs)], near_mass))
+    _say(f"{cfg.name} [{layout}]: out err {worst_out:.3e}  mass err {worst_mass:.3e}  against rounded moved keys {worst_near:.3e}")
     assert worst_out <= G.OUT_TOL[g.dtype]
     assert worst_mass <= mass_tol
+    assert worst_near <= G.MASS_TOL[g.dtype]
     return cfg, st, t, pb, dev, out
 
 
@@ -300,16 +307,43 @@ def test_attention_flags_bad_table_entries():
 
 
 # ----------------------------------------------------------------------------- 16-bit MFMA path
+def _cut_against_oracle(cfg, st, t, pb, dev, out):
+    """The prune event of a configuration on the scores the device accumulated: exact for those scores, and against
+    the cut the oracle takes on its own scores by the margin rule (equal sets where the oracle's gap at the cut is at
+    least 1e-3, as for the LLaMA-2-7B layer's seed; with 45 unplanted documents of the Qwen2-7B layer the gap is
+    ~1e-4 whatever the seed, and only documents within 1e-3 of the cut may fall either way); planted documents
+    kept; the survivors' positions those of the oracle's allocator."""
+    g = cfg.geometry
+    pb.prune(cfg.keep, cf.CF_ALLOC_SORT)
+    torch.cuda.synchronize()
+    assert pb.flags() == 0
+    for b in range(cfg.batch):
+        ref_segs, ref_q, lens = H.initial_segments(cfg, st, b)
+        _, ref_mass = H.oracle_query(cfg, st, t, b, ref_segs, ref_q)
+        ref_score = H.doc_scores(ref_segs, ref_mass, cfg.docs_per_query)
+        alive = list(range(cfg.docs_per_query))
+        kept = pb.keep_idx[b, :cfg.keep].tolist()
+        assert kept == orc.prune_topk(pb.score.cpu().numpy()[b], lens, alive, cfg.keep)
+        gap = H.check_cut(kept, ref_score, lens, alive, cfg.keep, st.planted[b])
+        _say(f"  {cfg.name}: oracle gap at the cut {gap:.2e}")
+        if cfg.name == "llama2_7b_layer":
+            assert gap >= 1e-3 and sorted(kept) == sorted(orc.prune_topk(ref_score, lens, alive, cfg.keep))
+        ref_ns, ref_qs, ref_nr = orc.assign_positions(lens, kept, cfg.prefix_len, g.max_positions - cfg.tq)
+        assert int(pb.next_q_start[b].item()) == ref_qs and int(pb.n_reuse[b].item()) == ref_nr
+        ns = pb.next_new_start.cpu().numpy()[b]
+        assert all(int(ns[s]) == p for s, p in ref_ns.items())
+
+
 @pytest.mark.parametrize("layout", ["token", "head"])
 def test_llama2_7b_layer_configuration(layout):
     """Configuration 2 (MHA, bf16, HBM-bound shape) at full size; head-major is the layout bench.py times."""
-    _run_single_layer(wl.CONFIGS["llama2_7b_layer"], layout=layout)
+    _cut_against_oracle(*_run_single_layer(wl.CONFIGS["llama2_7b_layer"], layout=layout))
 
 
 @pytest.mark.parametrize("layout", ["token", "head"])
 def test_qwen2_7b_layer_configuration(layout):
     """Configuration 3 (GQA 28/4, bf16, 50 ragged documents) at full size."""
-    _run_single_layer(wl.CONFIGS["qwen2_7b_layer"], layout=layout)
+    _cut_against_oracle(*_run_single_layer(wl.CONFIGS["qwen2_7b_layer"], layout=layout))
 
 
 def test_qwen2_1p5b_batch_reduced():
@@ -725,7 +759,8 @@ def test_llama2_7b_stack_full_size():
     """Configuration 4 at full size (32 layers, 30 documents x 160 tokens, pruning to 60 % after layers
     8/16/24/32), head-major store as bench.py runs it.  Every layer: flags, mass total, accumulated
     scores finite; every prune: the cut exact for the device's scores, the allocation bit-exact.  The
-    oracle attends on sampled layers (before and after each prune) on the tables the device holds."""
+    oracle attends on every layer, on the tables the device holds, and accumulates its own scores: every cut also
+    obeys the margin rule against those, and equals the oracle's cut where the oracle's gap is at least 1e-3."""
     cfg = wl.CONFIGS["llama2_7b_stack"]
     g = cfg.geometry
     st = wl.build_structure(cfg)
@@ -739,13 +774,15 @@ def test_llama2_7b_stack_full_size():
     pb.allocate_initial()
     assert int(pb.n_reuse[0].item()) == 2                      # 30 x 160 tokens do not fit 4096 positions once
     alive = list(range(cfg.docs_per_query))
-    sampled = {0, 7, 8, 16, 24, 31}
+    ref_score = np.zeros(cfg.docs_per_query)
+    sampled = set(range(cfg.n_layers))
     for layer in range(cfg.n_layers):
         t = wl.build_layer(cfg, st, layer)
         dev = G.upload_layer(cfg, t, "head")
         out = torch.empty_like(dev["q"])
         if layer in sampled:
             segs, ref_out, ref_mass = G.oracle_on_device_segments(cfg, t, pb, 0)
+            ref_score += H.doc_scores(segs, ref_mass, cfg.docs_per_query)
         pb.layer(dev["q"], dev["k_self"], dev["v_self"], dev["k_store"], dev["v_store"], out, keep=keeps.get(layer),
                  strategy=cf.CF_ALLOC_SORT)
         torch.cuda.synchronize()
@@ -757,11 +794,14 @@ def test_llama2_7b_stack_full_size():
             _say(f"stack layer {layer}: {len(alive)} documents")
             assert G.row_error(out.float().cpu().numpy(), ref_out) <= G.OUT_TOL[g.dtype]
             assert G.rel_error(mass, ref_mass) <= G.MASS_TOL[g.dtype]
+            assert G.rel_error(pb.score.cpu().numpy()[0][alive], ref_score[alive]) <= G.MASS_TOL[g.dtype]
         if layer in keeps:
             keep = keeps[layer]
             dev_score = pb.score.cpu().numpy()[0]
             kept = pb.keep_idx[0, :keep].tolist()
             assert kept == orc.prune_topk(dev_score, lens, alive, keep)
+            gap = H.check_cut(kept, ref_score, lens, alive, keep, st.planted[0])
+            _say(f"  prune to {keep}: oracle gap at the cut {gap:.2e}")
             ref_ns, ref_q, ref_nr = orc.assign_positions(lens, kept, cfg.prefix_len, g.max_positions - cfg.tq)
             pb.advance()
             assert int(pb.q_start[0].item()) == ref_q and int(pb.n_reuse[0].item()) == ref_nr
@@ -772,8 +812,8 @@ def test_llama2_7b_stack_full_size():
 
 def test_qwen2_1p5b_batch_full_size_sampled():
     """Configuration 5 at full size (store of 10 000 documents, 64 queries x 20 documents, fp16 GQA 12/2):
-    every query's mass total and the planted documents' survival, and three sampled queries against the
-    oracle element by element."""
+    every query against the oracle element by element (outputs, masses), every cut against the oracle's own scores
+    by the margin rule, the planted documents' survival."""
     cfg = wl.CONFIGS["qwen2_1p5b_batch"]
     g = cfg.geometry
     st = wl.build_structure(cfg)
@@ -795,12 +835,22 @@ def test_qwen2_1p5b_batch_full_size_sampled():
         qlens = st.doc_lens[st.query_docs[b]]
         assert keep_idx[b, :cfg.keep].tolist() == orc.prune_topk(score[b], qlens, list(range(cfg.docs_per_query)), cfg.keep)
         assert set(st.planted[b].tolist()) <= set(keep_idx[b, :cfg.keep].tolist())
-    for b in (0, 31, 63):
-        _say(f"batch query {b}")
-        ref_segs, ref_q, _ = H.initial_segments(cfg, st, b)
-        ref_out, ref_mass = H.oracle_query(cfg, st, t, b, ref_segs, ref_q)
-        assert G.row_error(out_np[b * cfg.tq:(b + 1) * cfg.tq], ref_out) <= G.OUT_TOL[g.dtype]
-        assert G.rel_error(mass[b, :len(ref_segs)], ref_mass) <= G.MASS_TOL[g.dtype]
+    worst_out = worst_mass = 0.0
+    smallest_gap = float("inf")
+    for b in range(cfg.batch):
+        ref_segs, ref_q, qlens = H.initial_segments(cfg, st, b)
+        k_small, v_small, table = H.compact_query(ref_segs, t["k_store"], t["v_store"])    # the store holds 1.5 M tokens
+        ref_out, ref_mass = orc.prefill_attention(H.f64(t["q"][b * cfg.tq:(b + 1) * cfg.tq]), 0, ref_q, k_small, v_small,
+                                                  t["k_self"], t["v_self"], table, g.n_kv_heads, g.rope_base)
+        worst_out = max(worst_out, G.row_error(out_np[b * cfg.tq:(b + 1) * cfg.tq], ref_out))
+        worst_mass = max(worst_mass, G.rel_error(mass[b, :len(ref_segs)], ref_mass))
+        ref_score = H.doc_scores(ref_segs, ref_mass, cfg.docs_per_query)
+        gap = H.check_cut(keep_idx[b, :cfg.keep].tolist(), ref_score, qlens, list(range(cfg.docs_per_query)), cfg.keep,
+                          st.planted[b])
+        smallest_gap = min(smallest_gap, gap)
+    _say(f"batch of {cfg.batch}: out err {worst_out:.3e}  mass err {worst_mass:.3e}  smallest oracle gap at a cut {smallest_gap:.2e}")
+    assert worst_out <= G.OUT_TOL[g.dtype]
+    assert worst_mass <= G.MASS_TOL[g.dtype]
 
 
 # ----------------------------------------------------------------------------- N_reuse ablation modes
@@ -1030,7 +1080,7 @@ def test_document_encoding_attention_shape():
         ref_out, ref_mass = orc.prefill_attention(q[lo:hi].astype(np.float64), prefix, prefix, k_store, v_store, k_self, v_self,
                                                   tables[b], g.n_kv_heads, g.rope_base)
         assert G.row_error(got[lo:hi], ref_out) <= G.OUT_TOL[g.dtype]
-        assert G.rel_error(m[b], ref_mass) <= (2e-3 if doc_lens[b] < 8 else G.MASS_TOL[g.dtype])
+        assert G.rel_error(m[b], ref_mass) <= G.MASS_TOL[g.dtype]           # nothing moves here: the keys are the oracle's
 
 
 @pytest.mark.parametrize("layout", ["head", "token"])
@@ -1081,10 +1131,15 @@ def test_offline_store_builder_writes_the_cache_store(layout):
     assert np.array_equal(v_dev, np.concatenate([fresh["prefix"][2], fresh["docs"][2]]))
     assert np.array_equal(k_dev[:prefix], fresh["prefix"][1])                  # the prefix does not move: exact copies
     assert not np.array_equal(k_dev[prefix:], fresh["docs"][1])
+    # the oracle's own store (moved keys rounded once to the storage type) is what every expected value below is
+    # computed on; the device's differs from it by at most one rounding step in a few elements (checked above)
+    k_orc = wl.round_to_dtype(k_ref.astype(np.float32), g.dtype)
+    v_orc = np.concatenate([fresh["prefix"][2], fresh["docs"][2]])
+    assert np.mean(k_dev != k_orc) < 2e-3
 
-    # ---- the encoders' outputs against the oracle, on the store the device holds
+    # ---- the encoders' outputs against the oracle
     q_p, k_p, v_p = fresh["prefix"]
-    ref, _ = orc.prefill_attention(q_p.astype(np.float64), 0, 0, k_dev, v_dev, k_p, v_p,
+    ref, _ = orc.prefill_attention(q_p.astype(np.float64), 0, 0, k_orc, v_orc, k_p, v_p,
                                    [orc.Segment(0, prefix, 0, 0, orc.KIND_SELF, -1)], g.n_kv_heads, g.rope_base)
     assert G.row_error(outs["prefix"].float().cpu().numpy(), ref) <= G.OUT_TOL[g.dtype]
     q_d, k_d, v_d = fresh["docs"]
@@ -1093,7 +1148,7 @@ def test_offline_store_builder_writes_the_cache_store(layout):
     for b in range(len(doc_lens)):
         lo, hi = int(q_off[b]), int(q_off[b + 1])
         table = [orc.Segment(0, prefix, 0, 0, orc.KIND_PREFIX, -1), orc.Segment(lo, hi - lo, 0, prefix, orc.KIND_SELF, -1)]
-        ref, _ = orc.prefill_attention(q_d[lo:hi].astype(np.float64), 0, prefix, k_dev, v_dev, k_d, v_d, table,
+        ref, _ = orc.prefill_attention(q_d[lo:hi].astype(np.float64), 0, prefix, k_orc, v_orc, k_d, v_d, table,
                                        g.n_kv_heads, g.rope_base)
         assert G.row_error(got[lo:hi], ref) <= G.OUT_TOL[g.dtype]
 
@@ -1108,16 +1163,27 @@ def test_offline_store_builder_writes_the_cache_store(layout):
     pb.layer(dq, dk, dv, k_store, v_store, out, keep=3)
     torch.cuda.synchronize()
     assert pb.flags() == 0
-    ref_out, ref_mass = orc.prefill_attention(q.astype(np.float64), 0, int(pb.q_start[0].item()), k_dev, v_dev, k_self, v_self,
+    q_start = int(pb.q_start[0].item())
+    ref_out, ref_mass = orc.prefill_attention(q.astype(np.float64), 0, q_start, k_orc, v_orc, k_self, v_self,
                                               segs, g.n_kv_heads, g.rope_base)
     assert G.row_error(out.float().cpu().numpy(), ref_out) <= G.OUT_TOL[g.dtype]
     mass = pb.mass.cpu().numpy()[0, :len(segs)]
-    long_ = np.array([sg.len >= 8 for sg in segs])            # a one-token document's mass hangs on one rounded key
-    assert G.rel_error(mass[long_], ref_mass[long_]) <= G.MASS_TOL[g.dtype]
-    assert G.rel_error(mass[~long_], ref_mass[~long_]) <= 2e-3
-    score = H.doc_scores(segs, ref_mass, len(doc_lens))
+    # loose: the keys were rounded when they entered the store and again when this call moved them, and a one-token
+    # document's mass hangs on one such key
+    long_ = np.array([sg.len >= 8 for sg in segs])
+    assert G.rel_error(mass[long_], ref_mass[long_]) <= 2e-4
+    assert G.rel_error(mass[~long_], ref_mass[~long_]) <= 4e-3
     assert pb.keep_idx[0, :3].tolist() == orc.prune_topk(pb.score.cpu().numpy()[0], [int(x) for x in doc_lens], list(range(len(doc_lens))), 3)
-    assert np.isfinite(score).all()
+    # tight: the same call over the oracle's store, against the oracle on keys moved and rounded as the kernel holds them
+    pb2 = pl.PrefillBatch(desc, doc_off[:-1][None, :], doc_lens[None, :], tq, prefix, prefix, n_store)
+    pb2.allocate_initial()
+    out2 = torch.empty_like(dq)
+    pb2.attention(dq, dk, dv, pl.store_to_device(k_orc, g.dtype, layout), pl.store_to_device(v_orc, g.dtype, layout), out2)
+    torch.cuda.synchronize()
+    assert pb2.flags() == 0
+    _, near_mass = H.rounded_key_reference(g.dtype, q, 0, q_start, k_orc, v_orc, k_self, v_self, segs, g.n_kv_heads, g.rope_base)
+    assert G.row_error(out2.float().cpu().numpy(), ref_out) <= G.OUT_TOL[g.dtype]
+    assert G.rel_error(pb2.mass.cpu().numpy()[0, :len(segs)], near_mass) <= G.MASS_TOL[g.dtype]
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
@@ -1161,8 +1227,12 @@ def test_ragged_batch_with_an_empty_query(dtype):
         ref_out, ref_mass = orc.prefill_attention(q[lo:hi].astype(np.float64), 0, q_pos[b], k_store, v_store, k_self, v_self,
                                                   tables[b], g.n_kv_heads, g.rope_base)
         assert G.row_error(got[lo:hi], ref_out) <= G.OUT_TOL[g.dtype]
+        # few rows, short documents: against the plain oracle the one rounding of a moved key shows
         assert G.rel_error(m[b], ref_mass) <= (4e-3 if dtype == "bf16" else G.MASS_TOL[g.dtype])
-        assert G.rel_error(sc[b], ref_mass[1:4]) <= (4e-3 if dtype == "bf16" else G.MASS_TOL[g.dtype])
+        _, near_mass = H.rounded_key_reference(g.dtype, q[lo:hi], 0, q_pos[b], k_store, v_store, k_self, v_self, tables[b],
+                                               g.n_kv_heads, g.rope_base)
+        assert G.rel_error(m[b], near_mass) <= G.MASS_TOL[g.dtype]
+        assert G.rel_error(sc[b], near_mass[1:4]) <= G.MASS_TOL[g.dtype]
     assert np.all(m[1] == 0.0) and np.all(sc[1] == 0.0)
 
 
@@ -1204,7 +1274,10 @@ def test_largest_relative_shifts(base, max_pos):
         ref_out, ref_mass = orc.prefill_attention(q[b * tq:(b + 1) * tq].astype(np.float64), 0, q_pos[b], k_store, v_store, k_self,
                                                   v_self, tables[b], g.n_kv_heads, g.rope_base)
         assert G.row_error(got[b * tq:(b + 1) * tq], ref_out) <= G.OUT_TOL[g.dtype]
-        assert G.rel_error(m[b], ref_mass) <= 4e-3
+        assert G.rel_error(m[b], ref_mass) <= 4e-3               # six rows: the one rounding of a moved key shows
+        _, near_mass = H.rounded_key_reference(g.dtype, q[b * tq:(b + 1) * tq], 0, q_pos[b], k_store, v_store, k_self, v_self,
+                                               tables[b], g.n_kv_heads, g.rope_base)
+        assert G.rel_error(m[b], near_mass) <= G.MASS_TOL[g.dtype]
 
 
 def test_layer_calls_replay_from_a_hip_graph():
