@@ -13,8 +13,10 @@
  *
  * Conventions for every call
  *   - "device" pointers are HIP device memory owned by the caller; "host" values are
- *     passed by value or as host pointers.  The library allocates nothing, keeps no
- *     state between calls, and never frees or retains caller memory.
+ *     passed by value or as host pointers.  The library allocates no device memory and
+ *     never frees or retains caller memory.  What it keeps between calls: the thread-local
+ *     text of cf_last_error() and — only while the measurement aids at the end of
+ *     this header are switched on — their events.  None of it changes a call's results.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     enqueue work and return; outputs are valid once the stream reaches that point.
  *   - Host arguments are validated before any HIP call; a failed validation returns a
@@ -326,14 +328,14 @@ CF_API cf_status cf_prefill_layer(const cf_layer_desc* desc,
 /* Thread-local text for the last non-OK status returned on this thread (static storage). */
 CF_API const char* cf_last_error(void);
 
-/* Profiling aid (not part of the method): restrict the kernels that later cf_prefill_attention
- * calls on this thread launch on the 16-bit path, so that one of them can be timed alone with
- * events.  Bit 0: the attention kernel proper (K/V streaming, re-rotation, MFMA, softmax);
- * bit 1: the merge of the splits' partial outputs; bit 2: the per-segment mass reduction.
- * Default 7 (all).  With a partial mask the call's outputs are not meaningful. */
-CF_API void cf_profile_phases(int32_t mask);
+/* Library version as major*10000 + minor*100 + patch. */
+CF_API int32_t cf_version(void);
 
-/* Profiling aid (not part of the method): while enabled (nonzero), every launch of the attention kernel proper
+/* =============================================================================================
+ * Measurement aids.  Not part of the method; none of them changes what the calls above compute.
+ * ============================================================================================= */
+
+/* While enabled (nonzero), every launch of the attention kernel proper
  * by cf_prefill_attention / cf_prefill_layer on this thread's 16-bit path carries a start and a stop event that
  * take the time at which that dispatch begins and ends on the GPU; the events of the last 1024 launches are kept.  Enabling creates the events (host memory
  * only) and forgets earlier launches; disabling destroys them.  Host call, not to be issued during stream capture.
@@ -345,8 +347,18 @@ CF_API cf_status cf_profile_kernel_events(int32_t enable);
  * CF_ERR_INVALID_ARG when timing is not enabled or a pointer is NULL, CF_ERR_DEVICE on a runtime error. */
 CF_API cf_status cf_profile_kernel_ms(double* mean_ms, int32_t* launches);
 
-/* Library version as major*10000 + minor*100 + patch. */
-CF_API int32_t cf_version(void);
+/* Calibration kernels of known size, for pricing measurements against what this GPU sustains rather than
+ * against its nominal peaks.  Each call enqueues ONE kernel on `stream` and returns; time it with events.
+ *   CF_CALIB_READ   reads `bytes` bytes of `src` once (16-byte loads, every workgroup a contiguous share)
+ *   CF_CALIB_COPY   reads `bytes` bytes of `src` and writes them to `dst`
+ *   CF_CALIB_MFMA_BF16 / _F16   no memory traffic: every wavefront of `workgroups` workgroups of 256 threads issues
+ *                   iters * 64 dense v_mfma_f32_32x32x16 (32 768 flops each) on eight independent accumulators;
+ *                   *flops receives the launch's flop count
+ * src, dst: device, 16-byte aligned, `bytes` a multiple of 16 (dst may be NULL except for COPY); sink: device,
+ * at least 16 bytes, receives nothing meaningful (it keeps the loads alive); flops: host, may be NULL. */
+typedef enum cf_calib_kind { CF_CALIB_READ = 0, CF_CALIB_COPY = 1, CF_CALIB_MFMA_BF16 = 2, CF_CALIB_MFMA_F16 = 3 } cf_calib_kind;
+CF_API cf_status cf_calibrate(int32_t kind, const void* src, void* dst, size_t bytes, int32_t workgroups, int32_t iters,
+                              void* sink, double* flops, void* stream);
 
 #ifdef __cplusplus
 }

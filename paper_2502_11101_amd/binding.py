@@ -28,7 +28,7 @@ CF_FLAG_POS_RANGE = 32
 DTYPE_CODE = {"f32": CF_F32, "bf16": CF_BF16, "f16": CF_F16}
 
 EXPORTS = ("cf_reposition_keys", "cf_prefill_workspace_bytes", "cf_prefill_attention", "cf_prune_topk",
-           "cf_assign_positions", "cf_gather_segments", "cf_last_error", "cf_version", "cf_profile_phases", "cf_profile_kernel_events", "cf_profile_kernel_ms",
+           "cf_assign_positions", "cf_gather_segments", "cf_last_error", "cf_version", "cf_calibrate", "cf_profile_kernel_events", "cf_profile_kernel_ms",
            "cf_prefill_layer", "cf_assemble_cache")
 
 
@@ -78,8 +78,8 @@ def load() -> C.CDLL:
     lib.cf_last_error.argtypes = []
     lib.cf_version.restype = i32
     lib.cf_version.argtypes = []
-    lib.cf_profile_phases.restype = None
-    lib.cf_profile_phases.argtypes = [i32]
+    lib.cf_calibrate.restype = i32
+    lib.cf_calibrate.argtypes = [i32, vp, vp, sz, i32, i32, vp, C.POINTER(C.c_double), vp]
     lib.cf_profile_kernel_events.restype = i32
     lib.cf_profile_kernel_events.argtypes = [i32]
     lib.cf_profile_kernel_ms.restype = i32
@@ -163,8 +163,15 @@ def cf_version() -> int:
     return load().cf_version()
 
 
-def cf_profile_phases(mask: int) -> None:
-    load().cf_profile_phases(mask)
+CF_CALIB_READ, CF_CALIB_COPY, CF_CALIB_MFMA_BF16, CF_CALIB_MFMA_F16 = 0, 1, 2, 3
+
+
+def cf_calibrate(kind: int, src, dst, nbytes: int, workgroups: int, iters: int, sink, stream=None) -> float:
+    """Enqueues one calibration kernel; returns the launch's flop count (0 for the memory kinds)."""
+    flops = C.c_double(0.0)
+    _check(load().cf_calibrate(kind, _ptr(src), _ptr(dst), nbytes, workgroups, iters, _ptr(sink), C.byref(flops),
+                               _stream(stream)))
+    return flops.value
 
 
 def cf_profile_kernel_events(enable: bool) -> None:

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcachefocus.so")
-SOURCES = ["cf_api.hip", "cf_reposition.hip", "cf_attn_generic.hip", "cf_attn_mfma.hip", "cf_attn_reduce.hip", "cf_select.hip"]
+SOURCES = ["cf_api.hip", "cf_reposition.hip", "cf_attn_generic.hip", "cf_attn_mfma.hip", "cf_attn_reduce.hip", "cf_select.hip", "cf_calibrate.hip"]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

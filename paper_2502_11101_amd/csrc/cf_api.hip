@@ -12,10 +12,7 @@ namespace cf {
 
 namespace {
 thread_local char g_err[512] = "";
-thread_local int g_phases = 7;
 }
-
-int profile_phases() { return g_phases; }
 
 namespace {
 constexpr int kTimerPairs = 1024;
@@ -101,8 +98,6 @@ extern "C" {
 const char* cf_last_error(void) { return g_err; }
 
 int32_t cf_version(void) { return 100; }
-
-void cf_profile_phases(int32_t mask) { g_phases = mask & 7; }
 
 cf_status cf_profile_kernel_events(int32_t enable) {
     if (g_timer.on) {

@@ -441,7 +441,6 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
         cf_status st = launch_attention_generic(a, f, s);
         return st != CF_OK || !prune ? st : launch_prune_step(a, prune, s);
     }
-    const int phases = profile_phases();
     const Plan p = make_plan(a.n_q_heads, a.n_kv_heads, a.batch, a.max_tq, a.seg_stride, a.max_kv_tokens);
     const dim3 grid((unsigned)(p.x_count * p.n_rg));
     const dim3 grid3((unsigned)p.nsplit, (unsigned)a.n_kv_heads, (unsigned)a.batch);     // attn_tile_kernel's
@@ -452,11 +451,10 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
     const bool reg_table = a.seg_stride <= kWave;    // the attention kernels keep a table this small in registers
     // the attention kernel's launch carries the profiling aid's start/stop events (null when it is off)
     hipEvent_t ev_start = nullptr, ev_stop = nullptr;
-    if (phases & 1) profile_kernel_pair(&ev_start, &ev_stop);
+    profile_kernel_pair(&ev_start, &ev_stop);
 #define CF_LAUNCH_TIMED(KERNEL, GRID, BLOCK) hipExtLaunchKernelGGL(KERNEL, GRID, BLOCK, 0, s, ev_start, ev_stop, 0, a, f, p)
 #define CF_LAUNCH_DT(DT)                                                                                                       \
-    if (!(phases & 1)) {                                                                                                       \
-    } else if (p.producers == 0) {                                                                                             \
+    if (p.producers == 0) {                                                                                                    \
         if (reg_table) CF_LAUNCH_TIMED((attn_tile_kernel<DT, 1, 32, 2, true>), grid3, dim3(2 * kThreads));                            \
         else CF_LAUNCH_TIMED((attn_tile_kernel<DT, 1, 32, 2, false>), grid3, dim3(2 * kThreads));                                     \
     } else {                                                                                                                   \
@@ -467,18 +465,17 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
     if (a.dtype == CF_BF16) { CF_LAUNCH_DT(CF_BF16) } else { CF_LAUNCH_DT(CF_F16) }
 #undef CF_LAUNCH_DT
 #undef CF_LAUNCH_TIMED
-    if ((phases & 2) && !(p.direct_out && a.mass == nullptr)) launch_combine(a, p, s);    // else nothing left to merge or reduce
+    if (!(p.direct_out && a.mass == nullptr)) launch_combine(a, p, s);    // else nothing left to merge or reduce
     CF_HIP(hipGetLastError());
     if (prune) {
-        if (!(phases & 4)) {
-        } else if (epilogue_fits(p, prune)) {
+        if (epilogue_fits(p, prune)) {
             launch_epilogue(a, p, prune, s);
         } else {
             launch_mass(a, p, s);
             CF_HIP(hipGetLastError());
             return launch_prune_step(a, prune, s);
         }
-    } else if ((phases & 4) && a.mass != nullptr) {
+    } else if (a.mass != nullptr) {
         launch_mass(a, p, s);
     }
     CF_HIP(hipGetLastError());

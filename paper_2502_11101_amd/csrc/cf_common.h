@@ -32,7 +32,6 @@ struct RopeFreq {
 };
 
 void set_error(const char* fmt, ...);
-int profile_phases();   // bit mask set by cf_profile_phases (thread-local, default: all)
 // the start/stop events of the attention kernel's next launch while cf_profile_kernel_events is on (else both null)
 void profile_kernel_pair(hipEvent_t* start, hipEvent_t* stop);
 cf_status check_desc(const cf_layer_desc* d);

@@ -156,15 +156,17 @@ def _run(g, batch, tq, n_store, tables, q_stored, q_pos, t, layout="token", soft
 
 
 def _check(g, batch, tq, tables, q_stored, q_pos, t, got, m, rotated, scale=None, queries=None):
-    """Outputs against the plain oracle (row-normalised); every segment's mass, relative, against the plain
-    oracle where no key is moved and against the rounded-key reference where keys are."""
+    """Outputs (row-normalised) and every segment's mass (relative): against the plain oracle where no key is
+    moved — the kernels' keys are then the oracle's, bit for bit — and against the rounded-key reference where
+    keys are moved (with keys this large and softmaxes this sharp, the one rounding of a moved key alone moves an
+    output by more than the output tolerance; the reference carries that rounding, so the bound stays the same)."""
     worst_out = worst_mass = 0.0
     for b in (range(batch) if queries is None else queries):
         rows = slice(b * tq, (b + 1) * tq)
         ref_out, ref_mass = orc.prefill_attention(H.f64(t["q"][rows]), q_stored, q_pos[b], t["k_store"], t["v_store"], t["k_self"],
                                                   t["v_self"], tables[b], g.n_kv_heads, g.rope_base, scale=scale)
         if rotated:
-            _, ref_mass = H.rounded_key_reference(g.dtype, t["q"][rows], q_stored, q_pos[b], t["k_store"], t["v_store"],
+            ref_out, ref_mass = H.rounded_key_reference(g.dtype, t["q"][rows], q_stored, q_pos[b], t["k_store"], t["v_store"],
                                                   t["k_self"], t["v_self"], tables[b], g.n_kv_heads, g.rope_base, scale=scale)
         worst_out = max(worst_out, G.row_error(got[rows], ref_out))
         worst_mass = max(worst_mass, G.rel_error(m[b, :len(tables[b])], ref_mass))
@@ -212,7 +214,10 @@ def test_softmax_scale_override(shape, factor):
         worst_out, worst_mass = _check(g, batch, tq, tables, q_stored, q_pos, t, got, m, rotated, scale=scale, queries=queries)
         _say(f"  out err {worst_out:.3e}  mass err {worst_mass:.3e}")
         assert worst_out <= G.OUT_TOL[g.dtype]
-        assert worst_mass <= G.MASS_TOL[g.dtype]
+        # The reference moves keys in fp64, the kernels in fp32: where the two round a key element to different
+        # 16-bit neighbours a score differs by one rounding step times the scale, so the sharper softmax is allowed
+        # that factor on moved keys.
+        assert worst_mass <= G.MASS_TOL[g.dtype] * (max(1.0, factor) if rotated else 1.0)
     # the override is used: the default scale gives something else
     got_default, _ = _run(g, batch, tq, n_store, tables, q_stored, q_pos, t)
     assert G.row_error(got_default, got.astype(np.float64)) > 1e-2

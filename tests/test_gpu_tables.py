@@ -106,9 +106,12 @@ def test_document_listed_as_several_segments(case):
         _, near_mass = H.rounded_key_reference(g.dtype, t["q"][rows], 0, q_pos[b], t["k_store"], t["v_store"], t["k_self"], t["v_self"],
                                                tables[b], g.n_kv_heads, g.rope_base)
         assert G.row_error(out[rows], ref_out) <= G.OUT_TOL[g.dtype]
-        assert G.rel_error(mass[b, :len(tables[b])], near_mass) <= G.MASS_TOL[g.dtype]
+        tol = G.NEAR_MASS_TOL[g.dtype]
+        if not G.rounds_moved_keys(g, cf.CF_ROPE_HALF, len(tables[b])):
+            near_mass, tol = ref_mass, G.MASS_TOL[g.dtype]         # the fp32 kernel rounds no moved key
+        assert G.rel_error(mass[b, :len(tables[b])], near_mass) <= tol
         expect = start.cpu().numpy()[b].astype(np.float64) + H.doc_scores(tables[b], near_mass, n_docs)
-        assert G.rel_error(score[b], expect) <= G.MASS_TOL[g.dtype]
+        assert G.rel_error(score[b], expect) <= tol
         # and exactly the sum, in table order, of the masses this call itself reported
         own = start.cpu().numpy()[b].copy()
         for d in range(n_docs):
@@ -168,7 +171,7 @@ def test_fused_layer_with_split_documents_matches_separate_calls():
     assert torch.equal(a["keep"], b["keep"]) and torch.equal(a["segs"][:, :5], b["segs"][:, :5])
     _, ref_mass = H.rounded_key_reference(g.dtype, t["q"][:cfg.tq], 0, a["q_start"], t["k_store"], t["v_store"], t["k_self"], t["v_self"],
                                           a["cut"], g.n_kv_heads, g.rope_base)
-    assert G.rel_error(a["score"].cpu().numpy()[0], H.doc_scores(a["cut"], ref_mass, 6)) <= G.MASS_TOL[g.dtype]
+    assert G.rel_error(a["score"].cpu().numpy()[0], H.doc_scores(a["cut"], ref_mass, 6)) <= G.NEAR_MASS_TOL[g.dtype]
     lens = [int(x) for x in st.doc_lens[st.query_docs[0]]]
     assert a["keep"][0, :3].tolist() == orc.prune_topk(a["score"].cpu().numpy()[0], lens, list(range(6)), 3)
 
@@ -185,8 +188,9 @@ RANGE_CASES = {
 @pytest.mark.parametrize("case", list(RANGE_CASES))
 def test_attention_flags_positions_outside_the_range(case):
     """Entries whose new or stored positions leave [0, max_positions) raise CF_FLAG_POS_RANGE and are skipped: the
-    call equals the one on the table without them.  A query placed beyond the range attends nothing (zero rows, zero
-    masses); the other query of the batch is unaffected."""
+    call gives what the table without them gives (to the last bits: a longer table may cut the tokens into splits
+    elsewhere, which changes the order of fp32 sums).  A query placed beyond the range attends nothing (zero rows,
+    zero masses); the other query of the batch is unaffected."""
     g, tq, extra = RANGE_CASES[case]
     _say(f"position range {case}")
     mp = g.max_positions
@@ -205,18 +209,19 @@ def test_attention_flags_positions_outside_the_range(case):
     assert ref[3] == 0
     got = _attend(g, t, [with_bad(0), with_bad(1)], tq, 0, [170, 170], n_store, 4)
     assert got[3] == cf.CF_FLAG_POS_RANGE
-    assert np.array_equal(got[0], ref[0])
+    ulp = 1e-6 if g.dtype == "f32" else 2.0 ** -7
+    assert G.row_error(got[0], ref[0].astype(np.float64)) <= ulp
     keep = [extra + 0, extra + 3, extra + 5]
-    assert np.array_equal(got[1][:, keep], ref[1][:, extra:extra + 3])
+    assert G.rel_error(got[1][:, keep], ref[1][:, extra:extra + 3]) <= 1e-5
     assert np.all(got[1][:, [extra + 1, extra + 2, extra + 4]] == 0.0)
-    assert np.array_equal(got[2], ref[2]) and np.all(got[2][:, [1, 3]] == 0.0)
+    assert G.rel_error(got[2][:, [0, 2]], ref[2][:, [0, 2]]) <= 1e-5 and np.all(got[2][:, [1, 3]] == 0.0)
     # an entry that ends exactly at max_positions is inside
     edge = [orc.Segment(int(doc_off[1]), 17, 0, mp - 17 - tq, orc.KIND_DOC, 1), orc.Segment(0, tq, 0, mp - tq, orc.KIND_SELF, -1)]
     assert _attend(g, t, [edge, edge], tq, 0, [mp - tq, mp - tq], n_store, 4)[3] == 0
     # query 1 placed so that its last row would sit at max_positions
     out, mass, score, flag = _attend(g, t, [good(0), good(1)], tq, 0, [170, mp - tq + 1], n_store, 4)
     assert flag == cf.CF_FLAG_POS_RANGE
-    assert np.array_equal(out[:tq], ref[0][:tq]) and np.array_equal(mass[0], ref[1][0])
+    assert G.row_error(out[:tq], ref[0][:tq].astype(np.float64)) <= ulp and G.rel_error(mass[0, extra:extra + 3], ref[1][0, extra:extra + 3]) <= 1e-5
     assert np.all(out[tq:] == 0.0) and np.all(mass[1, :extra + 3] == 0.0) and np.all(score[1] == 0.0)
 
 
