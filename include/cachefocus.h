@@ -15,7 +15,8 @@
  *   - "device" pointers are HIP device memory owned by the caller; "host" values are
  *     passed by value or as host pointers.  The library allocates no device memory and
  *     never frees or retains caller memory.  What it keeps between calls: the thread-local
- *     text of cf_last_error() and — only while the measurement aids at the end of
+ *     text of cf_last_error(), the per-device address of the buffer behind
+ *     cf_prefill_attention_static, and — only while the measurement aids at the end of
  *     this header are switched on — their events.  None of it changes a call's results.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     enqueue work and return; outputs are valid once the stream reaches that point.
@@ -179,6 +180,32 @@ CF_API cf_status cf_prefill_attention(const cf_layer_desc* desc,
                                int32_t batch, int32_t max_tq, int64_t max_kv_tokens,
                                void* out, float* mass, float* score_accum, int32_t score_stride,
                                void* workspace, size_t workspace_bytes,
+                               int32_t* dev_flag, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * cf_prefill_attention for callers that cannot allocate device memory or hand in a workspace: code that
+ * runs under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments,
+ * same kernels and bit-identical results, but the partial results of the splits live in a buffer the
+ * library owns: a file-scope device array of CF_STATIC_SCRATCH_BYTES that every GPU the library runs on
+ * holds until the process ends.  The call itself allocates nothing (no hipMalloc / hipFree, no
+ * allocating library routine).
+ *   - Shapes whose workspace (cf_prefill_workspace_bytes) exceeds CF_STATIC_SCRATCH_BYTES are
+ *     rejected with CF_ERR_WORKSPACE before anything is launched.
+ *   - The first call on a device looks the array's address up (hipGetSymbolAddress, once per device,
+ *     with that device current); make that call outside stream capture.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ *     streams or threads) race and must be serialised by the caller.  The array keeps the last call's
+ *     contents; nothing in it needs clearing between calls.
+ */
+#define CF_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+CF_API cf_status cf_prefill_attention_static(const cf_layer_desc* desc,
+                               const void* q, const int32_t* q_off, int32_t q_stored_start,
+                               const int32_t* q_new_start,
+                               const void* k_store, const void* v_store, int64_t n_store_tokens,
+                               const void* k_self, const void* v_self,
+                               const cf_segment* segs, const int32_t* n_seg, int32_t seg_stride,
+                               int32_t batch, int32_t max_tq, int64_t max_kv_tokens,
+                               void* out, float* mass, float* score_accum, int32_t score_stride,
                                int32_t* dev_flag, void* stream);
 
 /* ---------------------------------------------------------------------------------------------

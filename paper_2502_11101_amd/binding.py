@@ -29,7 +29,8 @@ DTYPE_CODE = {"f32": CF_F32, "bf16": CF_BF16, "f16": CF_F16}
 
 EXPORTS = ("cf_reposition_keys", "cf_prefill_workspace_bytes", "cf_prefill_attention", "cf_prune_topk",
            "cf_assign_positions", "cf_gather_segments", "cf_last_error", "cf_version", "cf_calibrate", "cf_profile_kernel_events", "cf_profile_kernel_ms",
-           "cf_prefill_layer", "cf_assemble_cache")
+           "cf_prefill_layer", "cf_assemble_cache", "cf_prefill_attention_static")
+CF_STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class cf_layer_desc(C.Structure):
@@ -91,6 +92,9 @@ def load() -> C.CDLL:
     lib.cf_prefill_attention.restype = i32
     lib.cf_prefill_attention.argtypes = [dp, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp, i32, i32, i32, i64,
                                          vp, vp, vp, i32, vp, sz, vp, vp]
+    lib.cf_prefill_attention_static.restype = i32
+    lib.cf_prefill_attention_static.argtypes = [dp, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp, i32, i32, i32, i64,
+                                                vp, vp, vp, i32, vp, vp]
     lib.cf_prefill_layer.restype = i32
     lib.cf_prefill_layer.argtypes = [dp, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp, i32, i32, i32, i64,
                                      vp, vp, vp, i32, vp, sz, C.POINTER(cf_prune_step), vp, vp]
@@ -208,6 +212,16 @@ def cf_prefill_attention(desc, q, q_off, q_stored_start: int, q_new_start, k_sto
         n_store_tokens, _ptr(k_self), _ptr(v_self), _ptr(segs), _ptr(n_seg), seg_stride, batch, max_tq,
         max_kv_tokens, _ptr(out), _ptr(mass), _ptr(score_accum), score_stride, _ptr(workspace), workspace_bytes,
         _ptr(dev_flag), _stream(stream)))
+
+
+def cf_prefill_attention_static(desc, q, q_off, q_stored_start: int, q_new_start, k_store, v_store, n_store_tokens: int,
+                                k_self, v_self, segs, n_seg, seg_stride: int, batch: int, max_tq: int,
+                                max_kv_tokens: int, out, mass, score_accum, score_stride: int, dev_flag=None,
+                                stream=None) -> None:
+    _check(load().cf_prefill_attention_static(
+        C.byref(desc), _ptr(q), _ptr(q_off), q_stored_start, _ptr(q_new_start), _ptr(k_store), _ptr(v_store),
+        n_store_tokens, _ptr(k_self), _ptr(v_self), _ptr(segs), _ptr(n_seg), seg_stride, batch, max_tq,
+        max_kv_tokens, _ptr(out), _ptr(mass), _ptr(score_accum), score_stride, _ptr(dev_flag), _stream(stream)))
 
 
 def make_prune_step(keep: int, strategy: int, force_n_reuse: int, normalise_by_len: bool, stride: int, pos_begin: int,

@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "cf_common.h"
 
@@ -262,6 +263,57 @@ cf_status cf_prefill_attention(const cf_layer_desc* desc, const void* q, const i
     return prefill_impl(desc, q, q_off, q_stored_start, q_new_start, k_store, v_store, n_store_tokens, k_self, v_self,
                         segs, n_seg, seg_stride, batch, max_tq, max_kv_tokens, out, mass, score_accum, score_stride,
                         workspace, workspace_bytes, nullptr, dev_flag, stream);
+}
+
+// The library-owned scratch of cf_prefill_attention_static: one copy per GPU, at an address of its own on each.
+// In host code the array's name is only a handle for the symbol lookup; kernels and copies use the looked-up
+// device address.
+static __device__ __attribute__((used)) __align__(256) unsigned char g_static_scratch[CF_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxScratchDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_addr[kMaxScratchDevices] = {};
+
+// the array's address on the current device, looked up once per device
+cf_status static_scratch(void** addr) {
+    int dev = -1;
+    CF_HIP(hipGetDevice(&dev));
+    CF_REQUIRE(dev >= 0 && dev < kMaxScratchDevices, CF_ERR_UNSUPPORTED, "device ordinal %d beyond %d", dev, kMaxScratchDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_addr[dev] == nullptr) {
+        void* p = nullptr;
+        CF_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)));
+        CF_REQUIRE(p != nullptr && (reinterpret_cast<uintptr_t>(p) & 255u) == 0, CF_ERR_DEVICE, "static scratch at a bad address");
+        g_scratch_addr[dev] = p;
+    }
+    *addr = g_scratch_addr[dev];
+    return CF_OK;
+}
+}  // namespace
+
+cf_status cf_prefill_attention_static(const cf_layer_desc* desc, const void* q, const int32_t* q_off,
+                                      int32_t q_stored_start, const int32_t* q_new_start, const void* k_store,
+                                      const void* v_store, int64_t n_store_tokens, const void* k_self,
+                                      const void* v_self, const cf_segment* segs, const int32_t* n_seg,
+                                      int32_t seg_stride, int32_t batch, int32_t max_tq, int64_t max_kv_tokens,
+                                      void* out, float* mass, float* score_accum, int32_t score_stride,
+                                      int32_t* dev_flag, void* stream) {
+    cf_status st = check_desc(desc);
+    if (st != CF_OK) return st;
+    CF_REQUIRE(batch >= 0 && max_tq >= 1 && seg_stride >= 1 && max_kv_tokens >= 0, CF_ERR_INVALID_ARG,
+               "batch, max_tq, seg_stride or max_kv_tokens out of range");
+    if (batch == 0) return CF_OK;
+    const size_t need = cf_prefill_workspace_bytes(desc, batch, max_tq, seg_stride, max_kv_tokens);
+    CF_REQUIRE(need <= CF_STATIC_SCRATCH_BYTES, CF_ERR_WORKSPACE,
+               "this shape needs %zu bytes of scratch, the library-owned buffer holds %zu: use cf_prefill_attention with a workspace",
+               need, (size_t)CF_STATIC_SCRATCH_BYTES);
+    void* scratch = nullptr;
+    st = static_scratch(&scratch);
+    if (st != CF_OK) return st;
+    return prefill_impl(desc, q, q_off, q_stored_start, q_new_start, k_store, v_store, n_store_tokens, k_self, v_self,
+                        segs, n_seg, seg_stride, batch, max_tq, max_kv_tokens, out, mass, score_accum, score_stride,
+                        scratch, CF_STATIC_SCRATCH_BYTES, nullptr, dev_flag, stream);
 }
 
 cf_status cf_prefill_layer(const cf_layer_desc* desc, const void* q, const int32_t* q_off, int32_t q_stored_start,
