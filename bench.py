@@ -1,18 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the re-positioned cached-KV prefill path on one MI355X.
 
-A step is one pass of the whole hot path over one layer of the LLaMA-2-7B-shaped workload
-(32-token shared prefix + 10 cached documents x 160 tokens + a 48-token query, bf16; the cache store
-head-major, [kv head][token][d], unless --store-layout token):
-one cf_prefill_layer call = cf_prefill_attention (keys re-positioned on the fly, attention,
-per-document mass, S += mass) + cf_prune_topk (keep 5) + cf_assign_positions + cf_gather_segments
-for the next layer's table.
-Steps cycle through distinct layer buffers whose total exceeds twice the 256 MB last-level
-cache, so every step streams its K/V from HBM.  Inputs are resident in HBM before timing.
+Headline (the default line): Alg. 2, Phase 1 over the LLaMA-2-7B-shaped layer stack — 32 layers, a 32-token
+shared prefix, 30 cached documents x 160 tokens, a 48-token query, bf16, every layer with K/V buffers of its own
+(2.5 GB in all: every layer streams from HBM), a prune event after layers 8/16/24/32 that keeps 60 % of the
+candidates and re-allocates the positions.  A step is the whole stack: the initial allocation plus 32
+cf_prefill_layer calls (keys re-positioned on the fly, attention, per-document mass, S += mass, and at the prune
+layers ranking, allocation and the next layer's table).  The value is KV tokens per second per layer: the key
+positions attended, summed over the 32 layers, over the step's time.
 
-Prints one JSON line: whole-step throughput in KV tokens/s per layer, the roofline of the
-attention call (algorithmic K+V bytes over its measured duration against 8 TB/s), and the
-CPU oracle timed on a bounded sample of the same workload.
+The same JSON line carries, under "configs", the single-layer workloads (LLaMA-2-7B layer, Qwen2-7B layer, Qwen2-1.5B
+batch of 64), each timed the same way: K back-to-back steps between two synchronisations, five repeats, the median.
+The dominant kernel's duration comes from start/stop events the library attaches to its dispatches on the launch
+stream.  "measured_peaks" holds what plain read / copy / dense-MFMA kernels sustain on this GPU in the same run;
+fractions are given against the nominal peaks (8 TB/s, 2.5 PFLOP/s) and against those.  Inputs are seeded and
+synthetic and resident in HBM before any timing.
 """
 
 from __future__ import annotations
@@ -31,15 +33,292 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = 2500.0      # dense bf16 / fp16
-# HBM bytes per launch of the dominant kernel on this workload, from the FETCH_SIZE and WRITE_SIZE counter runs
-# summarised in profiles/attn_tile_kernel_llama2_7b_layer.md (scaled by a 1 GiB copy kernel: x2.000 and x1.000)
-TRAFFIC_BYTES_PER_LAUNCH = 30_892_694 + 6_660_096
-WORKLOAD = "llama2_7b_layer"
+HEADLINE = "llama2_7b_stack"
+REPEATS = 5
+# HBM bytes per launch of each workload's dominant kernel (read + written), from the FETCH_SIZE and WRITE_SIZE
+# counter runs summarised under profiles/ (one file per kernel and workload, with the commands; both counters
+# scaled by what they read for a copy kernel of known size).  None: not measured for the kernels as they stand.
+TRAFFIC_BYTES_PER_LAUNCH = {
+    "llama2_7b_stack": None,
+    "llama2_7b_layer": None,
+    "qwen2_7b_layer": None,
+    "qwen2_1p5b_batch": None,
+}
 
 
-def cpu_baseline(cfg, st, budget_s: float = 12.0) -> dict:
-    """The oracle as it stands, on the host cores, on as many layer passes of the same
-    workload as fit the time budget (at least one)."""
+def _median(xs):
+    xs = sorted(xs)
+    n = len(xs)
+    return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
+
+
+def timed_repeats(step, steps: int, warmup: int, repeats: int = REPEATS):
+    """`warmup` untimed steps, then `repeats` blocks of exactly `steps` back-to-back steps, each block bracketed by
+    a device synchronisation on both sides.  Returns (median ms per step, every block's ms per step)."""
+    import torch
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    per_step = []
+    n = warmup
+    for _ in range(repeats):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(n + i)
+        torch.cuda.synchronize()
+        per_step.append(1e3 * (time.perf_counter() - t0) / steps)
+        n += steps
+    return _median(per_step), per_step
+
+
+def attention_kernel_ms(step, n_steps: int, launches_per_step: int):
+    """Mean duration of the attention kernel's launches over `n_steps` more steps, from start/stop events that the
+    library attaches to those dispatches on the launch stream (at most 1024 launches are kept)."""
+    import torch
+    from paper_2502_11101_amd import binding as cf
+    n_steps = max(1, min(n_steps, 1000 // launches_per_step))
+    cf.cf_profile_kernel_events(True)
+    for i in range(n_steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms, n = cf.cf_profile_kernel_ms()
+    cf.cf_profile_kernel_events(False)
+    assert n == n_steps * launches_per_step, (n, n_steps, launches_per_step)
+    return ms, n
+
+
+def single_step_latency_ms(step, n: int = 20) -> float:
+    """Isolated latency: one step between two synchronisations, the median of n."""
+    import torch
+    lat = []
+    for i in range(n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        step(i)
+        torch.cuda.synchronize()
+        lat.append(1e3 * (time.perf_counter() - t0))
+    return _median(lat)
+
+
+def measure_peaks() -> dict:
+    """What plain kernels of known size sustain on this GPU (cf_calibrate): a streaming read and a copy of 2 GiB
+    (eight times the 256 MB last-level cache), and a dense 32x32x16 MFMA loop on every SIMD."""
+    import torch
+    from paper_2502_11101_amd import binding as cf
+    nbytes = 2 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    src.fill_(1)
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def best(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return _median(ts)
+
+    out = {}
+    wgs = 256 * 16
+    out["hbm_read_gbs"] = nbytes / (best(lambda: cf.cf_calibrate(cf.CF_CALIB_READ, src, None, nbytes, wgs, 0, sink)) * 1e-3) / 1e9
+    out["hbm_copy_gbs"] = 2 * nbytes / (best(lambda: cf.cf_calibrate(cf.CF_CALIB_COPY, src, dst, nbytes, wgs, 0, sink)) * 1e-3) / 1e9
+    for name, kind in (("mfma_bf16_tflops", cf.CF_CALIB_MFMA_BF16), ("mfma_f16_tflops", cf.CF_CALIB_MFMA_F16)):
+        flops = [0.0]
+
+        def run(kind=kind):
+            flops[0] = cf.cf_calibrate(kind, None, None, 0, 256 * 8, 400, sink)
+        ms = best(run)
+        out[name] = flops[0] / (ms * 1e-3) / 1e12
+    out["what"] = ("cf_calibrate: read and copy of 2 GiB (copy counts read + written bytes), 4096 workgroups; "
+                   "MFMA: 2048 workgroups x 4 wavefronts x 400 x 64 v_mfma_f32_32x32x16, no memory traffic")
+    del src, dst
+    torch.cuda.empty_cache()
+    return out
+
+
+def roofline_entry(workload: str, kernel: str, kernel_ms: float, launches: int, bytes_per_launch: float,
+                   flops_per_launch: float, bound: str, peaks: dict, dtype: str) -> dict:
+    if bound == "hbm":
+        achieved = bytes_per_launch / (kernel_ms * 1e-3) / 1e9
+        peak, unit, measured = HBM_PEAK_GBS, "GB/s", peaks.get("hbm_read_gbs") if peaks else None
+    else:
+        achieved = flops_per_launch / (kernel_ms * 1e-3) / 1e12
+        peak, unit = MFMA_PEAK_TFLOPS, "TFLOP/s"
+        measured = peaks.get("mfma_f16_tflops" if dtype == "f16" else "mfma_bf16_tflops") if peaks else None
+    r = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+         "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(workload), "kernel": kernel, "ms_per_launch": kernel_ms,
+         "launches_timed": launches, "algorithmic_bytes_per_launch": bytes_per_launch}
+    if flops_per_launch:
+        r["algorithmic_flops_per_launch"] = flops_per_launch
+    if measured:
+        r["measured_peak"] = measured
+        r["frac_of_measured_peak"] = achieved / measured
+    return r
+
+
+def setup_stack(args):
+    """Alg. 2 Phase 1 over the whole layer stack (LLaMA-2-7B geometry): returns (step, info)."""
+    import math
+
+    import torch
+    from paper_2502_11101_amd import binding as cf
+    from paper_2502_11101_amd import pipeline as pl
+    from paper_2502_11101_amd import workloads as wl
+
+    cfg = wl.CONFIGS["llama2_7b_stack"]
+    g = cfg.geometry
+    st = wl.build_structure(cfg)
+    ts, hs = pl.store_strides(st.n_store_tokens, g.n_kv_heads, g.head_dim, args.store_layout)
+    desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions,
+                        store_token_stride=ts, store_head_stride=hs)
+    pb = pl.PrefillBatch(desc, st.doc_off[:-1][st.query_docs], st.doc_lens[st.query_docs], cfg.tq, cfg.prefix_len,
+                         cfg.doc_stored_start, st.n_store_tokens)
+    layers = []
+    for layer in range(cfg.n_layers):
+        t = wl.build_layer(cfg, st, layer)
+        layers.append({k: (pl.store_to_device(v, g.dtype, args.store_layout) if k in ("k_store", "v_store")
+                           else pl.to_device(v, g.dtype)) for k, v in t.items()})
+    out = torch.empty_like(layers[0]["q"])
+    keeps, alive, k = {}, [], cfg.docs_per_query
+    for layer in range(cfg.n_layers):
+        alive.append(k)
+        if layer in cfg.prune_layers:
+            k = max(1, math.ceil(cfg.keep_frac * k))
+            keeps[layer] = k
+    doc_len = int(st.doc_lens[0])
+    kv_tokens = sum(cfg.prefix_len + n * doc_len + cfg.tq for n in alive)
+    cand0 = torch.arange(pb.stride, dtype=torch.int32, device="cuda").repeat(pb.batch, 1)
+
+    def step(_: int) -> None:
+        pb.cand.copy_(cand0)
+        pb.n_cand.fill_(pb.stride)
+        pb.score.zero_()
+        pb.n_alive = pb.stride
+        pb.allocate_initial()
+        for layer, L in enumerate(layers):
+            pb.layer(L["q"], L["k_self"], L["v_self"], L["k_store"], L["v_store"], out, keep=keeps.get(layer),
+                     strategy=cf.CF_ALLOC_SORT)
+            if layer in keeps:
+                pb.advance()
+
+    def check() -> None:
+        assert pb.flags() == 0 and int(pb.n_cand[0].item()) == k
+
+    info = dict(cfg=cfg, st=st, kv_tokens=kv_tokens, launches_per_step=cfg.n_layers, bound="hbm", check=check,
+                kernel="attn_tile_kernel<bf16,1,32,2,true>, the 32 launches of a step taken together",
+                config={"workload": "llama2_7b_stack", "layers": cfg.n_layers, "documents_per_layer": alive,
+                        "kv_tokens_per_step": kv_tokens, "q_heads": g.n_q_heads, "kv_heads": g.n_kv_heads,
+                        "head_dim": g.head_dim, "tq": cfg.tq, "batch": 1, "store_layout": args.store_layout,
+                        "step": "initial allocation + 32 x cf_prefill_layer (prune events after layers 8, 16, 24, 32: "
+                                "keep 60 %, positions re-allocated)"})
+    return step, info
+
+
+def setup_layer(name: str, args):
+    """One layer of a single-layer workload per step (cf_prefill_layer with its prune event), cycling through
+    distinct layer buffers whose total exceeds twice the 256 MB last-level cache: returns (step, info)."""
+    import torch
+    from paper_2502_11101_amd import binding as cf
+    from paper_2502_11101_amd import pipeline as pl
+    from paper_2502_11101_amd import workloads as wl
+
+    cfg = wl.CONFIGS[name]
+    g = cfg.geometry
+    n_layers = args.layers
+    if args.batch > 1 and name == "llama2_7b_layer":
+        cfg = wl.scaled(cfg, batch=args.batch, n_store_docs=args.batch * cfg.docs_per_query)
+        per_layer = args.batch * cfg.docs_per_query * cfg.doc_len_range[1] * 2 * g.n_kv_heads * g.head_dim * 2
+        n_layers = max(2, min(n_layers, int(3.0e9 // per_layer)))
+    st = wl.build_structure(cfg)
+    ts, hs = pl.store_strides(st.n_store_tokens, g.n_kv_heads, g.head_dim, args.store_layout)
+    desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions,
+                        store_token_stride=ts, store_head_stride=hs)
+    pb = pl.PrefillBatch(desc, st.doc_off[:-1][st.query_docs], st.doc_lens[st.query_docs], cfg.tq, cfg.prefix_len,
+                         cfg.doc_stored_start, st.n_store_tokens)
+    layers = []
+    values = "seeded NumPy draws (workloads.build_layer)"
+    if name == "qwen2_1p5b_batch":
+        # 1.5 M store tokens: the store of each layer copy is drawn on the device (N(0,1), seeded), the queries' own
+        # tensors on the host as everywhere else; two copies (3.1 GB) are cycled through
+        n_layers = 2
+        values = "store: torch.randn on the device (seeded); q / own block: seeded NumPy draws"
+        dt = pl.TORCH_DTYPE[g.dtype]
+        gen = torch.Generator(device="cuda").manual_seed(5000)
+        shape = (st.n_store_tokens, g.n_kv_heads, g.head_dim) if args.store_layout == "token" else \
+            (g.n_kv_heads, st.n_store_tokens, g.head_dim)
+        rng = np.random.default_rng(5001)
+        nq = cfg.batch * cfg.tq
+        for _ in range(n_layers):
+            L = {k: torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(dt) for k in ("k_store", "v_store")}
+            for k, h in (("q", g.n_q_heads), ("k_self", g.n_kv_heads), ("v_self", g.n_kv_heads)):
+                L[k] = pl.to_device(wl.round_to_dtype(rng.standard_normal((nq, h, g.head_dim), dtype=np.float32), g.dtype), g.dtype)
+            layers.append(L)
+    else:
+        for layer in range(n_layers):
+            t = wl.build_layer(cfg, st, layer)
+            layers.append({k: (pl.store_to_device(v, g.dtype, args.store_layout) if k in ("k_store", "v_store")
+                               else pl.to_device(v, g.dtype)) for k, v in t.items()})
+    out = torch.empty_like(layers[0]["q"])
+    pb.allocate_initial()
+    torch.cuda.synchronize()
+    kv_tokens = wl.kv_tokens_per_call(cfg, st)
+
+    def step(i: int) -> None:
+        L = layers[i % len(layers)]
+        # attention + mass + S += mass + prune + allocation + next layer's table (this layer's table stays in use)
+        pb.layer(L["q"], L["k_self"], L["v_self"], L["k_store"], L["v_store"], out, keep=cfg.keep,
+                 strategy=cf.CF_ALLOC_SORT)
+
+    def check() -> None:
+        assert pb.flags() == 0, f"device flag {pb.flags()}"
+
+    mha = g.n_q_heads == g.n_kv_heads
+    kernel = ("attn_tile_kernel" if mha else "attn_pc_kernel") + f"<{g.dtype}> (first kernel of cf_prefill_layer)"
+    info = dict(cfg=cfg, st=st, kv_tokens=kv_tokens, launches_per_step=1, bound="hbm" if mha else "mfma", check=check,
+                kernel=kernel,
+                config={"workload": name, "batch": cfg.batch, "kv_tokens_per_step": kv_tokens, "q_heads": g.n_q_heads,
+                        "kv_heads": g.n_kv_heads, "head_dim": g.head_dim, "tq": cfg.tq, "docs": cfg.docs_per_query,
+                        "keep": cfg.keep, "layer_buffers": len(layers), "store_layout": args.store_layout, "values": values,
+                        "step": "cf_prefill_layer: attention + mass + prune_topk + assign_positions + gather_segments"})
+    return step, info
+
+
+def run_workload(name: str, args, steps: int, warmup: int, peaks: dict) -> dict:
+    step, info = setup_stack(args) if name == HEADLINE else setup_layer(name, args)
+    cfg = info["cfg"]
+    g = cfg.geometry
+    ms_per_step, repeats = timed_repeats(step, steps, warmup)
+    info["check"]()
+    kernel_ms, launches = attention_kernel_ms(step, steps, info["launches_per_step"])
+    latency_ms = single_step_latency_ms(step)
+    info["check"]()
+    kv_tokens = info["kv_tokens"]
+    bytes_per_token = 2 * g.n_kv_heads * g.head_dim * (4 if g.dtype == "f32" else 2)
+    n_launch = info["launches_per_step"]
+    bytes_per_launch = kv_tokens * bytes_per_token / n_launch
+    flops_per_launch = kv_tokens * 4.0 * cfg.tq * g.head_dim * g.n_q_heads / n_launch
+    roof = roofline_entry(name, info["kernel"], kernel_ms, launches, bytes_per_launch, flops_per_launch, info["bound"], peaks, g.dtype)
+    step_gbs = kv_tokens * bytes_per_token / (ms_per_step * 1e-3) / 1e9
+    step_tflops = flops_per_launch * n_launch / (ms_per_step * 1e-3) / 1e12
+    cfg_out = dict(info["config"])
+    cfg_out.update({"whole_step_gbs": step_gbs, "whole_step_tflops": step_tflops,
+                    "whole_step_frac_of_peak": step_gbs / HBM_PEAK_GBS if info["bound"] == "hbm" else step_tflops / MFMA_PEAK_TFLOPS})
+    return {"value": kv_tokens / (ms_per_step * 1e-3), "ms_per_step": ms_per_step, "ms_per_step_repeats": repeats,
+            "single_step_latency_ms": latency_ms, "dtype": g.dtype, "config": cfg_out, "roofline": roof,
+            "_cfg": cfg, "_st": info["st"]}
+
+
+def cpu_baseline(cfg, st, workload: str, budget_s: float = 12.0) -> dict:
+    """The oracle as it stands, on the host cores, on as many layer passes of the same workload as fit the time
+    budget (at least one): for the layer stack its first layers (all 30 documents alive), for a batch its first query.
+    A pass is the oracle's attention with per-document mass, the ranking and the allocation of the survivors."""
     from oracle import cachefocus_oracle as orc
     from paper_2502_11101_amd import workloads as wl
     try:
@@ -81,7 +360,7 @@ def cpu_baseline(cfg, st, budget_s: float = 12.0) -> dict:
         if time.perf_counter() - t0 > budget_s:
             break
     return {"value": tokens / cpu_time, "unit": "KV tokens/s per layer", "cores": int(cores), "kind": "oracle",
-            "sample": f"{passes} layer pass(es) of {WORKLOAD} (batch 1), input generation excluded"}
+            "sample": f"{passes} layer pass(es) of {workload} (its first layers, one query, {cfg.docs_per_query} documents alive), input generation excluded"}
 
 
 def bench_assemble(args) -> int:
@@ -250,95 +529,6 @@ def bench_assemble(args) -> int:
     return 0
 
 
-def bench_stack(args) -> int:
-    """Alg. 2 Phase 1 over a whole layer stack (LLaMA-2-7B geometry, 32 layers, 30 documents x 160 tokens, a prune
-    event after layers 8/16/24/32 that keeps 60 % of the candidates, positions re-allocated each time): one step is
-    the initial allocation plus 32 cf_prefill_layer calls, every layer with K/V buffers of its own.  The roofline
-    entry adds up the algorithmic K+V bytes of all attention launches of a step over the sum of their durations."""
-    import math
-
-    import torch
-    from paper_2502_11101_amd import binding as cf
-    from paper_2502_11101_amd import pipeline as pl
-    from paper_2502_11101_amd import workloads as wl
-
-    cfg = wl.CONFIGS["llama2_7b_stack"]
-    g = cfg.geometry
-    st = wl.build_structure(cfg)
-    ts, hs = pl.store_strides(st.n_store_tokens, g.n_kv_heads, g.head_dim, args.store_layout)
-    desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions,
-                        store_token_stride=ts, store_head_stride=hs)
-    pb = pl.PrefillBatch(desc, st.doc_off[:-1][st.query_docs], st.doc_lens[st.query_docs], cfg.tq, cfg.prefix_len,
-                         cfg.doc_stored_start, st.n_store_tokens)
-    layers = []
-    for layer in range(cfg.n_layers):
-        t = wl.build_layer(cfg, st, layer)
-        layers.append({k: (pl.store_to_device(v, g.dtype, args.store_layout) if k in ("k_store", "v_store")
-                           else pl.to_device(v, g.dtype)) for k, v in t.items()})
-    out = torch.empty_like(layers[0]["q"])
-    keeps, alive, k = {}, [], cfg.docs_per_query
-    for layer in range(cfg.n_layers):
-        alive.append(k)
-        if layer in cfg.prune_layers:
-            k = max(1, math.ceil(cfg.keep_frac * k))
-            keeps[layer] = k
-    doc_len = int(st.doc_lens[0])
-    kv_tokens = sum(cfg.prefix_len + n * doc_len + cfg.tq for n in alive)
-    bytes_per_token = 2 * g.n_kv_heads * g.head_dim * 2
-    cand0 = torch.arange(pb.stride, dtype=torch.int32, device="cuda").repeat(pb.batch, 1)
-
-    def step(_: int) -> None:
-        pb.cand.copy_(cand0)
-        pb.n_cand.fill_(pb.stride)
-        pb.score.zero_()
-        pb.n_alive = pb.stride
-        pb.allocate_initial()
-        for layer, L in enumerate(layers):
-            pb.layer(L["q"], L["k_self"], L["v_self"], L["k_store"], L["v_store"], out, keep=keeps.get(layer),
-                     strategy=cf.CF_ALLOC_SORT)
-            if layer in keeps:
-                pb.advance()
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    assert pb.flags() == 0 and int(pb.n_cand[0].item()) == k
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    assert pb.flags() == 0 and int(pb.n_cand[0].item()) == k
-    ms_per_step = 1e3 * elapsed / args.steps
-    cf.cf_profile_kernel_events(True)
-    n_timed = min(args.steps, 1000 // cfg.n_layers)
-    for i in range(n_timed):
-        step(i)
-    torch.cuda.synchronize()
-    kernel_ms, n_bracketed = cf.cf_profile_kernel_ms()
-    cf.cf_profile_kernel_events(False)
-    assert n_bracketed == n_timed * cfg.n_layers
-    attn_ms = kernel_ms * cfg.n_layers                      # all attention launches of one step
-    achieved = kv_tokens * bytes_per_token / (attn_ms * 1e-3) / 1e9
-    step_gbs = kv_tokens * bytes_per_token / (ms_per_step * 1e-3) / 1e9
-    print(json.dumps({
-        "metric": "KV tokens/s per layer, re-positioned cached-KV prefill over a pruned layer stack",
-        "value": kv_tokens / (ms_per_step * 1e-3), "unit": "KV tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": g.dtype, "data": "synthetic",
-        "config": {"workload": "llama2_7b_stack", "layers": cfg.n_layers, "documents_per_layer": alive,
-                   "kv_tokens_per_step": kv_tokens, "q_heads": g.n_q_heads, "kv_heads": g.n_kv_heads, "head_dim": g.head_dim,
-                   "tq": cfg.tq, "store_layout": args.store_layout, "whole_step_gbs": step_gbs,
-                   "whole_step_frac_of_hbm_peak": step_gbs / HBM_PEAK_GBS,
-                   "step": "initial allocation + 32 x cf_prefill_layer (prune events after layers 8, 16, 24, 32)"},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "attn_tile_kernel<bf16,1,32,2,true>, the 32 launches of a step taken together",
-                     "ms_per_launch": kernel_ms, "launches_timed": n_bracketed,
-                     "algorithmic_bytes_per_launch": kv_tokens * bytes_per_token / cfg.n_layers}}))
-    return 0
-
-
 def bench_encode(args) -> int:
     """Query-independent parallel document caching (Sec. 2.2) for one layer: a step encodes the documents of the
     LLaMA-2-7B stack geometry (each attends to the 32-token prefix in the store and causally to itself) and writes
@@ -417,29 +607,31 @@ def bench_encode(args) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--layers", type=int, default=24, help="distinct layer buffers cycled through")
+    ap.add_argument("--steps", type=int, default=100,
+                    help="steps per timed block of the headline workload (a step is the whole 32-layer stack)")
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--layers", type=int, default=24, help="distinct layer buffers the single-layer workloads cycle through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=[WORKLOAD, "qwen2_7b_layer", "qwen2_1p5b_batch"], default=WORKLOAD,
-                    help="the headline workload (default), or one of the GQA configurations, whose attention kernel is "
-                         "priced against the MFMA peak instead of HBM bandwidth")
+    ap.add_argument("--no-configs", action="store_true", help="headline only: skip the single-layer workloads")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the calibration kernels")
+    ap.add_argument("--workload", choices=[HEADLINE, "llama2_7b_layer", "qwen2_7b_layer", "qwen2_1p5b_batch"], default=HEADLINE,
+                    help="the workload of the line's value (default: the layer stack, with the others nested under "
+                         "\"configs\"); naming another one times that workload alone, e.g. for a profiler run")
     ap.add_argument("--batch", type=int, default=0,
                     help="queries per step for --workload llama2_7b_layer (default: the configuration's own, 1); each query "
                          "gets documents of its own, so the step streams batch times the K/V")
     ap.add_argument("--store-layout", choices=["head", "token"], default="head",
                     help="layout of the cache store: head-major [kv head][token][d] (default, the layout the "
                          "store is meant to be kept in) or token-major [token][kv head][d]")
-    ap.add_argument("--path", choices=["prefill", "assemble", "decode", "reposition", "stack", "encode"], default="prefill",
+    ap.add_argument("--path", choices=["prefill", "assemble", "decode", "reposition", "encode"], default="prefill",
                     help="prefill: the per-layer hot path (the headline metric).  assemble: Alg. 2 Phase 2, "
                          "cf_assemble_cache of one layer of the final survivor set into a decode cache.  decode: one "
                          "decode step's attention (one new token) over an assembled cache, Alg. 2 Phase 3.  reposition: "
-                         "the stand-alone Eq. 5 call, cf_reposition_keys, out of place over the documents of one layer.  stack: "
-                         "Alg. 2 Phase 1 over 32 layers with four prune events (one step = the whole stack).  encode: offline "
+                         "the stand-alone Eq. 5 call, cf_reposition_keys, out of place over the documents of one layer.  encode: offline "
                          "document encoding of one layer into the cache store (Sec. 2.2), --assemble-docs documents")
     ap.add_argument("--assemble-docs", type=int, default=5, help="surviving documents per query for --path assemble")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="run only 10 elementwise copies of 1 GiB (read 1 GiB + write 1 GiB each): the known-size "
+                    help="run only 10 copies of 1 GiB (read 1 GiB + write 1 GiB each) through cf_calibrate: the known-size "
                          "kernel that scales the HBM byte counters of a profiler run")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -449,138 +641,61 @@ def main() -> int:
 
     import torch
     from paper_2502_11101_amd import binding as cf
-    from paper_2502_11101_amd import pipeline as pl
-    from paper_2502_11101_amd import workloads as wl
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
-    if args.copy_calibration:
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(10):
-            torch.mul(src, 1.0, out=dst)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_calibration": {"launches": 10, "read_bytes": src.numel() * 4,
-                                               "write_bytes": dst.numel() * 4}}))
-        return 0
     cf.load()
+    if args.copy_calibration:
+        n = 1 << 30
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        sink = torch.zeros(64, dtype=torch.uint8, device="cuda")
+        for _ in range(10):
+            cf.cf_calibrate(cf.CF_CALIB_COPY, src, dst, n, 4096, 0, sink)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"kernel": "calib_copy_kernel", "launches": 10, "read_bytes": n, "write_bytes": n}}))
+        return 0
     if args.path in ("assemble", "decode", "reposition"):
         return bench_assemble(args)
-    if args.path == "stack":
-        return bench_stack(args)
     if args.path == "encode":
         return bench_encode(args)
 
-    cfg = wl.CONFIGS[args.workload]
-    g = cfg.geometry
-    if args.workload == "qwen2_1p5b_batch":
-        args.layers = min(args.layers, 2)             # 1.5 GB of store per layer copy
-    if args.batch > 1 and args.workload == WORKLOAD:
-        cfg = wl.scaled(cfg, batch=args.batch, n_store_docs=args.batch * cfg.docs_per_query)
-        per_layer = args.batch * cfg.docs_per_query * cfg.doc_len_range[1] * 2 * g.n_kv_heads * g.head_dim * 2
-        args.layers = max(2, min(args.layers, int(3.0e9 // per_layer)))       # still well past the last-level cache
-    st = wl.build_structure(cfg)
-    ts, hs = pl.store_strides(st.n_store_tokens, g.n_kv_heads, g.head_dim, args.store_layout)
-    desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions,
-                        store_token_stride=ts, store_head_stride=hs)
-    off = st.doc_off[:-1][st.query_docs]
-    lens = st.doc_lens[st.query_docs]
-    pb = pl.PrefillBatch(desc, off, lens, cfg.tq, cfg.prefix_len, cfg.doc_stored_start, st.n_store_tokens)
-    layers = []
-    for layer in range(args.layers):
-        t = wl.build_layer(cfg, st, layer)
-        layers.append({k: (pl.store_to_device(v, g.dtype, args.store_layout) if k in ("k_store", "v_store")
-                           else pl.to_device(v, g.dtype)) for k, v in t.items()})
-    out = torch.empty_like(layers[0]["q"])
-    pb.allocate_initial()
-    torch.cuda.synchronize()
-    kv_tokens = wl.kv_tokens_per_call(cfg, st)
-    bytes_per_token = 2 * g.n_kv_heads * g.head_dim * (4 if g.dtype == "f32" else 2)
-
-    def step(i: int) -> None:
-        L = layers[i % len(layers)]
-        # attention + mass + S += mass + prune + allocation + next layer's table (this layer's table stays in use)
-        pb.layer(L["q"], L["k_self"], L["v_self"], L["k_store"], L["v_store"], out, keep=cfg.keep,
-                 strategy=cf.CF_ALLOC_SORT)
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    assert pb.flags() == 0, f"device flag {pb.flags()}"
-    ms_per_step = 1e3 * elapsed / args.steps
-
-    # The dominant kernel (the attention kernel proper: K/V streaming, re-rotation, MFMA, softmax) where it runs:
-    # the same steps once more with the library bracketing each launch of that kernel by two events on the
-    # launch stream (the figure a kernel trace reports for it); and, as a cross-check, the steps' time with and
-    # without that kernel between two events of this script (its marginal cost in the stream, which is lower:
-    # a kernel's ramp-up overlaps its predecessor's tail when nothing sits between them).
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-
-    def timed_steps(phases: int, n: int) -> float:
-        cf.cf_profile_phases(phases)
-        for i in range(min(50, args.warmup + 1)):
-            step(i)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(n):
-            step(i)
-        e1.record()
-        torch.cuda.synchronize()
-        cf.cf_profile_phases(7)
-        return e0.elapsed_time(e1) / n
-
-    step_ms = timed_steps(7, args.steps)
-    rest_ms = timed_steps(6, args.steps)
-    cf.cf_profile_kernel_events(True)
-    timed_steps(7, min(args.steps, 1000))
-    kernel_ms, n_bracketed = cf.cf_profile_kernel_ms()
-    cf.cf_profile_kernel_events(False)
-    assert n_bracketed > 0
-    assert pb.flags() == 0, f"device flag {pb.flags()}"
-    achieved = kv_tokens * bytes_per_token / (kernel_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH if cfg.batch == 1 else None,
-                "kernel": "attn_tile_kernel<bf16,1,32,2,true> (first kernel of cf_prefill_layer / cf_prefill_attention)",
-                "ms_per_launch": kernel_ms, "algorithmic_bytes_per_launch": kv_tokens * bytes_per_token,
-                "launches_timed": n_bracketed, "ms_per_step_events": step_ms, "ms_per_step_without_this_kernel": rest_ms}
-    if args.workload != WORKLOAD:
-        # GQA shapes: a dense contraction, 4 * Tq * d * Hq flops per attended token (S = Q K^T and O = P V)
-        flops = kv_tokens * 4.0 * cfg.tq * g.head_dim * g.n_q_heads
-        tflops = flops / (kernel_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "achieved": tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": tflops / MFMA_PEAK_TFLOPS, "traffic": None,
-                    "kernel": f"attn_pc_kernel<{g.dtype},2> (first kernel of cf_prefill_layer / cf_prefill_attention)",
-                    "ms_per_launch": kernel_ms, "algorithmic_flops_per_launch": flops,
-                    "algorithmic_bytes_per_launch": kv_tokens * bytes_per_token, "launches_timed": n_bracketed, "ms_per_step_events": step_ms, "ms_per_step_without_this_kernel": rest_ms}
-
+    peaks = None if args.no_peaks else measure_peaks()
+    main_run = run_workload(args.workload, args, args.steps, args.warmup, peaks)
     result = {
         "metric": "KV tokens/s per layer, re-positioned cached-KV prefill",
-        "value": kv_tokens / (ms_per_step * 1e-3),
+        "value": main_run["value"],
         "unit": "KV tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": main_run["ms_per_step"],
+        "ms_per_step_repeats": main_run["ms_per_step_repeats"],
+        "single_step_latency_ms": main_run["single_step_latency_ms"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": g.dtype,
+        "dtype": main_run["dtype"],
         "data": "synthetic",
-        "config": {"workload": args.workload, "batch": cfg.batch, "kv_tokens_per_step": kv_tokens,
-                   "q_heads": g.n_q_heads, "kv_heads": g.n_kv_heads, "head_dim": g.head_dim, "tq": cfg.tq,
-                   "docs": cfg.docs_per_query, "keep": cfg.keep, "layer_buffers": len(layers),
-                   "store_layout": args.store_layout,
-                   "step": "cf_prefill_layer: attention + mass + prune_topk + assign_positions + gather_segments"},
-        "roofline": roofline,
+        "config": main_run["config"],
+        "roofline": main_run["roofline"],
     }
+    if peaks:
+        result["measured_peaks"] = peaks
+    if args.workload == HEADLINE and not args.no_configs:
+        # the single-layer workloads: >= 200 back-to-back steps per block, five blocks, the median
+        sub_steps = max(200, args.steps)
+        result["configs"] = []
+        for name in ("llama2_7b_layer", "qwen2_7b_layer", "qwen2_1p5b_batch"):
+            r = run_workload(name, args, sub_steps, 50, peaks)
+            result["configs"].append({"workload": name, "value": r["value"], "unit": "KV tokens/s", "steps": sub_steps,
+                                      "ms_per_step": r["ms_per_step"], "ms_per_step_repeats": r["ms_per_step_repeats"],
+                                      "single_step_latency_ms": r["single_step_latency_ms"], "dtype": r["dtype"],
+                                      "config": r["config"], "roofline": r["roofline"]})
+            torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, st)
+        result["cpu_baseline"] = cpu_baseline(main_run["_cfg"], main_run["_st"], args.workload)
     print(json.dumps(result))
     return 0
 
