@@ -280,7 +280,7 @@ def setup_layer(name: str, args):
         assert pb.flags() == 0, f"device flag {pb.flags()}"
 
     mha = g.n_q_heads == g.n_kv_heads
-    kernel = ("attn_tile_kernel" if mha else "attn_pc_kernel") + f"<{g.dtype}> (first kernel of cf_prefill_layer)"
+    kernel = ("attn_tile_kernel" if mha else "attn_pipe_kernel") + f"<{g.dtype}> (first kernel of cf_prefill_layer)"
     info = dict(cfg=cfg, st=st, kv_tokens=kv_tokens, launches_per_step=1, bound="hbm" if mha else "mfma", check=check,
                 kernel=kernel,
                 config={"workload": name, "batch": cfg.batch, "kv_tokens_per_step": kv_tokens, "q_heads": g.n_q_heads,
@@ -599,7 +599,7 @@ def bench_encode(args) -> int:
                    "step": "cf_prefill_attention (each document over the prefix and causally over itself) + cf_assemble_cache into the store"},
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops / MFMA_PEAK_TFLOPS, "traffic": None,
-                     "kernel": f"attn_pc_kernel<{g.dtype},2> (first kernel of cf_prefill_attention)",
+                     "kernel": f"attn_pipe_kernel<{g.dtype},2> (first kernel of cf_prefill_attention)",
                      "ms_per_launch": kernel_ms, "launches_timed": n_bracketed, "algorithmic_flops_per_launch": flops}}))
     return 0
 

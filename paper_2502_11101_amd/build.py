@@ -24,7 +24,7 @@ FLAGS = [
 RESOURCES = os.path.join(HERE, "kernel_resources.json")
 # kernels on the hot path that must keep everything in registers: a spill to scratch memory there
 # (a few lines of source can tip the register allocator over) costs far more than any tuning gains
-NO_SCRATCH = ("attn_tile_kernel", "attn_pc_kernel", "attn_combine_kernel", "layer_epilogue_kernel", "reposition_kernel",
+NO_SCRATCH = ("attn_tile_kernel", "attn_pipe_kernel", "attn_combine_kernel", "layer_epilogue_kernel", "reposition_kernel",
               "assemble_kernel")
 
 

@@ -27,7 +27,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 struct Plan {
     int group;          // query heads per kv head
     int row_blocks;     // 16-row blocks of the stacked rows of one kv head
-    int producers;      // 0: attn_tile_kernel (few rows); else attn_pc_kernel with that many loading wavefronts
+    int producers;      // 0: attn_tile_kernel (few rows); else attn_pipe_kernel with that many loading wavefronts
     int nrb;            // 64-row passes of a workgroup's rows (what the combine kernel handles at a time)
     int rows_wg;        // rows a workgroup has room for: 64 * nrb
     int n_rg;           // row groups per (query, kv head)
@@ -39,7 +39,7 @@ struct Plan {
     size_t off_ml, off_opart, off_massml, off_masspart, total;
 };
 
-constexpr int kPcWaves = 8;         // wavefronts of an attn_pc_kernel workgroup
+constexpr int kPcWaves = 8;         // wavefronts of an attn_pipe_kernel workgroup
 constexpr int kPcProducers = 2;     // of which load and stage
 constexpr int kPcNrb = 2;           // 16-row blocks per math wavefront
 
@@ -59,12 +59,12 @@ inline Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int 
         p.tile = 32;
         p.groups = 2;
     } else {
-        // Many rows (GQA, long queries): 64-token tiles, two row blocks per math wavefront.
+        // Many rows (GQA, long queries): 32-token units, two row blocks per math wavefront.
         const int blocks_wg = kPcNrb * (kPcWaves - kPcProducers);
         p.producers = kPcProducers;
         p.n_rg = (row_blocks + blocks_wg - 1) / blocks_wg;
         p.nrb = blocks_wg / 4;
-        p.tile = 64;
+        p.tile = 32;
         p.groups = 1;
     }
     p.blocks_rg = (row_blocks + p.n_rg - 1) / p.n_rg;
@@ -72,7 +72,7 @@ inline Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int 
     p.units_per_b = n_kv_heads * p.n_rg;
     p.units = batch * p.units_per_b;
     const int64_t est_tiles = max_kv_tokens / p.tile + seg_stride;
-    // One workgroup per CU and launch wave.  A CU holds one attn_pc_kernel workgroup at a time, so there the
+    // One workgroup per CU and launch wave.  A CU holds one attn_pipe_kernel workgroup at a time, so there the
     // count stays within the 256 CUs; two of the small kernel's fit, and a few more than 256 do no harm.
     int64_t ns = p.producers ? 256 / p.units : (256 + p.units - 1) / p.units;
     const int64_t cap = est_tiles / (2 * p.groups) > 1 ? est_tiles / (2 * p.groups) : 1;
@@ -278,14 +278,19 @@ __device__ __forceinline__ FoundSegment find_segment(const SegTable& tbl, int x,
         const unsigned long long hit = __ballot(idx < tbl.n && tbl.tile0[idx + 1] > x);
         if (hit) { s = s0 + __builtin_ctzll(hit); break; }
     }
+    // (the values are the same in every lane; taking them from the first one tells the compiler so, which keeps
+    // everything derived from them — tile descriptions, base addresses — on the scalar unit)
     FoundSegment f;
     f.seg = s;
-    f.first = tbl.tile0[s];
-    f.end = tbl.tile0[s + 1];
-    f.vis = tbl.vis[s];
-    f.delta = tbl.delta[s];
-    f.self = tbl.self[s];
-    f.tok = tbl.tok[s];
+    f.first = __builtin_amdgcn_readfirstlane(tbl.tile0[s]);
+    f.end = __builtin_amdgcn_readfirstlane(tbl.tile0[s + 1]);
+    f.vis = __builtin_amdgcn_readfirstlane(tbl.vis[s]);
+    f.delta = __builtin_amdgcn_readfirstlane(tbl.delta[s]);
+    f.self = __builtin_amdgcn_readfirstlane(tbl.self[s]);
+    const int64_t tok = tbl.tok[s];
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)tok);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)tok >> 32));
+    f.tok = (int64_t)(((uint64_t)hi << 32) | lo);
     return f;
 }
 

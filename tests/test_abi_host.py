@@ -186,7 +186,7 @@ def test_hot_path_kernels_keep_everything_in_registers():
             assert u["scratch_bytes"] == 0, (k, u)
     # both attention kernels are sized for one workgroup per CU: two wavefronts per SIMD
     for k, u in usage.items():
-        if "attn_tile_kernel" in k or "attn_pc_kernel" in k:
+        if "attn_tile_kernel" in k or "attn_pipe_kernel" in k:
             assert u["waves_per_simd"] == 2 and u["vgprs"] + u["agprs"] <= 256, (k, u)
 
 

@@ -38,9 +38,9 @@ SHAPES = {
     "few_rows_splits": (wl.Geometry(8, 8, 128, "bf16", 1.0e6, 32768), 1, 48, 32, 6, (160, 160)),
     # the same kernel with one split per (query, head): it normalises and writes the rows itself
     "few_rows_one_split": (wl.Geometry(8, 8, 128, "f16", 1.0e6, 32768), 32, 5, 3, 3, (20, 70)),
-    # 28 row blocks per kv head in three row groups: attn_pc_kernel, several splits
+    # 28 row blocks per kv head in three row groups: attn_pipe_kernel, several splits
     "many_rows_splits": (wl.Geometry(28, 4, 128, "bf16", 1.0e6, 32768), 1, 64, 32, 8, (100, 200)),
-    # 15 row blocks in two row groups, many units: attn_pc_kernel, one split
+    # 15 row blocks in two row groups, many units: attn_pipe_kernel, one split
     "many_rows_one_split": (wl.Geometry(12, 2, 128, "f16", 1.0e6, 32768), 40, 40, 0, 3, (20, 90)),
     # more than 64 table entries: the segment table lives in LDS instead of registers
     "few_rows_long_table": (wl.Geometry(4, 4, 128, "bf16", 1.0e6, 32768), 1, 16, 2, 70, (1, 9)),
