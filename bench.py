@@ -203,8 +203,9 @@ def setup_stack(args):
         pb.n_alive = pb.stride
         pb.allocate_initial()
         for layer, L in enumerate(layers):
+            # Alg. 2 reads S only at the prune events: the layers in between leave their scores pending
             pb.layer(L["q"], L["k_self"], L["v_self"], L["k_store"], L["v_store"], out, keep=keeps.get(layer),
-                     strategy=cf.CF_ALLOC_SORT)
+                     strategy=cf.CF_ALLOC_SORT, defer=layer not in keeps)
             if layer in keeps:
                 pb.advance()
 
@@ -217,7 +218,8 @@ def setup_stack(args):
                         "kv_tokens_per_step": kv_tokens, "q_heads": g.n_q_heads, "kv_heads": g.n_kv_heads,
                         "head_dim": g.head_dim, "tq": cfg.tq, "batch": 1, "store_layout": args.store_layout,
                         "step": "initial allocation + 32 x cf_prefill_layer (prune events after layers 8, 16, 24, 32: "
-                                "keep 60 %, positions re-allocated)"})
+                                "keep 60 %, positions re-allocated; the seven layers before each event defer their scores "
+                                "to it)"})
     return step, info
 
 

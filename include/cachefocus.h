@@ -317,7 +317,20 @@ CF_API cf_status cf_assemble_cache(const cf_layer_desc* desc, const void* k_stor
  * (stride = document slots per query; next_segs has the same seg_stride as segs).
  * With strategy CF_ALLOC_KEEP new_start / q_start are not written: hand in arrays that already
  * hold the current positions.
+ *
+ * Deferred scores.  Alg. 2 reads the accumulated scores S only at a prune event (every n-th layer), so the layers
+ * in between need not bring S up to date themselves.  A call with `defer` = 1 (and no prune step) runs the attention
+ * and leaves the layer's per-slot partial masses in the workspace instead of reducing them: neither `mass` nor
+ * `score_accum` is touched and the call is one launch shorter.  The next call with `defer` = 0 — with or without a
+ * prune step — is told in `n_pending` how many such layers precede it and adds their masses to S first, oldest first,
+ * then its own: S, `mass` (the last layer's) and every later result are bit-identical to those of calls that never
+ * deferred.  Rules: every call passes the number of layers pending before it (0 after a call that did not defer); at
+ * most CF_MAX_PENDING layers may be pending; the pending layers and the call that takes them in must use the same
+ * workspace, descriptor, batch, max_tq, seg_stride and max_kv_tokens, and the same, unchanged segs / n_seg / q_off /
+ * q_new_start (a prune step changes the tables, so scores cannot be pending across one).  Shapes served by the generic
+ * kernel do not defer: there a `defer` call accumulates at once and `n_pending` is ignored, with the same results.
  */
+#define CF_MAX_PENDING 15
 typedef struct cf_prune_step {
     int32_t keep;              /* documents kept per query, 0 <= keep <= stride                    */
     int32_t strategy;          /* cf_alloc_strategy                                                */
@@ -350,7 +363,8 @@ CF_API cf_status cf_prefill_layer(const cf_layer_desc* desc,
                                   int32_t batch, int32_t max_tq, int64_t max_kv_tokens,
                                   void* out, float* mass, float* score_accum, int32_t score_stride,
                                   void* workspace, size_t workspace_bytes,
-                                  const cf_prune_step* prune, int32_t* dev_flag, void* stream);
+                                  const cf_prune_step* prune, int32_t n_pending, int32_t defer,
+                                  int32_t* dev_flag, void* stream);
 
 /* Thread-local text for the last non-OK status returned on this thread (static storage). */
 CF_API const char* cf_last_error(void);

@@ -31,6 +31,7 @@ EXPORTS = ("cf_reposition_keys", "cf_prefill_workspace_bytes", "cf_prefill_atten
            "cf_assign_positions", "cf_gather_segments", "cf_last_error", "cf_version", "cf_calibrate", "cf_profile_kernel_events", "cf_profile_kernel_ms",
            "cf_prefill_layer", "cf_assemble_cache", "cf_prefill_attention_static")
 CF_STATIC_SCRATCH_BYTES = 32 << 20
+CF_MAX_PENDING = 15
 
 
 class cf_layer_desc(C.Structure):
@@ -97,7 +98,7 @@ def load() -> C.CDLL:
                                                 vp, vp, vp, i32, vp, vp]
     lib.cf_prefill_layer.restype = i32
     lib.cf_prefill_layer.argtypes = [dp, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp, i32, i32, i32, i64,
-                                     vp, vp, vp, i32, vp, sz, C.POINTER(cf_prune_step), vp, vp]
+                                     vp, vp, vp, i32, vp, sz, C.POINTER(cf_prune_step), i32, i32, vp, vp]
     lib.cf_prune_topk.restype = i32
     lib.cf_prune_topk.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp]
     lib.cf_assign_positions.restype = i32
@@ -236,12 +237,13 @@ def make_prune_step(keep: int, strategy: int, force_n_reuse: int, normalise_by_l
 def cf_prefill_layer(desc, q, q_off, q_stored_start: int, q_new_start, k_store, v_store, n_store_tokens: int,
                      k_self, v_self, segs, n_seg, seg_stride: int, batch: int, max_tq: int, max_kv_tokens: int, out,
                      mass, score_accum, score_stride: int, workspace, workspace_bytes: int,
-                     prune: Optional[cf_prune_step] = None, dev_flag=None, stream=None) -> None:
+                     prune: Optional[cf_prune_step] = None, dev_flag=None, stream=None, n_pending: int = 0,
+                     defer: bool = False) -> None:
     _check(load().cf_prefill_layer(
         C.byref(desc), _ptr(q), _ptr(q_off), q_stored_start, _ptr(q_new_start), _ptr(k_store), _ptr(v_store),
         n_store_tokens, _ptr(k_self), _ptr(v_self), _ptr(segs), _ptr(n_seg), seg_stride, batch, max_tq,
         max_kv_tokens, _ptr(out), _ptr(mass), _ptr(score_accum), score_stride, _ptr(workspace), workspace_bytes,
-        C.byref(prune) if prune is not None else None, _ptr(dev_flag), _stream(stream)))
+        C.byref(prune) if prune is not None else None, n_pending, 1 if defer else 0, _ptr(dev_flag), _stream(stream)))
 
 
 def cf_assemble_cache(desc, k_store, v_store, n_store_tokens: int, k_self, v_self, q_off, segs, n_seg, seg_stride: int,

@@ -196,10 +196,14 @@ static cf_status prefill_impl(const cf_layer_desc* desc, const void* q, const in
                                int32_t seg_stride, int32_t batch, int32_t max_tq, int64_t max_kv_tokens,
                                void* out, float* mass, float* score_accum, int32_t score_stride,
                                void* workspace, size_t workspace_bytes, const cf_prune_step* prune,
-                               int32_t* dev_flag, void* stream) {
+                               int32_t n_pending, int32_t defer, int32_t* dev_flag, void* stream) {
     cf_status st = check_desc(desc);
     if (st != CF_OK) return st;
     CF_REQUIRE(batch >= 0, CF_ERR_INVALID_ARG, "batch is negative");
+    CF_REQUIRE(n_pending >= 0 && n_pending <= kMaxPending && (defer == 0 || defer == 1), CF_ERR_INVALID_ARG,
+               "n_pending must be in [0, %d] and defer 0 or 1", kMaxPending);
+    CF_REQUIRE(!(defer && prune), CF_ERR_INVALID_ARG, "a call with a prune step cannot defer its scores");
+    CF_REQUIRE(!(defer && n_pending == kMaxPending), CF_ERR_INVALID_ARG, "%d layers are pending already: flush first", kMaxPending);
     CF_REQUIRE(max_tq >= 1, CF_ERR_INVALID_ARG, "max_tq must be >= 1");
     CF_REQUIRE(seg_stride >= 1, CF_ERR_INVALID_ARG, "seg_stride must be >= 1");
     CF_REQUIRE(n_store_tokens >= 0 && max_kv_tokens >= 0, CF_ERR_INVALID_ARG, "negative token count");
@@ -244,6 +248,8 @@ static cf_status prefill_impl(const cf_layer_desc* desc, const void* q, const in
     a.store_ts = store_token_stride(desc);
     a.store_hs = store_head_stride(desc);
     a.max_positions = desc->max_positions;
+    a.n_pending = n_pending;
+    a.defer = defer;
     RopeFreq f;
     fill_rope_freq(desc, &f);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -262,7 +268,7 @@ cf_status cf_prefill_attention(const cf_layer_desc* desc, const void* q, const i
                                void* workspace, size_t workspace_bytes, int32_t* dev_flag, void* stream) {
     return prefill_impl(desc, q, q_off, q_stored_start, q_new_start, k_store, v_store, n_store_tokens, k_self, v_self,
                         segs, n_seg, seg_stride, batch, max_tq, max_kv_tokens, out, mass, score_accum, score_stride,
-                        workspace, workspace_bytes, nullptr, dev_flag, stream);
+                        workspace, workspace_bytes, nullptr, 0, 0, dev_flag, stream);
 }
 
 // The library-owned scratch of cf_prefill_attention_static: one copy per GPU, at an address of its own on each.
@@ -313,7 +319,7 @@ cf_status cf_prefill_attention_static(const cf_layer_desc* desc, const void* q, 
     if (st != CF_OK) return st;
     return prefill_impl(desc, q, q_off, q_stored_start, q_new_start, k_store, v_store, n_store_tokens, k_self, v_self,
                         segs, n_seg, seg_stride, batch, max_tq, max_kv_tokens, out, mass, score_accum, score_stride,
-                        scratch, CF_STATIC_SCRATCH_BYTES, nullptr, dev_flag, stream);
+                        scratch, CF_STATIC_SCRATCH_BYTES, nullptr, 0, 0, dev_flag, stream);
 }
 
 cf_status cf_prefill_layer(const cf_layer_desc* desc, const void* q, const int32_t* q_off, int32_t q_stored_start,
@@ -321,12 +327,12 @@ cf_status cf_prefill_layer(const cf_layer_desc* desc, const void* q, const int32
                            int64_t n_store_tokens, const void* k_self, const void* v_self, const cf_segment* segs,
                            const int32_t* n_seg, int32_t seg_stride, int32_t batch, int32_t max_tq,
                            int64_t max_kv_tokens, void* out, float* mass, float* score_accum, int32_t score_stride,
-                           void* workspace, size_t workspace_bytes, const cf_prune_step* prune, int32_t* dev_flag,
-                           void* stream) {
+                           void* workspace, size_t workspace_bytes, const cf_prune_step* prune, int32_t n_pending,
+                           int32_t defer, int32_t* dev_flag, void* stream) {
     CF_REQUIRE(score_accum != nullptr, CF_ERR_INVALID_ARG, "cf_prefill_layer needs score_accum");
     return prefill_impl(desc, q, q_off, q_stored_start, q_new_start, k_store, v_store, n_store_tokens, k_self, v_self,
                         segs, n_seg, seg_stride, batch, max_tq, max_kv_tokens, out, mass, score_accum, score_stride,
-                        workspace, workspace_bytes, prune, dev_flag, stream);
+                        workspace, workspace_bytes, prune, n_pending, defer, dev_flag, stream);
 }
 
 cf_status cf_prune_topk(const float* score, const int32_t* len, const int32_t* cand, const int32_t* n_cand,

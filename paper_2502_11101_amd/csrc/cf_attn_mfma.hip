@@ -679,8 +679,10 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
 #undef CF_LAUNCH_TIMED
     if (!(p.direct_out && a.mass == nullptr)) launch_combine(a, p, s);    // else nothing left to merge or reduce
     CF_HIP(hipGetLastError());
+    if (a.defer) return CF_OK;                       // the slot partials stay in the ledger for a later call
     if (prune) {
         if (epilogue_fits(p, prune)) {
+            if (a.n_pending > 0) launch_pending_masses(a, p, s);
             launch_epilogue(a, p, prune, s);
         } else {
             launch_mass(a, p, s);

@@ -37,6 +37,7 @@ struct Plan {
     int groups;         // groups of four wavefronts per workgroup (each streams its own run of tiles): 1 or 2
     int direct_out;     // one split: the attention kernel writes the output rows itself, nothing to merge
     size_t off_ml, off_opart, off_massml, off_masspart, total;
+    size_t masspart_bytes;      // one layer's slot partials (the ledger holds kMaxPending + 1 such parts)
 };
 
 constexpr int kPcWaves = 8;         // wavefronts of an attn_pipe_kernel workgroup
@@ -88,7 +89,8 @@ inline Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int 
     p.off_ml = take((size_t)p.units * p.nsplit * p.rows_wg * sizeof(float2));
     p.off_opart = take(p.direct_out ? 0 : (size_t)p.units * p.nsplit * p.rows_wg * kD * sizeof(float));
     p.off_massml = take((size_t)p.units * p.slots * p.rows_wg * sizeof(float2));
-    p.off_masspart = take((size_t)p.units * p.nrb * p.slots * sizeof(float));
+    p.masspart_bytes = ((size_t)p.units * p.nrb * p.slots * sizeof(float) + 255) & ~(size_t)255;
+    p.off_masspart = take(p.masspart_bytes * (kMaxPending + 1));
     p.total = off;
     return p;
 }
@@ -353,6 +355,8 @@ struct TileWalk {
 // The kernels that follow the attention kernel of a call (defined with them; `a.dtype` selects the instance).
 void launch_combine(const AttnArgs& a, const attn::Plan& p, hipStream_t s);
 void launch_mass(const AttnArgs& a, const attn::Plan& p, hipStream_t s);
+// S += the masses of the layers whose scores are pending in the ledger (not the current call's): ahead of the fused epilogue
+void launch_pending_masses(const AttnArgs& a, const attn::Plan& p, hipStream_t s);
 // The fused epilogue keeps every per-document row and the slot partials of a query in LDS: whether they fit.
 bool epilogue_fits(const attn::Plan& p, const cf_prune_step* prune);
 void launch_epilogue(const AttnArgs& a, const attn::Plan& p, const cf_prune_step* prune, hipStream_t s);

@@ -130,7 +130,7 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     // slot partials: slot k = segment + split; slots no split wrote this call hold stale pairs and
     // give meaningless numbers that the mass kernel never reads
     if (a.mass != nullptr) {
-        float* masspart = reinterpret_cast<float*>(ws + p.off_masspart) + ((int64_t)unit * p.nrb + pass) * p.slots;
+        float* masspart = reinterpret_cast<float*>(ws + p.off_masspart + (size_t)a.n_pending * p.masspart_bytes) + ((int64_t)unit * p.nrb + pass) * p.slots;
         const float2 st = make_float2(row_max(lane), pass * 64 + lane < rows_here ? row_inv_sum(lane) : 0.f);   // padding rows carry no mass
         auto reduce = [&](int k, float2 v) {
             const float c = wave_sum_dpp(st.y > 0.f ? v.y * exp2f(v.x - st.x) * st.y : 0.f);
@@ -294,7 +294,9 @@ __device__ __forceinline__ float segment_masses_wave(const Plan& p, const RegSeg
 }
 
 // Third kernel: per-segment attention mass, one workgroup per query; then S += mass.
-__global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p) {
+// Takes parts 0 .. n_parts - 1 of the ledger in order; the last one's masses go to `mass` when `write_mass` is set
+// (it is not when only layers that deferred their scores are taken in, ahead of the fused epilogue).
+__global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p, int n_parts, int write_mass) {
     __shared__ SegTable tbl;
     __shared__ MassScratch ms;
     __shared__ float stage[kMassStage];
@@ -302,35 +304,51 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p)
     const int b = __builtin_amdgcn_readfirstlane(blockIdx.x);
     const int tid = threadIdx.x;
     const int n_part_floats = p.units_per_b * p.nrb * p.slots;
-    const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * n_part_floats;
+    // part j of the ledger: the slot partials of the j-th layer still pending (the last one is this call's)
+    auto part = [&](int j) { return reinterpret_cast<const float*>(ws + p.off_masspart + (size_t)j * p.masspart_bytes) + (int64_t)b * n_part_floats; };
     if (p.slots <= 2 * kWave && a.seg_stride <= kWave && n_part_floats <= kMassStage) {
         // small query: the partials go to LDS in one batch (requested before the query's scalars are waited for),
         // then one wavefront finishes alone from a table in its registers — the same sums in the same order
         float r_part[kMassStage / kThreads];
+        const float* mp0 = part(0);
 #pragma unroll
-        for (int i = 0; i < kMassStage / kThreads; ++i) r_part[i] = mp_b[min(tid + i * kThreads, n_part_floats - 1)];   // unconditional
+        for (int i = 0; i < kMassStage / kThreads; ++i) r_part[i] = mp0[min(tid + i * kThreads, n_part_floats - 1)];   // unconditional
         const QueryHead qh = load_query_head(a, b, tid & (kWave - 1));
 #pragma unroll
         for (int i = 0; i < kMassStage / kThreads; ++i)
             if (tid + i * kThreads < n_part_floats) stage[tid + i * kThreads] = r_part[i];
         __syncthreads();
-        if (tid >= kWave) return;
-        const RegSegTable rtbl = build_reg_table(a, qh, tid, p.tile);
-        const float m = segment_masses_wave(p, rtbl, stage, tid);
-        if (tid < rtbl.n) a.mass[(int64_t)b * a.seg_stride + tid] = m;
-        if (a.score_accum)                           // qh.seg is this lane's entry
-            add_doc_scores_wave(qh.seg.doc, m, rtbl.n, tid, a.score_accum + (int64_t)b * a.score_stride, a.score_stride);
+        if (n_parts == 1 && tid >= kWave) return;    // the other wavefronts only help to fetch further parts
+        const RegSegTable rtbl = build_reg_table(a, qh, tid & (kWave - 1), p.tile);
+        for (int j = 0; j < n_parts; ++j) {
+            if (j > 0) {
+                __syncthreads();                     // the staged part has been read
+                const float* mp = part(j);
+                for (int i = tid; i < n_part_floats; i += kThreads) stage[i] = mp[i];
+                __syncthreads();
+            }
+            if (tid < kWave) {
+                const float m = segment_masses_wave(p, rtbl, stage, tid);
+                if (write_mass && j == n_parts - 1 && tid < rtbl.n) a.mass[(int64_t)b * a.seg_stride + tid] = m;
+                if (a.score_accum)                   // qh.seg is this lane's entry
+                    add_doc_scores_wave(qh.seg.doc, m, rtbl.n, tid, a.score_accum + (int64_t)b * a.score_stride, a.score_stride);
+            }
+        }
         return;
     }
     const QueryHead qh = load_query_head(a, b, (int)threadIdx.x);
     build_table(a, qh, &tbl, p.tile);
-    segment_masses_block(p, tbl, const_cast<float*>(mp_b), stage, &ms, [&](int s, float m) {
-        a.mass[(int64_t)b * a.seg_stride + s] = m;
-        ms.seg_mass[s] = m;
-    });
-    if (a.score_accum == nullptr) return;
-    __syncthreads();
-    add_doc_scores_block(tbl.doc, ms.seg_mass, tbl.n, a.score_accum + (int64_t)b * a.score_stride, a.score_stride);
+    for (int j = 0; j < n_parts; ++j) {
+        const bool last = write_mass && j == n_parts - 1;
+        segment_masses_block(p, tbl, const_cast<float*>(part(j)), stage, &ms, [&](int s, float m) {
+            if (last) a.mass[(int64_t)b * a.seg_stride + s] = m;
+            ms.seg_mass[s] = m;
+        });
+        if (a.score_accum == nullptr) continue;
+        __syncthreads();
+        add_doc_scores_block(tbl.doc, ms.seg_mass, tbl.n, a.score_accum + (int64_t)b * a.score_stride, a.score_stride);
+        __syncthreads();
+    }
 }
 
 // Fused layer epilogue (third kernel of cf_prefill_layer): one workgroup per query computes the
@@ -339,6 +357,7 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p)
 // table, i.e. Alg. 2's "S += s; ids_sort = argsort(S); ids = prun(ids_sort)" followed by the
 // allocation of Sec. 2.5, without leaving the GPU.
 constexpr int kEpiThreads = 1024;
+
 
 struct PruneArgs {
     int32_t enabled, keep, strategy, force_n_reuse, normalise_by_len, stride, pos_begin, pos_end, prefix_len,
@@ -384,7 +403,9 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
     const int b = __builtin_amdgcn_readfirstlane(blockIdx.x);
     const int64_t off = (int64_t)b * stride;
     const int nparts = p.units_per_b * p.nrb;
-    const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart) + (int64_t)b * nparts * p.slots;
+    // this call's own slot partials are part n_pending of the ledger (earlier parts, of layers that deferred their
+    // scores, have been taken in by the mass kernel before this one)
+    const float* mp_b = reinterpret_cast<const float*>(ws + p.off_masspart + (size_t)a.n_pending * p.masspart_bytes) + (int64_t)b * nparts * p.slots;
     // The first batch of row loads, the slot partials and the query's scalars all go out before anything is waited
     // for; every load is unconditional (a clamped, in-bounds index: threads past the end re-read the last element and
     // drop it), since a load inside a branch is waited for before the branch ends.
@@ -415,14 +436,15 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
         l_start[i] = pr.new_start[off + i];
         l_order[i] = pr.order[off + i];
     }
+    // With few candidates one wavefront finishes alone: the others leave, and the barriers of the stages
+    // below (which only wait for wavefronts that are still running) cost nothing.
+    const int nthr = n_cand <= 2 * kWave ? kWave : kEpiThreads;
+    const bool small = nthr == kWave && p.slots <= 2 * kWave && a.seg_stride <= kWave;
 #pragma unroll
     for (int i = 0; i < kPartRegs; ++i)
         if (tid + i * kEpiThreads < n_part_floats) l_part[tid + i * kEpiThreads] = r_part[i];
     for (int i = tid + kPartRegs * kEpiThreads; i < n_part_floats; i += kEpiThreads) l_part[i] = mp_b[i];
-    // With few candidates one wavefront finishes alone: the others leave, and the barriers of the stages
-    // below (which only wait for wavefronts that are still running) cost nothing.
-    const int nthr = n_cand <= 2 * kWave ? kWave : kEpiThreads;
-    if (nthr == kWave && p.slots <= 2 * kWave && a.seg_stride <= kWave) {
+    if (small) {
         // small query: the first wavefront also does the masses, from a table in its registers
         __syncthreads();                             // publishes the rows above
         if (tid >= kWave) return;
@@ -485,7 +507,11 @@ void launch_combine(const AttnArgs& a, const Plan& p, hipStream_t s) {
 }
 
 void launch_mass(const AttnArgs& a, const Plan& p, hipStream_t s) {
-    hipLaunchKernelGGL(attn_mass_kernel, dim3((unsigned)a.batch), dim3(kThreads), 0, s, a, p);
+    hipLaunchKernelGGL(attn_mass_kernel, dim3((unsigned)a.batch), dim3(kThreads), 0, s, a, p, a.n_pending + 1, 1);
+}
+
+void launch_pending_masses(const AttnArgs& a, const Plan& p, hipStream_t s) {
+    hipLaunchKernelGGL(attn_mass_kernel, dim3((unsigned)a.batch), dim3(kThreads), 0, s, a, p, a.n_pending, 0);
 }
 
 static size_t epilogue_lds_bytes(const Plan& p, const cf_prune_step* prune) {

@@ -185,7 +185,12 @@ struct AttnArgs {
     float scale_log2e;   // softmax scale times log2(e)
     int64_t store_ts, store_hs;   // element strides of the cache store between tokens / kv heads
     int32_t max_positions;        // positions are valid in [0, max_positions)
+    // Deferred document-wise scores (cf_prefill_layer): this call's slot partials go to part `n_pending` of the
+    // workspace's ledger; with `defer` set nothing reduces them yet, otherwise the reduction takes parts 0 .. n_pending
+    // in order (S += s^l layer by layer, Alg. 2).
+    int32_t n_pending, defer;
 };
+constexpr int kMaxPending = 15;   // layers whose scores may be pending in a workspace
 
 inline int64_t store_token_stride(const cf_layer_desc* d) {
     return d->store_token_stride ? d->store_token_stride : (int64_t)d->n_kv_heads * d->head_dim;

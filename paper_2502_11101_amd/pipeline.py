@@ -93,6 +93,7 @@ class PrefillBatch:
         self.ws_bytes = cf.cf_prefill_workspace_bytes(desc, self.batch, tq, self.seg_stride, self.max_kv_tokens)
         self.workspace = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=device)   # contents are scratch
         self.n_alive = self.stride
+        self.n_pending = 0          # layers whose scores are still pending in the workspace (layer(defer=True))
         self._cache = None          # device addresses and the prune-step struct of the current tables (layer())
 
     # -- Alg. 2 init: every document is a candidate, placement order = retriever order
@@ -132,8 +133,11 @@ class PrefillBatch:
         self._pending_keep = keep
 
     # -- Alg. 2, one whole layer in one call: attention, S += s^l and, with `keep` given, the prune event
+    # With `defer` (no prune event in this layer) the layer's scores stay pending in the workspace and are taken in, in
+    # layer order, by the next call that does not defer — Alg. 2 reads S only at the prune events.
     def layer(self, q, k_self, v_self, k_store, v_store, out, keep: Optional[int] = None,
-              strategy: int = cf.CF_ALLOC_SORT, normalise_by_len: bool = True, force_n_reuse: int = 0) -> None:
+              strategy: int = cf.CF_ALLOC_SORT, normalise_by_len: bool = True, force_n_reuse: int = 0,
+              defer: bool = False) -> None:
         # the tables' addresses only change in advance(): marshal them once, not per call
         c = self._cache
         if c is None:
@@ -158,10 +162,13 @@ class PrefillBatch:
         cf.cf_prefill_layer(self.desc, q.data_ptr(), c["q_off"], self.q_stored_start, c["q_start"], k_store.data_ptr(),
                             v_store.data_ptr(), self.n_store_tokens, k_self.data_ptr(), v_self.data_ptr(), c["segs"],
                             c["n_seg"], self.seg_stride, self.batch, self.tq, self.max_kv_tokens, out.data_ptr(),
-                            c["mass"], c["score"], self.stride, c["workspace"], self.ws_bytes, step, c["dev_flag"])
+                            c["mass"], c["score"], self.stride, c["workspace"], self.ws_bytes, step, c["dev_flag"],
+                            None, self.n_pending, defer)
+        self.n_pending = self.n_pending + 1 if defer else 0
 
     # -- the survivors, in placement order, become the candidates of the following layers
     def advance(self) -> None:
+        assert self.n_pending == 0, "scores cannot be pending across a change of the tables"
         self.cand, self.order = self.order, self.cand
         self.n_cand, self.n_keep = self.n_keep, self.n_cand
         self.segs, self.next_segs = self.next_segs, self.segs

@@ -112,6 +112,35 @@ def test_prefill_argument_checks():
                             None, 0, None, 0, stream=0)
 
 
+def test_deferred_score_and_static_scratch_argument_checks():
+    """cf_prefill_layer's n_pending / defer and cf_prefill_attention_static's size limit are checked on the host, before
+    any HIP call."""
+    d = _desc()
+    layer = dict(desc=d, q=FAKE, q_off=FAKE, q_stored_start=0, q_new_start=FAKE, k_store=FAKE, v_store=FAKE, n_store_tokens=100,
+                 k_self=FAKE, v_self=FAKE, segs=FAKE, n_seg=FAKE, seg_stride=4, batch=1, max_tq=8, max_kv_tokens=100, out=FAKE,
+                 mass=FAKE, score_accum=FAKE, score_stride=2, workspace=None, workspace_bytes=0, stream=0)
+    assert _status(cf.cf_prefill_layer, **layer)[0] == cf.CF_ERR_WORKSPACE                    # everything else is accepted
+    assert _status(cf.cf_prefill_layer, **dict(layer, n_pending=-1))[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.cf_prefill_layer, **dict(layer, n_pending=cf.CF_MAX_PENDING + 1))[0] == cf.CF_ERR_INVALID_ARG
+    st, msg = _status(cf.cf_prefill_layer, **dict(layer, n_pending=cf.CF_MAX_PENDING, defer=True))
+    assert st == cf.CF_ERR_INVALID_ARG and "flush" in msg
+    assert _status(cf.cf_prefill_layer, **dict(layer, n_pending=cf.CF_MAX_PENDING))[0] == cf.CF_ERR_WORKSPACE
+    assert _status(cf.cf_prefill_layer, **dict(layer, score_accum=None))[0] == cf.CF_ERR_INVALID_ARG
+    # the library-owned scratch: a shape whose workspace exceeds it is refused with the sizes in the message
+    big = _desc()
+    big.n_q_heads, big.n_kv_heads = 28, 4
+    need = cf.cf_prefill_workspace_bytes(big, 64, 64, 52, 8000)
+    assert need > cf.CF_STATIC_SCRATCH_BYTES
+    static = {k: v for k, v in layer.items() if k not in ("workspace", "workspace_bytes")}
+    st, msg = _status(cf.cf_prefill_attention_static, **dict(static, desc=big, batch=64, max_tq=64, seg_stride=52, max_kv_tokens=8000))
+    assert st == cf.CF_ERR_WORKSPACE and str(need) in msg and "library-owned" in msg
+    # calibration kernels: bad arguments
+    assert _status(cf.cf_calibrate, cf.CF_CALIB_READ, None, None, 1024, 16, 0, FAKE, stream=0)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.cf_calibrate, cf.CF_CALIB_COPY, FAKE, FAKE, 1024, 16, 0, FAKE, stream=0)[0] == cf.CF_ERR_INVALID_ARG   # dst == src
+    assert _status(cf.cf_calibrate, 9, FAKE, FAKE + 4096, 1024, 16, 0, FAKE, stream=0)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.cf_calibrate, cf.CF_CALIB_MFMA_BF16, None, None, 0, 16, 0, FAKE, stream=0)[0] == cf.CF_ERR_INVALID_ARG     # iters 0
+
+
 def test_prune_and_assign_argument_checks():
     assert _status(cf.cf_prune_topk, FAKE, None, FAKE, FAKE, 5, 1, 4, FAKE + 64, FAKE, stream=0)[0] == cf.CF_ERR_INVALID_ARG  # keep > stride
     assert _status(cf.cf_prune_topk, FAKE, None, FAKE, FAKE, -1, 1, 4, FAKE + 64, FAKE, stream=0)[0] == cf.CF_ERR_INVALID_ARG
