@@ -37,12 +37,13 @@ HEADLINE = "llama2_7b_stack"
 REPEATS = 5
 # HBM bytes per launch of each workload's dominant kernel (read + written), from the FETCH_SIZE and WRITE_SIZE
 # counter runs summarised under profiles/ (one file per kernel and workload, with the commands; both counters
-# scaled by what they read for a copy kernel of known size).  None: not measured for the kernels as they stand.
+# scaled by what they read for a copy kernel of known size: FETCH_SIZE reads half the bytes of a 1 GiB copy, hence
+# the factor 2 on it, WRITE_SIZE reads them all; both are in KiB).  None: not measured for the kernels as they stand.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    "llama2_7b_stack": None,
-    "llama2_7b_layer": None,
-    "qwen2_7b_layer": None,
-    "qwen2_1p5b_batch": None,
+    "llama2_7b_stack": int((2 * 23406.6 + 6606.0) * 1024),      # mean of the stack's 32 launches
+    "llama2_7b_layer": int((2 * 15084.8 + 6504.0) * 1024),
+    "qwen2_7b_layer": int((2 * 16983.6 + 20020.0) * 1024),
+    "qwen2_1p5b_batch": int((2 * 103536.1 + 20736.0) * 1024),
 }
 
 

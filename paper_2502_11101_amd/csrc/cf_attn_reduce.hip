@@ -351,6 +351,50 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p,
     }
 }
 
+// The same for a small query with several parts to take in (layers that deferred their scores): one wavefront per
+// part works out that layer's masses straight from the ledger, all parts at once; the first wavefront then adds them
+// to the scores part by part — S += s^l in layer order, each document slot by the lane of its first table entry, so
+// the sums are those of the one-part-after-the-other form above, bit for bit.  Block: 64 * n_parts threads.
+__global__ __launch_bounds__(kWave * (kMaxPending + 1)) void pending_masses_kernel(AttnArgs a, Plan p, int n_parts, int write_mass) {
+    __shared__ float m_all[kMaxPending + 1][kWave];
+    const char* ws = static_cast<const char*>(a.workspace);
+    const int b = __builtin_amdgcn_readfirstlane(blockIdx.x);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave);
+    const int n_part_floats = p.units_per_b * p.nrb * p.slots;
+    const QueryHead qh = load_query_head(a, b, lane);
+    const RegSegTable rtbl = build_reg_table(a, qh, lane, p.tile);
+    const float* mp = reinterpret_cast<const float*>(ws + p.off_masspart + (size_t)wave * p.masspart_bytes) + (int64_t)b * n_part_floats;
+    const float m = segment_masses_wave(p, rtbl, mp, lane);
+    m_all[wave][lane] = m;
+    if (write_mass && wave == n_parts - 1 && lane < rtbl.n) a.mass[(int64_t)b * a.seg_stride + lane] = m;
+    __syncthreads();
+    if (wave != 0 || a.score_accum == nullptr) return;
+    // which entries feed this lane's document slot, and whether this lane is the slot's first entry: as in
+    // add_doc_scores_wave, with the table walked once for all parts
+    const int doc = qh.seg.doc;
+    const bool valid = lane < rtbl.n && doc >= 0 && doc < a.score_stride;
+    const int d = valid ? doc : -1;
+    bool first = valid;
+    unsigned long long later = 0;                    // entries after this one that feed the same slot
+    for (int j = 0; j < rtbl.n; ++j) {
+        const int dj = __builtin_amdgcn_readlane(d, j);
+        if (dj == d) {
+            if (j < lane) first = false;
+            else if (j > lane) later |= 1ull << j;
+        }
+    }
+    if (!first) return;
+    float* slot = a.score_accum + (int64_t)b * a.score_stride + d;
+    float s = *slot;
+    for (int part = 0; part < n_parts; ++part) {
+        float sum = m_all[part][lane];
+        for (unsigned long long rest = later; rest; rest &= rest - 1) sum += m_all[part][__builtin_ctzll(rest)];
+        s += sum;
+    }
+    *slot = s;
+}
+
 // Fused layer epilogue (third kernel of cf_prefill_layer): one workgroup per query computes the
 // attention mass of every segment (fixed summation order), adds it to the accumulated scores, and — when a prune step is attached —
 // ranks the candidates, allocates the survivors' positions and writes the next layer's segment
@@ -506,13 +550,18 @@ void launch_combine(const AttnArgs& a, const Plan& p, hipStream_t s) {
     else hipLaunchKernelGGL((attn_combine_kernel<CF_F16>), grid, block, 0, s, a, p);
 }
 
-void launch_mass(const AttnArgs& a, const Plan& p, hipStream_t s) {
-    hipLaunchKernelGGL(attn_mass_kernel, dim3((unsigned)a.batch), dim3(kThreads), 0, s, a, p, a.n_pending + 1, 1);
+// several parts of a small query: one wavefront per part (see pending_masses_kernel); else one part after the other
+static void launch_masses(const AttnArgs& a, const Plan& p, int n_parts, int write_mass, hipStream_t s) {
+    const bool small = p.slots <= 2 * kWave && a.seg_stride <= kWave;
+    if (n_parts > 1 && small)
+        hipLaunchKernelGGL(pending_masses_kernel, dim3((unsigned)a.batch), dim3(kWave * n_parts), 0, s, a, p, n_parts, write_mass);
+    else
+        hipLaunchKernelGGL(attn_mass_kernel, dim3((unsigned)a.batch), dim3(kThreads), 0, s, a, p, n_parts, write_mass);
 }
 
-void launch_pending_masses(const AttnArgs& a, const Plan& p, hipStream_t s) {
-    hipLaunchKernelGGL(attn_mass_kernel, dim3((unsigned)a.batch), dim3(kThreads), 0, s, a, p, a.n_pending, 0);
-}
+void launch_mass(const AttnArgs& a, const Plan& p, hipStream_t s) { launch_masses(a, p, a.n_pending + 1, 1, s); }
+
+void launch_pending_masses(const AttnArgs& a, const Plan& p, hipStream_t s) { launch_masses(a, p, a.n_pending, 0, s); }
 
 static size_t epilogue_lds_bytes(const Plan& p, const cf_prune_step* prune) {
     return (size_t)44 * prune->stride + (size_t)4 * p.units_per_b * p.nrb * p.slots;
