@@ -677,12 +677,15 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
     if (a.dtype == CF_BF16) { CF_LAUNCH_DT(CF_BF16) } else { CF_LAUNCH_DT(CF_F16) }
 #undef CF_LAUNCH_DT
 #undef CF_LAUNCH_TIMED
-    if (!(p.direct_out && a.mass == nullptr)) launch_combine(a, p, s);    // else nothing left to merge or reduce
+    const bool combine = !(p.direct_out && a.mass == nullptr);            // else nothing left to merge or reduce
+    // before a fused epilogue the pending score parts are taken in by one more row of the combine kernel's grid
+    const bool pending_beside = combine && !a.defer && prune && a.n_pending > 0 && epilogue_fits(p, prune) && pending_fit_combine(a, p);
+    if (combine) launch_combine(a, p, pending_beside, s);
     CF_HIP(hipGetLastError());
     if (a.defer) return CF_OK;                       // the slot partials stay in the ledger for a later call
     if (prune) {
         if (epilogue_fits(p, prune)) {
-            if (a.n_pending > 0) launch_pending_masses(a, p, s);
+            if (a.n_pending > 0 && !pending_beside) launch_pending_masses(a, p, s);
             launch_epilogue(a, p, prune, s);
         } else {
             launch_mass(a, p, s);

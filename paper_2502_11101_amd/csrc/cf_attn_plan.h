@@ -353,7 +353,8 @@ struct TileWalk {
 }  // namespace attn
 
 // The kernels that follow the attention kernel of a call (defined with them; `a.dtype` selects the instance).
-void launch_combine(const AttnArgs& a, const attn::Plan& p, hipStream_t s);
+void launch_combine(const AttnArgs& a, const attn::Plan& p, bool take_pending, hipStream_t s);
+bool pending_fit_combine(const AttnArgs& a, const attn::Plan& p);
 void launch_mass(const AttnArgs& a, const attn::Plan& p, hipStream_t s);
 // S += the masses of the layers whose scores are pending in the ledger (not the current call's): ahead of the fused epilogue
 void launch_pending_masses(const AttnArgs& a, const attn::Plan& p, hipStream_t s);

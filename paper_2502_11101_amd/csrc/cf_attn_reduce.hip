@@ -11,9 +11,21 @@ namespace {
 // splits' partial outputs and writes its output rows; the eight workgroups of a (unit, pass) also share
 // the reduction, over the pass's 64 rows, of every (segment, split) slot's (max, sum) pairs to
 // sum * exp2(max - row max) / row sum, which the mass kernel then only has to add up.
+__device__ __forceinline__ void pending_masses_block(const AttnArgs& a, const Plan& p, int b, int n_parts, int write_mass,
+                                                     float (*m_all)[kWave]);
+
+// With take_pending the grid has one more row of workgroups (the last blockIdx.y); the first of them, per query, takes
+// the ledger's pending score parts in beside the merge (pending_masses_block), the others leave at once.
 template <int DT>
-__global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan p) {
+__global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan p, int take_pending) {
     __shared__ float2 mlw[kMaxSplit * 64];       // (m, l) per split and row, then exp2(m - row maximum) in .x
+    static_assert(sizeof(float2) * kMaxSplit * 64 >= sizeof(float) * (kMaxPending + 1) * kWave, "the parts' masses reuse mlw");
+    const int units_y = (int)gridDim.y - take_pending;
+    if (take_pending && (int)blockIdx.y == units_y) {
+        if (blockIdx.x == 0)
+            pending_masses_block(a, p, __builtin_amdgcn_readfirstlane(blockIdx.z), a.n_pending, 0, reinterpret_cast<float (*)[kWave]>(mlw));
+        return;
+    }
     __shared__ float part_stat[kWaves][64], part_sum[kWaves][64];   // per wavefront: its splits' maximum and sum, per row
     constexpr int kPre = 8;                      // splits whose partial outputs are fetched before the statistics are ready
 
@@ -30,7 +42,7 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     const int b = blockIdx.z;
     const int hkv = p.n_rg == 1 ? (int)blockIdx.y : (int)div_exact(blockIdx.y, (unsigned)p.n_rg);
     const int rg = (int)blockIdx.y - hkv * p.n_rg;
-    const int unit = b * (int)gridDim.y + (int)blockIdx.y;
+    const int unit = b * units_y + (int)blockIdx.y;
     const int q0 = a.q_off[b], q1 = a.q_off[b + 1];
     const float2* ml = reinterpret_cast<const float2*>(ws + p.off_ml) + (int64_t)unit * p.nsplit * p.rows_wg + pass * 64;
     const f32x4* opart = reinterpret_cast<const f32x4*>(ws + p.off_opart) + (int64_t)unit * p.nsplit * p.rows_wg * (kD / 4);
@@ -354,20 +366,23 @@ __global__ __launch_bounds__(kThreads) void attn_mass_kernel(AttnArgs a, Plan p,
 // The same for a small query with several parts to take in (layers that deferred their scores): one wavefront per
 // part works out that layer's masses straight from the ledger, all parts at once; the first wavefront then adds them
 // to the scores part by part — S += s^l in layer order, each document slot by the lane of its first table entry, so
-// the sums are those of the one-part-after-the-other form above, bit for bit.  Block: 64 * n_parts threads.
-__global__ __launch_bounds__(kWave * (kMaxPending + 1)) void pending_masses_kernel(AttnArgs a, Plan p, int n_parts, int write_mass) {
-    __shared__ float m_all[kMaxPending + 1][kWave];
+// the sums are those of the one-part-after-the-other form above, bit for bit.  Any whole number of wavefronts per block;
+// with fewer wavefronts than parts a wavefront takes several parts, one after the other.
+__device__ __forceinline__ void pending_masses_block(const AttnArgs& a, const Plan& p, int b, int n_parts, int write_mass,
+                                                     float (*m_all)[kWave]) {
     const char* ws = static_cast<const char*>(a.workspace);
-    const int b = __builtin_amdgcn_readfirstlane(blockIdx.x);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave);
+    const int n_waves = (int)blockDim.x / kWave;
     const int n_part_floats = p.units_per_b * p.nrb * p.slots;
     const QueryHead qh = load_query_head(a, b, lane);
     const RegSegTable rtbl = build_reg_table(a, qh, lane, p.tile);
-    const float* mp = reinterpret_cast<const float*>(ws + p.off_masspart + (size_t)wave * p.masspart_bytes) + (int64_t)b * n_part_floats;
-    const float m = segment_masses_wave(p, rtbl, mp, lane);
-    m_all[wave][lane] = m;
-    if (write_mass && wave == n_parts - 1 && lane < rtbl.n) a.mass[(int64_t)b * a.seg_stride + lane] = m;
+    for (int part = wave; part < n_parts; part += n_waves) {
+        const float* mp = reinterpret_cast<const float*>(ws + p.off_masspart + (size_t)part * p.masspart_bytes) + (int64_t)b * n_part_floats;
+        const float m = segment_masses_wave(p, rtbl, mp, lane);
+        m_all[part][lane] = m;
+        if (write_mass && part == n_parts - 1 && lane < rtbl.n) a.mass[(int64_t)b * a.seg_stride + lane] = m;
+    }
     __syncthreads();
     if (wave != 0 || a.score_accum == nullptr) return;
     // which entries feed this lane's document slot, and whether this lane is the slot's first entry: as in
@@ -393,6 +408,11 @@ __global__ __launch_bounds__(kWave * (kMaxPending + 1)) void pending_masses_kern
         s += sum;
     }
     *slot = s;
+}
+
+__global__ __launch_bounds__(kWave * (kMaxPending + 1)) void pending_masses_kernel(AttnArgs a, Plan p, int n_parts, int write_mass) {
+    __shared__ float m_all[kMaxPending + 1][kWave];
+    pending_masses_block(a, p, __builtin_amdgcn_readfirstlane(blockIdx.x), n_parts, write_mass, m_all);
 }
 
 // Fused layer epilogue (third kernel of cf_prefill_layer): one workgroup per query computes the
@@ -544,16 +564,18 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
 
 }  // namespace
 
-void launch_combine(const AttnArgs& a, const Plan& p, hipStream_t s) {
-    const dim3 grid((unsigned)((p.direct_out ? 1 : 8) * p.nrb), (unsigned)(a.n_kv_heads * p.n_rg), (unsigned)a.batch), block(kThreads);
-    if (a.dtype == CF_BF16) hipLaunchKernelGGL((attn_combine_kernel<CF_BF16>), grid, block, 0, s, a, p);
-    else hipLaunchKernelGGL((attn_combine_kernel<CF_F16>), grid, block, 0, s, a, p);
+bool pending_fit_combine(const AttnArgs& a, const Plan& p) { return p.slots <= 2 * kWave && a.seg_stride <= kWave; }
+
+void launch_combine(const AttnArgs& a, const Plan& p, bool take_pending, hipStream_t s) {
+    const int extra = take_pending ? 1 : 0;
+    const dim3 grid((unsigned)((p.direct_out ? 1 : 8) * p.nrb), (unsigned)(a.n_kv_heads * p.n_rg + extra), (unsigned)a.batch), block(kThreads);
+    if (a.dtype == CF_BF16) hipLaunchKernelGGL((attn_combine_kernel<CF_BF16>), grid, block, 0, s, a, p, extra);
+    else hipLaunchKernelGGL((attn_combine_kernel<CF_F16>), grid, block, 0, s, a, p, extra);
 }
 
 // several parts of a small query: one wavefront per part (see pending_masses_kernel); else one part after the other
 static void launch_masses(const AttnArgs& a, const Plan& p, int n_parts, int write_mass, hipStream_t s) {
-    const bool small = p.slots <= 2 * kWave && a.seg_stride <= kWave;
-    if (n_parts > 1 && small)
+    if (n_parts > 1 && pending_fit_combine(a, p))
         hipLaunchKernelGGL(pending_masses_kernel, dim3((unsigned)a.batch), dim3(kWave * n_parts), 0, s, a, p, n_parts, write_mass);
     else
         hipLaunchKernelGGL(attn_mass_kernel, dim3((unsigned)a.batch), dim3(kThreads), 0, s, a, p, n_parts, write_mass);
