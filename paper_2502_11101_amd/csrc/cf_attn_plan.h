@@ -87,7 +87,7 @@ inline Plan make_plan(int n_q_heads, int n_kv_heads, int batch, int max_tq, int 
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
     p.off_ml = take((size_t)p.units * p.nsplit * p.rows_wg * sizeof(float2));
-    p.off_opart = take(p.direct_out ? 0 : (size_t)p.units * p.nsplit * p.rows_wg * kD * sizeof(float));
+    p.off_opart = take(p.direct_out ? 0 : (size_t)p.units * p.nsplit * p.rows_wg * kD * sizeof(uint16_t));
     p.off_massml = take((size_t)p.units * p.slots * p.rows_wg * sizeof(float2));
     p.masspart_bytes = ((size_t)p.units * p.nrb * p.slots * sizeof(float) + 255) & ~(size_t)255;
     p.off_masspart = take(p.masspart_bytes * (kMaxPending + 1));

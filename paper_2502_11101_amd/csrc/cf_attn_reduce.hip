@@ -18,7 +18,7 @@ __device__ __forceinline__ void pending_masses_block(const AttnArgs& a, const Pl
 // the ledger's pending score parts in beside the merge (pending_masses_block), the others leave at once.
 template <int DT>
 __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan p, int take_pending) {
-    __shared__ float2 mlw[kMaxSplit * 64];       // (m, l) per split and row, then exp2(m - row maximum) in .x
+    __shared__ float2 mlw[kMaxSplit * 64];       // (m, l) per split and row, then the split's weight l * exp2(m - row maximum) in .x
     static_assert(sizeof(float2) * kMaxSplit * 64 >= sizeof(float) * (kMaxPending + 1) * kWave, "the parts' masses reuse mlw");
     const int units_y = (int)gridDim.y - take_pending;
     if (take_pending && (int)blockIdx.y == units_y) {
@@ -45,9 +45,10 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     const int unit = b * units_y + (int)blockIdx.y;
     const int q0 = a.q_off[b], q1 = a.q_off[b + 1];
     const float2* ml = reinterpret_cast<const float2*>(ws + p.off_ml) + (int64_t)unit * p.nsplit * p.rows_wg + pass * 64;
-    const f32x4* opart = reinterpret_cast<const f32x4*>(ws + p.off_opart) + (int64_t)unit * p.nsplit * p.rows_wg * (kD / 4);
+    const uint2* opart = reinterpret_cast<const uint2*>(ws + p.off_opart) + (int64_t)unit * p.nsplit * p.rows_wg * (kD / 4);
     const int blk = pass * kWaves + wave;                      // row block inside the workgroup tile
-    const f32x4* src = opart + ((int64_t)blk * 8 + dbq) * kWave + lane;
+    const uint2* src = opart + ((int64_t)blk * 8 + dbq) * kWave + lane;
+    auto widen = [](uint2 w) { return f32x4{Mma<DT>::lo(w.x), Mma<DT>::hi(w.x), Mma<DT>::lo(w.y), Mma<DT>::hi(w.y)}; };
     const int64_t split_stride = (int64_t)p.rows_wg / 16 * 8 * kWave;
     const float2* massml = reinterpret_cast<const float2*>(ws + p.off_massml) + (int64_t)unit * p.slots * p.rows_wg + pass * 64 + lane;
     const int k_first = dbq * kWaves + wave, k_step = kWaves << x_shift;
@@ -69,9 +70,9 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
         const int idx = min(tid + i * kThreads, n_ml - 1);
         ml_regs[i] = ml[(idx >> 6) * p.rows_wg + (idx & 63)];
     }
-    const f32x4* src_safe = merge ? src : reinterpret_cast<const f32x4*>(ws + p.off_ml) + (lane & 31);
+    const uint2* src_safe = merge ? src : reinterpret_cast<const uint2*>(ws + p.off_ml) + (lane & 31);
     const int64_t stride_safe = merge ? split_stride : 0;
-    f32x4 pre[kPre];
+    uint2 pre[kPre];
 #pragma unroll
     for (int s = 0; s < kPre; ++s) pre[s] = src_safe[min(s, p.nsplit - 1) * stride_safe];
     float2 sv[kSv];
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
             const float2 v = mlw[s * 64 + lane];
             const float e = exp2f(v.x - ms);
             z += v.y * e;
-            mlw[s * 64 + lane].x = e;
+            mlw[s * 64 + lane].x = v.y * e;          // the split's rows arrive divided by their own sum
         }
         part_sum[wave][lane] = z;
     }
@@ -118,15 +119,15 @@ __global__ __launch_bounds__(kThreads) void attn_combine_kernel(AttnArgs a, Plan
     f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < kPre; ++s)
-        if (s < p.nsplit) o += pre[s] * mlw[s * 64 + wave * 16 + li].x;
+        if (s < p.nsplit) o += widen(pre[s]) * mlw[s * 64 + wave * 16 + li].x;
     if (merge && blk_has_rows)
         for (int s0 = kPre; s0 < p.nsplit; s0 += kPre) {         // further splits, eight loads at a time
-            f32x4 more[kPre];
+            uint2 more[kPre];
 #pragma unroll
             for (int i = 0; i < kPre; ++i) more[i] = src[min(s0 + i, p.nsplit - 1) * split_stride];      // unconditional, as above
 #pragma unroll
             for (int i = 0; i < kPre; ++i)
-                if (s0 + i < p.nsplit) o += more[i] * mlw[(s0 + i) * 64 + wave * 16 + li].x;
+                if (s0 + i < p.nsplit) o += widen(more[i]) * mlw[(s0 + i) * 64 + wave * 16 + li].x;
         }
     const int lrow = pass * 64 + wave * 16 + li;
     o *= row_inv_sum(wave * 16 + li);

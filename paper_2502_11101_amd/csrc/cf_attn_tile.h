@@ -256,8 +256,8 @@ __device__ __forceinline__ void emit_segment(const RowState<NRB>& st, float2* ma
     }
 }
 
-// Results of a split.  Several splits: partial O^T in MFMA layout (one float4 per lane, row block and
-// channel block) for the merge kernel.  One split: nothing to merge, the rows are normalised and written to
+// Results of a split.  Several splits: partial O^T in MFMA layout (four 16-bit values per lane, row block and
+// channel block, each row divided by the split's own row sum) for the merge kernel.  One split: nothing to merge, the rows are normalised and written to
 // `out` here (row m = g*tq + t of the stacked rows is out[q0 + t][hkv*group + g]).  Either way (reference,
 // row sum) per row, which the mass reduction needs.
 template <int DT, int NRB>
@@ -287,12 +287,18 @@ __device__ __forceinline__ void store_partials(const AttnArgs& a, const Plan& p,
         }
         return;
     }
-    f32x4* opart = reinterpret_cast<f32x4*>(ws + p.off_opart) +
+    // the split's rows leave normalised by their own sums, in the tensors' 16-bit type: bounded by the values
+    // themselves whatever the sums are, and half the bytes of the accumulators
+    uint2* opart = reinterpret_cast<uint2*>(ws + p.off_opart) +
                    (((int64_t)unit * p.nsplit + split) * p.rows_wg / 16 + first_blk) * 8 * kWave + lane;
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
+        const float inv = l_row[rb] > 0.f ? 1.f / l_row[rb] : 0.f;
 #pragma unroll
-        for (int db = 0; db < 8; ++db) opart[(rb * 8 + db) * kWave] = st.acc[rb][db];
+        for (int db = 0; db < 8; ++db) {
+            const f32x4 o = st.acc[rb][db] * inv;
+            opart[(rb * 8 + db) * kWave] = make_uint2(Mma<DT>::pack(o[0], o[1]), Mma<DT>::pack(o[2], o[3]));
+        }
         if ((lane >> 4) == 0) ml[(first_blk + rb) * 16 + (lane & 15)] = make_float2(st.m_run[rb], l_row[rb]);
     }
 }
