@@ -40,10 +40,10 @@ REPEATS = 5
 # scaled by what they read for a copy kernel of known size: FETCH_SIZE reads half the bytes of a 1 GiB copy, hence
 # the factor 2 on it, WRITE_SIZE reads them all; both are in KiB).  None: not measured for the kernels as they stand.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    "llama2_7b_stack": int((2 * 23406.6 + 6606.0) * 1024),      # mean of the stack's 32 launches
-    "llama2_7b_layer": int((2 * 15084.8 + 6504.0) * 1024),
-    "qwen2_7b_layer": int((2 * 16983.6 + 20020.0) * 1024),
-    "qwen2_1p5b_batch": int((2 * 103536.1 + 20736.0) * 1024),
+    "llama2_7b_stack": int((2 * 23409.1 + 3534.0) * 1024),      # mean of the stack's 32 launches
+    "llama2_7b_layer": int((2 * 15087.3 + 3432.0) * 1024),
+    "qwen2_7b_layer": int((2 * 16987.6 + 10612.0) * 1024),
+    "qwen2_1p5b_batch": int((2 * 103534.6 + 20736.0) * 1024),
 }
 
 
@@ -73,20 +73,25 @@ def timed_repeats(step, steps: int, warmup: int, repeats: int = REPEATS):
     return _median(per_step), per_step
 
 
-def attention_kernel_ms(step, n_steps: int, launches_per_step: int):
-    """Mean duration of the attention kernel's launches over `n_steps` more steps, from start/stop events that the
-    library attaches to those dispatches on the launch stream (at most 1024 launches are kept)."""
+def attention_kernel_ms(step, n_steps: int, launches_per_step: int, batches: int = REPEATS):
+    """Duration of the attention kernel's launches, from start/stop events that the library attaches to those
+    dispatches on the launch stream: `batches` batches of up to `n_steps` more steps (at most 1024 launches are kept
+    per batch), each batch's mean taken, the median of the batch means returned with the number of launches timed."""
     import torch
     from paper_2502_11101_amd import binding as cf
     n_steps = max(1, min(n_steps, 1000 // launches_per_step))
-    cf.cf_profile_kernel_events(True)
-    for i in range(n_steps):
-        step(i)
-    torch.cuda.synchronize()
-    ms, n = cf.cf_profile_kernel_ms()
-    cf.cf_profile_kernel_events(False)
-    assert n == n_steps * launches_per_step, (n, n_steps, launches_per_step)
-    return ms, n
+    means, total = [], 0
+    for _ in range(batches):
+        cf.cf_profile_kernel_events(True)
+        for i in range(n_steps):
+            step(i)
+        torch.cuda.synchronize()
+        ms, n = cf.cf_profile_kernel_ms()
+        cf.cf_profile_kernel_events(False)
+        assert n == n_steps * launches_per_step, (n, n_steps, launches_per_step)
+        means.append(ms)
+        total += n
+    return _median(means), total
 
 
 def single_step_latency_ms(step, n: int = 20) -> float:
