@@ -245,6 +245,9 @@ def setup_layer(name: str, args):
         per_layer = args.batch * cfg.docs_per_query * cfg.doc_len_range[1] * 2 * g.n_kv_heads * g.head_dim * 2
         n_layers = max(2, min(n_layers, int(3.0e9 // per_layer)))
     st = wl.build_structure(cfg)
+    # enough distinct layer buffers that what a step reads was evicted since its last use: twice the 256 MB cache
+    store_bytes = 2 * st.n_store_tokens * g.n_kv_heads * g.head_dim * 2
+    n_layers = max(n_layers, min(96, -(-2 * (256 << 20) // store_bytes)))
     ts, hs = pl.store_strides(st.n_store_tokens, g.n_kv_heads, g.head_dim, args.store_layout)
     desc = cf.make_desc(g.n_q_heads, g.n_kv_heads, g.head_dim, g.dtype, g.rope_base, g.max_positions,
                         store_token_stride=ts, store_head_stride=hs)
