@@ -48,6 +48,11 @@ SHAPES = {
     # fp32, head_dim 64: the generic kernel
     "f32_generic": (wl.Geometry(4, 2, 64, "f32", 1.0e6, 32768), 2, 8, 4, 4, (20, 40)),
 }
+# fp16 shapes whose plans have several splits (used by the range test at the end)
+FP16_SHAPES = {
+    "few_rows_splits_f16": (wl.Geometry(8, 8, 128, "f16", 1.0e6, 32768), 1, 48, 32, 12, (160, 160)),
+    "many_rows_splits_f16": (wl.Geometry(28, 4, 128, "f16", 1.0e6, 32768), 1, 64, 32, 16, (100, 200)),
+}
 PATTERNS = ["rising", "falling", "late_spike", "sawtooth", "equal"]
 SPREAD = 4.0            # largest coefficient of the common direction: about 45 nats between first and last key
 
@@ -65,11 +70,11 @@ def _common_direction(d):
     return u
 
 
-def _build_case(shape, pattern, rotated, seed):
+def _build_case(shape, pattern, rotated, seed, shapes=None):
     """Inputs and tables of one case.  Unrotated: every segment sits where it was cached and the query where it
     was computed, so the kernels rotate nothing and their keys equal the oracle's bit for bit.  Rotated: documents
     were cached at the prefix length and are moved to packed positions, the query from 0 to behind them."""
-    g, batch, tq, prefix, docs, (lo, hi) = SHAPES[shape]
+    g, batch, tq, prefix, docs, (lo, hi) = (shapes or SHAPES)[shape]
     rng = np.random.default_rng(seed)
     lens = rng.integers(lo, hi + 1, size=(batch, docs))
     doc_off = prefix + np.concatenate([[0], np.cumsum(lens.reshape(-1))])
@@ -219,3 +224,24 @@ def test_softmax_scale_override(shape, factor):
     # the override is used: the default scale gives something else
     got_default, _ = _run(g, batch, tq, n_store, tables, q_stored, q_pos, t)
     assert G.row_error(got_default, got.astype(np.float64)) > 1e-2
+
+
+@pytest.mark.parametrize("shape", ["few_rows_splits_f16", "many_rows_splits_f16"])
+def test_values_near_the_top_of_fp16_survive_the_split_merge(shape):
+    """Several splits per row hand partial rows to the merge in the tensors' 16-bit type.  With values of a few
+    ten thousand — the top of fp16 — and thousands of keys, a row's unnormalised accumulator passes fp16's range by
+    orders of magnitude; the partial rows are therefore divided by the split's own row sum first and stay bounded by
+    the values themselves.  Outputs (Eq. 1) must still match the oracle in the usual metric and none may be
+    infinite."""
+    _say(f"fp16 range {shape}")
+    g, batch, tq, n_store, tables, q_stored, q_pos, t = _build_case(shape, "sawtooth", False, seed=len(shape), shapes=FP16_SHAPES)
+    rng = np.random.default_rng(99)
+    for name in ("v_store", "v_self"):
+        big = rng.uniform(-3.0e4, 3.0e4, size=t[name].shape).astype(np.float32)
+        t[name] = wl.round_to_dtype(big, g.dtype)
+    got, m = _run(g, batch, tq, n_store, tables, q_stored, q_pos, t)
+    assert np.isfinite(got).all()
+    worst_out, worst_mass = _check(g, batch, tq, tables, q_stored, q_pos, t, got, m, rotated=False)
+    _say(f"  out err {worst_out:.3e}  mass err {worst_mass:.3e}")
+    assert worst_out <= G.OUT_TOL[g.dtype]
+    assert worst_mass <= G.MASS_TOL[g.dtype]
