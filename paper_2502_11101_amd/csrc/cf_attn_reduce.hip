@@ -278,14 +278,37 @@ __device__ __forceinline__ void segment_masses_block(const Plan& p, const SegTab
 // The same for one wavefront on its own, for a query with at most 128 slots and a register table: lane k adds
 // up columns k and k + 64, lane s then collects segment s's slots — the same sums in the same order, no barrier.
 // Returns lane s's segment mass (0 for lanes past the table).
+// FROM_MEMORY: `parts` is read from memory, not LDS: a column of at most 32 parts is then requested in one batch
+// (clamped, unconditional loads) before the first add, instead of a round trip per group of eight.
+template <bool FROM_MEMORY = false>
 __device__ __forceinline__ float segment_masses_wave(const Plan& p, const RegSegTable& t, const float* parts, int lane) {
     const unsigned total = (unsigned)t.total;
     const unsigned nsub = (unsigned)(p.nsplit * p.groups);
     const int nparts = p.units_per_b * p.nrb;
     constexpr int kGroup = 8;
     float c[2] = {0.f, 0.f};                         // columns lane, lane + 64
+    int first_looped = 0;
+    if constexpr (FROM_MEMORY) {
+        constexpr int kBatch = 32;
+        if (nparts <= kBatch) {
+            float v[kBatch];
+            const float* col = parts + min(lane, p.slots - 1);
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+            for (int i = 0; i < kBatch; ++i) v[i] = col[min(i, nparts - 1) * p.slots];
+            if (lane < p.slots) {
+#pragma unroll
+                for (int g0 = 0; g0 < kBatch; g0 += kGroup) {
+                    float gs = 0.f;                  // the same sums in the same order as group_sum
+#pragma unroll
+                    for (int i = 0; i < kGroup; ++i)
+                        if (g0 + i < nparts) gs += v[g0 + i];
+                    if (g0 < nparts) c[0] += gs;
+                }
+            }
+            first_looped = 1;
+        }
+    }
+    for (int j = first_looped; j < 2; ++j)
         if (lane + 64 * j < p.slots)
             for (int g0 = 0; g0 < nparts; g0 += kGroup)
                 c[j] += group_sum(parts + g0 * p.slots + lane + 64 * j, p.slots, min(kGroup, nparts - g0));
@@ -380,7 +403,7 @@ __device__ __forceinline__ void pending_masses_block(const AttnArgs& a, const Pl
     const RegSegTable rtbl = build_reg_table(a, qh, lane, p.tile);
     for (int part = wave; part < n_parts; part += n_waves) {
         const float* mp = reinterpret_cast<const float*>(ws + p.off_masspart + (size_t)part * p.masspart_bytes) + (int64_t)b * n_part_floats;
-        const float m = segment_masses_wave(p, rtbl, mp, lane);
+        const float m = segment_masses_wave<true>(p, rtbl, mp, lane);
         m_all[part][lane] = m;
         if (write_mass && part == n_parts - 1 && lane < rtbl.n) a.mass[(int64_t)b * a.seg_stride + lane] = m;
     }
