@@ -203,10 +203,31 @@ __device__ __forceinline__ void add_doc_scores_block(const int32_t* doc, const f
         if (first) score[d] += sum;
     }
 }
-// Wavefront form: lane s < n holds entry s's slot and mass.  The loop runs once per table entry.
+// Bitwise OR over the 64 lanes of a wavefront, handed to every lane (DPP row shifts, then the two row broadcasts).
+__device__ __forceinline__ uint32_t wave_or_u32(uint32_t x) {
+    int v = (int)x;
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v |= __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+    return (uint32_t)__builtin_amdgcn_readlane(v, 63);
+}
+// Wavefront form: lane s < n holds entry s's slot and mass.  With at most 64 document slots a bit mask tells whether
+// every slot is fed by one entry only — the usual table — and then every entry adds its own mass (the same single
+// addend as below); otherwise the loop runs once per table entry.
 __device__ __forceinline__ void add_doc_scores_wave(int doc, float m, int n, int lane, float* score, int stride) {
     const bool valid = lane < n && doc >= 0 && doc < stride;
     const int d = valid ? doc : -1;
+    if (stride <= kWave) {
+        const unsigned long long bit = valid ? 1ull << d : 0ull;
+        const int slots_fed = __builtin_popcount(wave_or_u32((uint32_t)bit)) + __builtin_popcount(wave_or_u32((uint32_t)(bit >> 32)));
+        if (slots_fed == __builtin_popcountll(__ballot(valid))) {
+            if (valid) score[d] += m;
+            return;
+        }
+    }
     bool first = valid;
     float sum = m;
     for (int j = 0; j < n; ++j) {
@@ -278,9 +299,9 @@ __device__ __forceinline__ void segment_masses_block(const Plan& p, const SegTab
 // The same for one wavefront on its own, for a query with at most 128 slots and a register table: lane k adds
 // up columns k and k + 64, lane s then collects segment s's slots — the same sums in the same order, no barrier.
 // Returns lane s's segment mass (0 for lanes past the table).
-// FROM_MEMORY: `parts` is read from memory, not LDS: a column of at most 32 parts is then requested in one batch
-// (clamped, unconditional loads) before the first add, instead of a round trip per group of eight.
-template <bool FROM_MEMORY = false>
+// BATCHED: a column of at most 40 parts is requested in one batch (clamped, unconditional loads) before the first
+// add, instead of a round trip — to memory or to LDS — per group of eight.
+template <bool BATCHED = false>
 __device__ __forceinline__ float segment_masses_wave(const Plan& p, const RegSegTable& t, const float* parts, int lane) {
     const unsigned total = (unsigned)t.total;
     const unsigned nsub = (unsigned)(p.nsplit * p.groups);
@@ -288,8 +309,8 @@ __device__ __forceinline__ float segment_masses_wave(const Plan& p, const RegSeg
     constexpr int kGroup = 8;
     float c[2] = {0.f, 0.f};                         // columns lane, lane + 64
     int first_looped = 0;
-    if constexpr (FROM_MEMORY) {
-        constexpr int kBatch = 32;
+    if constexpr (BATCHED) {
+        constexpr int kBatch = 40;
         if (nparts <= kBatch) {
             float v[kBatch];
             const float* col = parts + min(lane, p.slots - 1);
@@ -474,6 +495,7 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
     __shared__ SegTable tbl;
     __shared__ MassScratch ms;
     __shared__ int s_int[6];
+    __shared__ uint4 s_bcast[kWave];
 
     const int tid = threadIdx.x;
     const int stride = pr.stride;
@@ -558,7 +580,7 @@ __global__ __launch_bounds__(kEpiThreads) void layer_epilogue_kernel(AttnArgs a,
     if (n_cand <= kWave) {                               // the usual case: everything in one wavefront's registers
         SelectWaveArgs sw;
         sw.score = l_score; sw.len = l_len; sw.cand = l_cand; sw.tok = l_tok; sw.keep_idx = l_keep; sw.new_start = l_start;
-        sw.order = l_order; sw.n = n_cand; sw.keep = pr.keep; sw.stride = stride; sw.normalise_by_len = pr.normalise_by_len;
+        sw.order = l_order; sw.bcast = s_bcast; sw.n = n_cand; sw.keep = pr.keep; sw.stride = stride; sw.normalise_by_len = pr.normalise_by_len;
         sw.strategy = pr.strategy; sw.force_n_reuse = pr.force_n_reuse; sw.pos_begin = pr.pos_begin; sw.pos_end = pr.pos_end;
         sw.prefix_len = pr.prefix_len; sw.doc_stored_start = pr.doc_stored_start; sw.q_stored_start = a.q_stored_start;
         sw.q_lo = qh.q0; sw.q_hi = qh.q0 + qh.tq_raw; sw.seg_stride = a.seg_stride;

@@ -217,6 +217,7 @@ __device__ inline void gather_segments_block(const int64_t* doc_tok_offset, cons
 struct SelectWaveArgs {
     const float* score; const int32_t* len; const int32_t* cand; const int64_t* tok;
     int32_t* keep_idx; int32_t* new_start; int32_t* order;
+    uint4* bcast;                                   // LDS, 64 entries: the ranking keys, read back as broadcasts
     int n, keep, stride, normalise_by_len, strategy, force_n_reuse, pos_begin, pos_end;
     int prefix_len, doc_stored_start, q_stored_start, q_lo, q_hi, seg_stride;
 };
@@ -265,13 +266,17 @@ __device__ inline bool select_wave64(const SelectWaveArgs& s, int* n_keep_out, i
         u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;
         const uint32_t low = ((uint32_t)(s.stride - 1 - c) << 6) | (uint32_t)(63 - lane);     // stride <= 2^26
         const uint64_t key = ((uint64_t)u << 32) | low;
-        for (int j0 = 0; j0 < n; j0 += 4) {          // four at a time: their lane reads and compares overlap
+        // every lane's key goes to LDS once; candidate j's key is then one broadcast read (the same address in every
+        // lane), eight requested at a time
+        // (lanes past n publish the smallest key: read, never counted)
+        s.bcast[lane] = have ? make_uint4(low, u, 0u, 0u) : make_uint4(0u, 0u, 0u, 0u);
+        __builtin_amdgcn_wave_barrier();
+        for (int j0 = 0; j0 < n; j0 += 8) {
+            uint2 e[8];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int j = j0 + i;                // lanes past n are read and not counted
-                const uint32_t hj = (uint32_t)__builtin_amdgcn_readlane((int)u, j & 63), lj = (uint32_t)__builtin_amdgcn_readlane((int)low, j & 63);
-                rank += (int)((j < n) & ((((uint64_t)hj << 32) | lj) > key));
-            }
+            for (int i = 0; i < 8; ++i) e[i] = *reinterpret_cast<const uint2*>(&s.bcast[(j0 + i) & 63]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) rank += ((((uint64_t)e[i].y << 32) | e[i].x) > key) ? 1 : 0;
         }
     } else {
         // Unequal lengths: the quotient score/len in fp64 orders exactly as the cross products of ranks_before do —
@@ -287,13 +292,22 @@ __device__ inline bool select_wave64(const SelectWaveArgs& s, int* n_keep_out, i
             return __builtin_bit_cast(double, bits);
         };
         if (s.stride <= (1 << 26)) {
-            for (int j0 = 0; j0 < n; j0 += 4) {      // four at a time: their lane reads and compares overlap
+            // as above: (quotient, tie-break word) of every lane in LDS, broadcast reads, eight at a time
+            // (lanes past n publish minus infinity: read, never counted; the selects keep the predicate in vector
+            // registers instead of wavefront masks worked on by the scalar unit)
+            const uint64_t never = __builtin_bit_cast(uint64_t, -__builtin_inf());
+            s.bcast[lane] = have ? make_uint4((uint32_t)q_lo, (uint32_t)q_hi, low, 0u) : make_uint4((uint32_t)never, (uint32_t)(never >> 32), 0u, 0u);
+            __builtin_amdgcn_wave_barrier();
+            for (int j0 = 0; j0 < n; j0 += 8) {
+                uint4 e[8];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int j = j0 + i;            // < 64 + 3; lanes past n are read and not counted
-                    const double qj = lane_quotient(j & 63);
-                    const bool tie_first = (uint32_t)__builtin_amdgcn_readlane((int)low, j & 63) > low;
-                    rank += (int)((j < n) & ((qj > q) | ((qj == q) & tie_first)));
+                for (int i = 0; i < 8; ++i) e[i] = s.bcast[(j0 + i) & 63];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const double qj = __builtin_bit_cast(double, ((uint64_t)e[i].y << 32) | e[i].x);
+                    const int tie = e[i].z > low ? 1 : 0;
+                    const int eq = qj == q ? tie : 0;
+                    rank += qj > q ? 1 : eq;
                 }
             }
         } else {                                     // `low` would not hold the slot
