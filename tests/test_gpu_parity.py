@@ -1290,10 +1290,12 @@ def test_largest_relative_shifts(base, max_pos):
         assert G.rel_error(m[b], near_mass) <= G.NEAR_MASS_TOL[g.dtype]
 
 
-def test_layer_calls_replay_from_a_hip_graph():
+@pytest.mark.parametrize("deferred", [False, True])
+def test_layer_calls_replay_from_a_hip_graph(deferred):
     """The library allocates nothing and clears nothing with memsets, so its calls can be captured: four layer calls
-    (a prune event in each) recorded into one HIP graph replay to exactly the eager results, several times, with
-    eager work and synchronisations between the replays."""
+    (a prune event in each — or, deferred, three layers that leave their scores pending and a prune event that takes
+    them in) recorded into one HIP graph replay to exactly the eager results, several times, with eager work and
+    synchronisations between the replays."""
     cfg = wl.CONFIGS["llama2_7b_layer"]
     st = wl.build_structure(cfg)
     layers = [G.upload_layer(cfg, wl.build_layer(cfg, st, layer), "head") for layer in range(4)]
@@ -1302,8 +1304,10 @@ def test_layer_calls_replay_from_a_hip_graph():
     outs = [torch.empty_like(layers[0]["q"]) for _ in layers]
 
     def run_all():
-        for L, o in zip(layers, outs):
-            pb.layer(L["q"], L["k_self"], L["v_self"], L["k_store"], L["v_store"], o, keep=cfg.keep)
+        for i, (L, o) in enumerate(zip(layers, outs)):
+            last = i == len(layers) - 1
+            pb.layer(L["q"], L["k_self"], L["v_self"], L["k_store"], L["v_store"], o,
+                     keep=cfg.keep if (last or not deferred) else None, defer=deferred and not last)
 
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):
