@@ -656,8 +656,9 @@ cf_status launch_attention_mfma(const AttnArgs& a, const RopeFreq& f, hipStream_
     const Plan p = make_plan(a.n_q_heads, a.n_kv_heads, a.batch, a.max_tq, a.seg_stride, a.max_kv_tokens);
     const dim3 grid((unsigned)(p.x_count * p.n_rg));
     const dim3 grid3((unsigned)p.nsplit, (unsigned)a.n_kv_heads, (unsigned)a.batch);     // attn_tile_kernel's
-    if (a.batch > 65535 || (int64_t)a.n_kv_heads * p.n_rg > 65535) {          // grid dimensions of this path's kernels
-        set_error("batch and n_kv_heads * row groups must not exceed 65535 on this path");
+    // grid dimensions of this path's kernels (the merge kernel's may carry one more row, for pending score parts)
+    if (a.batch > 65535 || (int64_t)a.n_kv_heads * p.n_rg + 1 > 65535) {
+        set_error("batch must not exceed 65535 and n_kv_heads * row groups 65534 on this path");
         return CF_ERR_UNSUPPORTED;
     }
     const bool reg_table = a.seg_stride <= kWave;    // the attention kernels keep a table this small in registers
